@@ -1,0 +1,139 @@
+/*
+ * tbn.h -- C ABI of libtbn: inference kernels for tiled-bit layers on AMD MI355X (gfx950).
+ *
+ * A tiled-bit layer (Tiled Bit Networks, arXiv 2407.12075, Section "Method") stores, for a
+ * layer with n weights, one tile of p = n / k entries in {-1,+1} and one or k scalars alpha.
+ * The dense weight it stands for is
+ *
+ *     B_hat[f] = alpha[n_alpha == 1 ? 0 : f / p] * t[f % p],      f = 0 .. n-1
+ *
+ * where f is the row-major flat index of the weight tensor ((out, in) for a fully-connected
+ * layer, (O, C, kh, kw) for a convolution; last index fastest) -- Eq. 4 (tile repeated k times
+ * back to back), Eq. 5 (reshape) and the per-tile scaling stated after Eq. 8.  The paper writes
+ * N, p, q for what is called n, k, p here.
+ *
+ * Tile format (the contract for "bit exact"): an array of 32-bit words, little endian; tile
+ * entry i lives in word i / 32 at bit i % 32 (least significant bit first); bit 1 means +1,
+ * bit 0 means -1; unused high bits of the last word are zero.
+ *
+ * Conventions for every entry point
+ *   - Pointers named below as DEVICE pointers must be device memory of the current HIP device;
+ *     the caller owns every buffer.  The library keeps no state between calls and allocates
+ *     no device memory.
+ *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).  Work is enqueued
+ *     on it and the call returns without synchronising.
+ *   - On TBN_ERR_NULL / _SHAPE / _UNSUPPORTED / _WORKSPACE nothing has been enqueued and no
+ *     output is touched.  TBN_ERR_DEVICE reports a failed HIP launch; work enqueued before the
+ *     failing launch may still run and outputs are then undefined.  tbn_last_error() describes
+ *     the problem.
+ *   - No bias term exists in this layer type (the paper does not use bias parameters).
+ */
+#ifndef TBN_H
+#define TBN_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+    TBN_OK = 0,
+    TBN_ERR_NULL = 1,        /* a required pointer is NULL */
+    TBN_ERR_SHAPE = 2,       /* non-positive size, n not divisible by k, n_alpha not in {1, k} */
+    TBN_ERR_UNSUPPORTED = 3, /* unknown dtype or flag, size beyond the supported range */
+    TBN_ERR_DEVICE = 4,      /* a HIP call failed; text in tbn_last_error() */
+    TBN_ERR_WORKSPACE = 5    /* workspace missing, misaligned or too small */
+} tbn_status;
+
+typedef enum {
+    TBN_F32 = 0,  /* IEEE binary32 activations, binary32 accumulation */
+    TBN_BF16 = 1  /* bfloat16 activations and outputs, binary32 accumulation, outputs rounded
+                     to nearest even */
+} tbn_dtype;
+
+/* flags of the forward entry points */
+#define TBN_FLAG_RELU 0x1u          /* y = max(0, y): the fused ReLU of Algorithm 1 */
+#define TBN_FLAG_FORCE_GENERIC 0x100u /* testing aid: skip the specialised kernels */
+
+/* Number of 32-bit words of a tile of n / k entries (ceil(n / k / 32)); 0 if n <= 0, k <= 0 or
+ * k does not divide n (the paper requires n divisible by the compression factor). */
+size_t tbn_tile_words(int64_t n, int32_t k);
+
+/* Message for the last non-OK status returned on the calling thread; never NULL. */
+const char *tbn_last_error(void);
+
+/* Library version string, static storage. */
+const char *tbn_version(void);
+
+/* Bytes of device workspace tbn_pack_tile needs for these sizes (0 on invalid sizes). */
+size_t tbn_pack_workspace_bytes(int64_t n, int32_t k, int32_t n_alpha);
+
+/*
+ * Tile construction, Eq. 1-3, and scalars, Eq. 6 (n_alpha == 1) or Eq. 7-8 (n_alpha == k).
+ *
+ *   s[i]      = sum_{r=0}^{k-1} w_real[r * p + i]      (double precision, r ascending)
+ *   tile[i]   = +1 if s[i] > 0, else -1                (zero and NaN give -1)
+ *   alpha[0]  = sum_f |a[f]| / n                                        if n_alpha == 1
+ *   alpha[r]  = sum_{i<p} |a[r * p + i]| / p,  r = 0..k-1               if n_alpha == k
+ *
+ * with a = a_real if it is not NULL, else w_real (the paper's separate tensor A for the
+ * scalars is optional).  alpha sums are taken in double precision and rounded once to float.
+ *
+ *   w_real, a_real : DEVICE, n floats each, flattened row-major weight tensor; read only
+ *   tile_out       : DEVICE, tbn_tile_words(n, k) words, fully overwritten
+ *   alpha_out      : DEVICE, n_alpha floats, overwritten
+ *   workspace      : DEVICE, at least tbn_pack_workspace_bytes(n, k, n_alpha) bytes, 8-byte
+ *                    aligned; contents on entry are ignored, contents on exit are undefined
+ * Errors: TBN_ERR_NULL, TBN_ERR_SHAPE (k <= 0, n <= 0, n % k != 0, n_alpha not 1 or k),
+ *         TBN_ERR_WORKSPACE, TBN_ERR_DEVICE.
+ */
+tbn_status tbn_pack_tile(const float *w_real, const float *a_real, int64_t n, int32_t k,
+                         int32_t n_alpha, uint32_t *tile_out, float *alpha_out,
+                         void *workspace, size_t workspace_bytes, void *stream);
+
+/*
+ * Fully-connected tiled-bit layer:  Y = X * B_hat^T  (the layer operation applied to B_hat,
+ * stated after Eq. 8; Algorithm 1 is the same computation for one input vector).
+ *
+ *   y[m, o] = sum_{j<in} x[m, j] * alpha[(o*in + j) / p or 0] * t[(o*in + j) % p],  p = in*out/k
+ *
+ *   x     : DEVICE, M x in, row-major, dense, element type dt; read only
+ *   y     : DEVICE, M x out, row-major, dense, element type dt; fully overwritten
+ *   tile  : DEVICE, tbn_tile_words(in*out, k) words; read only
+ *   alpha : DEVICE, n_alpha floats (n_alpha is 1 or k); read only
+ *   flags : 0 or TBN_FLAG_RELU (| TBN_FLAG_FORCE_GENERIC)
+ * M == 0 is legal and does nothing (x and y may then be NULL).  x and y must not overlap.
+ * Errors: TBN_ERR_NULL, TBN_ERR_SHAPE, TBN_ERR_UNSUPPORTED, TBN_ERR_DEVICE.
+ */
+tbn_status tbn_linear_forward(const void *x, void *y, tbn_dtype dt, int64_t M, int64_t in,
+                              int64_t out, const uint32_t *tile, int32_t k, const float *alpha,
+                              int32_t n_alpha, uint32_t flags, void *stream);
+
+/*
+ * Convolutional tiled-bit layer (the paper tiles the flattened (O, C, kh, kw) weight the same
+ * way, Section "Method"; Section "CNN Architectures" gives the replicated-channel example):
+ * cross-correlation with zero padding, stride (stride_h, stride_w), dilation 1, one group.
+ *
+ *   y[b, o, yo, xo] = sum_{c, dy, dx} B_hat[o, c, dy, dx] * x[b, c, yo*stride_h + dy - pad_h,
+ *                                                                   xo*stride_w + dx - pad_w]
+ *   Ho = (H + 2*pad_h - kh) / stride_h + 1,  Wo = (W + 2*pad_w - kw) / stride_w + 1
+ *
+ *   x : DEVICE, (N, C, H, W) row-major dense, element type dt; read only
+ *   y : DEVICE, (N, O, Ho, Wo) row-major dense, element type dt; fully overwritten
+ *   tile, alpha, flags : as for tbn_linear_forward with n = O*C*kh*kw
+ * N == 0 is legal and does nothing (x and y may then be NULL).
+ * Errors: TBN_ERR_NULL, TBN_ERR_SHAPE (also: kernel larger than the padded input),
+ *         TBN_ERR_UNSUPPORTED, TBN_ERR_DEVICE.
+ */
+tbn_status tbn_conv2d_forward(const void *x, void *y, tbn_dtype dt, int64_t N, int64_t C,
+                              int64_t H, int64_t W, int64_t O, int32_t kh, int32_t kw,
+                              int32_t stride_h, int32_t stride_w, int32_t pad_h, int32_t pad_w,
+                              const uint32_t *tile, int32_t k, const float *alpha,
+                              int32_t n_alpha, uint32_t flags, void *stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* TBN_H */

@@ -1,0 +1,179 @@
+// C ABI of libtbn: argument validation and choice of kernel family.  See include/tbn.h for the
+// contract of each entry point and the passages of the paper that define the operations.
+#include "tbn_common.h"
+
+#include <cstdarg>
+#include <cstdio>
+#include <numeric>
+
+namespace tbn {
+
+static thread_local char g_err[512] = "";
+
+void set_error(const char *fmt, ...) {
+    va_list ap;
+    va_start(ap, fmt);
+    vsnprintf(g_err, sizeof(g_err), fmt, ap);
+    va_end(ap);
+}
+
+tbn_status check_launch(const char *what) {
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) {
+        set_error("%s: %s", what, hipGetErrorString(e));
+        return TBN_ERR_DEVICE;
+    }
+    return TBN_OK;
+}
+
+int64_t unique_rows(int64_t rows, int64_t row_len, int64_t p) {
+    // row o starts at tile bit (o * row_len) % p; that offset has period p / gcd(row_len, p) in o
+    const int64_t g = std::gcd(row_len, p);
+    const int64_t period = p / g;
+    return period < rows ? period : rows;
+}
+
+static bool mul_ok(int64_t a, int64_t b, int64_t *r) { return !__builtin_mul_overflow(a, b, r); }
+
+static tbn_status check_tiling(int64_t n, int32_t k, int32_t n_alpha) {
+    if (n <= 0 || k <= 0) {
+        set_error("n (%lld) and k (%d) must be positive", (long long)n, k);
+        return TBN_ERR_SHAPE;
+    }
+    if (n % k != 0) {
+        set_error("the number of weights %lld is not divisible by the compression factor %d", (long long)n, k);
+        return TBN_ERR_SHAPE;
+    }
+    if (n_alpha != 1 && n_alpha != k) {
+        set_error("n_alpha must be 1 or k (%d), got %d", k, n_alpha);
+        return TBN_ERR_SHAPE;
+    }
+    return TBN_OK;
+}
+
+}  // namespace tbn
+
+using namespace tbn;
+
+extern "C" {
+
+size_t tbn_tile_words(int64_t n, int32_t k) {
+    if (n <= 0 || k <= 0 || n % k != 0) return 0;
+    return static_cast<size_t>((n / k + 31) / 32);
+}
+
+const char *tbn_last_error(void) { return g_err; }
+
+const char *tbn_version(void) { return "libtbn 0.1 (gfx950)"; }
+
+size_t tbn_pack_workspace_bytes(int64_t n, int32_t k, int32_t n_alpha) {
+    if (n <= 0 || k <= 0 || n % k != 0 || (n_alpha != 1 && n_alpha != k)) return 0;
+    return pack_workspace_bytes(n, k, n_alpha);
+}
+
+tbn_status tbn_pack_tile(const float *w_real, const float *a_real, int64_t n, int32_t k,
+                         int32_t n_alpha, uint32_t *tile_out, float *alpha_out,
+                         void *workspace, size_t workspace_bytes, void *stream) {
+    if (!w_real || !tile_out || !alpha_out) {
+        set_error("tbn_pack_tile: w_real, tile_out and alpha_out must not be NULL");
+        return TBN_ERR_NULL;
+    }
+    tbn_status st = check_tiling(n, k, n_alpha);
+    if (st != TBN_OK) return st;
+    const size_t need = pack_workspace_bytes(n, k, n_alpha);
+    if (!workspace || workspace_bytes < need || (reinterpret_cast<uintptr_t>(workspace) & 7u)) {
+        set_error("tbn_pack_tile: workspace of %zu bytes, 8-byte aligned, required (got %zu at %p)",
+                  need, workspace_bytes, workspace);
+        return TBN_ERR_WORKSPACE;
+    }
+    return launch_pack(w_real, a_real, n, k, n_alpha, tile_out, alpha_out, workspace,
+                       static_cast<hipStream_t>(stream));
+}
+
+tbn_status tbn_linear_forward(const void *x, void *y, tbn_dtype dt, int64_t M, int64_t in,
+                              int64_t out, const uint32_t *tile, int32_t k, const float *alpha,
+                              int32_t n_alpha, uint32_t flags, void *stream) {
+    if (!tile || !alpha || (M > 0 && (!x || !y))) {  // an empty batch may come with NULL x and y
+        set_error("tbn_linear_forward: x, y, tile and alpha must not be NULL");
+        return TBN_ERR_NULL;
+    }
+    if (dt != TBN_F32 && dt != TBN_BF16) {
+        set_error("tbn_linear_forward: unknown dtype %d", (int)dt);
+        return TBN_ERR_UNSUPPORTED;
+    }
+    if (flags & ~(TBN_FLAG_RELU | TBN_FLAG_FORCE_GENERIC)) {
+        set_error("tbn_linear_forward: unknown flag bits 0x%x", flags);
+        return TBN_ERR_UNSUPPORTED;
+    }
+    if (M < 0 || in <= 0 || out <= 0) {
+        set_error("tbn_linear_forward: M >= 0, in > 0, out > 0 required (M=%lld in=%lld out=%lld)",
+                  (long long)M, (long long)in, (long long)out);
+        return TBN_ERR_SHAPE;
+    }
+    int64_t n, xs, ys;
+    if (!mul_ok(in, out, &n) || !mul_ok(M, in, &xs) || !mul_ok(M, out, &ys) || n > (int64_t(1) << 40) ||
+        xs > (int64_t(1) << 40) || ys > (int64_t(1) << 40)) {
+        set_error("tbn_linear_forward: sizes beyond the supported range");
+        return TBN_ERR_UNSUPPORTED;
+    }
+    tbn_status st = check_tiling(n, k, n_alpha);
+    if (st != TBN_OK) return st;
+    if (M == 0) return TBN_OK;
+
+    LinearArgs a{x, y, (int)dt, M, in, out, tile, n / k, k, alpha, n_alpha, flags,
+                 static_cast<hipStream_t>(stream)};
+    if (!(flags & TBN_FLAG_FORCE_GENERIC)) {
+        if (linear_rows_supported(a)) return launch_linear_rows(a);
+        if (linear_mfma_supported(a)) return launch_linear_mfma(a);
+    }
+    return launch_linear_generic(a);
+}
+
+tbn_status tbn_conv2d_forward(const void *x, void *y, tbn_dtype dt, int64_t N, int64_t C,
+                              int64_t H, int64_t W, int64_t O, int32_t kh, int32_t kw,
+                              int32_t stride_h, int32_t stride_w, int32_t pad_h, int32_t pad_w,
+                              const uint32_t *tile, int32_t k, const float *alpha,
+                              int32_t n_alpha, uint32_t flags, void *stream) {
+    if (!tile || !alpha || (N > 0 && (!x || !y))) {  // an empty batch may come with NULL x and y
+        set_error("tbn_conv2d_forward: x, y, tile and alpha must not be NULL");
+        return TBN_ERR_NULL;
+    }
+    if (dt != TBN_F32 && dt != TBN_BF16) {
+        set_error("tbn_conv2d_forward: unknown dtype %d", (int)dt);
+        return TBN_ERR_UNSUPPORTED;
+    }
+    if (flags & ~(TBN_FLAG_RELU | TBN_FLAG_FORCE_GENERIC)) {
+        set_error("tbn_conv2d_forward: unknown flag bits 0x%x", flags);
+        return TBN_ERR_UNSUPPORTED;
+    }
+    if (N < 0 || C <= 0 || H <= 0 || W <= 0 || O <= 0 || kh <= 0 || kw <= 0 || stride_h <= 0 ||
+        stride_w <= 0 || pad_h < 0 || pad_w < 0) {
+        set_error("tbn_conv2d_forward: sizes and strides must be positive, padding non-negative");
+        return TBN_ERR_SHAPE;
+    }
+    if (H + 2 * (int64_t)pad_h < kh || W + 2 * (int64_t)pad_w < kw) {
+        set_error("tbn_conv2d_forward: kernel %dx%d larger than the padded input", kh, kw);
+        return TBN_ERR_SHAPE;
+    }
+    const int64_t lim = int64_t(1) << 40;
+    int64_t filt, n, xs, ys;
+    const int64_t Ho = (H + 2 * (int64_t)pad_h - kh) / stride_h + 1;
+    const int64_t Wo = (W + 2 * (int64_t)pad_w - kw) / stride_w + 1;
+    if (!mul_ok(C, (int64_t)kh * kw, &filt) || !mul_ok(filt, O, &n) || n > lim ||
+        !mul_ok(N * C, H * W, &xs) || xs > lim || !mul_ok(N * O, Ho * Wo, &ys) || ys > lim ||
+        H > (1 << 20) || W > (1 << 20) || C > (1 << 24) || O > (1 << 24) || N > (int64_t(1) << 31) ||
+        kh > 4096 || kw > 4096 || pad_h > 4096 || pad_w > 4096) {
+        set_error("tbn_conv2d_forward: sizes beyond the supported range");
+        return TBN_ERR_UNSUPPORTED;
+    }
+    tbn_status st = check_tiling(n, k, n_alpha);
+    if (st != TBN_OK) return st;
+    if (N == 0) return TBN_OK;
+
+    ConvArgs a{x, y, (int)dt, N, C, H, W, O, Ho, Wo, kh, kw, stride_h, stride_w, pad_h, pad_w,
+               tile, n / k, k, alpha, n_alpha, flags, static_cast<hipStream_t>(stream)};
+    if (!(flags & TBN_FLAG_FORCE_GENERIC) && conv_mfma_supported(a)) return launch_conv_mfma(a);
+    return launch_conv_generic(a);
+}
+
+}  // extern "C"

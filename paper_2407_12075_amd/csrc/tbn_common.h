@@ -1,0 +1,103 @@
+// Shared declarations of the libtbn translation units (host dispatch + gfx950 device helpers).
+// Notation follows the paper's Method section with the letters of include/tbn.h:
+// n weights, k tile repeats, p = n / k tile bits; flat weight index f -> tile bit f % p,
+// scalar alpha[f / p] (Eq. 4-5 and the scaling stated after Eq. 8).
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+#include <stddef.h>
+#include "../../include/tbn.h"
+
+namespace tbn {
+
+constexpr int kWave = 64;
+
+// ---- host side -----------------------------------------------------------------------------
+void set_error(const char *fmt, ...);
+tbn_status check_launch(const char *what);
+
+struct LinearArgs {
+    const void *x;
+    void *y;
+    int dt;            // tbn_dtype
+    int64_t M, in, out;
+    const uint32_t *tile;
+    int64_t p;         // tile bits
+    int32_t k;
+    const float *alpha;
+    int32_t n_alpha;
+    uint32_t flags;
+    hipStream_t stream;
+};
+
+struct ConvArgs {
+    const void *x;
+    void *y;
+    int dt;
+    int64_t N, C, H, W, O, Ho, Wo;
+    int32_t kh, kw, sh, sw, ph, pw;
+    const uint32_t *tile;
+    int64_t p;
+    int32_t k;
+    const float *alpha;
+    int32_t n_alpha;
+    uint32_t flags;
+    hipStream_t stream;
+};
+
+// kernel families; each returns TBN_OK after enqueueing, or an error with nothing enqueued
+tbn_status launch_pack(const float *w, const float *a, int64_t n, int32_t k, int32_t n_alpha,
+                       uint32_t *tile_out, float *alpha_out, void *workspace, hipStream_t stream);
+size_t pack_workspace_bytes(int64_t n, int32_t k, int32_t n_alpha);
+
+tbn_status launch_linear_generic(const LinearArgs &a);
+bool linear_rows_supported(const LinearArgs &a);   // small-batch wave-per-row kernel
+tbn_status launch_linear_rows(const LinearArgs &a);
+bool linear_mfma_supported(const LinearArgs &a);   // matrix-core kernel
+tbn_status launch_linear_mfma(const LinearArgs &a);
+
+tbn_status launch_conv_generic(const ConvArgs &a);
+bool conv_mfma_supported(const ConvArgs &a);
+tbn_status launch_conv_mfma(const ConvArgs &a);
+
+// number of distinct bit rows of the (rows x row_len) weight: row o repeats row o % U
+int64_t unique_rows(int64_t rows, int64_t row_len, int64_t p);
+
+// ---- device side ---------------------------------------------------------------------------
+#if defined(__HIPCC__)
+
+__device__ __forceinline__ float bf16_bits_to_f32(uint16_t b) {
+    return __uint_as_float(static_cast<uint32_t>(b) << 16);
+}
+
+// round to nearest even; NaN stays NaN (quiet)
+__device__ __forceinline__ uint16_t f32_to_bf16_bits(float f) {
+    uint32_t u = __float_as_uint(f);
+    if ((u & 0x7fffffffu) > 0x7f800000u) return static_cast<uint16_t>((u >> 16) | 0x0040u);
+    u += 0x7fffu + ((u >> 16) & 1u);
+    return static_cast<uint16_t>(u >> 16);
+}
+
+// 32 tile bits starting at bit position `pos` (0 <= pos, pos + 32 may run past the last word:
+// the caller guarantees words [pos/32, pos/32 + 1] are readable or passes clamp_words)
+__device__ __forceinline__ uint32_t tile_window32(const uint32_t *tile, int64_t pos, int64_t n_words) {
+    const int64_t w = pos >> 5;
+    const uint32_t sh = static_cast<uint32_t>(pos & 31);
+    const uint32_t lo = tile[w];
+    const uint32_t hi = (w + 1 < n_words) ? tile[w + 1] : 0u;
+    return sh ? __funnelshift_r(lo, hi, sh) : lo;
+}
+
+template <typename T> struct ElemIO;
+template <> struct ElemIO<float> {
+    static __device__ __forceinline__ float load(const float *p) { return *p; }
+    static __device__ __forceinline__ void store(float *p, float v) { *p = v; }
+};
+template <> struct ElemIO<uint16_t> {   // bfloat16 bit patterns
+    static __device__ __forceinline__ float load(const uint16_t *p) { return bf16_bits_to_f32(*p); }
+    static __device__ __forceinline__ void store(uint16_t *p, float v) { *p = f32_to_bf16_bits(v); }
+};
+
+#endif  // __HIPCC__
+
+}  // namespace tbn

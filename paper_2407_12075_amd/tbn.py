@@ -1,0 +1,167 @@
+"""Thin ctypes binding of libtbn (include/tbn.h).  Argument marshalling only: every step of the
+computation runs in the HIP kernels of the library.  PyTorch supplies device memory and the
+stream; tensors must live on the current CUDA (HIP) device and be contiguous.
+
+There is no CPU fallback: if ``libtbn.so`` is missing the import of a symbol raises.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+from typing import Optional, Tuple
+
+import torch
+
+TBN_OK = 0
+TBN_F32 = 0
+TBN_BF16 = 1
+TBN_FLAG_RELU = 0x1
+TBN_FLAG_FORCE_GENERIC = 0x100
+
+_STATUS = {1: "TBN_ERR_NULL", 2: "TBN_ERR_SHAPE", 3: "TBN_ERR_UNSUPPORTED", 4: "TBN_ERR_DEVICE",
+           5: "TBN_ERR_WORKSPACE"}
+
+_LIB_PATH = os.path.join(os.path.dirname(os.path.abspath(__file__)), "libtbn.so")
+_lib = None
+
+_c_i64, _c_i32, _c_u32, _c_vp, _c_sz = ctypes.c_int64, ctypes.c_int32, ctypes.c_uint32, ctypes.c_void_p, ctypes.c_size_t
+
+
+class TbnError(RuntimeError):
+    def __init__(self, status: int, message: str):
+        super().__init__(f"{_STATUS.get(status, status)}: {message}")
+        self.status = status
+
+
+def lib() -> ctypes.CDLL:
+    """Load libtbn.so (built by ``python -m paper_2407_12075_amd.build``)."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(_LIB_PATH):
+            raise ImportError(f"{_LIB_PATH} not found: build it with `python -m paper_2407_12075_amd.build`")
+        L = ctypes.CDLL(_LIB_PATH)
+        L.tbn_tile_words.restype = _c_sz
+        L.tbn_tile_words.argtypes = [_c_i64, _c_i32]
+        L.tbn_last_error.restype = ctypes.c_char_p
+        L.tbn_last_error.argtypes = []
+        L.tbn_version.restype = ctypes.c_char_p
+        L.tbn_version.argtypes = []
+        L.tbn_pack_workspace_bytes.restype = _c_sz
+        L.tbn_pack_workspace_bytes.argtypes = [_c_i64, _c_i32, _c_i32]
+        L.tbn_pack_tile.restype = ctypes.c_int
+        L.tbn_pack_tile.argtypes = [_c_vp, _c_vp, _c_i64, _c_i32, _c_i32, _c_vp, _c_vp, _c_vp, _c_sz, _c_vp]
+        L.tbn_linear_forward.restype = ctypes.c_int
+        L.tbn_linear_forward.argtypes = [_c_vp, _c_vp, ctypes.c_int, _c_i64, _c_i64, _c_i64, _c_vp, _c_i32, _c_vp,
+                                         _c_i32, _c_u32, _c_vp]
+        L.tbn_conv2d_forward.restype = ctypes.c_int
+        L.tbn_conv2d_forward.argtypes = [_c_vp, _c_vp, ctypes.c_int, _c_i64, _c_i64, _c_i64, _c_i64, _c_i64, _c_i32,
+                                         _c_i32, _c_i32, _c_i32, _c_i32, _c_i32, _c_vp, _c_i32, _c_vp, _c_i32, _c_u32,
+                                         _c_vp]
+        _lib = L
+    return _lib
+
+
+def _raise(status: int):
+    raise TbnError(status, lib().tbn_last_error().decode())
+
+
+def _stream(stream) -> int:
+    if stream is None:
+        return torch.cuda.current_stream().cuda_stream
+    return stream.cuda_stream if hasattr(stream, "cuda_stream") else int(stream)
+
+
+def _dev(t: torch.Tensor, name: str, dtype=None) -> int:
+    if not t.is_cuda:
+        raise ValueError(f"{name} must be a device tensor")
+    if not t.is_contiguous():
+        raise ValueError(f"{name} must be contiguous")
+    if dtype is not None and t.dtype != dtype:
+        raise ValueError(f"{name} must have dtype {dtype}, got {t.dtype}")
+    return t.data_ptr()
+
+
+def _dt(t: torch.Tensor) -> int:
+    if t.dtype == torch.float32:
+        return TBN_F32
+    if t.dtype == torch.bfloat16:
+        return TBN_BF16
+    raise ValueError(f"activations must be float32 or bfloat16, got {t.dtype}")
+
+
+def tbn_version() -> str:
+    return lib().tbn_version().decode()
+
+
+def tbn_tile_words(n: int, k: int) -> int:
+    return int(lib().tbn_tile_words(n, k))
+
+
+def tbn_pack_workspace_bytes(n: int, k: int, n_alpha: int) -> int:
+    return int(lib().tbn_pack_workspace_bytes(n, k, n_alpha))
+
+
+def tbn_pack_tile(w_real: torch.Tensor, k: int, n_alpha: int = 1, a_real: Optional[torch.Tensor] = None,
+                  tile_out: Optional[torch.Tensor] = None, alpha_out: Optional[torch.Tensor] = None,
+                  workspace: Optional[torch.Tensor] = None, stream=None) -> Tuple[torch.Tensor, torch.Tensor]:
+    """Tile (int32 tensor holding the 32-bit words) and alpha (float32) from real weights."""
+    n = w_real.numel()
+    words = tbn_tile_words(n, k)
+    dev = w_real.device
+    if tile_out is None:
+        tile_out = torch.empty(max(words, 1), dtype=torch.int32, device=dev)
+    if alpha_out is None:
+        alpha_out = torch.empty(max(n_alpha, 1), dtype=torch.float32, device=dev)
+    need = tbn_pack_workspace_bytes(n, k, n_alpha)
+    if workspace is None:
+        workspace = torch.empty(max(need, 8), dtype=torch.uint8, device=dev)
+    st = lib().tbn_pack_tile(_dev(w_real, "w_real", torch.float32),
+                             None if a_real is None else _dev(a_real, "a_real", torch.float32),
+                             n, k, n_alpha, _dev(tile_out, "tile_out", torch.int32),
+                             _dev(alpha_out, "alpha_out", torch.float32), _dev(workspace, "workspace"),
+                             workspace.numel() * workspace.element_size(), _stream(stream))
+    if st != TBN_OK:
+        _raise(st)
+    return tile_out, alpha_out
+
+
+def tbn_linear_forward(x: torch.Tensor, tile: torch.Tensor, alpha: torch.Tensor, out_features: int, k: int,
+                       y: Optional[torch.Tensor] = None, flags: int = 0, stream=None) -> torch.Tensor:
+    """Y = X * B_hat^T for x of shape (M, in); y has shape (M, out_features) and x's dtype."""
+    if x.dim() != 2:
+        raise ValueError("x must be (M, in)")
+    M, cin = x.shape
+    if y is None:
+        y = torch.empty((M, out_features), dtype=x.dtype, device=x.device)
+    elif tuple(y.shape) != (M, out_features) or y.dtype != x.dtype:
+        raise ValueError("y must be (M, out) with x's dtype")
+    st = lib().tbn_linear_forward(_dev(x, "x"), _dev(y, "y"), _dt(x), M, cin, out_features,
+                                  _dev(tile, "tile", torch.int32), k, _dev(alpha, "alpha", torch.float32),
+                                  alpha.numel(), flags, _stream(stream))
+    if st != TBN_OK:
+        _raise(st)
+    return y
+
+
+def conv_out_hw(H: int, W: int, kh: int, kw: int, stride, pad) -> Tuple[int, int]:
+    return (H + 2 * pad[0] - kh) // stride[0] + 1, (W + 2 * pad[1] - kw) // stride[1] + 1
+
+
+def tbn_conv2d_forward(x: torch.Tensor, tile: torch.Tensor, alpha: torch.Tensor, out_channels: int, kh: int,
+                       kw: int, k: int, stride=(1, 1), pad=(0, 0), y: Optional[torch.Tensor] = None,
+                       flags: int = 0, stream=None) -> torch.Tensor:
+    """NCHW convolution with the implicit (O, C, kh, kw) tiled-bit weight."""
+    if x.dim() != 4:
+        raise ValueError("x must be (N, C, H, W)")
+    N, C, H, W = x.shape
+    Ho, Wo = conv_out_hw(H, W, kh, kw, stride, pad)
+    if y is None:
+        y = torch.empty((N, out_channels, max(Ho, 0), max(Wo, 0)), dtype=x.dtype, device=x.device)
+    elif tuple(y.shape) != (N, out_channels, Ho, Wo) or y.dtype != x.dtype:
+        raise ValueError("y must be (N, O, Ho, Wo) with x's dtype")
+    st = lib().tbn_conv2d_forward(_dev(x, "x"), _dev(y, "y"), _dt(x), N, C, H, W, out_channels, kh, kw,
+                                  stride[0], stride[1], pad[0], pad[1], _dev(tile, "tile", torch.int32), k,
+                                  _dev(alpha, "alpha", torch.float32), alpha.numel(), flags, _stream(stream))
+    if st != TBN_OK:
+        _raise(st)
+    return y

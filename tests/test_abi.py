@@ -1,0 +1,98 @@
+"""CPU-side checks of the C ABI: the library loads, exports what include/tbn.h declares, and its
+argument validation (which runs before any device call) reports the documented status codes."""
+import ctypes
+import os
+import re
+
+import pytest
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+HEADER = os.path.join(ROOT, "include", "tbn.h")
+LIB = os.path.join(ROOT, "paper_2407_12075_amd", "libtbn.so")
+
+
+@pytest.fixture(scope="module")
+def lib():
+    if not os.path.exists(LIB):
+        from paper_2407_12075_amd import build
+        build.build(verbose=False)
+    from paper_2407_12075_amd import tbn
+    return tbn.lib()
+
+
+def declared_symbols():
+    text = open(HEADER).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(tbn_[a-z0-9_]+)\s*\(", text)))
+
+
+def test_header_declares_the_three_entry_points():
+    syms = declared_symbols()
+    for name in ("tbn_pack_tile", "tbn_linear_forward", "tbn_conv2d_forward", "tbn_tile_words", "tbn_last_error"):
+        assert name in syms
+
+
+def test_library_exports_every_declared_symbol(lib):
+    for name in declared_symbols():
+        assert hasattr(lib, name), f"libtbn.so does not export {name}"
+
+
+def test_tile_words(lib):
+    assert lib.tbn_tile_words(65536, 4) == 512
+    assert lib.tbn_tile_words(784 * 128, 4) == 784          # 25,088 bits: the microcontroller MLP's first layer
+    assert lib.tbn_tile_words(33, 1) == 2
+    assert lib.tbn_tile_words(32, 1) == 1
+    assert lib.tbn_tile_words(10, 3) == 0                    # k must divide n
+    assert lib.tbn_tile_words(0, 1) == 0
+    assert lib.tbn_tile_words(8, 0) == 0
+    assert lib.tbn_tile_words(4096 * 4096, 8) == 65536
+
+
+def test_pack_workspace_bytes(lib):
+    assert lib.tbn_pack_workspace_bytes(10, 3, 1) == 0
+    assert lib.tbn_pack_workspace_bytes(16, 4, 2) == 0
+    need = lib.tbn_pack_workspace_bytes(4096 * 4096, 8, 8)
+    assert need > 0 and need % 8 == 0
+
+
+def _err(lib):
+    return lib.tbn_last_error().decode()
+
+
+def test_validation_status_codes(lib):
+    p = ctypes.c_void_p
+    fake = p(256)  # never dereferenced: validation fails first
+    # NULL pointers
+    assert lib.tbn_pack_tile(None, None, 16, 2, 1, fake, fake, fake, 1 << 20, None) == 1
+    assert "NULL" in _err(lib)
+    assert lib.tbn_linear_forward(None, fake, 0, 1, 4, 4, fake, 2, fake, 1, 0, None) == 1
+    assert lib.tbn_conv2d_forward(fake, None, 0, 1, 1, 4, 4, 2, 3, 3, 1, 1, 0, 0, fake, 2, fake, 1, 0, None) == 1
+    # n not divisible by k, n_alpha not in {1, k}
+    assert lib.tbn_pack_tile(fake, None, 10, 3, 1, fake, fake, fake, 1 << 20, None) == 2
+    assert "divisible" in _err(lib)
+    assert lib.tbn_pack_tile(fake, None, 16, 4, 2, fake, fake, fake, 1 << 20, None) == 2
+    assert lib.tbn_linear_forward(fake, fake, 0, 1, 5, 3, fake, 2, fake, 1, 0, None) == 2
+    assert lib.tbn_linear_forward(fake, fake, 0, -1, 4, 4, fake, 2, fake, 1, 0, None) == 2
+    assert lib.tbn_linear_forward(fake, fake, 0, 1, 0, 4, fake, 2, fake, 1, 0, None) == 2
+    # kernel larger than the padded input
+    assert lib.tbn_conv2d_forward(fake, fake, 0, 1, 1, 2, 2, 2, 5, 5, 1, 1, 0, 0, fake, 2, fake, 1, 0, None) == 2
+    assert lib.tbn_conv2d_forward(fake, fake, 0, 1, 1, 4, 4, 2, 3, 3, 0, 1, 0, 0, fake, 2, fake, 1, 0, None) == 2
+    # unknown dtype / flag
+    assert lib.tbn_linear_forward(fake, fake, 7, 1, 4, 4, fake, 2, fake, 1, 0, None) == 3
+    assert lib.tbn_linear_forward(fake, fake, 0, 1, 4, 4, fake, 2, fake, 1, 0x8000, None) == 3
+    assert lib.tbn_conv2d_forward(fake, fake, 9, 1, 1, 4, 4, 2, 3, 3, 1, 1, 0, 0, fake, 2, fake, 1, 0, None) == 3
+    # workspace too small / missing / misaligned
+    assert lib.tbn_pack_tile(fake, None, 1 << 20, 2, 1, fake, fake, fake, 8, None) == 5
+    assert lib.tbn_pack_tile(fake, None, 1 << 20, 2, 1, fake, fake, None, 1 << 30, None) == 5
+    assert lib.tbn_pack_tile(fake, None, 1 << 20, 2, 1, fake, fake, p(260), 1 << 30, None) == 5
+    # empty batch is legal and touches nothing
+    assert lib.tbn_linear_forward(fake, fake, 0, 0, 4, 4, fake, 2, fake, 1, 0, None) == 0
+    assert lib.tbn_conv2d_forward(fake, fake, 0, 0, 1, 4, 4, 2, 3, 3, 1, 1, 0, 0, fake, 2, fake, 1, 0, None) == 0
+
+
+def test_binding_refuses_host_tensors():
+    import torch
+    from paper_2407_12075_amd import tbn
+    w = torch.zeros(16)
+    with pytest.raises(ValueError):
+        tbn.tbn_pack_tile(w, 2)
