@@ -1,0 +1,232 @@
+#!/usr/bin/env python3
+"""Benchmark of the libtbn hot path on one MI355X.
+
+A step is one pass of the whole path on the shape the headline metric is quoted on (tiled-bit
+linear layer 4096 x 4096, k = 8, bfloat16 activations, one alpha per tile):
+
+    tbn_pack_tile(W_real)  ->  tbn_linear_forward at batch 8192, 16 and 1
+
+with all inputs resident in HBM.  `value` is the dense-equivalent rate of the three forward
+passes, 2 * in * out * (8192 + 16 + 1) flop per step, over the wall time of the step (so the
+packing pass and launch gaps count against it).  The `roofline` object describes the dominant
+kernel, the batch-8192 forward, whose duration is measured with events on the launch stream
+inside the timed steps.  `cpu_baseline` times the CPU oracle on a sample of the same batch.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--no-cpu-baseline] [--all-configs]
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0          # MI355X HBM3E
+MFMA_BF16_PEAK_TFLOPS = 2500.0  # dense bf16
+
+
+def parse_args():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=200)
+    ap.add_argument("--warmup", type=int, default=20)
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--cpu-seconds", type=float, default=12.0, help="target CPU time of the oracle sample")
+    ap.add_argument("--all-configs", action="store_true", help="also time the other layer shapes (extra lines on stderr)")
+    ap.add_argument("--copy-calibration", action="store_true",
+                    help="run only a plain device copy of 256 MiB (for scaling rocprofv3 FETCH_SIZE / WRITE_SIZE)")
+    return ap.parse_args()
+
+
+def device_inputs(c, torch, wl):
+    """Seeded synthetic tensors of workload c on the GPU (same recipe as the parity tests)."""
+    w = torch.from_numpy(wl.draw_w_real(c.n, c.cfg, c.layer)).cuda()
+    xv, xb = wl.draw_x((c.M, c.cin), c.cfg, c.layer, c.dtype)
+    if xb is not None:
+        import numpy as np
+        x = torch.from_numpy(xb.view(np.int16)).cuda().view(torch.bfloat16)
+    else:
+        x = torch.from_numpy(xv).cuda()
+    return w, x, xv
+
+
+def event_pair(torch):
+    return torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+
+
+def main():
+    args = parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on exactly one GPU (the tiled-bit forward needs no second "
+              "device); --gpus must be 1", file=sys.stderr)
+        sys.exit(2)
+
+    import numpy as np
+    import torch
+    from paper_2407_12075_amd import tbn, workloads as wl
+
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        sys.exit(2)
+    tbn.lib()
+    torch.cuda.set_device(0)
+
+    if args.copy_calibration:
+        a = torch.empty(256 << 20, dtype=torch.uint8, device="cuda")
+        b = torch.empty_like(a)
+        for _ in range(5):
+            b.copy_(a)
+        torch.cuda.synchronize()
+        print(json.dumps({"copy_bytes_read": a.numel(), "copy_bytes_written": b.numel(), "launches": 5}))
+        return
+
+    big = wl.METRIC                       # batch 8192
+    mid, small = wl.CFG4[1], wl.CFG4[0]   # batch 16 and 1
+    cin, cout, k, n_alpha = big.cin, big.cout, big.k, big.n_alpha
+    n = big.n
+
+    w_real, x_big, x_big_vals = device_inputs(big, torch, wl)
+    _, x_mid, _ = device_inputs(mid, torch, wl)
+    _, x_small, _ = device_inputs(small, torch, wl)
+    tile = torch.empty(tbn.tbn_tile_words(n, k), dtype=torch.int32, device="cuda")
+    alpha = torch.empty(n_alpha, dtype=torch.float32, device="cuda")
+    workspace = torch.empty(tbn.tbn_pack_workspace_bytes(n, k, n_alpha) + 8, dtype=torch.uint8, device="cuda")
+    y_big = torch.empty((big.M, cout), dtype=torch.bfloat16, device="cuda")
+    y_mid = torch.empty((mid.M, cout), dtype=torch.bfloat16, device="cuda")
+    y_small = torch.empty((small.M, cout), dtype=torch.bfloat16, device="cuda")
+
+    def step(ev=None):
+        tbn.tbn_pack_tile(w_real, k, n_alpha, tile_out=tile, alpha_out=alpha, workspace=workspace)
+        if ev is not None:
+            ev[0].record()
+        tbn.tbn_linear_forward(x_big, tile, alpha, cout, k, y=y_big)
+        if ev is not None:
+            ev[1].record()
+        tbn.tbn_linear_forward(x_mid, tile, alpha, cout, k, y=y_mid)
+        tbn.tbn_linear_forward(x_small, tile, alpha, cout, k, y=y_small)
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+
+    events = [event_pair(torch) for _ in range(args.steps)]
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for i in range(args.steps):
+        step(events[i])
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+
+    ms_per_step = (t1 - t0) * 1e3 / args.steps
+    flop_per_step = 2.0 * cin * cout * (big.M + mid.M + small.M)
+    value = flop_per_step / (ms_per_step * 1e-3) / 1e12
+
+    kern_ms = sorted(e0.elapsed_time(e1) for e0, e1 in events)
+    kern_avg_ms = sum(kern_ms) / len(kern_ms)
+    # algorithmic bytes of the batch-8192 forward: X read once, Y written once, packed tile and alpha read once
+    alg_bytes = big.M * cin * 2 + big.M * cout * 2 + big.p // 8 + n_alpha * 4
+    achieved = alg_bytes / (kern_avg_ms * 1e-3) / 1e9
+    U = big.p // cin
+    alg_flop = 2.0 * big.M * cin * U
+    roofline = {
+        "bound": "hbm", "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
+        "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": None,
+        "kernel": "linear_mfma_kernel<bf16> (batch 8192)", "avg_kernel_ms": round(kern_avg_ms, 5),
+        "median_kernel_ms": round(kern_ms[len(kern_ms) // 2], 5),
+        "algorithmic_bytes": alg_bytes,
+        "algorithmic_tflops": round(alg_flop / (kern_avg_ms * 1e-3) / 1e12, 1),
+        "mfma_frac": round(alg_flop / (kern_avg_ms * 1e-3) / 1e12 / MFMA_BF16_PEAK_TFLOPS, 4),
+        "dense_equiv_tflops": round(2.0 * big.M * cin * cout / (kern_avg_ms * 1e-3) / 1e12, 1),
+    }
+
+    cpu_baseline = None
+    if not args.no_cpu_baseline:
+        from oracle import tbn_oracle as orc
+        tile_h = tile.cpu().numpy().view(np.uint32)
+        alpha_h = alpha.cpu().numpy()
+        # calibrate on 16 rows, then time a sample sized for the requested CPU seconds
+        t = time.perf_counter()
+        orc.linear_forward(x_big_vals[:16], tile_h, alpha_h, cout, k)
+        per_row = max((time.perf_counter() - t) / 16, 1e-6)
+        rows = int(min(big.M, max(64, args.cpu_seconds / per_row)))
+        t = time.perf_counter()
+        orc.linear_forward(x_big_vals[:rows], tile_h, alpha_h, cout, k)
+        dt = time.perf_counter() - t
+        cpu_baseline = {
+            "value": round(2.0 * cin * cout * rows / dt / 1e12, 5), "unit": "dense-equiv TFLOP/s",
+            "cores": orc.threads(), "kind": "oracle",
+            "sample": f"first {rows} of the 8192 batch rows of the 4096x4096 k=8 forward "
+                      f"(dense weight materialised from the tile, double accumulation), {dt:.1f} s",
+        }
+
+    line = {
+        "metric": "dense-equiv TFLOP/s, TBN linear 4096x4096 k=8 at batch 1/16/8192 (pack + three forwards per step)",
+        "value": round(value, 2), "unit": "TFLOP/s (dense-equivalent)",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(ms_per_step, 5),
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": "metric: tiled-bit linear in=out=4096, k=8, 8 alphas, bf16, batch 8192 + 16 + 1, "
+                               "preceded by tbn_pack_tile of the 4096x4096 real weight",
+                   "n": n, "k": k, "p_bits": big.p, "unique_rows": U},
+        "hbm_gbs": round(achieved, 1),
+        "roofline": roofline,
+        "cpu_baseline": cpu_baseline,
+    }
+
+    if args.all_configs:
+        line["other_configs"] = time_other_configs(torch, tbn, wl)
+    print(json.dumps(line))
+
+
+def time_other_configs(torch, tbn, wl, iters=30):
+    """Kernel time of the remaining layer shapes (events around back-to-back calls)."""
+    out = {}
+
+    def timed(fn):
+        for _ in range(3):
+            fn()
+        torch.cuda.synchronize()
+        e0, e1 = event_pair(torch)
+        e0.record()
+        for _ in range(iters):
+            fn()
+        e1.record()
+        torch.cuda.synchronize()
+        return e0.elapsed_time(e1) * 1e3 / iters   # microseconds
+
+    lin = [wl.CFG1, *wl.CFG2, *wl.CFG4, wl.METRIC, *wl.CFG5, *wl.CFG5_MISALIGNED]
+    for c in lin:
+        w, x, _ = device_inputs(c, torch, wl)
+        tile, alpha = tbn.tbn_pack_tile(w, c.k, c.n_alpha)
+        y = torch.empty((c.M, c.cout), dtype=x.dtype, device="cuda")
+        us = timed(lambda: tbn.tbn_linear_forward(x, tile, alpha, c.cout, c.k, y=y))
+        esz = x.element_size()
+        byts = (c.M * c.cin + c.M * c.cout) * esz + c.p // 8
+        out[c.name] = {"us": round(us, 2), "dense_equiv_tflops": round(2.0 * c.M * c.cin * c.cout / us / 1e6, 1),
+                       "alg_gbs": round(byts / us / 1e3, 1)}
+        ws = torch.empty(tbn.tbn_pack_workspace_bytes(c.n, c.k, c.n_alpha) + 8, dtype=torch.uint8, device="cuda")
+        us = timed(lambda: tbn.tbn_pack_tile(w, c.k, c.n_alpha, tile_out=tile, alpha_out=alpha, workspace=ws))
+        out[c.name + ":pack"] = {"us": round(us, 2), "alg_gbs": round(c.n * 4 / us / 1e3, 1)}
+        del w, x, y
+    for c in (wl.CFG3, wl.CFG3_MISALIGNED):
+        w = torch.from_numpy(wl.draw_w_real(c.n, c.cfg, c.layer)).cuda()
+        xv, _ = wl.draw_x((c.N, c.C, c.H, c.W), c.cfg, c.layer, c.dtype)
+        x = torch.from_numpy(xv).cuda()
+        tile, alpha = tbn.tbn_pack_tile(w, c.k, c.n_alpha)
+        Ho, Wo = tbn.conv_out_hw(c.H, c.W, c.kh, c.kw, c.stride, c.pad)
+        y = torch.empty((c.N, c.O, Ho, Wo), dtype=x.dtype, device="cuda")
+        us = timed(lambda: tbn.tbn_conv2d_forward(x, tile, alpha, c.O, c.kh, c.kw, c.k, stride=c.stride, pad=c.pad, y=y))
+        flop = 2.0 * c.N * Ho * Wo * c.O * c.C * c.kh * c.kw
+        byts = (x.numel() + y.numel()) * 4 + c.p // 8
+        out[c.name] = {"us": round(us, 2), "dense_equiv_tflops": round(flop / us / 1e6, 1),
+                       "alg_gbs": round(byts / us / 1e3, 1)}
+    return out
+
+
+if __name__ == "__main__":
+    main()

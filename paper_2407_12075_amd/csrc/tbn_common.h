@@ -53,6 +53,7 @@ size_t pack_workspace_bytes(int64_t n, int32_t k, int32_t n_alpha);
 tbn_status launch_linear_generic(const LinearArgs &a);
 bool linear_rows_supported(const LinearArgs &a);   // small-batch wave-per-row kernel
 tbn_status launch_linear_rows(const LinearArgs &a);
+tbn_status launch_linear_rows_fixup(const LinearArgs &a);  // recompute the columns whose row holds a tile end
 bool linear_mfma_supported(const LinearArgs &a);   // matrix-core kernel
 tbn_status launch_linear_mfma(const LinearArgs &a);
 

@@ -121,6 +121,14 @@ LINEAR_SMALL = [
     (16, 1024, 1024, 8, 8),
     (200, 384, 1536, 4, 1),    # ViT MLP shapes at small batch
     (200, 1536, 384, 4, 1),
+    (150, 200, 90, 4, 4),      # p = 4500 = 22.5 rows: 45 distinct rows, tile ends mid-row, odd U
+    (150, 200, 90, 4, 1),
+    (4, 200, 90, 4, 4),
+    (40, 3000, 96, 9, 9),      # p = 32000 = 10 2/3 rows, 32 distinct rows, in % 32 != 0
+    (16, 3000, 96, 9, 9),
+    (1, 3000, 96, 9, 9),
+    (300, 264, 136, 3, 3),     # p = 11968 = 45 1/3 rows: no row repeats at all (U = out)
+    (129, 64, 64, 64, 64),     # p = in: every row is the whole tile
 ]
 
 
