@@ -9,14 +9,16 @@
 // observation the paper makes for convolution channels, applied to matrix columns.
 //
 // gfx950 mapping
-//   * one workgroup (4 waves, 2 x 2) owns a 128 x 128 block of Z; X is staged in LDS as bf16 in
-//     the operand order of v_mfma_f32_32x32x16_bf16 and double buffered against global loads;
+//   * one workgroup (4 waves, 2 x 2) owns a 128 x 128 block of Z; X is staged in LDS as bf16 and
+//     read back as operands of v_mfma_f32_32x32x16_bf16; a ring of stages is kept in flight in
+//     registers between global memory and LDS so that HBM latency is covered even when only one
+//     workgroup fits the problem per CU;
 //   * float32 activations are split exactly into three bf16 terms (8 + 8 + 8 significand bits;
 //     the weights are +-1, so each product is exact and the sums are float32 accumulations);
-//   * the +-1 operand never exists in memory: 32-bit tile windows (aligned for the row's start
-//     bit, wrapped at the tile end) are staged in LDS and expanded in registers, two VALU
-//     operations per packed bf16 pair, using an operand order in which bits j and j+16 of a
-//     window share one register;
+//   * the +-1 operand never exists in memory: 32-bit tile windows (shifted to the row's start
+//     bit, continued at the tile start after the tile end) are staged in LDS with even and odd
+//     bits separated, so that the two bits of a packed bf16 pair sit 16 apart and one shift plus
+//     one and-or turns a window into an operand register;
 //   * the epilogue scales by alpha and writes the replicated column blocks straight from the
 //     accumulators; a lane owns adjacent columns so that a half-wave writes a contiguous run.
 // Rows whose weights straddle a tile end use two different alphas when one alpha per tile is
@@ -37,8 +39,10 @@ constexpr int kBM = kWavesM * kTM * 32;          // 128
 constexpr int kBN = kWavesN * kTN * 32;          // 128
 constexpr int kBK = 64;                          // K elements per pipeline stage
 constexpr int kKB = kBK / 32;                    // 32-bit tile windows per stage and row
-constexpr int kRowPad = 8;                       // bf16 elements of padding per LDS row (16 B)
-constexpr int kRowStride = kBK + kRowPad;        // in bf16 elements
+constexpr int kPieces = kBK / 8;                 // 8-element (16-byte bf16) pieces per row and stage
+constexpr int kRowStride = kBK + 8;              // LDS row stride in bf16 elements (16 B of padding)
+constexpr int kPlaneElems = kBM * kRowStride;
+constexpr int kItems = kBM * kPieces / kThreads; // pieces staged per thread and stage
 
 union Frag {
     bf16x8_t v;
@@ -46,90 +50,75 @@ union Frag {
     uint4 q;
 };
 
-template <typename XT> struct Planes;
-template <> struct Planes<uint16_t> { static constexpr int n = 1; };
-template <> struct Planes<float> { static constexpr int n = 3; };
-
-// one staging item: 8 + 8 activations (columns c..c+7 and c+16..c+23 of a 32-column block)
-template <typename XT> struct StageRegs;
-template <> struct StageRegs<uint16_t> { uint4 lo, hi; };
-template <> struct StageRegs<float> { float4 lo0, lo1, hi0, hi1; };
-
-__device__ __forceinline__ void stage_load(StageRegs<uint16_t> &r, const uint16_t *src, bool ok_lo, bool ok_hi) {
-    r.lo = ok_lo ? *reinterpret_cast<const uint4 *>(src) : make_uint4(0, 0, 0, 0);
-    r.hi = ok_hi ? *reinterpret_cast<const uint4 *>(src + 16) : make_uint4(0, 0, 0, 0);
-}
-__device__ __forceinline__ void stage_load(StageRegs<float> &r, const float *src, bool ok_lo, bool ok_hi) {
-    const float4 z = make_float4(0.f, 0.f, 0.f, 0.f);
-    r.lo0 = ok_lo ? *reinterpret_cast<const float4 *>(src) : z;
-    r.lo1 = ok_lo ? *reinterpret_cast<const float4 *>(src + 4) : z;
-    r.hi0 = ok_hi ? *reinterpret_cast<const float4 *>(src + 16) : z;
-    r.hi1 = ok_hi ? *reinterpret_cast<const float4 *>(src + 20) : z;
-}
-
-// interleave: out element 2c+h = (h ? hi : lo)[c]  -> register d holds (lo[d], hi[d]) as (low, high) half
-__device__ __forceinline__ void stage_store(const StageRegs<uint16_t> &r, uint16_t *dst, int /*plane_stride*/) {
-    const uint32_t lo[4] = {r.lo.x, r.lo.y, r.lo.z, r.lo.w};
-    const uint32_t hi[4] = {r.hi.x, r.hi.y, r.hi.z, r.hi.w};
-    uint32_t o[8];
+template <typename XT> struct Traits;
+template <> struct Traits<uint16_t> {
+    static constexpr int planes = 1;   // bf16 activations go to LDS as they are
+    static constexpr int depth = 3;    // stages in flight in registers
+    struct Piece { uint4 v; };
+    static __device__ __forceinline__ void load(Piece &r, const uint16_t *src) {
+        r.v = *reinterpret_cast<const uint4 *>(src);
+    }
+    static __device__ __forceinline__ void zero(Piece &r) { r.v = make_uint4(0, 0, 0, 0); }
+    static __device__ __forceinline__ void store(const Piece &r, uint16_t *dst) {
+        *reinterpret_cast<uint4 *>(dst) = r.v;
+    }
+};
+template <> struct Traits<float> {
+    static constexpr int planes = 3;   // exact split x = t0 + t1 + t2 into bf16 terms
+    static constexpr int depth = 2;
+    struct Piece { float4 a, b; };
+    static __device__ __forceinline__ void load(Piece &r, const float *src) {
+        r.a = *reinterpret_cast<const float4 *>(src);
+        r.b = *reinterpret_cast<const float4 *>(src + 4);
+    }
+    static __device__ __forceinline__ void zero(Piece &r) {
+        r.a = make_float4(0.f, 0.f, 0.f, 0.f);
+        r.b = r.a;
+    }
+    // truncation split: t0 = top 8 significand bits, t1 = next 8, t2 = the rest (at most 8 bits)
+    static __device__ __forceinline__ void split3(float x, uint32_t &t0, uint32_t &t1, uint32_t &t2) {
+        t0 = __float_as_uint(x) & 0xffff0000u;
+        const float r1 = x - __uint_as_float(t0);
+        t1 = __float_as_uint(r1) & 0xffff0000u;
+        const float r2 = r1 - __uint_as_float(t1);
+        t2 = __float_as_uint(r2);
+    }
+    static __device__ __forceinline__ void store(const Piece &r, uint16_t *dst) {
+        const float x[8] = {r.a.x, r.a.y, r.a.z, r.a.w, r.b.x, r.b.y, r.b.z, r.b.w};
+        uint32_t o[3][4];
 #pragma unroll
-    for (int d = 0; d < 4; ++d) {
-        o[2 * d] = __byte_perm(lo[d], hi[d], 0x5410);      // (lo[d].low16, hi[d].low16)
-        o[2 * d + 1] = __byte_perm(lo[d], hi[d], 0x7632);  // (lo[d].high16, hi[d].high16)
-    }
-    uint4 *d4 = reinterpret_cast<uint4 *>(dst);
-    d4[0] = make_uint4(o[0], o[1], o[2], o[3]);
-    d4[1] = make_uint4(o[4], o[5], o[6], o[7]);
-}
-
-// exact three-way split of a float into bf16 terms by truncation: x = t0 + t1 + t2
-__device__ __forceinline__ void split3(float x, uint32_t &t0, uint32_t &t1, uint32_t &t2) {
-    const uint32_t b0 = __float_as_uint(x) & 0xffff0000u;
-    const float r1 = x - __uint_as_float(b0);
-    const uint32_t b1 = __float_as_uint(r1) & 0xffff0000u;
-    const float r2 = r1 - __uint_as_float(b1);
-    t0 = b0;
-    t1 = b1;
-    t2 = __float_as_uint(r2);  // at most 8 significant bits are left, the low half is zero
-}
-
-__device__ __forceinline__ void stage_store(const StageRegs<float> &r, uint16_t *dst, int plane_stride) {
-    const float lo[8] = {r.lo0.x, r.lo0.y, r.lo0.z, r.lo0.w, r.lo1.x, r.lo1.y, r.lo1.z, r.lo1.w};
-    const float hi[8] = {r.hi0.x, r.hi0.y, r.hi0.z, r.hi0.w, r.hi1.x, r.hi1.y, r.hi1.z, r.hi1.w};
-    uint32_t o[3][8];
+        for (int d = 0; d < 4; ++d) {
+            uint32_t e0, e1, e2, f0, f1, f2;
+            split3(x[2 * d], e0, e1, e2);
+            split3(x[2 * d + 1], f0, f1, f2);
+            o[0][d] = (e0 >> 16) | f0;
+            o[1][d] = (e1 >> 16) | f1;
+            o[2][d] = (e2 >> 16) | (f2 & 0xffff0000u);
+        }
 #pragma unroll
-    for (int c = 0; c < 8; ++c) {
-        uint32_t l0, l1, l2, h0, h1, h2;
-        split3(lo[c], l0, l1, l2);
-        split3(hi[c], h0, h1, h2);
-        o[0][c] = (l0 >> 16) | h0;   // the masked high terms already have a zero low half
-        o[1][c] = (l1 >> 16) | h1;
-        o[2][c] = (l2 >> 16) | (h2 & 0xffff0000u);
+        for (int pl = 0; pl < 3; ++pl)
+            *reinterpret_cast<uint4 *>(dst + pl * kPlaneElems) = make_uint4(o[pl][0], o[pl][1], o[pl][2], o[pl][3]);
     }
-#pragma unroll
-    for (int pl = 0; pl < 3; ++pl) {
-        uint4 *d4 = reinterpret_cast<uint4 *>(dst + pl * plane_stride);
-        d4[0] = make_uint4(o[pl][0], o[pl][1], o[pl][2], o[pl][3]);
-        d4[1] = make_uint4(o[pl][4], o[pl][5], o[pl][6], o[pl][7]);
-    }
-}
+};
 
-// 32 tile bits at cyclic position pos (0 <= pos < p), continuing at bit 0 after bit p-1.  p >= 32.
-__device__ __forceinline__ uint32_t cyclic_window(const uint32_t *__restrict__ tile, int64_t pos, int64_t p,
-                                                  int64_t n_words) {
-    uint32_t w = tile_window32(tile, pos, n_words);
-    const int64_t left = p - pos;  // bits before the tile end
-    if (left < 32) {
-        const uint32_t head = tile[0];
-        w = (w & ((1u << left) - 1u)) | (head << left);
-    }
-    return w;
+// even bits of x to the low half, odd bits to the high half (both in order)
+__device__ __forceinline__ uint32_t unshuffle_bits(uint32_t x) {
+    uint32_t t;
+    t = (x ^ (x >> 1)) & 0x22222222u; x ^= t ^ (t << 1);
+    t = (x ^ (x >> 2)) & 0x0c0c0c0cu; x ^= t ^ (t << 2);
+    t = (x ^ (x >> 4)) & 0x00f000f0u; x ^= t ^ (t << 4);
+    t = (x ^ (x >> 8)) & 0x0000ff00u; x ^= t ^ (t << 8);
+    return x;
 }
 
 template <typename OT> struct OutPack;
 template <> struct OutPack<uint16_t> {
     static __device__ __forceinline__ void store2(uint16_t *p, float a, float b) {
-        *reinterpret_cast<uint32_t *>(p) = uint32_t(f32_to_bf16_bits(a)) | (uint32_t(f32_to_bf16_bits(b)) << 16);
+        typedef __bf16 bf16x2_t __attribute__((ext_vector_type(2)));
+        typedef float f32x2_t __attribute__((ext_vector_type(2)));
+        const f32x2_t f = {a, b};
+        const bf16x2_t h = __builtin_convertvector(f, bf16x2_t);   // round to nearest even in hardware
+        *reinterpret_cast<bf16x2_t *>(p) = h;
     }
 };
 template <> struct OutPack<float> {
@@ -148,12 +137,13 @@ struct MfmaParams {
     int64_t tiles_m;
 };
 
-template <typename XT>
-__global__ __launch_bounds__(kThreads) void linear_mfma_kernel(const XT *__restrict__ x, XT *__restrict__ y,
+template <typename XT, bool RELU>
+__global__ __launch_bounds__(kThreads, 2) void linear_mfma_kernel(const XT *__restrict__ x, XT *__restrict__ y,
                                                                const uint32_t *__restrict__ tile,
                                                                const float *__restrict__ alpha, MfmaParams P) {
-    constexpr int NP = Planes<XT>::n;
-    constexpr int kPlaneElems = kBM * kRowStride;
+    using T = Traits<XT>;
+    constexpr int NP = T::planes;
+    constexpr int D = T::depth;
     extern __shared__ __attribute__((aligned(16))) unsigned char lds_raw[];
     typedef uint16_t (*LdsA)[NP][kPlaneElems];
     typedef uint32_t (*LdsBits)[kKB][kBN];
@@ -169,77 +159,81 @@ __global__ __launch_bounds__(kThreads) void linear_mfma_kernel(const XT *__restr
 
     // Workgroups that share rows of X are given consecutive slots on one XCD (workgroup ids are
     // dealt round-robin to the 8 XCDs), so the later column blocks find X in that XCD's L2.
-    int64_t bid = blockIdx.x;
     int64_t tile_m, tile_n;
     {
+        const int64_t bid = blockIdx.x;
         const int64_t xcd = bid & 7, slot = bid >> 3;
-        const int64_t total = P.tiles_m * P.tiles_n;
-        const int64_t per_xcd_full = (total / (8 * P.tiles_n)) * P.tiles_n;  // slots per XCD in the regular part
+        const int64_t per_xcd_full = (P.tiles_m / 8) * P.tiles_n;   // slots per XCD in the regular part
         if (slot < per_xcd_full) {
             tile_n = slot % P.tiles_n;
             tile_m = (slot / P.tiles_n) * 8 + xcd;
-        } else {  // remainder: plain order
+        } else {  // remaining row blocks: plain order
             const int64_t rest = bid - per_xcd_full * 8;
-            const int64_t base_m = (per_xcd_full / P.tiles_n) * 8;
             tile_n = rest % P.tiles_n;
-            tile_m = base_m + rest / P.tiles_n;
+            tile_m = (P.tiles_m / 8) * 8 + rest / P.tiles_n;
         }
     }
     const int64_t m0 = tile_m * kBM;
     const int64_t n0 = tile_n * kBN;
 
-    // ---- staging assignments -------------------------------------------------------------
-    // activations: item = (row r, window kb, pair pr) -> columns kb*32 + pr*8 + {0..7, 16..23}
-    constexpr int kItems = kBM * kKB * 2 / kThreads;  // per thread
-    int a_row[kItems], a_col[kItems];
+    // ---- staging assignments ---------------------------------------------------------------
+    // activations: item i of a thread = 8 consecutive columns (one 16-byte bf16 piece) of one row;
+    // 8 consecutive threads cover the 64 columns of a row.  Rows past M are clamped to row M-1
+    // (their results are never written).
+    const int a_piece = tid % kPieces;
     const XT *a_src[kItems];
-    bool a_row_ok[kItems];
+    int a_lds[kItems];
 #pragma unroll
     for (int i = 0; i < kItems; ++i) {
-        const int id = tid + i * kThreads;
-        const int pr = id & 1, kb = (id >> 1) % kKB, r = id / (2 * kKB);
-        a_row[i] = r;
-        a_col[i] = kb * 32 + pr * 8;
-        a_row_ok[i] = (m0 + r) < P.M;
-        a_src[i] = x + (a_row_ok[i] ? (m0 + r) : 0) * P.in + a_col[i];
+        const int r = tid / kPieces + i * (kThreads / kPieces);
+        const int64_t m = (m0 + r) < P.M ? (m0 + r) : (P.M - 1);
+        a_src[i] = x + m * P.in;
+        a_lds[i] = r * kRowStride + a_piece * 8;
     }
-    // tile windows: item = (column c, window kb); one per thread (kBN * kKB == kThreads)
+    // tile windows: one (column, window) per thread and stage (kBN * kKB == kThreads)
     static_assert(kBN * kKB == kThreads, "one tile window per thread and stage");
     const int b_col = tid % kBN, b_kb = tid / kBN;
-    const int64_t b_u = n0 + b_col;
-    const bool b_ok = b_u < P.U;
-    int64_t b_pos = 0;  // cyclic bit position of this window at k0 = 0
+    const bool b_ok = (n0 + b_col) < P.U;
+    int64_t b_pos = 0;  // cyclic bit position of this thread's window at k0 = 0
     if (b_ok) {
-        b_pos = (b_u * P.in) % P.p + b_kb * 32;
+        b_pos = ((n0 + b_col) * P.in) % P.p + b_kb * 32;
         if (b_pos >= P.p) b_pos -= P.p;
     }
+    const uint32_t tile_head = tile[0];   // continues a window that runs past the tile end
 
-    StageRegs<XT> areg[kItems];
-    uint32_t breg = 0;
+    typename T::Piece areg[D][kItems];
+    uint32_t breg_lo[D], breg_hi[D];
 
-    auto load_stage = [&](int64_t k0) {
+    // Loads are unconditional (addresses are clamped into the tensors) so that they stay in flight
+    // across stages; what lies past the end of a row is zeroed when the stage is written to LDS.
+    auto load_stage = [&](int slot, int64_t k0) {
+        int64_t c = k0 + a_piece * 8;
+        c = c < P.in - 8 ? c : P.in - 8;   // in % 8 == 0: a piece is entirely inside or outside the row
 #pragma unroll
-        for (int i = 0; i < kItems; ++i) {
-            const int64_t c = k0 + a_col[i];
-            stage_load(areg[i], a_src[i] + k0, a_row_ok[i] && c < P.in, a_row_ok[i] && (c + 16) < P.in);
-        }
-        if (b_ok && k0 + b_kb * 32 < P.in) {
-            int64_t pos = b_pos + k0;
-            if (pos >= P.p) pos -= P.p;
-            breg = cyclic_window(tile, pos, P.p, P.n_words);
-        } else {
-            breg = 0;
-        }
+        for (int i = 0; i < kItems; ++i) T::load(areg[slot][i], a_src[i] + c);
+        int64_t pos = b_pos + k0;
+        if (pos >= P.p) pos -= P.p;
+        const int64_t w = pos >> 5;
+        breg_lo[slot] = tile[w];
+        breg_hi[slot] = tile[(w + 1 < P.n_words) ? (w + 1) : w];
     };
-    auto store_stage = [&](int buf) {
+    auto store_stage = [&](int slot, int buf, int64_t k0) {
+        if (k0 + a_piece * 8 >= P.in) {
 #pragma unroll
-        for (int i = 0; i < kItems; ++i)
-            stage_store(areg[i], &lds_a[buf][0][a_row[i] * kRowStride + 2 * a_col[i] - (a_col[i] & ~31)], kPlaneElems);
-        lds_bits[buf][b_kb][b_col] = breg;
+            for (int i = 0; i < kItems; ++i) T::zero(areg[slot][i]);
+        }
+#pragma unroll
+        for (int i = 0; i < kItems; ++i) T::store(areg[slot][i], &lds_a[buf][0][a_lds[i]]);
+        // 32 tile bits from the window's cyclic position on; bits past the tile end come from its start
+        int64_t pos = b_pos + k0;
+        if (pos >= P.p) pos -= P.p;
+        const uint32_t sh = static_cast<uint32_t>(pos & 31);
+        const uint32_t hi = ((pos >> 5) + 1 < P.n_words) ? breg_hi[slot] : 0u;
+        uint32_t wbits = __funnelshift_r(breg_lo[slot], hi, sh);   // shift 0 returns the low word
+        const int64_t left = P.p - pos;
+        if (left < 32) wbits = (wbits & ((1u << left) - 1u)) | (tile_head << left);
+        lds_bits[buf][b_kb][b_col] = b_ok ? unshuffle_bits(wbits) : 0u;
     };
-    // LDS element offset of an item inside its row: window kb occupies [kb*32, kb*32+32); pair pr
-    // fills the 16 elements at pr*16.  a_col = kb*32 + pr*8, so kb*32 + pr*16 = 2*a_col - kb*32
-    // and kb*32 = a_col & ~31 (pr*8 < 32).
 
     f32x16_t acc[kTM][kTN];
 #pragma unroll
@@ -252,14 +246,10 @@ __global__ __launch_bounds__(kThreads) void linear_mfma_kernel(const XT *__restr
     const int a_row_base = (wm * kTM * 32 + ln) * kRowStride;   // + tm*32*kRowStride
     const int b_col_base = wn * kTN * 32 + ln * kTN;            // + tn  (a lane owns kTN adjacent columns)
 
-    const int64_t n_stages = (P.in + kBK - 1) / kBK;
-    load_stage(0);
-    store_stage(0);
-    __syncthreads();
-
-    for (int64_t st = 0; st < n_stages; ++st) {
-        const int buf = st & 1;
-        if (st + 1 < n_stages) load_stage((st + 1) * kBK);
+    // One MFMA step covers 16 columns; lane group lg supplies columns 16*s + 8*lg .. + 7 of the
+    // 32-column window, i.e. element pairs 8*s + 4*lg + v (v = register).  After unshuffle_bits the
+    // two bits of pair i are bits i and i + 16 of the window.
+    auto multiply_stage = [&](int buf) {
 #pragma unroll
         for (int kb = 0; kb < kKB; ++kb) {
             uint32_t nw[kTN];
@@ -279,7 +269,7 @@ __global__ __launch_bounds__(kThreads) void linear_mfma_kernel(const XT *__restr
 #pragma unroll
                     for (int tm = 0; tm < kTM; ++tm)
                         a[tm].q = *reinterpret_cast<const uint4 *>(
-                            &lds_a[buf][pl][a_row_base + tm * 32 * kRowStride + kb * 32 + (s * 2 + lg) * 8]);
+                            &lds_a[buf][pl][a_row_base + tm * 32 * kRowStride + kb * 32 + s * 16 + lg * 8]);
 #pragma unroll
                     for (int tm = 0; tm < kTM; ++tm)
 #pragma unroll
@@ -288,23 +278,99 @@ __global__ __launch_bounds__(kThreads) void linear_mfma_kernel(const XT *__restr
                 }
             }
         }
-        if (st + 1 < n_stages) {
-            store_stage(buf ^ 1);
+    };
+
+    const int64_t n_stages = (P.in + kBK - 1) / kBK;
+#pragma unroll
+    for (int d = 0; d < D; ++d)
+        if (d < n_stages) load_stage(d, int64_t(d) * kBK);
+    store_stage(0, 0, 0);
+    __syncthreads();
+
+    // Steady state: every sub-iteration issues the loads of stage st + D, multiplies stage st and
+    // moves stage st + 1 from registers to LDS.  No condition depends on the stage number here, so
+    // the compiler can count exactly how many younger loads may stay in flight at each wait.
+    int64_t st0 = 0;
+    for (; st0 + 2 * D <= n_stages; st0 += D) {
+#pragma unroll
+        for (int d = 0; d < D; ++d) {
+            const int64_t st = st0 + d;
+            const int buf = static_cast<int>(st & 1);
+            load_stage(d, (st + D) * kBK);
+            multiply_stage(buf);
+            store_stage((d + 1) % D, buf ^ 1, (st + 1) * kBK);
             __syncthreads();
+        }
+    }
+    // Drain: at most 2*D - 1 stages are left; st0 is a multiple of D, so slot numbers stay static.
+    for (; st0 < n_stages; st0 += D) {
+#pragma unroll
+        for (int d = 0; d < D; ++d) {
+            const int64_t st = st0 + d;
+            if (st < n_stages) {   // uniform
+                const int buf = static_cast<int>(st & 1);
+                if (st + D < n_stages) load_stage(d, (st + D) * kBK);
+                multiply_stage(buf);
+                if (st + 1 < n_stages) {
+                    store_stage((d + 1) % D, buf ^ 1, (st + 1) * kBK);
+                    __syncthreads();
+                }
+            }
         }
     }
 
     // ---- epilogue: y[m, u + t*U] = alpha(u + t*U) * Z[m, u] --------------------------------------
     const int64_t u_base = n0 + b_col_base;   // first of this lane's kTN adjacent unique columns
     static_assert(kTN == 2, "the epilogue writes column pairs");
-    for (int64_t t = 0; u_base + t * P.U < P.out && u_base < P.U; ++t) {
+    if (u_base >= P.U) return;
+    const bool pair_ok = (u_base + 1 < P.U);
+    const int64_t m_wave = m0 + wm * kTM * 32 + 4 * lg;
+
+    const int64_t reps = (P.out - u_base + P.U - 1) / P.U;   // replicas of column u_base
+    const bool all_pairs = pair_ok && (u_base + (reps - 1) * P.U + 1 < P.out);
+    if ((P.n_alpha == 1 || P.aligned) && P.vec_store && all_pairs) {
+        // alpha depends on the replica only and every replica is a whole, aligned column pair.
+        // Replicas are taken in chunks whose alphas are fetched up front; inside a chunk the rows
+        // are outermost, so the stores of one row of Y are issued back to back.
+        constexpr int kChunk = 8;
+        for (int64_t t0 = 0; t0 < reps; t0 += kChunk) {
+            float al[kChunk];
+#pragma unroll
+            for (int j = 0; j < kChunk; ++j) {
+                const int64_t t = (t0 + j < reps) ? (t0 + j) : (reps - 1);
+                al[j] = alpha[P.n_alpha == 1 ? 0 : t];
+            }
+            const int n_here = static_cast<int>((reps - t0) < kChunk ? (reps - t0) : kChunk);
+#pragma unroll
+            for (int tm = 0; tm < kTM; ++tm) {
+#pragma unroll
+                for (int e = 0; e < 16; ++e) {
+                    const int64_t m = m_wave + tm * 32 + 8 * (e >> 2) + (e & 3);
+                    if (m >= P.M) continue;
+                    XT *dst = y + m * P.out + u_base + t0 * P.U;
+                    const float z0 = acc[tm][0][e], z1 = acc[tm][1][e];
+#pragma unroll
+                    for (int j = 0; j < kChunk; ++j) {
+                        if (j < n_here) {
+                            float v0 = al[j] * z0, v1 = al[j] * z1;
+                            if (RELU) { v0 = fmaxf(v0, 0.f); v1 = fmaxf(v1, 0.f); }
+                            OutPack<XT>::store2(dst + j * P.U, v0, v1);
+                        }
+                    }
+                }
+            }
+        }
+        return;
+    }
+
+    // general case (odd sizes, or tile ends inside rows so that alpha(o) = alpha[(o*in) / p] differs
+    // per lane): replicas outermost
+    for (int64_t t = 0; t < reps; ++t) {
         const int64_t o0 = u_base + t * P.U, o1 = o0 + 1;
-        const bool ok1 = (u_base + 1 < P.U) && (o1 < P.out);
+        const bool ok1 = pair_ok && (o1 < P.out);
         float al0, al1;
         if (P.n_alpha == 1) {
             al0 = al1 = alpha[0];
-        } else if (P.aligned) {
-            al0 = al1 = alpha[t];
         } else {
             al0 = alpha[(o0 * P.in) / P.p];
             al1 = ok1 ? alpha[(o1 * P.in) / P.p] : 0.f;
@@ -313,11 +379,11 @@ __global__ __launch_bounds__(kThreads) void linear_mfma_kernel(const XT *__restr
         for (int tm = 0; tm < kTM; ++tm) {
 #pragma unroll
             for (int e = 0; e < 16; ++e) {
-                const int64_t m = m0 + wm * kTM * 32 + tm * 32 + 8 * (e >> 2) + 4 * lg + (e & 3);
+                const int64_t m = m_wave + tm * 32 + 8 * (e >> 2) + (e & 3);
                 if (m >= P.M) continue;
                 float v0 = al0 * acc[tm][0][e];
                 float v1 = al1 * acc[tm][1][e];
-                if (P.relu) { v0 = fmaxf(v0, 0.f); v1 = fmaxf(v1, 0.f); }
+                if (RELU) { v0 = fmaxf(v0, 0.f); v1 = fmaxf(v1, 0.f); }
                 XT *dst = y + m * P.out + o0;
                 if (P.vec_store && ok1) {
                     OutPack<XT>::store2(dst, v0, v1);
@@ -330,11 +396,32 @@ __global__ __launch_bounds__(kThreads) void linear_mfma_kernel(const XT *__restr
     }
 }
 
+template <typename XT> size_t lds_bytes() {
+    return sizeof(uint16_t) * 2 * Traits<XT>::planes * kPlaneElems + sizeof(uint32_t) * 2 * kKB * kBN;
+}
+
+template <typename XT, bool RELU> tbn_status launch_typed(const LinearArgs &a, const MfmaParams &P, dim3 grid) {
+    static bool attr_set = false;   // dynamic LDS above the default limit has to be allowed once
+    const size_t lds = lds_bytes<XT>();
+    if (!attr_set) {
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(&linear_mfma_kernel<XT, RELU>),
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, static_cast<int>(lds));
+        if (e != hipSuccess) {
+            set_error("tbn_linear_forward: cannot reserve %zu bytes of LDS: %s", lds, hipGetErrorString(e));
+            return TBN_ERR_DEVICE;
+        }
+        attr_set = true;
+    }
+    hipLaunchKernelGGL((linear_mfma_kernel<XT, RELU>), grid, dim3(kThreads), lds, a.stream, static_cast<const XT *>(a.x),
+                       static_cast<XT *>(a.y), a.tile, a.alpha, P);
+    return check_launch("tbn_linear_forward (matrix-core kernel)");
+}
+
 }  // namespace
 
 bool linear_mfma_supported(const LinearArgs &a) {
     if (a.p < a.in || a.p < 64) return false;   // at most one tile end per row, windows never wrap twice
-    if (a.in % 8 != 0) return false;            // 16-byte activation loads
+    if (a.in % 8 != 0) return false;            // 16-byte (bf16) / 32-byte (f32) activation pieces
     if (reinterpret_cast<uintptr_t>(a.x) & 15u) return false;
     if (a.M < 16) return false;
     return true;
@@ -357,29 +444,12 @@ tbn_status launch_linear_mfma(const LinearArgs &a) {
         set_error("tbn_linear_forward: problem too large for one launch");
         return TBN_ERR_UNSUPPORTED;
     }
-    const dim3 grid(static_cast<unsigned>(blocks)), block(kThreads);
-    const int planes = (a.dt == TBN_F32) ? 3 : 1;
-    const size_t lds = sizeof(uint16_t) * 2 * planes * kBM * kRowStride + sizeof(uint32_t) * 2 * kKB * kBN;
-    static bool attr_set[2] = {false, false};   // large dynamic LDS has to be allowed once per kernel
-    if (!attr_set[a.dt == TBN_F32]) {
-        hipError_t e = (a.dt == TBN_F32)
-                           ? hipFuncSetAttribute(reinterpret_cast<const void *>(&linear_mfma_kernel<float>),
-                                                 hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds)
-                           : hipFuncSetAttribute(reinterpret_cast<const void *>(&linear_mfma_kernel<uint16_t>),
-                                                 hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
-        if (e != hipSuccess) {
-            set_error("tbn_linear_forward: cannot reserve %zu bytes of LDS: %s", lds, hipGetErrorString(e));
-            return TBN_ERR_DEVICE;
-        }
-        attr_set[a.dt == TBN_F32] = true;
-    }
+    const dim3 grid(static_cast<unsigned>(blocks));
+    tbn_status st;
     if (a.dt == TBN_F32)
-        hipLaunchKernelGGL(linear_mfma_kernel<float>, grid, block, lds, a.stream, static_cast<const float *>(a.x),
-                           static_cast<float *>(a.y), a.tile, a.alpha, P);
+        st = P.relu ? launch_typed<float, true>(a, P, grid) : launch_typed<float, false>(a, P, grid);
     else
-        hipLaunchKernelGGL(linear_mfma_kernel<uint16_t>, grid, block, lds, a.stream,
-                           static_cast<const uint16_t *>(a.x), static_cast<uint16_t *>(a.y), a.tile, a.alpha, P);
-    tbn_status st = check_launch("tbn_linear_forward (matrix-core kernel)");
+        st = P.relu ? launch_typed<uint16_t, true>(a, P, grid) : launch_typed<uint16_t, false>(a, P, grid);
     if (st != TBN_OK) return st;
     // columns whose weight row straddles a tile end need two alphas
     if (a.n_alpha > 1 && !P.aligned) return launch_linear_rows_fixup(a);
