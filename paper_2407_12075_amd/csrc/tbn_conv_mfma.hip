@@ -1,5 +1,367 @@
+// Matrix-core kernel for the convolutional tiled-bit layer when the tile holds whole filters.
+//
+// The flattened (O, C, kh, kw) weight is the tile repeated k times (Eq. 4-5).  If the tile length p
+// is a multiple of the filter length F = C*kh*kw, the tile is R = p / F whole filters and output
+// channel o uses filter o % R scaled by alpha[o / R]: only R distinct filters exist and, as the paper
+// notes for its two-channel example (Section "CNN Architectures"), the other output channels are
+// copies.  The kernel computes the R distinct channels once per image block and writes every
+// replica o = u + t*R as alpha * Z[u].
+//
+// gfx950 mapping (implicit GEMM on v_mfma_f32_16x16x32_bf16, filters as rows, pixels as columns):
+//   * workgroup = one image, a block of output rows (<= 128 pixels) and 32 distinct filters;
+//     4 waves, each owning up to 2 tiles of 16 pixels x the 2 tiles of 16 filters;
+//   * K runs over chunks of 32 input channels; inside a chunk over the kh*kw taps, so that one MFMA
+//     step (K = 32) is "32 channels of one tap".  The input patch of a chunk (with its zero halo)
+//     is staged in LDS channel-last as bf16, which makes the 8 channels a lane needs one 16-byte
+//     LDS read at (pixel + tap offset); float32 inputs are split exactly into three bf16 planes
+//     (the weights are +-1, so products are exact; sums are float32 in the matrix pipe);
+//   * the filter bits are reordered once per workgroup from (channel, tap) to (tap, channel) order
+//     into LDS, 32 channels per word, even/odd bits separated so that a lane expands a word into
+//     a +-1 bf16 operand with one shift and one and-or per register;
+//   * the next chunk's input is prefetched into registers while the current one is multiplied.
 #include "tbn_common.h"
+
 namespace tbn {
-bool conv_mfma_supported(const ConvArgs &) { return false; }
-tbn_status launch_conv_mfma(const ConvArgs &) { set_error("not built"); return TBN_ERR_UNSUPPORTED; }
+
+typedef __bf16 bf16x8_t __attribute__((ext_vector_type(8)));
+typedef float f32x4_t __attribute__((ext_vector_type(4)));
+typedef uint32_t u32x4_t __attribute__((ext_vector_type(4)));
+
+namespace {
+
+constexpr int kThreads = 256;
+constexpr int kFB = 32;            // distinct filters per workgroup (2 MFMA row tiles)
+constexpr int kCK = 32;            // input channels per chunk (one MFMA step per tap)
+constexpr int kMaxPix = 128;       // output pixels per workgroup (8 MFMA column tiles)
+constexpr int kMaxItems = 10;      // staged (channel pair, pixel) items per thread and chunk
+constexpr int kPixStride = kCK * 2 + 16;   // bytes per patch pixel in LDS: 32 bf16 channels + 16 B padding
+
+struct ConvMfmaParams {
+    int64_t N, C, H, W, O, Ho, Wo;
+    int32_t kh, kw, sh, sw, ph, pw;
+    int64_t F;            // filter length C*kh*kw
+    int64_t R;            // distinct filters = filters per tile
+    int32_t n_alpha;
+    int32_t rows_per_blk; // output rows per workgroup
+    int32_t PR, PC;       // input patch rows / columns (with halo)
+    int32_t plane_bytes;  // PR*PC*kPixStride
+};
+
+template <typename XT> struct CTraits;
+template <> struct CTraits<float> { static constexpr int planes = 3; };
+template <> struct CTraits<uint16_t> { static constexpr int planes = 1; };
+
+__device__ __forceinline__ uint32_t unshuffle_bits32(uint32_t x) {
+    uint32_t t;
+    t = (x ^ (x >> 1)) & 0x22222222u; x ^= t ^ (t << 1);
+    t = (x ^ (x >> 2)) & 0x0c0c0c0cu; x ^= t ^ (t << 2);
+    t = (x ^ (x >> 4)) & 0x00f000f0u; x ^= t ^ (t << 4);
+    t = (x ^ (x >> 8)) & 0x0000ff00u; x ^= t ^ (t << 8);
+    return x;
 }
+
+// truncation split of a float into three bf16 terms (top 8 significand bits, next 8, the rest)
+__device__ __forceinline__ void split3(float x, uint32_t &t0, uint32_t &t1, uint32_t &t2) {
+    t0 = __float_as_uint(x) & 0xffff0000u;
+    const float r1 = x - __uint_as_float(t0);
+    t1 = __float_as_uint(r1) & 0xffff0000u;
+    const float r2 = r1 - __uint_as_float(t1);
+    t2 = __float_as_uint(r2);
+}
+
+__device__ __forceinline__ float load_elem(const float *p) { return *p; }
+__device__ __forceinline__ float load_elem(const uint16_t *p) { return bf16_bits_to_f32(*p); }
+
+template <typename XT, int T, bool RELU>
+__global__ __launch_bounds__(kThreads, 2) void conv_mfma_kernel(const XT *__restrict__ x, XT *__restrict__ y,
+                                                                  const uint32_t *__restrict__ tile,
+                                                                  const float *__restrict__ alpha, ConvMfmaParams P) {
+    constexpr int NP = CTraits<XT>::planes;
+    extern __shared__ __attribute__((aligned(16))) unsigned char lds_raw[];
+    // layout: patch buffers [2][NP][PR*PC][kPixStride bytes], then filter bits [chunk][tap][32 filters]
+    unsigned char *lds_patch = lds_raw;
+    const int buf_bytes = NP * P.plane_bytes;
+    uint32_t *lds_bits = reinterpret_cast<uint32_t *>(lds_raw + 2 * buf_bytes);
+
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int ln = lane & 15, lg = lane >> 4;
+    const int n_chunks = static_cast<int>(P.C / kCK);
+    const int64_t img = blockIdx.y;
+    const int row0 = blockIdx.x * P.rows_per_blk;                         // first output row of the block
+    const int rows = (P.Ho - row0) < P.rows_per_blk ? static_cast<int>(P.Ho - row0) : P.rows_per_blk;
+    const int PX = rows * static_cast<int>(P.Wo);                         // output pixels of the block
+    const int64_t u0 = int64_t(blockIdx.z) * kFB;                         // first distinct filter of the block
+
+    // ---- zero both patch buffers (halo positions and padding stay zero for the whole kernel) ----
+    for (int i = tid * 16; i < 2 * buf_bytes; i += kThreads * 16)
+        *reinterpret_cast<u32x4_t *>(lds_patch + i) = u32x4_t{0u, 0u, 0u, 0u};
+
+    // ---- filter bits: (channel, tap) order in the tile -> one word per (chunk, tap, filter) -------
+    // A thread transposes the 32 x T bit block of one (filter, chunk): T consecutive words in, T out.
+    for (int id = tid; id < kFB * n_chunks; id += kThreads) {
+        const int u = id % kFB, chunk = id / kFB;
+        uint32_t w[T], o[T];
+        const bool live = (u0 + u) < P.R;
+        const int64_t word0 = ((u0 + u) * P.F) / 32 + int64_t(chunk) * T;   // F % 32 == 0: filters start on words
+#pragma unroll
+        for (int i = 0; i < T; ++i) w[i] = live ? tile[word0 + i] : 0u;
+#pragma unroll
+        for (int tap = 0; tap < T; ++tap) {
+            uint32_t acc = 0;
+#pragma unroll
+            for (int j = 0; j < 32; ++j) {
+                const int pos = j * T + tap;   // bit of channel j, this tap, inside the block
+                acc |= ((w[pos >> 5] >> (pos & 31)) & 1u) << j;
+            }
+            o[tap] = unshuffle_bits32(acc);
+        }
+#pragma unroll
+        for (int tap = 0; tap < T; ++tap) lds_bits[(chunk * T + tap) * kFB + u] = o[tap];
+    }
+
+    // ---- staging items: (channel pair cp, valid patch pixel) -> registers -> LDS --------------------
+    // valid patch pixels = patch positions inside the image, enumerated row-major
+    const int iy_first = row0 * P.sh - P.ph;                               // image row of patch row 0 (may be < 0)
+    const int ix_first = -P.pw;
+    const int py_lo = iy_first < 0 ? -iy_first : 0;
+    const int py_hi = (iy_first + P.PR) > P.H ? static_cast<int>(P.H - iy_first) : P.PR;   // exclusive
+    const int px_lo = ix_first < 0 ? -ix_first : 0;
+    const int px_hi = (ix_first + P.PC) > P.W ? static_cast<int>(P.W - ix_first) : P.PC;   // exclusive
+    const int vrows = py_hi > py_lo ? py_hi - py_lo : 0, vcols = px_hi > px_lo ? px_hi - px_lo : 0;
+    const int npix = vrows * vcols;
+    const int n_items = npix * (kCK / 2);
+    int32_t it_goff[kMaxItems];   // element offset inside the chunk's first channel plane, or -1
+    int32_t it_loff[kMaxItems];   // byte offset inside a patch plane
+#pragma unroll
+    for (int i = 0; i < kMaxItems; ++i) {
+        const int q = tid + i * kThreads;
+        if (q < n_items) {
+            const int cp = q / npix, pix = q % npix;
+            const int py = py_lo + pix / vcols, px = px_lo + pix % vcols;
+            it_goff[i] = static_cast<int32_t>((2 * cp) * P.H * P.W + int64_t(iy_first + py) * P.W + (ix_first + px));
+            it_loff[i] = (py * P.PC + px) * kPixStride + cp * 4;
+        } else {
+            it_goff[i] = -1;
+            it_loff[i] = 0;
+        }
+    }
+    const int64_t plane_hw = P.H * P.W;
+    const XT *x_img = x + img * P.C * plane_hw;
+
+    float st_a[kMaxItems], st_b[kMaxItems];   // the two channels of a pair
+    auto load_chunk = [&](int chunk) {
+        const XT *base = x_img + int64_t(chunk) * kCK * plane_hw;
+#pragma unroll
+        for (int i = 0; i < kMaxItems; ++i) {
+            const int32_t g = it_goff[i] < 0 ? 0 : it_goff[i];
+            st_a[i] = load_elem(base + g);
+            st_b[i] = load_elem(base + g + plane_hw);
+        }
+    };
+    auto store_chunk = [&](int buf) {
+        unsigned char *dst = lds_patch + buf * buf_bytes;
+#pragma unroll
+        for (int i = 0; i < kMaxItems; ++i) {
+            if (it_goff[i] < 0) continue;
+            if (NP == 3) {
+                uint32_t a0, a1, a2, b0, b1, b2;
+                split3(st_a[i], a0, a1, a2);
+                split3(st_b[i], b0, b1, b2);
+                *reinterpret_cast<uint32_t *>(dst + it_loff[i]) = (a0 >> 16) | b0;
+                *reinterpret_cast<uint32_t *>(dst + P.plane_bytes + it_loff[i]) = (a1 >> 16) | b1;
+                *reinterpret_cast<uint32_t *>(dst + 2 * P.plane_bytes + it_loff[i]) = (a2 >> 16) | (b2 & 0xffff0000u);
+            } else {   // bf16 input: the float holds the exact value, its top half is the bf16 pattern
+                *reinterpret_cast<uint32_t *>(dst + it_loff[i]) =
+                    (__float_as_uint(st_a[i]) >> 16) | (__float_as_uint(st_b[i]) & 0xffff0000u);
+            }
+        }
+    };
+
+    // ---- MFMA operands of this lane -----------------------------------------------------------------
+    // pixel tiles of the wave: wave and wave + 4; lane column = pixel ln of the tile
+    int pix_off[2];
+    bool tile_live[2];
+#pragma unroll
+    for (int j = 0; j < 2; ++j) {
+        const int pt = wave + 4 * j;
+        tile_live[j] = pt * 16 < PX;
+        int q = pt * 16 + ln;
+        q = q < PX ? q : (PX > 0 ? PX - 1 : 0);   // lanes past the block read a valid pixel; results are dropped
+        const int yo = q / static_cast<int>(P.Wo), xo = q % static_cast<int>(P.Wo);
+        pix_off[j] = ((yo * P.sh) * P.PC + xo * P.sw) * kPixStride + lg * 16;
+    }
+    f32x4_t acc[2][2];   // [filter tile][pixel tile]
+#pragma unroll
+    for (int a = 0; a < 2; ++a)
+#pragma unroll
+        for (int b = 0; b < 2; ++b) acc[a][b] = f32x4_t{0.f, 0.f, 0.f, 0.f};
+
+    union Frag { bf16x8_t v; uint32_t u[4]; u32x4_t q; };
+    int tap_off[T];   // byte offset of a tap inside the patch (uniform)
+#pragma unroll
+    for (int tap = 0; tap < T; ++tap) tap_off[tap] = ((tap / P.kw) * P.PC + (tap % P.kw)) * kPixStride;
+
+    auto multiply_chunk = [&](int buf, int chunk) {
+        const unsigned char *src = lds_patch + buf * buf_bytes;
+        const uint32_t *bits = lds_bits + chunk * T * kFB + ln;
+#pragma unroll
+        for (int tap = 0; tap < T; ++tap) {
+            Frag wf[2];
+#pragma unroll
+            for (int ft = 0; ft < 2; ++ft) {
+                const uint32_t nw = (~bits[tap * kFB + ft * 16]) >> (4 * lg);
+#pragma unroll
+                for (int v = 0; v < 4; ++v) wf[ft].u[v] = ((nw << (15 - v)) & 0x80008000u) | 0x3f803f80u;
+            }
+#pragma unroll
+            for (int j = 0; j < 2; ++j) {
+                if (!tile_live[j]) continue;   // uniform per wave
+#pragma unroll
+                for (int pl = 0; pl < NP; ++pl) {
+                    Frag xf;
+                    xf.q = *reinterpret_cast<const u32x4_t *>(src + pl * P.plane_bytes + pix_off[j] + tap_off[tap]);
+#pragma unroll
+                    for (int ft = 0; ft < 2; ++ft)
+                        acc[ft][j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(wf[ft].v, xf.v, acc[ft][j], 0, 0, 0);
+                }
+            }
+        }
+    };
+
+    // ---- main loop over channel chunks -----------------------------------------------------------------
+    load_chunk(0);
+    __syncthreads();            // zero fill and filter bits are in place
+    store_chunk(0);
+    __syncthreads();
+    for (int chunk = 0; chunk < n_chunks; ++chunk) {
+        const int buf = chunk & 1;
+        if (chunk + 1 < n_chunks) load_chunk(chunk + 1);
+        multiply_chunk(buf, chunk);
+        if (chunk + 1 < n_chunks) store_chunk(buf ^ 1);
+        __syncthreads();
+    }
+
+    // ---- epilogue: y[img, u + t*R, row0.., :] = alpha[t] * Z[u] ---------------------------------------------
+    // lane holds pixel ln of its tiles and filters 4*lg + i of each filter tile
+    const int64_t plane_out = P.Ho * P.Wo;
+    const int64_t reps = (P.O + P.R - 1) / P.R;
+    for (int64_t t = 0; t < reps; ++t) {
+        const float al = alpha[P.n_alpha == 1 ? 0 : t];
+#pragma unroll
+        for (int ft = 0; ft < 2; ++ft) {
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                const int64_t u = u0 + ft * 16 + 4 * lg + i;
+                const int64_t o = u + t * P.R;
+                if (u >= P.R || o >= P.O) continue;
+                XT *dst = y + ((img * P.O + o) * plane_out) + int64_t(row0) * P.Wo;
+#pragma unroll
+                for (int j = 0; j < 2; ++j) {
+                    const int q = (wave + 4 * j) * 16 + ln;
+                    if (q >= PX) continue;
+                    float v = al * acc[ft][j][i];
+                    if (RELU) v = fmaxf(v, 0.f);
+                    ElemIO<XT>::store(dst + q, v);
+                }
+            }
+        }
+    }
+}
+
+struct ConvPlan {
+    bool ok;
+    int rows_per_blk, PR, PC, nblk;
+    size_t lds;
+};
+
+ConvPlan plan_conv(const ConvArgs &a) {
+    ConvPlan pl{false, 0, 0, 0, 0, 0};
+    const int64_t F = a.C * a.kh * a.kw;
+    const int T = a.kh * a.kw;
+    if (T != 1 && T != 9) return pl;                     // instantiated tap counts: 1x1 and 3x3
+    if (a.p % F != 0) return pl;                         // the tile must hold whole filters
+    if (a.C % kCK != 0) return pl;
+    if (a.Wo > kMaxPix || a.Wo <= 0 || a.Ho <= 0) return pl;
+    if (a.C * a.H * a.W >= (int64_t(1) << 31)) return pl;   // 32-bit element offsets inside an image
+    if (a.N > 65535) return pl;
+    const int planes = (a.dt == TBN_F32) ? 3 : 1;
+    const size_t bits_bytes = size_t(T) * a.C * 4;       // 32 filters * T * C/32 words
+    // balanced row blocks of at most kMaxPix pixels whose valid input patch fits the staging budget
+    int64_t rows = kMaxPix / a.Wo;
+    if (rows > a.Ho) rows = a.Ho;
+    const int64_t nblk0 = (a.Ho + rows - 1) / rows;
+    rows = (a.Ho + nblk0 - 1) / nblk0;
+    for (; rows >= 1; --rows) {
+        const int64_t PR = (rows - 1) * a.sh + a.kh, PC = (a.Wo - 1) * a.sw + a.kw;
+        const int64_t vrows = PR < a.H ? PR : a.H, vcols = PC < a.W ? PC : a.W;
+        const size_t lds = 2 * size_t(planes) * PR * PC * kPixStride + bits_bytes;
+        if (vrows * vcols * (kCK / 2) <= int64_t(kMaxItems) * kThreads && lds <= 150 * 1024) {
+            pl.ok = true;
+            pl.rows_per_blk = static_cast<int>(rows);
+            pl.PR = static_cast<int>(PR);
+            pl.PC = static_cast<int>(PC);
+            pl.nblk = static_cast<int>((a.Ho + rows - 1) / rows);
+            pl.lds = lds;
+            return pl;
+        }
+    }
+    return pl;
+}
+
+template <typename XT, int T, bool RELU>
+tbn_status launch_conv_typed(const ConvArgs &a, const ConvMfmaParams &P, const ConvPlan &pl, dim3 grid) {
+    static size_t attr_bytes = 0;   // largest dynamic LDS size allowed so far for this instantiation
+    if (pl.lds > attr_bytes) {
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(&conv_mfma_kernel<XT, T, RELU>),
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, static_cast<int>(pl.lds));
+        if (e != hipSuccess) {
+            set_error("tbn_conv2d_forward: cannot reserve %zu bytes of LDS: %s", pl.lds, hipGetErrorString(e));
+            return TBN_ERR_DEVICE;
+        }
+        attr_bytes = pl.lds;
+    }
+    hipLaunchKernelGGL((conv_mfma_kernel<XT, T, RELU>), grid, dim3(kThreads), pl.lds, a.stream,
+                       static_cast<const XT *>(a.x), static_cast<XT *>(a.y), a.tile, a.alpha, P);
+    return check_launch("tbn_conv2d_forward (matrix-core kernel)");
+}
+
+template <typename XT, int T>
+tbn_status launch_conv_relu(const ConvArgs &a, const ConvMfmaParams &P, const ConvPlan &pl, dim3 grid) {
+    return (a.flags & TBN_FLAG_RELU) ? launch_conv_typed<XT, T, true>(a, P, pl, grid)
+                                     : launch_conv_typed<XT, T, false>(a, P, pl, grid);
+}
+
+template <typename XT>
+tbn_status launch_conv_taps(const ConvArgs &a, const ConvMfmaParams &P, const ConvPlan &pl, dim3 grid) {
+    return (a.kh * a.kw == 1) ? launch_conv_relu<XT, 1>(a, P, pl, grid) : launch_conv_relu<XT, 9>(a, P, pl, grid);
+}
+
+}  // namespace
+
+bool conv_mfma_supported(const ConvArgs &a) { return plan_conv(a).ok; }
+
+tbn_status launch_conv_mfma(const ConvArgs &a) {
+    const ConvPlan pl = plan_conv(a);
+    if (!pl.ok) {
+        set_error("tbn_conv2d_forward: shape not supported by the matrix-core kernel");
+        return TBN_ERR_UNSUPPORTED;
+    }
+    ConvMfmaParams P;
+    P.N = a.N; P.C = a.C; P.H = a.H; P.W = a.W; P.O = a.O; P.Ho = a.Ho; P.Wo = a.Wo;
+    P.kh = a.kh; P.kw = a.kw; P.sh = a.sh; P.sw = a.sw; P.ph = a.ph; P.pw = a.pw;
+    P.F = a.C * a.kh * a.kw;
+    P.R = a.p / P.F;
+    P.n_alpha = a.n_alpha;
+    P.rows_per_blk = pl.rows_per_blk;
+    P.PR = pl.PR; P.PC = pl.PC;
+    P.plane_bytes = pl.PR * pl.PC * kPixStride;
+    const int64_t fblocks = (P.R + kFB - 1) / kFB;
+    if (fblocks > 65535) {
+        set_error("tbn_conv2d_forward: too many distinct filters for one launch");
+        return TBN_ERR_UNSUPPORTED;
+    }
+    const dim3 grid(static_cast<unsigned>(pl.nblk), static_cast<unsigned>(a.N), static_cast<unsigned>(fblocks));
+    return (a.dt == TBN_F32) ? launch_conv_taps<float>(a, P, pl, grid) : launch_conv_taps<uint16_t>(a, P, pl, grid);
+}
+
+}  // namespace tbn

@@ -260,6 +260,11 @@ CONV_SMALL = [
     (2, 64, 14, 14, 64, 3, 3, (1, 1), (1, 1), 3, 3),     # tile ends mid-filter
     (2, 32, 28, 28, 32, 3, 3, (2, 2), (1, 1), 4, 1),
     (1, 1, 8, 8, 2, 3, 3, (1, 1), (1, 1), 2, 1),         # the paper's two-identical-channels example
+    (2, 64, 7, 7, 128, 1, 1, (1, 1), (0, 0), 2, 2),      # 1x1, 64 whole filters per tile (two filter blocks)
+    (1, 32, 5, 20, 48, 3, 3, (1, 1), (1, 1), 3, 3),      # 16 whole filters per tile, 100 pixels in one block
+    (3, 64, 14, 14, 64, 3, 3, (1, 1), (1, 1), 2, 1),     # 32 whole filters per tile, two row blocks per image
+    (1, 32, 9, 9, 32, 3, 3, (1, 1), (0, 0), 4, 4),       # no padding
+    (2, 32, 12, 10, 32, 3, 3, (2, 1), (1, 1), 2, 2),     # mixed stride
 ]
 
 
