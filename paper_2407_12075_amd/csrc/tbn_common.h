@@ -51,7 +51,9 @@ tbn_status launch_pack(const float *w, const float *a, int64_t n, int32_t k, int
 size_t pack_workspace_bytes(int64_t n, int32_t k, int32_t n_alpha);
 
 tbn_status launch_linear_generic(const LinearArgs &a);
-bool linear_rows_supported(const LinearArgs &a);   // small-batch wave-per-row kernel
+bool linear_skinny_supported(const LinearArgs &a); // small-batch (decode-shaped) matrix-core kernel
+tbn_status launch_linear_skinny(const LinearArgs &a);
+bool linear_rows_supported(const LinearArgs &a);   // wave-per-row kernel (also repairs tile-end columns)
 tbn_status launch_linear_rows(const LinearArgs &a);
 tbn_status launch_linear_rows_fixup(const LinearArgs &a);  // recompute the columns whose row holds a tile end
 bool linear_mfma_supported(const LinearArgs &a);   // matrix-core kernel

@@ -129,6 +129,11 @@ LINEAR_SMALL = [
     (1, 3000, 96, 9, 9),
     (300, 264, 136, 3, 3),     # p = 11968 = 45 1/3 rows: no row repeats at all (U = out)
     (129, 64, 64, 64, 64),     # p = in: every row is the whole tile
+    (64, 1024, 512, 4, 4),     # largest batch of the small-batch kernel
+    (17, 512, 256, 8, 8),      # two batch slabs, the second almost empty
+    (48, 200, 90, 4, 4),       # small batch with tile ends inside rows
+    (65, 1024, 512, 4, 4),     # smallest batch of the large-batch kernel
+    (2, 4096, 40, 5, 5),       # 8 distinct rows only: a partly filled column tile
 ]
 
 
