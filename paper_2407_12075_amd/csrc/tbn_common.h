@@ -60,6 +60,7 @@ bool linear_mfma_supported(const LinearArgs &a);   // matrix-core kernel
 tbn_status launch_linear_mfma(const LinearArgs &a);
 
 tbn_status launch_conv_generic(const ConvArgs &a);
+tbn_status launch_conv_generic_tile_ends(const ConvArgs &a);   // only the channels whose filter holds a tile end
 bool conv_mfma_supported(const ConvArgs &a);
 tbn_status launch_conv_mfma(const ConvArgs &a);
 

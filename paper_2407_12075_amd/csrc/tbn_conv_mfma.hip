@@ -1,11 +1,13 @@
-// Matrix-core kernel for the convolutional tiled-bit layer when the tile holds whole filters.
+// Matrix-core kernel for the convolutional tiled-bit layer.
 //
-// The flattened (O, C, kh, kw) weight is the tile repeated k times (Eq. 4-5).  If the tile length p
-// is a multiple of the filter length F = C*kh*kw, the tile is R = p / F whole filters and output
-// channel o uses filter o % R scaled by alpha[o / R]: only R distinct filters exist and, as the paper
-// notes for its two-channel example (Section "CNN Architectures"), the other output channels are
-// copies.  The kernel computes the R distinct channels once per image block and writes every
-// replica o = u + t*R as alpha * Z[u].
+// The flattened (O, C, kh, kw) weight is the tile repeated k times (Eq. 4-5), so the filter of
+// output channel o is the cyclic tile window that starts at bit (o*F) % p, F = C*kh*kw.  That start
+// has period R = p / gcd(F, p) in o: only R distinct +-1 filters exist and, as the paper notes for
+// its two-channel example (Section "CNN Architectures"), the other output channels are copies up
+// to alpha.  The kernel computes the R distinct channels once per image block and writes every
+// replica o = u + t*R as alpha(o) * Z[u].  When the tile holds whole filters (p % F == 0), R = p / F
+// and alpha(o) = alpha[t]; otherwise alpha(o) = alpha[(o*F) / p] and the few channels whose filter
+// contains a tile end (two alphas) are recomputed afterwards by the shape-agnostic kernel.
 //
 // gfx950 mapping (implicit GEMM on v_mfma_f32_16x16x32_bf16, filters as rows, pixels as columns):
 //   * workgroup = one image, a block of output rows (<= 128 pixels) and 32 distinct filters;
@@ -20,6 +22,8 @@
 //     a +-1 bf16 operand with one shift and one and-or per register;
 //   * the next chunk's input is prefetched into registers while the current one is multiplied.
 #include "tbn_common.h"
+
+#include <type_traits>
 
 namespace tbn {
 
@@ -40,7 +44,9 @@ struct ConvMfmaParams {
     int64_t N, C, H, W, O, Ho, Wo;
     int32_t kh, kw, sh, sw, ph, pw;
     int64_t F;            // filter length C*kh*kw
-    int64_t R;            // distinct filters = filters per tile
+    int64_t R;            // distinct filters
+    int64_t p, n_words;   // tile bits / words
+    int32_t aligned;      // p % F == 0
     int32_t n_alpha;
     int32_t rows_per_blk; // output rows per workgroup
     int32_t PR, PC;       // input patch rows / columns (with halo)
@@ -96,15 +102,42 @@ __global__ __launch_bounds__(kThreads, 2) void conv_mfma_kernel(const XT *__rest
     for (int i = tid * 16; i < 2 * buf_bytes; i += kThreads * 16)
         *reinterpret_cast<u32x4_t *>(lds_patch + i) = u32x4_t{0u, 0u, 0u, 0u};
 
+    const uint32_t tile_head = tile[0];
     // ---- filter bits: (channel, tap) order in the tile -> one word per (chunk, tap, filter) -------
     // A thread transposes the 32 x T bit block of one (filter, chunk): T consecutive words in, T out.
     for (int id = tid; id < kFB * n_chunks; id += kThreads) {
         const int u = id % kFB, chunk = id / kFB;
         uint32_t w[T], o[T];
         const bool live = (u0 + u) < P.R;
-        const int64_t word0 = ((u0 + u) * P.F) / 32 + int64_t(chunk) * T;   // F % 32 == 0: filters start on words
+        if (P.aligned) {
+            // whole filters per tile and F % 32 == 0: the block is T consecutive words of the tile
+            const int64_t word0 = ((u0 + u) * P.F) / 32 + int64_t(chunk) * T;
 #pragma unroll
-        for (int i = 0; i < T; ++i) w[i] = live ? tile[word0 + i] : 0u;
+            for (int i = 0; i < T; ++i) w[i] = live ? tile[word0 + i] : 0u;
+        } else {
+            // the 32*T bits of this (filter, chunk) start at cyclic tile position pos; all loads are
+            // issued first (unconditionally, with clamped indices) so that they overlap
+            int64_t pos = live ? ((u0 + u) * P.F + int64_t(chunk) * 32 * T) % P.p : 0;
+            uint32_t lo[T], hi[T];
+            int64_t wpos[T];
+    #pragma unroll
+            for (int i = 0; i < T; ++i) {
+                wpos[i] = pos;
+                const int64_t wi = pos >> 5;
+                lo[i] = tile[wi];
+                hi[i] = tile[(wi + 1 < P.n_words) ? (wi + 1) : wi];
+                pos += 32;
+                if (pos >= P.p) pos -= P.p;
+            }
+    #pragma unroll
+            for (int i = 0; i < T; ++i) {
+                const uint32_t hi_ok = ((wpos[i] >> 5) + 1 < P.n_words) ? hi[i] : 0u;
+                uint32_t v = __funnelshift_r(lo[i], hi_ok, static_cast<uint32_t>(wpos[i] & 31));
+                const int64_t left = P.p - wpos[i];   // bits before the tile end; the window continues at bit 0
+                if (left < 32) v = (v & ((1u << left) - 1u)) | (tile_head << left);
+                w[i] = live ? v : 0u;
+            }
+        }
 #pragma unroll
         for (int tap = 0; tap < T; ++tap) {
             uint32_t acc = 0;
@@ -245,27 +278,33 @@ __global__ __launch_bounds__(kThreads, 2) void conv_mfma_kernel(const XT *__rest
     // lane holds pixel ln of its tiles and filters 4*lg + i of each filter tile
     const int64_t plane_out = P.Ho * P.Wo;
     const int64_t reps = (P.O + P.R - 1) / P.R;
-    for (int64_t t = 0; t < reps; ++t) {
-        const float al = alpha[P.n_alpha == 1 ? 0 : t];
+    const bool per_replica = (P.n_alpha == 1) || P.aligned;   // alpha depends on the replica only (uniform)
+    auto write_all = [&](auto per_replica_c) __attribute__((always_inline)) {
+        constexpr bool kPerReplica = decltype(per_replica_c)::value;
+        for (int64_t t = 0; t < reps; ++t) {
+            const float al_t = kPerReplica ? alpha[P.n_alpha == 1 ? 0 : t] : 0.f;
 #pragma unroll
-        for (int ft = 0; ft < 2; ++ft) {
+            for (int ft = 0; ft < 2; ++ft) {
 #pragma unroll
-            for (int i = 0; i < 4; ++i) {
-                const int64_t u = u0 + ft * 16 + 4 * lg + i;
-                const int64_t o = u + t * P.R;
-                if (u >= P.R || o >= P.O) continue;
-                XT *dst = y + ((img * P.O + o) * plane_out) + int64_t(row0) * P.Wo;
+                for (int i = 0; i < 4; ++i) {
+                    const int64_t u = u0 + ft * 16 + 4 * lg + i;
+                    const int64_t o = u + t * P.R;
+                    if (u >= P.R || o >= P.O) continue;
+                    const float al = kPerReplica ? al_t : alpha[(o * P.F) / P.p];
+                    XT *dst = y + ((img * P.O + o) * plane_out) + int64_t(row0) * P.Wo;
 #pragma unroll
-                for (int j = 0; j < 2; ++j) {
-                    const int q = (wave + 4 * j) * 16 + ln;
-                    if (q >= PX) continue;
-                    float v = al * acc[ft][j][i];
-                    if (RELU) v = fmaxf(v, 0.f);
-                    ElemIO<XT>::store(dst + q, v);
+                    for (int j = 0; j < 2; ++j) {
+                        const int q = (wave + 4 * j) * 16 + ln;
+                        if (q >= PX) continue;
+                        float v = al * acc[ft][j][i];
+                        if (RELU) v = fmaxf(v, 0.f);
+                        ElemIO<XT>::store(dst + q, v);
+                    }
                 }
             }
         }
-    }
+    };
+    if (per_replica) write_all(std::true_type{}); else write_all(std::false_type{});
 }
 
 struct ConvPlan {
@@ -279,7 +318,7 @@ ConvPlan plan_conv(const ConvArgs &a) {
     const int64_t F = a.C * a.kh * a.kw;
     const int T = a.kh * a.kw;
     if (T != 1 && T != 9) return pl;                     // instantiated tap counts: 1x1 and 3x3
-    if (a.p % F != 0) return pl;                         // the tile must hold whole filters
+    if (a.p < F || a.p < 64) return pl;                  // at most one tile end per filter
     if (a.C % kCK != 0) return pl;
     if (a.Wo > kMaxPix || a.Wo <= 0 || a.Ho <= 0) return pl;
     if (a.C * a.H * a.W >= (int64_t(1) << 31)) return pl;   // 32-bit element offsets inside an image
@@ -350,7 +389,10 @@ tbn_status launch_conv_mfma(const ConvArgs &a) {
     P.N = a.N; P.C = a.C; P.H = a.H; P.W = a.W; P.O = a.O; P.Ho = a.Ho; P.Wo = a.Wo;
     P.kh = a.kh; P.kw = a.kw; P.sh = a.sh; P.sw = a.sw; P.ph = a.ph; P.pw = a.pw;
     P.F = a.C * a.kh * a.kw;
-    P.R = a.p / P.F;
+    P.R = unique_rows(a.O, P.F, a.p);
+    P.p = a.p;
+    P.n_words = (a.p + 31) / 32;
+    P.aligned = (a.p % P.F == 0) ? 1 : 0;
     P.n_alpha = a.n_alpha;
     P.rows_per_blk = pl.rows_per_blk;
     P.PR = pl.PR; P.PC = pl.PC;
@@ -361,7 +403,11 @@ tbn_status launch_conv_mfma(const ConvArgs &a) {
         return TBN_ERR_UNSUPPORTED;
     }
     const dim3 grid(static_cast<unsigned>(pl.nblk), static_cast<unsigned>(a.N), static_cast<unsigned>(fblocks));
-    return (a.dt == TBN_F32) ? launch_conv_taps<float>(a, P, pl, grid) : launch_conv_taps<uint16_t>(a, P, pl, grid);
+    tbn_status st = (a.dt == TBN_F32) ? launch_conv_taps<float>(a, P, pl, grid) : launch_conv_taps<uint16_t>(a, P, pl, grid);
+    if (st != TBN_OK) return st;
+    // channels whose filter contains a tile end are scaled by two alphas
+    if (a.n_alpha > 1 && !P.aligned) return launch_conv_generic_tile_ends(a);
+    return TBN_OK;
 }
 
 }  // namespace tbn

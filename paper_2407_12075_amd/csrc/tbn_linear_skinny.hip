@@ -50,6 +50,7 @@ __device__ __forceinline__ void expand_byte(Frag &f, uint32_t byte) {
 template <typename XT> struct SkTraits;
 template <> struct SkTraits<uint16_t> {
     static constexpr int planes = 1;
+    static constexpr int blocks_in_flight = 4;
     struct Piece { u32x4_t v; };
     static __device__ __forceinline__ void load(Piece &r, const uint16_t *p) { r.v = *reinterpret_cast<const u32x4_t *>(p); }
     static __device__ __forceinline__ void zero(Piece &r) { r.v = u32x4_t{0u, 0u, 0u, 0u}; }
@@ -57,6 +58,7 @@ template <> struct SkTraits<uint16_t> {
 };
 template <> struct SkTraits<float> {
     static constexpr int planes = 3;
+    static constexpr int blocks_in_flight = 2;
     struct Piece { f32x4_t a, b; };
     static __device__ __forceinline__ void load(Piece &r, const float *p) {
         r.a = *reinterpret_cast<const f32x4_t *>(p);
@@ -109,15 +111,16 @@ __global__ __launch_bounds__(kThreads) void linear_skinny_kernel(const XT *__res
 
     // K index of (block b, step s, lane group lg, element i) is 128*b + 32*lg + 8*s + i: a lane reads
     // 64 contiguous bytes (bf16) of its batch row per block and one 32-bit tile window.
-    typename T::Piece cur[4], nxt[4];
-    uint32_t cur_lo = 0, cur_hi = 0, nxt_lo = 0, nxt_hi = 0;
-    auto issue = [&](int b, typename T::Piece (&pc)[4], uint32_t &lo, uint32_t &hi) {
+    constexpr int NB = T::blocks_in_flight;
+    typename T::Piece pc[NB][4];
+    uint32_t w_lo[NB], w_hi[NB];
+    auto issue = [&](int b, typename T::Piece (&dst)[4], uint32_t &lo, uint32_t &hi) {
         const int64_t kb = int64_t(b) * kKBlock + 32 * lg;
 #pragma unroll
         for (int s = 0; s < 4; ++s) {
             int64_t k = kb + 8 * s;
-            k = k < P.in - 8 ? k : P.in - 8;   // in % 8 == 0; pieces past the end are zeroed below
-            T::load(pc[s], xrow + k);
+            k = k < P.in - 8 ? k : P.in - 8;   // in % 8 == 0; pieces past the end are zeroed when used
+            T::load(dst[s], xrow + k);
         }
         int64_t pos = off + (kb < P.in ? kb : 0);
         if (pos >= P.p) pos -= P.p;
@@ -125,7 +128,7 @@ __global__ __launch_bounds__(kThreads) void linear_skinny_kernel(const XT *__res
         lo = tile[w];
         hi = tile[(w + 1 < P.n_words) ? (w + 1) : w];
     };
-    auto consume = [&](int b, typename T::Piece (&pc)[4], uint32_t lo, uint32_t hi) {
+    auto consume = [&](int b, typename T::Piece (&src)[4], uint32_t lo, uint32_t hi) {
         const int64_t kb = int64_t(b) * kKBlock + 32 * lg;
         int64_t pos = off + (kb < P.in ? kb : 0);
         if (pos >= P.p) pos -= P.p;
@@ -135,30 +138,29 @@ __global__ __launch_bounds__(kThreads) void linear_skinny_kernel(const XT *__res
         if (left < 32) wbits = (wbits & ((1u << left) - 1u)) | (tile_head << left);
 #pragma unroll
         for (int s = 0; s < 4; ++s) {
-            if (kb + 8 * s >= P.in) T::zero(pc[s]);
+            if (kb + 8 * s >= P.in) T::zero(src[s]);
             Frag bw, a[NP];
             expand_byte(bw, (wbits >> (8 * s)) & 0xffu);
-            T::planes_of(pc[s], a);
+            T::planes_of(src[s], a);
 #pragma unroll
             for (int pl = 0; pl < NP; ++pl)
                 acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a[pl].v, bw.v, acc, 0, 0, 0);
         }
     };
 
-    // blocks wave, wave + 8, ...; the next block's loads are issued before the current one is used
-    int b = wave;
-    if (b < n_blocks) issue(b, cur, cur_lo, cur_hi);
-    while (b < n_blocks) {
-        const int bn = b + kWaves;
-        if (bn < n_blocks) issue(bn, nxt, nxt_lo, nxt_hi);
-        consume(b, cur, cur_lo, cur_hi);
-        if (bn < n_blocks) {
+    // The wave's blocks are wave, wave + 8, ...; NB of them are loaded at once (for in <= 4096 with
+    // bf16 that is all of them: one round trip to memory), then multiplied.
+    for (int b0 = wave; b0 < n_blocks; b0 += kWaves * NB) {
 #pragma unroll
-            for (int s = 0; s < 4; ++s) cur[s] = nxt[s];
-            cur_lo = nxt_lo;
-            cur_hi = nxt_hi;
+        for (int j = 0; j < NB; ++j) {
+            const int b = b0 + j * kWaves;
+            issue(b < n_blocks ? b : b0, pc[j], w_lo[j], w_hi[j]);   // a repeated block is loaded but not used
         }
-        b = bn;
+#pragma unroll
+        for (int j = 0; j < NB; ++j) {
+            const int b = b0 + j * kWaves;
+            if (b < n_blocks) consume(b, pc[j], w_lo[j], w_hi[j]);
+        }
     }
 
     // accumulator layout: lane holds column ln, batch rows 4*lg + i

@@ -270,6 +270,9 @@ CONV_SMALL = [
     (3, 64, 14, 14, 64, 3, 3, (1, 1), (1, 1), 2, 1),     # 32 whole filters per tile, two row blocks per image
     (1, 32, 9, 9, 32, 3, 3, (1, 1), (0, 0), 4, 4),       # no padding
     (2, 32, 12, 10, 32, 3, 3, (2, 1), (1, 1), 2, 2),     # mixed stride
+    (2, 32, 10, 10, 48, 3, 3, (1, 1), (1, 1), 9, 1),     # 5 1/3 filters per tile, one alpha
+    (2, 32, 10, 10, 48, 3, 3, (1, 1), (1, 1), 9, 9),     # same with one alpha per tile (two-alpha channels)
+    (1, 64, 6, 6, 40, 1, 1, (1, 1), (0, 0), 5, 5),       # 1x1, 8 filters per tile
 ]
 
 
