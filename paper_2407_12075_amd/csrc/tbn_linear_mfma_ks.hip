@@ -240,6 +240,10 @@ __device__ __forceinline__ void form_window(const KsParams &P, const uint32_t (&
 // 2*ks + lg of the (inverted) window; register v holds elements 2v and 2v + 1.
 __device__ __forceinline__ void expand_operand(uint32_t win_lo, uint32_t win_hi, uint32_t byte_sel, uint32_t sign_mask,
                                                uint32_t one_bits, Frag &b) {
+#if TBN_KS_EXP & 4
+    b.q = u32x4_t{win_lo, win_hi, win_lo, win_hi};
+    return;
+#endif
     const uint32_t rep = __builtin_amdgcn_perm(win_hi, win_lo, byte_sel);   // the byte, four times
     const u16x2_t r2 = __builtin_bit_cast(u16x2_t, rep);
 #pragma unroll
@@ -435,7 +439,7 @@ __global__ __launch_bounds__(kThreads, 1) void linear_mfma_ks_bf16_kernel(const 
                                                                           const float *__restrict__ alpha, KsParams P) {
     extern __shared__ __attribute__((aligned(1024))) unsigned char lds_raw[];
 #if TBN_KS_EXP & 64
-    long long ts[6];
+    long long ts[8];
 #endif
     TBN_TS(0);
     const int tid = threadIdx.x;
@@ -516,9 +520,8 @@ __global__ __launch_bounds__(kThreads, 1) void linear_mfma_ks_bf16_kernel(const 
         }
         load_window<BK>(P, tile, pos, wreg[slot], wpos[slot]);
     };
-    // Makes stage v readable: its loads must have landed (the caller has waited for them), the part of
-    // it past the end of K is zeroed, its tile windows are formed, then the workgroup meets.
-    auto publish_stage = [&](int slot, int32_t v) {
+    // Zeroes the part of stage v that lies past the end of K (its loads are waited for first).
+    auto zero_tail = [&](int32_t v) {
         const int32_t k0 = (v * kKG + grp) * BK;
         if (k0 + BK > P.in) {   // uniform over the group: the last stages only
             __builtin_amdgcn_s_waitcnt(vmcnt_imm(0));
@@ -527,11 +530,12 @@ __global__ __launch_bounds__(kThreads, 1) void linear_mfma_ks_bf16_kernel(const 
             for (int j = 0; j < kLoads; ++j)
                 if (k0 + a_chunk[j] * 8 >= P.in) *reinterpret_cast<u32x4_t *>(dst + j * 1024) = u32x4_t{0, 0, 0, 0};
         }
-        form_window<BK>(P, wreg[slot], wpos[slot], head, win);
-        // a plain barrier (no fence: the waits that matter are explicit, and a fence would make the
-        // compiler wait for every asynchronous load in flight)
-        asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
-        __builtin_amdgcn_s_barrier();
+    };
+    // The workgroup meets.  A plain barrier, no fence: the waits that matter are explicit, and a fence
+    // would make the compiler wait for every asynchronous load in flight.
+    auto meet = [&](bool lds_writes_pending) {
+        if (lds_writes_pending) asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+        if (!(TBN_KS_EXP & 16)) __builtin_amdgcn_s_barrier();
     };
 
     f32x16_t acc[kTM][kTN];
@@ -542,9 +546,6 @@ __global__ __launch_bounds__(kThreads, 1) void linear_mfma_ks_bf16_kernel(const 
 #pragma unroll
             for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.f;
 
-#if TBN_KS_EXP & (128 | 256)
-    long long sec[4] = {0, 0, 0, 0};
-#endif
     // operand reads: row slot 32*tm + ln, chunk 2*ks + lg at chunk slot (2*ks + lg) ^ ((ln >> 1) & 7)
     uint32_t a_rd[KS];
 #pragma unroll
@@ -561,13 +562,18 @@ __global__ __launch_bounds__(kThreads, 1) void linear_mfma_ks_bf16_kernel(const 
     typedef __attribute__((address_space(3))) unsigned char lds_byte_t;
     const uint32_t lds_grp_addr = static_cast<uint32_t>(reinterpret_cast<uintptr_t>((lds_byte_t *)lds_grp));
     auto read_frags = [&](Frag (&a)[kTM], uint32_t base, int ks) {
+#if TBN_KS_EXP & 8
+        if (ks > 0) { a[0].q = a[1].q = a[2].q = a[3].q = u32x4_t{base, base, base, base}; return; }
+#endif
         const uint32_t addr = base + a_rd[ks];
         lds_read16<0 * 32 * kRowBytes>(a[0].q, addr);
         lds_read16<1 * 32 * kRowBytes>(a[1].q, addr);
         lds_read16<2 * 32 * kRowBytes>(a[2].q, addr);
         lds_read16<3 * 32 * kRowBytes>(a[3].q, addr);
     };
-    auto multiply_stage = [&](int32_t v) {
+    // Multiplies stage v (drain form: every step's operands are requested one step ahead, nothing
+    // is carried over from or into the neighbouring stages).
+    auto multiply_plain = [&](int32_t v) {
         const uint32_t base = lds_grp_addr + static_cast<uint32_t>((v & (kNB - 1)) * kStageBytes);
         Frag a[2][kTM];
         read_frags(a[0], base, 0);
@@ -587,58 +593,54 @@ __global__ __launch_bounds__(kThreads, 1) void linear_mfma_ks_bf16_kernel(const 
         }
     };
 
-    // Steady-state form: multiplies stage v and, spread between its MFMAs, issues the loads of the full
-    // stage vl into ring slot `slot`, so that neither this wave nor the CU's load path sees them as a burst.
-    auto multiply_and_load = [&](int32_t v, int slot, int32_t vl) {
-        const uint32_t base = lds_grp_addr + static_cast<uint32_t>((v & (kNB - 1)) * kStageBytes);
+    // Steady-state round st (ring slot d = st % D).  On entry the operands of its first step are in
+    // pa[0] / pb[0], requested during the round before; stages st + 1 .. st + 3 lie inside K.
+    //   * the round opens with the meeting that makes stage st + 1 readable (its loads were issued two
+    //     rounds ago) and frees the buffer of stage st - 1 for the loads of stage st + 3;
+    //   * those loads are spread between the MFMAs, two per step, so that neither this wave nor the CU's
+    //     load path sees them as a burst;
+    //   * step ks requests the operands of step ks + 1, the last step those of stage st + 1's first
+    //     step; the tile windows of stage st + 1 are formed once step 3's operands exist.
+    Frag pa[2][kTM];
+    Frag pb[2][kTN];
+    auto steady_round = [&](int32_t st, int d) {
+        __builtin_amdgcn_s_waitcnt(vmcnt_imm(kVmPerStage));   // only the loads of stage st + 2 may be in flight
+        meet(false);
+        const uint32_t base = lds_grp_addr + static_cast<uint32_t>((st & (kNB - 1)) * kStageBytes);
+        const uint32_t base_next = lds_grp_addr + static_cast<uint32_t>(((st + 1) & (kNB - 1)) * kStageBytes);
+        const int32_t vl = st + D;
         const int32_t k0 = (vl * kKG + grp) * BK;
         const unsigned char *src = x_blk - kBias + static_cast<uint32_t>(k0) * 2u;   // wave-uniform
-        asm volatile("" : "+s"(src));
+        asm volatile("" : "+s"(src));   // one scalar base, so that the lane offset stays a 32-bit register
         unsigned char *dst = lds_grp + (vl & (kNB - 1)) * kStageBytes + wn * (kStageBytes / 2);
-        Frag a[2][kTM];
-        Frag b[2][kTN];
-        read_frags(a[0], base, 0);
-#pragma unroll
-        for (int tn = 0; tn < kTN; ++tn)
-            expand_operand(win[tn][0], win[tn][WW - 1], byte_sel[0], sign_mask, one_bits, b[0][tn]);
 #pragma unroll
         for (int ks = 0; ks < KS; ++ks) {
-#if TBN_KS_EXP & 256
-            long long q0 = clock64();
-#endif
-            if (ks + 1 < KS) {
-                read_frags(a[(ks + 1) & 1], base, ks + 1);
+            const int nx = (ks + 1) & 1;
+            if (ks + 1 < KS) read_frags(pa[nx], base, ks + 1); else read_frags(pa[nx], base_next, 0);
 #pragma unroll
-                for (int tn = 0; tn < kTN; ++tn)
-                    expand_operand(win[tn][0], win[tn][WW - 1], byte_sel[ks + 1], sign_mask, one_bits, b[(ks + 1) & 1][tn]);
-                lds_wait<kTM>(a[ks & 1]);
-            } else {
-                lds_wait<0>(a[ks & 1]);
-            }
+            for (int tn = 0; tn < kTN; ++tn)
+                expand_operand(win[tn][0], win[tn][WW - 1], byte_sel[(ks + 1) % KS], sign_mask, one_bits, pb[nx][tn]);
+            lds_wait<kTM>(pa[ks & 1]);
 #pragma unroll
             for (int tm = 0; tm < kTM / 2; ++tm)
 #pragma unroll
                 for (int tn = 0; tn < kTN; ++tn)
-                    acc[tm][tn] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[ks & 1][tm].v, b[ks & 1][tn].v, acc[tm][tn], 0, 0, 0);
+                    acc[tm][tn] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(pa[ks & 1][tm].v, pb[ks & 1][tn].v, acc[tm][tn], 0, 0, 0);
             __builtin_amdgcn_sched_barrier(0);
-#if TBN_KS_EXP & 256
-            long long q1 = clock64();
-#endif
+            if (!(TBN_KS_EXP & 1)) {
             if (ks == 0) { stage_load_one<0>(src, a_off, dst); stage_load_one<1>(src, a_off, dst); }
             if (ks == 1) { stage_load_one<2>(src, a_off, dst); stage_load_one<3>(src, a_off, dst); }
             if (ks == 2) { stage_load_one<4>(src, a_off, dst); stage_load_one<5>(src, a_off, dst); }
             if (ks == 3) { stage_load_one<6>(src, a_off, dst); stage_load_one<7>(src, a_off, dst); }
-            if (ks == KS - 1) load_window<BK>(P, tile, pos, wreg[slot], wpos[slot]);
+            if (ks == KS - 1) load_window<BK>(P, tile, pos, wreg[d], wpos[d]);
+            }
+            if (ks == KS - 2) form_window<BK>(P, wreg[(d + 1) % D], wpos[(d + 1) % D], head, win);   // stage st + 1
 #pragma unroll
             for (int tm = kTM / 2; tm < kTM; ++tm)
 #pragma unroll
                 for (int tn = 0; tn < kTN; ++tn)
-                    acc[tm][tn] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[ks & 1][tm].v, b[ks & 1][tn].v, acc[tm][tn], 0, 0, 0);
+                    acc[tm][tn] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(pa[ks & 1][tm].v, pb[ks & 1][tn].v, acc[tm][tn], 0, 0, 0);
             __builtin_amdgcn_sched_barrier(0);
-#if TBN_KS_EXP & 256
-            long long q2 = clock64();
-            if (ks < 3) { sec[0] += q1 - q0; sec[2] += q2 - q1; } else { sec[1] += q1 - q0; sec[3] += q2 - q1; }
-#endif
         }
     };
     static_assert(KS == 4 && kLoads == 8, "two wave-loads per MFMA step");
@@ -650,55 +652,43 @@ __global__ __launch_bounds__(kThreads, 1) void linear_mfma_ks_bf16_kernel(const 
         if (d < n_stages) load_stage_any(d, d);
     TBN_TS(1);
     __builtin_amdgcn_s_waitcnt(vmcnt_imm(0));
-    publish_stage(0, 0);
+    zero_tail(0);
+    form_window<BK>(P, wreg[0], wpos[0], head, win);
+    meet(true);   // stage 0 is readable
     TBN_TS(2);
 
-    // Steady state: every sub-iteration issues the loads of stage st + D (into the buffer that stage
-    // st - 1 has just left), multiplies stage st and publishes stage st + 1, for which the loads of
-    // the D - 1 stages after it may stay in flight.
     int32_t st0 = 0;
+    if (2 * D <= n_full) {   // the steady loop runs: request the first operands
+        read_frags(pa[0], lds_grp_addr, 0);
+#pragma unroll
+        for (int tn = 0; tn < kTN; ++tn)
+            expand_operand(win[tn][0], win[tn][WW - 1], byte_sel[0], sign_mask, one_bits, pb[0][tn]);
+    }
     for (; st0 + 2 * D <= n_full; st0 += D) {
 #pragma unroll
-        for (int d = 0; d < D; ++d) {
-            const int32_t st = st0 + d;
-#if TBN_KS_EXP & 128
-            long long c0 = clock64();
-            long long c1 = clock64();
-            multiply_and_load(st, d, st + D);
-            long long c2 = clock64();
-            __builtin_amdgcn_s_waitcnt(vmcnt_imm((D - 1) * kVmPerStage));
-            long long c3 = clock64();
-            publish_stage((d + 1) % D, st + 1);
-            long long c4 = clock64();
-#if !(TBN_KS_EXP & 256)
-            sec[0] += c1 - c0; sec[1] += c2 - c1; sec[2] += c3 - c2; sec[3] += c4 - c3;
-#endif
-#else
-            multiply_and_load(st, d, st + D);
-            __builtin_amdgcn_s_waitcnt(vmcnt_imm((D - 1) * kVmPerStage));
-            publish_stage((d + 1) % D, st + 1);
-#endif
-        }
+        for (int d = 0; d < D; ++d) steady_round(st0 + d, d);
     }
-    // Drain: st0 is a multiple of D, so slot numbers stay static.
+    TBN_TS(6);
+    // Drain: st0 is a multiple of D, so slot numbers stay static.  Every round opens with the meeting
+    // that makes stage st + 1 readable; `win` holds the windows of stage st on entry.
     for (; st0 < n_stages; st0 += D) {
 #pragma unroll
         for (int d = 0; d < D; ++d) {
             const int32_t st = st0 + d;
             if (st < n_stages) {   // uniform
-                if (st + D < n_stages) load_stage_any(d, st + D);
-                multiply_stage(st);
                 if (st + 1 < n_stages) {
-                    const int32_t later = n_stages - (st + 2);   // stages after st + 1 whose loads are in flight
-                    if (later >= D - 1) __builtin_amdgcn_s_waitcnt(vmcnt_imm((D - 1) * kVmPerStage));
-                    else if (later == 1) __builtin_amdgcn_s_waitcnt(vmcnt_imm(kVmPerStage));
+                    if (st + 2 < n_stages) __builtin_amdgcn_s_waitcnt(vmcnt_imm(kVmPerStage));
                     else __builtin_amdgcn_s_waitcnt(vmcnt_imm(0));
-                    publish_stage((d + 1) % D, st + 1);
+                    zero_tail(st + 1);
+                    meet(true);
                 }
+                if (st + D < n_stages) load_stage_any(d, st + D);
+                multiply_plain(st);
+                if (st + 1 < n_stages) form_window<BK>(P, wreg[(d + 1) % D], wpos[(d + 1) % D], head, win);
             }
         }
     }
-    static_assert(D == 3, "the drain's wait counts are written for three stages in flight");
+    static_assert(D == 3 && kNB == 4, "the wait counts are written for three stages in flight");
 
     TBN_TS(3);
     exchange_partials(acc, lds_raw, wave, lane);
@@ -708,10 +698,7 @@ __global__ __launch_bounds__(kThreads, 1) void linear_mfma_ks_bf16_kernel(const 
     if (tid == 0 && (blockIdx.x == 0 || blockIdx.x == 255)) {
         ts[5] = wall_clock64();
         long long *dbg = reinterpret_cast<long long *>(y) + (blockIdx.x ? 8 : 0);
-        for (int i = 0; i < 6; ++i) dbg[i] = ts[i];
-#if TBN_KS_EXP & 128
-        for (int i = 0; i < 4; ++i) dbg[16 + i] = sec[i];
-#endif
+        for (int i = 0; i < 7; ++i) dbg[i] = ts[i];
     }
 #endif
 }
