@@ -133,10 +133,11 @@ def main():
     achieved = alg_bytes / (kern_avg_ms * 1e-3) / 1e9
     U = big.p // cin
     alg_flop = 2.0 * big.M * cin * U
+    traffic, traffic_src = measured_traffic()
     roofline = {
         "bound": "hbm", "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
-        "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": None,
-        "kernel": "linear_mfma_kernel<bf16> (batch 8192)", "avg_kernel_ms": round(kern_avg_ms, 5),
+        "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": traffic, "traffic_source": traffic_src,
+        "kernel": "linear_mfma_bf16_kernel (batch 8192)", "avg_kernel_ms": round(kern_avg_ms, 5),
         "median_kernel_ms": round(kern_ms[len(kern_ms) // 2], 5),
         "algorithmic_bytes": alg_bytes,
         "algorithmic_tflops": round(alg_flop / (kern_avg_ms * 1e-3) / 1e12, 1),
@@ -149,11 +150,17 @@ def main():
         from oracle import tbn_oracle as orc
         tile_h = tile.cpu().numpy().view(np.uint32)
         alpha_h = alpha.cpu().numpy()
-        # calibrate on 16 rows, then time a sample sized for the requested CPU seconds
-        t = time.perf_counter()
-        orc.linear_forward(x_big_vals[:16], tile_h, alpha_h, cout, k)
-        per_row = max((time.perf_counter() - t) / 16, 1e-6)
-        rows = int(min(big.M, max(64, args.cpu_seconds / per_row)))
+        # Calibrate with two short calls (every call first materialises the dense weight, a fixed cost),
+        # then time a sample sized for the requested CPU seconds.
+        def timed_rows(r):
+            t = time.perf_counter()
+            orc.linear_forward(x_big_vals[:r], tile_h, alpha_h, cout, k)
+            return time.perf_counter() - t
+        timed_rows(8)
+        t_a, t_b = timed_rows(16), timed_rows(80)
+        per_row = max((t_b - t_a) / 64, 1e-6)
+        fixed = max(t_a - 16 * per_row, 0.0)
+        rows = int(min(big.M, max(64, (args.cpu_seconds - fixed) / per_row)))
         t = time.perf_counter()
         orc.linear_forward(x_big_vals[:rows], tile_h, alpha_h, cout, k)
         dt = time.perf_counter() - t
@@ -181,6 +188,26 @@ def main():
     if args.all_configs:
         line["other_configs"] = time_other_configs(torch, tbn, wl)
     print(json.dumps(line))
+
+
+def measured_traffic():
+    """HBM bytes per launch of the batch-8192 forward from the committed rocprofv3 counter summary.
+
+    bench.py cannot collect hardware counters itself; the figure is read from the summary that the
+    documented rocprofv3 --pmc runs of this very command produced (FETCH_SIZE and WRITE_SIZE, each
+    scaled by the same counter on a plain copy of known size).  None when no summary is there.
+    """
+    path = os.path.join(ROOT, "profiles", "linear_mfma_bf16_metric_4096x4096_k8_hbm_traffic.txt")
+    try:
+        vals = {}
+        for ln in open(path):
+            if "=" in ln and not ln.lstrip().startswith("#"):
+                key, v = ln.split("=", 1)
+                vals[key.strip()] = v.strip()
+        return int(float(vals["fetch_bytes_per_launch"]) + float(vals["write_bytes_per_launch"])), \
+            "profiles/" + os.path.basename(path)
+    except (OSError, KeyError, ValueError):
+        return None, None
 
 
 def time_other_configs(torch, tbn, wl, iters=30):

@@ -124,7 +124,6 @@ tbn_status tbn_linear_forward(const void *x, void *y, tbn_dtype dt, int64_t M, i
                  static_cast<hipStream_t>(stream)};
     if (!(flags & TBN_FLAG_FORCE_GENERIC)) {
         if (linear_skinny_supported(a)) return launch_linear_skinny(a);
-        if (linear_mfma_ks_supported(a)) return launch_linear_mfma_ks(a);
         if (linear_mfma_supported(a)) return launch_linear_mfma(a);
         if (linear_rows_supported(a)) return launch_linear_rows(a);
     }

@@ -58,8 +58,6 @@ tbn_status launch_linear_rows(const LinearArgs &a);
 tbn_status launch_linear_rows_fixup(const LinearArgs &a);  // recompute the columns whose row holds a tile end
 bool linear_mfma_supported(const LinearArgs &a);   // matrix-core kernel
 tbn_status launch_linear_mfma(const LinearArgs &a);
-bool linear_mfma_ks_supported(const LinearArgs &a);   // matrix-core kernel, K split inside the workgroup
-tbn_status launch_linear_mfma_ks(const LinearArgs &a);
 
 tbn_status launch_conv_generic(const ConvArgs &a);
 tbn_status launch_conv_generic_tile_ends(const ConvArgs &a);   // only the channels whose filter holds a tile end

@@ -1,121 +1,99 @@
-// Matrix-core kernel for the fully-connected tiled-bit layer at medium and large batch.
+// Matrix-core kernels for the fully-connected tiled-bit layer, K split inside the workgroup.
 //
 // What is computed (Section "Method", Eq. 4-5 and the scaling after Eq. 8; Algorithm 1 gives the
 // same sums with a running index): the (out x in) weight is the tile repeated along the
 // flattened index, so weight row o carries the cyclic tile window that starts at bit
 // (o*in) % p.  That start repeats with period U = p / gcd(in, p) rows, hence only U distinct
-// +-1 rows exist.  The kernel forms Z = X * T_U^T for those U rows once and writes every output
-// column o = u + t*U as alpha(o) * Z[:, u] -- the "compute one tile, replicate the others"
-// observation the paper makes for convolution channels, applied to matrix columns.
+// +-1 rows exist.  The kernels form Z = X * T_U^T for those U rows once and write every output
+// column o = u + t*U as alpha(o) * Z[:, u].
 //
-// gfx950 mapping
-//   * one workgroup (4 waves, 2 x 2) owns a 128 x 128 block of Z; X is staged in LDS as bf16 and
-//     read back as operands of v_mfma_f32_32x32x16_bf16; a ring of stages is kept in flight in
-//     registers between global memory and LDS so that HBM latency is covered even when only one
-//     workgroup fits the problem per CU;
-//   * float32 activations are split exactly into three bf16 terms (8 + 8 + 8 significand bits;
-//     the weights are +-1, so each product is exact and the sums are float32 accumulations);
-//   * the +-1 operand never exists in memory: 32-bit tile windows (shifted to the row's start
-//     bit, continued at the tile start after the tile end) are staged in LDS with even and odd
-//     bits separated, so that the two bits of a packed bf16 pair sit 16 apart and one shift plus
-//     one and-or turns a window into an operand register;
+// gfx950 mapping, chosen from measurements on the chip: one v_mfma_f32_32x32x16_bf16 keeps a SIMD's
+// matrix pipe busy for 32 cycles, and the wave that issued it can slip in about five independent
+// VALU / LDS / memory instructions meanwhile; every instruction beyond that costs issue time.  Turning
+// tile bits into a +-1 bf16 operand costs 9 VALU instructions per operand, so an operand has to feed
+// four MFMAs, i.e. a wave needs a 128-row block.  With only U/64 column strips that would leave most
+// SIMDs idle for a small U, so K is split instead:
+//   * a workgroup (4 waves) owns a 128 x 128 block of Z; wave (g, h) multiplies all 128 rows with
+//     column half h over the stages of K congruent to g mod 2 (128 accumulator registers); the two
+//     partial blocks are added through LDS at the end and every wave writes 64 rows x 64 columns;
+//   * bf16 activations go from global memory straight into LDS (global_load_lds_dwordx4, four stage
+//     buffers per K group, no staging registers, no LDS stores); rows are unpadded and their
+//     16-byte chunks are XOR-swizzled by choosing which chunk each lane fetches, so that the
+//     operand reads are free of bank conflicts;
+//   * float32 activations are loaded into a register ring and split exactly into three bf16 terms
+//     when they are written to LDS (8 + 8 + 8 significand bits; the weights are +-1, so every product
+//     is exact and the sums are float32 accumulations in the matrix pipe);
+//   * the +-1 operand never exists in memory, nor the tile bits in LDS: every lane fetches the
+//     words of its own column's cyclic tile window (they stay in L1 / L2), and per MFMA step
+//     replicates its byte (v_perm), shifts both 16-bit halves so that two neighbouring bits land
+//     on the two sign positions (v_pk_lshlrev_b16), and merges with the pattern of 1.0;
 //   * the epilogue scales by alpha and writes the replicated column blocks straight from the
-//     accumulators; a lane owns adjacent columns so that a half-wave writes a contiguous run.
+//     accumulators; a lane owns two adjacent columns so that a half-wave writes a contiguous run.
 // Rows whose weights straddle a tile end use two different alphas when one alpha per tile is
 // given; those few columns are recomputed afterwards by the row kernel (see tbn_linear_rows.hip).
 #include "tbn_common.h"
 
+#include <type_traits>
+
 namespace tbn {
 
 typedef __bf16 bf16x8_t __attribute__((ext_vector_type(8)));
+typedef __bf16 bf16x2_t __attribute__((ext_vector_type(2)));
 typedef float f32x16_t __attribute__((ext_vector_type(16)));
+typedef float f32x4_t __attribute__((ext_vector_type(4)));
+typedef float f32x2_t __attribute__((ext_vector_type(2)));
+typedef uint32_t u32x4_t __attribute__((ext_vector_type(4)));
+typedef uint16_t u16x2_t __attribute__((ext_vector_type(2)));
 
 namespace {
 
 constexpr int kThreads = 256;
-constexpr int kWavesM = 2, kWavesN = 2;
-constexpr int kTM = 2, kTN = 2;                  // 32x32 MFMA tiles per wave along M and N
-constexpr int kBM = kWavesM * kTM * 32;          // 128
-constexpr int kBN = kWavesN * kTN * 32;          // 128
-constexpr int kBK = 64;                          // K elements per pipeline stage
-constexpr int kKB = kBK / 32;                    // 32-bit tile windows per stage and row
-constexpr int kPieces = kBK / 8;                 // 8-element (16-byte bf16) pieces per row and stage
-constexpr int kRowStride = kBK + 8;              // LDS row stride in bf16 elements (16 B of padding)
-constexpr int kPlaneElems = kBM * kRowStride;
-constexpr int kItems = kBM * kPieces / kThreads; // pieces staged per thread and stage
+constexpr int kKG = 2;                 // K groups per workgroup
+constexpr int kGroupThreads = kThreads / kKG;
+constexpr int kTM = 4, kTN = 2;        // 32 x 32 MFMA tiles per wave along M and N
+constexpr int kBM = kTM * 32;          // 128 rows per workgroup, all of them taken by every wave
+constexpr int kWN = kTN * 32;          // 64 columns per wave
+constexpr int kBN = 2 * kWN;           // 128 columns per workgroup
+constexpr int kTmOut = kTM / 2;        // row blocks a wave writes after the exchange
+constexpr int kExchangeBytes = kThreads * kTmOut * kTN * 16 * 4;   // partial sums handed over at the end
 
 union Frag {
     bf16x8_t v;
-    uint32_t u[4];
-    uint4 q;
+    u32x4_t q;
 };
 
-template <typename XT> struct Traits;
-template <> struct Traits<uint16_t> {
-    static constexpr int planes = 1;   // bf16 activations go to LDS as they are
-    static constexpr int depth = 3;    // stages in flight in registers
-    struct Piece { uint4 v; };
-    static __device__ __forceinline__ void load(Piece &r, const uint16_t *src) {
-        r.v = *reinterpret_cast<const uint4 *>(src);
-    }
-    static __device__ __forceinline__ void zero(Piece &r) { r.v = make_uint4(0, 0, 0, 0); }
-    static __device__ __forceinline__ void store(const Piece &r, uint16_t *dst) {
-        *reinterpret_cast<uint4 *>(dst) = r.v;
-    }
-};
-template <> struct Traits<float> {
-    static constexpr int planes = 3;   // exact split x = t0 + t1 + t2 into bf16 terms
-    static constexpr int depth = 2;
-    struct Piece { float4 a, b; };
-    static __device__ __forceinline__ void load(Piece &r, const float *src) {
-        r.a = *reinterpret_cast<const float4 *>(src);
-        r.b = *reinterpret_cast<const float4 *>(src + 4);
-    }
-    static __device__ __forceinline__ void zero(Piece &r) {
-        r.a = make_float4(0.f, 0.f, 0.f, 0.f);
-        r.b = r.a;
-    }
-    // truncation split: t0 = top 8 significand bits, t1 = next 8, t2 = the rest (at most 8 bits)
-    static __device__ __forceinline__ void split3(float x, uint32_t &t0, uint32_t &t1, uint32_t &t2) {
-        t0 = __float_as_uint(x) & 0xffff0000u;
-        const float r1 = x - __uint_as_float(t0);
-        t1 = __float_as_uint(r1) & 0xffff0000u;
-        const float r2 = r1 - __uint_as_float(t1);
-        t2 = __float_as_uint(r2);
-    }
-    static __device__ __forceinline__ void store(const Piece &r, uint16_t *dst) {
-        const float x[8] = {r.a.x, r.a.y, r.a.z, r.a.w, r.b.x, r.b.y, r.b.z, r.b.w};
-        uint32_t o[3][4];
-#pragma unroll
-        for (int d = 0; d < 4; ++d) {
-            uint32_t e0, e1, e2, f0, f1, f2;
-            split3(x[2 * d], e0, e1, e2);
-            split3(x[2 * d + 1], f0, f1, f2);
-            o[0][d] = (e0 >> 16) | f0;
-            o[1][d] = (e1 >> 16) | f1;
-            o[2][d] = (e2 >> 16) | (f2 & 0xffff0000u);
-        }
-#pragma unroll
-        for (int pl = 0; pl < 3; ++pl)
-            *reinterpret_cast<uint4 *>(dst + pl * kPlaneElems) = make_uint4(o[pl][0], o[pl][1], o[pl][2], o[pl][3]);
-    }
+struct MfmaParams {
+    int64_t M, out, U;
+    int32_t in, p, n_words;
+    int32_t n_alpha;
+    int aligned;      // p % in == 0: alpha index of column o is o / U
+    int vec_store;    // adjacent column pairs can be written with one aligned vector store
+    int tiles_n;      // column blocks of U
+    uint32_t tiles_m;
+    int32_t reps_all; // out / U when U divides out, else 0
 };
 
-// even bits of x to the low half, odd bits to the high half (both in order)
-__device__ __forceinline__ uint32_t unshuffle_bits(uint32_t x) {
-    uint32_t t;
-    t = (x ^ (x >> 1)) & 0x22222222u; x ^= t ^ (t << 1);
-    t = (x ^ (x >> 2)) & 0x0c0c0c0cu; x ^= t ^ (t << 2);
-    t = (x ^ (x >> 4)) & 0x00f000f0u; x ^= t ^ (t << 4);
-    t = (x ^ (x >> 8)) & 0x0000ff00u; x ^= t ^ (t << 8);
-    return x;
+// x mod p for x < 2^53 and p < 2^31: the float64 quotient is off by at most one.
+__device__ __forceinline__ uint32_t mod_u53(uint64_t x, uint32_t p) {
+    const uint64_t q = static_cast<uint64_t>(static_cast<double>(x) / static_cast<double>(p));
+    int64_t r = static_cast<int64_t>(x - q * p);
+    if (r < 0) r += p;
+    if (r >= static_cast<int64_t>(p)) r -= p;
+    return static_cast<uint32_t>(r);
+}
+
+// truncation split: t0 = top 8 significand bits, t1 = next 8, t2 = the rest (at most 8 bits)
+__device__ __forceinline__ void split3(float x, uint32_t &t0, uint32_t &t1, uint32_t &t2) {
+    t0 = __float_as_uint(x) & 0xffff0000u;
+    const float r1 = x - __uint_as_float(t0);
+    t1 = __float_as_uint(r1) & 0xffff0000u;
+    const float r2 = r1 - __uint_as_float(t1);
+    t2 = __float_as_uint(r2);
 }
 
 template <typename OT> struct OutPack;
 template <> struct OutPack<uint16_t> {
     static __device__ __forceinline__ void store2(uint16_t *p, float a, float b) {
-        typedef __bf16 bf16x2_t __attribute__((ext_vector_type(2)));
-        typedef float f32x2_t __attribute__((ext_vector_type(2)));
         const f32x2_t f = {a, b};
         const bf16x2_t h = __builtin_convertvector(f, bf16x2_t);   // round to nearest even in hardware
         *reinterpret_cast<bf16x2_t *>(p) = h;
@@ -123,245 +101,262 @@ template <> struct OutPack<uint16_t> {
 };
 template <> struct OutPack<float> {
     static __device__ __forceinline__ void store2(float *p, float a, float b) {
-        *reinterpret_cast<float2 *>(p) = make_float2(a, b);
+        *reinterpret_cast<f32x2_t *>(p) = f32x2_t{a, b};
     }
 };
 
-struct MfmaParams {
-    int64_t M, in, out, p, n_words, U;
-    int32_t n_alpha;
-    int relu;
-    int aligned;      // p % in == 0: alpha index of column o is o / U
-    int vec_store;    // adjacent column pairs can be written with one aligned vector store
-    int tiles_n;      // column blocks of U
-    int64_t tiles_m;
-};
+// s_waitcnt immediate that waits for the vector-memory counter only (gfx9 encoding: vmcnt in bits
+// 3:0 and 15:14, expcnt 6:4 and lgkmcnt 11:8 left at their maxima).
+constexpr int vmcnt_imm(int n) { return (n & 15) | ((n >> 4) << 14) | (7 << 4) | (15 << 8); }
 
-template <typename XT, bool RELU>
-__global__ __launch_bounds__(kThreads, 2) void linear_mfma_kernel(const XT *__restrict__ x, XT *__restrict__ y,
-                                                               const uint32_t *__restrict__ tile,
-                                                               const float *__restrict__ alpha, MfmaParams P) {
-    using T = Traits<XT>;
-    constexpr int NP = T::planes;
-    constexpr int D = T::depth;
-    extern __shared__ __attribute__((aligned(16))) unsigned char lds_raw[];
-    typedef uint16_t (*LdsA)[NP][kPlaneElems];
-    typedef uint32_t (*LdsBits)[kKB][kBN];
-    LdsA lds_a = reinterpret_cast<LdsA>(lds_raw);
-    LdsBits lds_bits = reinterpret_cast<LdsBits>(lds_raw + sizeof(uint16_t) * 2 * NP * kPlaneElems);
-
-    const int tid = threadIdx.x;
-    const int lane = tid & 63;
-    const int wave = tid >> 6;
-    const int wm = wave / kWavesN, wn = wave % kWavesN;
-    const int ln = lane & 31;   // column (B operand) / row (A operand) inside a 32 x 32 tile
-    const int lg = lane >> 5;   // K half of the operand registers
-
-    // Workgroups that share rows of X are given consecutive slots on one XCD (workgroup ids are
-    // dealt round-robin to the 8 XCDs), so the later column blocks find X in that XCD's L2.
-    int64_t tile_m, tile_n;
-    {
-        const int64_t bid = blockIdx.x;
-        const int64_t xcd = bid & 7, slot = bid >> 3;
-        const int64_t per_xcd_full = (P.tiles_m / 8) * P.tiles_n;   // slots per XCD in the regular part
-        if (slot < per_xcd_full) {
-            tile_n = slot % P.tiles_n;
-            tile_m = (slot / P.tiles_n) * 8 + xcd;
-        } else {  // remaining row blocks: plain order
-            const int64_t rest = bid - per_xcd_full * 8;
-            tile_n = rest % P.tiles_n;
-            tile_m = (P.tiles_m / 8) * 8 + rest / P.tiles_n;
-        }
+// Workgroups that share rows of X are given consecutive slots on one XCD (workgroup ids are dealt
+// round-robin to the 8 XCDs), so the later column blocks find X in that XCD's L2.
+__device__ __forceinline__ void block_coords(const MfmaParams &P, uint32_t &tile_m, uint32_t &tile_n) {
+    const uint32_t bid = blockIdx.x;
+    const uint32_t xcd = bid & 7, slot = bid >> 3;
+    const uint32_t tiles_n = static_cast<uint32_t>(P.tiles_n);
+    const uint32_t per_xcd_full = (P.tiles_m / 8) * tiles_n;   // slots per XCD in the regular part
+    if (slot < per_xcd_full) {
+        const uint32_t q = slot / tiles_n;
+        tile_n = slot - q * tiles_n;
+        tile_m = q * 8 + xcd;
+    } else {  // remaining row blocks: plain order
+        const uint32_t rest = bid - per_xcd_full * 8;
+        const uint32_t q = rest / tiles_n;
+        tile_n = rest - q * tiles_n;
+        tile_m = (P.tiles_m / 8) * 8 + q;
     }
-    const int64_t m0 = tile_m * kBM;
-    const int64_t n0 = tile_n * kBN;
+}
 
-    // ---- staging assignments ---------------------------------------------------------------
-    // activations: item i of a thread = 8 consecutive columns (one 16-byte bf16 piece) of one row;
-    // 8 consecutive threads cover the 64 columns of a row.  Rows past M are clamped to row M-1
-    // (their results are never written).
-    const int a_piece = tid % kPieces;
-    const XT *a_src[kItems];
-    int a_lds[kItems];
-#pragma unroll
-    for (int i = 0; i < kItems; ++i) {
-        const int r = tid / kPieces + i * (kThreads / kPieces);
-        const int64_t m = (m0 + r) < P.M ? (m0 + r) : (P.M - 1);
-        a_src[i] = x + m * P.in;
-        a_lds[i] = r * kRowStride + a_piece * 8;
+// Cyclic bit positions, at the K group's first stage, of the tile windows of a lane's two adjacent columns.
+template <int BK>
+__device__ __forceinline__ void window_start(const MfmaParams &P, int64_t col0, int grp, uint32_t (&pos)[kTN]) {
+    static_assert(kTN == 2, "two adjacent columns per lane");
+    int64_t u0 = col0;
+    u0 = u0 < P.U ? u0 : P.U - 1;   // columns past U repeat the last one; they are never written
+    pos[0] = mod_u53(static_cast<uint64_t>(u0) * static_cast<uint32_t>(P.in) + static_cast<uint32_t>(grp * BK),
+                     static_cast<uint32_t>(P.p));
+    pos[1] = pos[0];
+    if (u0 + 1 < P.U) {   // the next row starts `in` bits further on (in <= p)
+        pos[1] += static_cast<uint32_t>(P.in);
+        if (pos[1] >= static_cast<uint32_t>(P.p)) pos[1] -= static_cast<uint32_t>(P.p);
     }
-    // tile windows: one (column, window) per thread and stage (kBN * kKB == kThreads)
-    static_assert(kBN * kKB == kThreads, "one tile window per thread and stage");
-    const int b_col = tid % kBN, b_kb = tid / kBN;
-    const bool b_ok = (n0 + b_col) < P.U;
-    int64_t b_pos = 0;  // cyclic bit position of this thread's window at k0 = 0
-    if (b_ok) {
-        b_pos = ((n0 + b_col) * P.in) % P.p + b_kb * 32;
-        if (b_pos >= P.p) b_pos -= P.p;
+}
+
+// WW + 1 tile words with one load instruction (dword alignment is all the hardware asks for).
+template <int N> struct WordVec;
+template <> struct WordVec<2> { typedef uint32_t type __attribute__((ext_vector_type(2), aligned(4))); };
+template <> struct WordVec<3> { typedef uint32_t type __attribute__((ext_vector_type(3), aligned(4))); };
+
+// Issues the load of the WW + 1 tile words that hold the BK window bits from pos on, and moves pos to
+// the group's next stage.  Near the tile end the load starts earlier so that it stays inside the tile
+// (n_words >= WW + 1); wpos keeps the window's cyclic position, wofs its bit offset in the loaded words.
+template <int BK>
+__device__ __forceinline__ void load_window(const MfmaParams &P, const uint32_t *__restrict__ tile, uint32_t (&pos)[kTN],
+                                            uint32_t (&wreg)[kTN][BK / 32 + 1], uint32_t (&wpos)[kTN]) {
+    constexpr int NW = BK / 32 + 1;
+#pragma unroll
+    for (int tn = 0; tn < kTN; ++tn) {
+        const uint32_t w = pos[tn] >> 5;
+        const uint32_t last = static_cast<uint32_t>(P.n_words - NW);
+        const uint32_t wb = w < last ? w : last;
+        const typename WordVec<NW>::type v = *reinterpret_cast<const typename WordVec<NW>::type *>(
+            reinterpret_cast<const unsigned char *>(tile) + (wb << 2));
+#pragma unroll
+        for (int j = 0; j < NW; ++j) wreg[tn][j] = v[j];
+        wpos[tn] = pos[tn];
+        pos[tn] += kKG * BK;   // p >= kKG * BK
+        if (pos[tn] >= static_cast<uint32_t>(P.p)) pos[tn] -= static_cast<uint32_t>(P.p);
     }
-    const uint32_t tile_head = tile[0];   // continues a window that runs past the tile end
+}
 
-    typename T::Piece areg[D][kItems];
-    uint32_t breg_lo[D], breg_hi[D];
-
-    // Loads are unconditional (addresses are clamped into the tensors) so that they stay in flight
-    // across stages; what lies past the end of a row is zeroed when the stage is written to LDS.
-    auto load_stage = [&](int slot, int64_t k0) {
-        int64_t c = k0 + a_piece * 8;
-        c = c < P.in - 8 ? c : P.in - 8;   // in % 8 == 0: a piece is entirely inside or outside the row
+// BK window bits from the cyclic position on (bits past the tile end come from its start), inverted:
+// bit 1 is weight +1, i.e. sign bit clear.
+template <int BK>
+__device__ __forceinline__ void form_window(const MfmaParams &P, const uint32_t (&wreg)[kTN][BK / 32 + 1],
+                                            const uint32_t (&wpos)[kTN], const uint32_t (&head)[BK / 32],
+                                            uint32_t (&win)[kTN][BK / 32]) {
+    constexpr int WW = BK / 32;
+    constexpr int NW = WW + 1;
+    bool special = false;   // the load was moved back, or the window runs past the tile end
+    const uint32_t last = static_cast<uint32_t>(P.n_words - NW);
 #pragma unroll
-        for (int i = 0; i < kItems; ++i) T::load(areg[slot][i], a_src[i] + c);
-        int64_t pos = b_pos + k0;
-        if (pos >= P.p) pos -= P.p;
-        const int64_t w = pos >> 5;
-        breg_lo[slot] = tile[w];
-        breg_hi[slot] = tile[(w + 1 < P.n_words) ? (w + 1) : w];
-    };
-    auto store_stage = [&](int slot, int buf, int64_t k0) {
-        if (k0 + a_piece * 8 >= P.in) {
+    for (int tn = 0; tn < kTN; ++tn) {
+        const uint32_t sh = wpos[tn] & 31u;
 #pragma unroll
-            for (int i = 0; i < kItems; ++i) T::zero(areg[slot][i]);
-        }
+        for (int j = 0; j < WW; ++j) win[tn][j] = __funnelshift_r(wreg[tn][j], wreg[tn][j + 1], sh);
+        special = special || ((wpos[tn] >> 5) > last) ||
+                  (static_cast<uint32_t>(P.p) - wpos[tn] < static_cast<uint32_t>(BK));
+    }
+    if (__any(special)) {   // rare
 #pragma unroll
-        for (int i = 0; i < kItems; ++i) T::store(areg[slot][i], &lds_a[buf][0][a_lds[i]]);
-        // 32 tile bits from the window's cyclic position on; bits past the tile end come from its start
-        int64_t pos = b_pos + k0;
-        if (pos >= P.p) pos -= P.p;
-        const uint32_t sh = static_cast<uint32_t>(pos & 31);
-        const uint32_t hi = ((pos >> 5) + 1 < P.n_words) ? breg_hi[slot] : 0u;
-        uint32_t wbits = __funnelshift_r(breg_lo[slot], hi, sh);   // shift 0 returns the low word
-        const int64_t left = P.p - pos;
-        if (left < 32) wbits = (wbits & ((1u << left) - 1u)) | (tile_head << left);
-        lds_bits[buf][b_kb][b_col] = b_ok ? unshuffle_bits(wbits) : 0u;
-    };
-
-    f32x16_t acc[kTM][kTN];
+        for (int tn = 0; tn < kTN; ++tn) {
+            const uint32_t w = wpos[tn] >> 5;
+            if (w > last) {   // the words were loaded from `last` on: skip w - last of them (zeros follow)
+                const uint32_t skip = w - last;   // 1 .. NW - 1
+                const uint32_t sh = wpos[tn] & 31u;
+                uint32_t t[NW + 1];
 #pragma unroll
-    for (int i = 0; i < kTM; ++i)
+                for (int j = 0; j <= NW; ++j) {
+                    uint32_t x = 0;
 #pragma unroll
-        for (int j = 0; j < kTN; ++j)
+                    for (int i = 1; i < NW; ++i)
+                        if (skip == static_cast<uint32_t>(i) && j + i < NW) x = wreg[tn][j + i];
+                    t[j] = x;
+                }
 #pragma unroll
-            for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.f;
-
-    const int a_row_base = (wm * kTM * 32 + ln) * kRowStride;   // + tm*32*kRowStride
-    const int b_col_base = wn * kTN * 32 + ln * kTN;            // + tn  (a lane owns kTN adjacent columns)
-
-    // One MFMA step covers 16 columns; lane group lg supplies columns 16*s + 8*lg .. + 7 of the
-    // 32-column window, i.e. element pairs 8*s + 4*lg + v (v = register).  After unshuffle_bits the
-    // two bits of pair i are bits i and i + 16 of the window.
-    auto multiply_stage = [&](int buf) {
-#pragma unroll
-        for (int kb = 0; kb < kKB; ++kb) {
-            uint32_t nw[kTN];
-#pragma unroll
-            for (int tn = 0; tn < kTN; ++tn) nw[tn] = (~lds_bits[buf][kb][b_col_base + tn]) >> (4 * lg);
-#pragma unroll
-            for (int s = 0; s < 2; ++s) {
-                Frag b[kTN];
-#pragma unroll
-                for (int tn = 0; tn < kTN; ++tn)
-#pragma unroll
-                    for (int v = 0; v < 4; ++v)
-                        b[tn].u[v] = ((nw[tn] << (15 - 8 * s - v)) & 0x80008000u) | 0x3f803f80u;
-#pragma unroll
-                for (int pl = 0; pl < NP; ++pl) {
-                    Frag a[kTM];
-#pragma unroll
-                    for (int tm = 0; tm < kTM; ++tm)
-                        a[tm].q = *reinterpret_cast<const uint4 *>(
-                            &lds_a[buf][pl][a_row_base + tm * 32 * kRowStride + kb * 32 + s * 16 + lg * 8]);
-#pragma unroll
-                    for (int tm = 0; tm < kTM; ++tm)
-#pragma unroll
-                        for (int tn = 0; tn < kTN; ++tn)
-                            acc[tm][tn] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[tm].v, b[tn].v, acc[tm][tn], 0, 0, 0);
+                for (int j = 0; j < WW; ++j) win[tn][j] = __funnelshift_r(t[j], t[j + 1], sh);
+            }
+            const uint32_t left = static_cast<uint32_t>(P.p) - wpos[tn];   // >= 1
+            if (left < static_cast<uint32_t>(BK)) {
+                if (WW == 2) {
+                    const uint64_t raw = (uint64_t(win[tn][WW - 1]) << 32) | win[tn][0];
+                    const uint64_t hd = (uint64_t(head[WW - 1]) << 32) | head[0];
+                    const uint64_t r = (raw & ((uint64_t(1) << left) - 1)) | (hd << left);
+                    win[tn][0] = static_cast<uint32_t>(r);
+                    win[tn][WW - 1] = static_cast<uint32_t>(r >> 32);
+                } else {
+                    win[tn][0] = (win[tn][0] & ((1u << left) - 1u)) | (head[0] << left);
                 }
             }
         }
-    };
-
-    const int64_t n_stages = (P.in + kBK - 1) / kBK;
+    }
 #pragma unroll
-    for (int d = 0; d < D; ++d)
-        if (d < n_stages) load_stage(d, int64_t(d) * kBK);
-    store_stage(0, 0, 0);
+    for (int tn = 0; tn < kTN; ++tn)
+#pragma unroll
+        for (int j = 0; j < WW; ++j) win[tn][j] = ~win[tn][j];
+}
+
+// The +-1 operand of MFMA step ks: lane group lg supplies K elements 16*ks + 8*lg .. + 7, i.e. byte
+// 2*ks + lg of the (inverted) window; register v holds elements 2v and 2v + 1.
+__device__ __forceinline__ void expand_operand(uint32_t win_lo, uint32_t win_hi, uint32_t byte_sel, uint32_t sign_mask,
+                                               uint32_t one_bits, Frag &b) {
+    const uint32_t rep = __builtin_amdgcn_perm(win_hi, win_lo, byte_sel);   // the byte, four times
+    const u16x2_t r2 = __builtin_bit_cast(u16x2_t, rep);
+#pragma unroll
+    for (int v = 0; v < 4; ++v) {
+        const u16x2_t sh = {static_cast<uint16_t>(15 - 2 * v), static_cast<uint16_t>(14 - 2 * v)};
+        const uint32_t s = __builtin_bit_cast(uint32_t, static_cast<u16x2_t>(r2 << sh));
+        b.q[v] = (s & sign_mask) | one_bits;
+    }
+}
+
+// Registers 2h and 2h + 1 of the same operand (so that the work can be spread between MFMAs).
+__device__ __forceinline__ void expand_operand_half(uint32_t win_lo, uint32_t win_hi, uint32_t byte_sel, uint32_t sign_mask,
+                                                    uint32_t one_bits, int h, Frag &b) {
+    const uint32_t rep = __builtin_amdgcn_perm(win_hi, win_lo, byte_sel);
+    const u16x2_t r2 = __builtin_bit_cast(u16x2_t, rep);
+#pragma unroll
+    for (int v = 2 * h; v < 2 * h + 2; ++v) {
+        const u16x2_t sh = {static_cast<uint16_t>(15 - 2 * v), static_cast<uint16_t>(14 - 2 * v)};
+        const uint32_t s = __builtin_bit_cast(uint32_t, static_cast<u16x2_t>(r2 << sh));
+        b.q[v] = (s & sign_mask) | one_bits;
+    }
+}
+
+// Adds the other K group's partial sums: accumulator index tm of group g stands for row block
+// (tm + 2g) % 4, so both groups keep acc[0..1] and hand over acc[2..3] with the same register
+// indices; afterwards acc[0..1] of wave (g, h) hold rows 64g .. 64g + 63 of column half h.
+__device__ __forceinline__ void exchange_partials(f32x16_t (&acc)[kTM][kTN], unsigned char *lds_raw, int wave, int lane) {
+    __syncthreads();   // all waves are done with the staging buffers
+    float *red = reinterpret_cast<float *>(lds_raw);
+    constexpr int kSlotFloats = kTmOut * kTN * 16 * 64;   // per wave
+    float *dst = red + (wave ^ 2) * kSlotFloats + lane * 4;    // the partner's slot
+#pragma unroll
+    for (int tm = 0; tm < kTmOut; ++tm)
+#pragma unroll
+        for (int tn = 0; tn < kTN; ++tn)
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+                const f32x16_t &s = acc[kTmOut + tm][tn];
+                *reinterpret_cast<f32x4_t *>(dst + ((tm * kTN + tn) * 4 + q) * 256) =
+                    f32x4_t{s[4 * q], s[4 * q + 1], s[4 * q + 2], s[4 * q + 3]};
+            }
     __syncthreads();
-
-    // Steady state: every sub-iteration issues the loads of stage st + D, multiplies stage st and
-    // moves stage st + 1 from registers to LDS.  No condition depends on the stage number here, so
-    // the compiler can count exactly how many younger loads may stay in flight at each wait.
-    int64_t st0 = 0;
-    for (; st0 + 2 * D <= n_stages; st0 += D) {
+    const float *src = red + wave * kSlotFloats + lane * 4;
 #pragma unroll
-        for (int d = 0; d < D; ++d) {
-            const int64_t st = st0 + d;
-            const int buf = static_cast<int>(st & 1);
-            load_stage(d, (st + D) * kBK);
-            multiply_stage(buf);
-            store_stage((d + 1) % D, buf ^ 1, (st + 1) * kBK);
-            __syncthreads();
-        }
-    }
-    // Drain: at most 2*D - 1 stages are left; st0 is a multiple of D, so slot numbers stay static.
-    for (; st0 < n_stages; st0 += D) {
+    for (int tm = 0; tm < kTmOut; ++tm)
 #pragma unroll
-        for (int d = 0; d < D; ++d) {
-            const int64_t st = st0 + d;
-            if (st < n_stages) {   // uniform
-                const int buf = static_cast<int>(st & 1);
-                if (st + D < n_stages) load_stage(d, (st + D) * kBK);
-                multiply_stage(buf);
-                if (st + 1 < n_stages) {
-                    store_stage((d + 1) % D, buf ^ 1, (st + 1) * kBK);
-                    __syncthreads();
-                }
+        for (int tn = 0; tn < kTN; ++tn)
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+                const f32x4_t v = *reinterpret_cast<const f32x4_t *>(src + ((tm * kTN + tn) * 4 + q) * 256);
+                acc[tm][tn][4 * q] += v[0];
+                acc[tm][tn][4 * q + 1] += v[1];
+                acc[tm][tn][4 * q + 2] += v[2];
+                acc[tm][tn][4 * q + 3] += v[3];
             }
-        }
-    }
+}
 
-    // ---- epilogue: y[m, u + t*U] = alpha(u + t*U) * Z[m, u] --------------------------------------
-    const int64_t u_base = n0 + b_col_base;   // first of this lane's kTN adjacent unique columns
+// Epilogue: y[m, u + t*U] = alpha(u + t*U) * Z[m, u] from acc[0..1] (rows 64*grp + 32*tm + 8*(e/4) +
+// 4*lg + e%4 of the block, columns b_col, b_col + 1).
+template <typename XT, bool RELU>
+__device__ __forceinline__ void write_output(const f32x16_t (&acc)[kTM][kTN], const MfmaParams &P, XT *__restrict__ y,
+                                             const float *__restrict__ alpha, int64_t m0, int64_t n0, int grp, int lg,
+                                             int b_col) {
     static_assert(kTN == 2, "the epilogue writes column pairs");
-    if (u_base >= P.U) return;
-    const bool pair_ok = (u_base + 1 < P.U);
-    const int64_t m_wave = m0 + wm * kTM * 32 + 4 * lg;
-
-    const int64_t reps = (P.out - u_base + P.U - 1) / P.U;   // replicas of column u_base
-    const bool all_pairs = pair_ok && (u_base + (reps - 1) * P.U + 1 < P.out);
-    if ((P.n_alpha == 1 || P.aligned) && P.vec_store && all_pairs) {
-        // alpha depends on the replica only and every replica is a whole, aligned column pair.
-        // Replicas are taken in chunks whose alphas are fetched up front; inside a chunk the rows
-        // are outermost, so the stores of one row of Y are issued back to back.
-        constexpr int kChunk = 8;
-        for (int64_t t0 = 0; t0 < reps; t0 += kChunk) {
-            float al[kChunk];
+    const int64_t u_base = n0 + b_col;   // first of this lane's two adjacent unique columns
+    if (P.reps_all > 0 && (P.n_alpha == 1 || P.aligned) && P.vec_store) {
+        // Every column has the same number of replicas, alpha depends on the replica only and every
+        // replica is a whole, aligned column pair.  Row and replica addresses are wave-uniform (scalar
+        // registers), the lane adds a fixed 32-bit offset; replicas are taken in chunks whose alphas
+        // are fetched up front, rows outermost inside a chunk, so that the stores of one row of Y are
+        // issued back to back.
+        constexpr int kChunk = 4;
+        const int reps_all = P.reps_all;
+        const uint32_t lane_off =
+            (static_cast<uint32_t>(4 * lg) * static_cast<uint32_t>(P.out) + static_cast<uint32_t>(b_col)) *
+            static_cast<uint32_t>(sizeof(XT));
+        unsigned char *y_blk = reinterpret_cast<unsigned char *>(y + m0 * P.out + n0);
+        const int64_t rows_left = P.M - m0;   // >= 1
+        auto write_all = [&](auto full_c) {
+            constexpr bool FULL = decltype(full_c)::value;
+            for (int t0 = 0; t0 < reps_all; t0 += kChunk) {
+                float al[kChunk];
 #pragma unroll
-            for (int j = 0; j < kChunk; ++j) {
-                const int64_t t = (t0 + j < reps) ? (t0 + j) : (reps - 1);
-                al[j] = alpha[P.n_alpha == 1 ? 0 : t];
-            }
-            const int n_here = static_cast<int>((reps - t0) < kChunk ? (reps - t0) : kChunk);
+                for (int j = 0; j < kChunk; ++j) {
+                    const int t = (t0 + j < reps_all) ? (t0 + j) : (reps_all - 1);
+                    al[j] = alpha[P.n_alpha == 1 ? 0 : t];
+                }
+                const int n_here = (reps_all - t0) < kChunk ? (reps_all - t0) : kChunk;
 #pragma unroll
-            for (int tm = 0; tm < kTM; ++tm) {
+                for (int tm = 0; tm < kTmOut; ++tm) {
 #pragma unroll
-                for (int e = 0; e < 16; ++e) {
-                    const int64_t m = m_wave + tm * 32 + 8 * (e >> 2) + (e & 3);
-                    if (m >= P.M) continue;
-                    XT *dst = y + m * P.out + u_base + t0 * P.U;
-                    const float z0 = acc[tm][0][e], z1 = acc[tm][1][e];
+                    for (int e = 0; e < 16; ++e) {
+                        const int row = grp * kTmOut * 32 + tm * 32 + 8 * (e >> 2) + (e & 3);   // + 4*lg
+                        if (!FULL && row + 4 * lg >= rows_left) continue;
+                        unsigned char *dst =
+                            y_blk + (int64_t(row) * P.out + int64_t(t0) * P.U) * static_cast<int64_t>(sizeof(XT));
+                        const float z0 = acc[tm][0][e], z1 = acc[tm][1][e];
+                        if (n_here == kChunk) {
 #pragma unroll
-                    for (int j = 0; j < kChunk; ++j) {
-                        if (j < n_here) {
-                            float v0 = al[j] * z0, v1 = al[j] * z1;
-                            if (RELU) { v0 = fmaxf(v0, 0.f); v1 = fmaxf(v1, 0.f); }
-                            OutPack<XT>::store2(dst + j * P.U, v0, v1);
+                            for (int j = 0; j < kChunk; ++j) {
+                                float v0 = al[j] * z0, v1 = al[j] * z1;
+                                if (RELU) { v0 = fmaxf(v0, 0.f); v1 = fmaxf(v1, 0.f); }
+                                OutPack<XT>::store2(
+                                    reinterpret_cast<XT *>(dst + int64_t(j) * P.U * sizeof(XT) + lane_off), v0, v1);
+                            }
+                        } else {
+                            for (int j = 0; j < n_here; ++j) {
+                                float v0 = al[j] * z0, v1 = al[j] * z1;
+                                if (RELU) { v0 = fmaxf(v0, 0.f); v1 = fmaxf(v1, 0.f); }
+                                OutPack<XT>::store2(
+                                    reinterpret_cast<XT *>(dst + int64_t(j) * P.U * sizeof(XT) + lane_off), v0, v1);
+                            }
                         }
                     }
                 }
             }
+        };
+        if (u_base < P.U) {   // U is even here, so the lane's second column exists as well
+            if (rows_left >= kBM) write_all(std::true_type{}); else write_all(std::false_type{});
         }
         return;
     }
+    if (u_base >= P.U) return;
+    const bool pair_ok = (u_base + 1 < P.U);
+    const int64_t m_wave = m0 + grp * kTmOut * 32 + 4 * lg;
+    const int64_t reps = (P.out - u_base + P.U - 1) / P.U;   // replicas of column u_base
 
     // general case (odd sizes, or tile ends inside rows so that alpha(o) = alpha[(o*in) / p] differs
     // per lane): replicas outermost
@@ -376,7 +371,7 @@ __global__ __launch_bounds__(kThreads, 2) void linear_mfma_kernel(const XT *__re
             al1 = ok1 ? alpha[(o1 * P.in) / P.p] : 0.f;
         }
 #pragma unroll
-        for (int tm = 0; tm < kTM; ++tm) {
+        for (int tm = 0; tm < kTmOut; ++tm) {
 #pragma unroll
             for (int e = 0; e < 16; ++e) {
                 const int64_t m = m_wave + tm * 32 + 8 * (e >> 2) + (e & 3);
@@ -396,32 +391,569 @@ __global__ __launch_bounds__(kThreads, 2) void linear_mfma_kernel(const XT *__re
     }
 }
 
-template <typename XT> size_t lds_bytes() {
-    return sizeof(uint16_t) * 2 * Traits<XT>::planes * kPlaneElems + sizeof(uint32_t) * 2 * kKB * kBN;
+// =====================================================================================================
+// bf16 activations: global memory -> LDS directly
+// =====================================================================================================
+namespace direct {
+
+constexpr int BK = 64;                         // K elements per stage
+constexpr int KS = BK / 16;                    // MFMA steps per stage
+constexpr int WW = BK / 32;                    // 32-bit window words per stage
+constexpr int kNB = 4;                         // LDS stage buffers per K group
+constexpr int kRowBytes = BK * 2;              // 128, unpadded
+constexpr int kStageBytes = kBM * kRowBytes;   // 16 KiB
+constexpr int kLoads = kStageBytes / (kGroupThreads / 64) / 1024;   // 1 KiB wave-loads per wave and stage: 8
+constexpr int kVmPerStage = kLoads + kTN;                           // vector-memory instructions per stage
+constexpr int kLdsBytes = kKG * kNB * kStageBytes;                   // 128 KiB
+static_assert(kLdsBytes >= kExchangeBytes, "the exchange reuses the stage buffers");
+constexpr int kBias = 3 * 1024;                // keeps the lane offsets non-negative, see below
+
+// Operand reads are written as inline assembly so that the compiler does not see LDS reads next to the
+// asynchronous global -> LDS loads (it would make every read wait for all of those loads).  The
+// waits are explicit; tying the destination registers to the wait keeps the MFMAs behind it.
+template <int OFF>
+__device__ __forceinline__ void lds_read16(u32x4_t &dst, uint32_t addr) {
+    asm volatile("ds_read_b128 %0, %1 offset:%2" : "=v"(dst) : "v"(addr), "n"(OFF));
+}
+template <int N>
+__device__ __forceinline__ void lds_wait(Frag (&a)[kTM]) {   // at most N younger LDS operations pending
+    static_assert(kTM == 4, "four operand fragments");
+    asm volatile("s_waitcnt lgkmcnt(%4)" : "+v"(a[0].q), "+v"(a[1].q), "+v"(a[2].q), "+v"(a[3].q) : "n"(N));
 }
 
-template <typename XT, bool RELU> tbn_status launch_typed(const LinearArgs &a, const MfmaParams &P, dim3 grid) {
-    static bool attr_set = false;   // dynamic LDS above the default limit has to be allowed once
-    const size_t lds = lds_bytes<XT>();
-    if (!attr_set) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(&linear_mfma_kernel<XT, RELU>),
-                                           hipFuncAttributeMaxDynamicSharedMemorySize, static_cast<int>(lds));
-        if (e != hipSuccess) {
-            set_error("tbn_linear_forward: cannot reserve %zu bytes of LDS: %s", lds, hipGetErrorString(e));
-            return TBN_ERR_DEVICE;
-        }
-        attr_set = true;
+template <int N>
+__device__ __forceinline__ void lds_wait2(Frag &a0, Frag &a1) {   // at most N younger LDS operations pending
+    asm volatile("s_waitcnt lgkmcnt(%2)" : "+v"(a0.q), "+v"(a1.q) : "n"(N));
+}
+
+// Wave-load J of a stage (the immediate offset has to be a compile-time constant).
+template <int J>
+__device__ __forceinline__ void stage_load_one(const unsigned char *src, const uint32_t (&a_off)[kLoads], unsigned char *dst) {
+    __builtin_amdgcn_global_load_lds(src + a_off[J], dst + (J >> 2) * 4096, 16, (J & 3) * 1024, 0);
+}
+template <int J>
+__device__ __forceinline__ void stage_load(const unsigned char *src, const uint32_t (&a_off)[kLoads], unsigned char *dst) {
+    stage_load_one<J>(src, a_off, dst);
+    if constexpr (J + 1 < kLoads) stage_load<J + 1>(src, a_off, dst);
+}
+
+template <bool RELU>
+__global__ __launch_bounds__(kThreads, 1) void linear_mfma_bf16_kernel(const uint16_t *__restrict__ x,
+                                                                          uint16_t *__restrict__ y,
+                                                                          const uint32_t *__restrict__ tile,
+                                                                          const float *__restrict__ alpha, MfmaParams P) {
+    extern __shared__ __attribute__((aligned(1024))) unsigned char lds_raw[];
+    const int tid = threadIdx.x;
+    const int lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int grp = wave >> 1;   // K group
+    const int wn = wave & 1;     // column half, also the wave's number inside its group
+    const int ln = lane & 31;    // column (B operand) / row (A operand) inside a 32 x 32 tile
+    const int lg = lane >> 5;    // K half of the operand registers
+    unsigned char *lds_grp = lds_raw + grp * kNB * kStageBytes;
+
+    uint32_t tile_m, tile_n;
+    block_coords(P, tile_m, tile_n);
+    const int64_t m0 = int64_t(tile_m) * kBM;
+    const int64_t n0 = int64_t(tile_n) * kBN;
+
+    // ---- activation loads ---------------------------------------------------------------------------
+    // Wave-load j of a wave fills the 1 KiB of LDS that holds row slots 8q .. 8q + 7 (q = 8*wn + j) of
+    // the stage: lane i writes bytes 16*i .. 16*i + 15 of it, i.e. row slot sr = 8q + i/8, chunk slot
+    // i%8.  Row slot block sr/32 holds row block (sr/32 + 2*grp) % 4 of X (both K groups then keep
+    // accumulators 0..1 at the end), and chunk slot s of row slot sr holds 16-byte chunk
+    // s ^ ((sr >> 1) & 7) of the stage's 128 bytes of that row.  Rows past M are clamped to row M-1
+    // (their results are never written).
+    // The instruction's immediate offset is added to the LDS address and to the global address alike;
+    // loads j = 0..3 and 4..7 share an LDS base and differ in that offset, which the per-lane global
+    // offset takes back out; kBias, subtracted from the scalar base instead, keeps it non-negative.
+    const unsigned char *x_blk = reinterpret_cast<const unsigned char *>(x + m0 * P.in);
+    uint32_t a_off[kLoads];      // bytes from (x_blk - kBias) + 2*k0, without the immediate offset
+    uint32_t a_row[kLoads];      // bytes of the row start from x_blk
+    int a_chunk[kLoads];
+#pragma unroll
+    for (int j = 0; j < kLoads; ++j) {
+        const int sr = 8 * (8 * wn + j) + (lane >> 3);
+        const int r = ((((sr >> 5) + 2 * grp) & 3) << 5) + (sr & 31);
+        const int64_t last = P.M - 1 - m0;
+        const uint32_t rr = static_cast<uint32_t>(r < last ? r : last);
+        a_chunk[j] = (lane & 7) ^ ((sr >> 1) & 7);
+        a_row[j] = rr * static_cast<uint32_t>(P.in) * 2u;
+        a_off[j] = a_row[j] + static_cast<uint32_t>(a_chunk[j]) * 16u + kBias - static_cast<uint32_t>((j & 3) * 1024);
     }
-    hipLaunchKernelGGL((linear_mfma_kernel<XT, RELU>), grid, dim3(kThreads), lds, a.stream, static_cast<const XT *>(a.x),
-                       static_cast<XT *>(a.y), a.tile, a.alpha, P);
+
+    // ---- tile windows of this lane's two columns ------------------------------------------------
+    const int b_col = wn * kWN + ln * kTN;   // + tn: a lane owns kTN adjacent columns of the block
+    uint32_t pos[kTN];
+    window_start<BK>(P, n0 + b_col, grp, pos);
+    uint32_t head[WW];   // start of the tile: continues a window that runs past the tile end
+#pragma unroll
+    for (int j = 0; j < WW; ++j) head[j] = tile[j];
+
+    constexpr int D = kNB - 1;   // stages in flight
+    uint32_t wreg[D][kTN][WW + 1];
+    uint32_t wpos[D][kTN];
+    uint32_t win[kTN][WW];
+
+    // Virtual stage v of group g is stage v*kKG + g.  A group whose stage lies past the end of K
+    // still goes through the motions (the barriers are shared); its activations are zeroed.
+    auto load_stage_full = [&](int slot, int32_t v) {   // the stage lies entirely inside K
+        const int32_t k0 = (v * kKG + grp) * BK;
+        const unsigned char *src = x_blk - kBias + static_cast<uint32_t>(k0) * 2u;   // wave-uniform
+        asm volatile("" : "+s"(src));   // one scalar base, so that the lane offset stays a 32-bit register
+        unsigned char *dst = lds_grp + (v & (kNB - 1)) * kStageBytes + wn * (kStageBytes / 2);
+        stage_load<0>(src, a_off, dst);
+        load_window<BK>(P, tile, pos, wreg[slot], wpos[slot]);
+    };
+    auto load_stage_any = [&](int slot, int32_t v) {
+        const int32_t k0 = (v * kKG + grp) * BK;
+        if (k0 + BK <= P.in) {
+            load_stage_full(slot, v);
+            return;
+        }
+        // chunks past the end of the row are fetched from a clamped address and zeroed before use
+        unsigned char *dst = lds_grp + (v & (kNB - 1)) * kStageBytes + wn * (kStageBytes / 2);
+#pragma unroll
+        for (int j = 0; j < kLoads; ++j) {
+            int32_t c = k0 + a_chunk[j] * 8;
+            c = c < P.in - 8 ? c : P.in - 8;
+            __builtin_amdgcn_global_load_lds(x_blk + (a_row[j] + static_cast<uint32_t>(c) * 2u), dst + j * 1024, 16, 0, 0);
+        }
+        load_window<BK>(P, tile, pos, wreg[slot], wpos[slot]);
+    };
+    // Zeroes the part of stage v that lies past the end of K (its loads are waited for first).
+    auto zero_tail = [&](int32_t v) {
+        const int32_t k0 = (v * kKG + grp) * BK;
+        if (k0 + BK > P.in) {   // uniform over the group: the last stages only
+            __builtin_amdgcn_s_waitcnt(vmcnt_imm(0));
+            unsigned char *dst = lds_grp + (v & (kNB - 1)) * kStageBytes + wn * (kStageBytes / 2) + lane * 16;
+#pragma unroll
+            for (int j = 0; j < kLoads; ++j)
+                if (k0 + a_chunk[j] * 8 >= P.in) *reinterpret_cast<u32x4_t *>(dst + j * 1024) = u32x4_t{0, 0, 0, 0};
+        }
+    };
+    // The workgroup meets.  A plain barrier, no fence: the waits that matter are explicit, and a fence
+    // would make the compiler wait for every asynchronous load in flight.
+    auto meet = [&](bool lds_writes_pending) {
+        if (lds_writes_pending) asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+        __builtin_amdgcn_s_barrier();
+    };
+
+    f32x16_t acc[kTM][kTN];
+#pragma unroll
+    for (int i = 0; i < kTM; ++i)
+#pragma unroll
+        for (int j = 0; j < kTN; ++j)
+#pragma unroll
+            for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.f;
+
+    // operand reads: row slot 32*tm + ln, chunk 2*ks + lg at chunk slot (2*ks + lg) ^ ((ln >> 1) & 7)
+    uint32_t a_rd[KS];
+#pragma unroll
+    for (int ks = 0; ks < KS; ++ks) a_rd[ks] = static_cast<uint32_t>(ln * kRowBytes + (((2 * ks + lg) ^ ((ln >> 1) & 7)) << 4));
+
+    // Operand constants kept in registers (two literals do not fit one instruction).
+    uint32_t sign_mask = 0x80008000u, one_bits = 0x3f803f80u;
+    asm volatile("" : "+v"(sign_mask), "+v"(one_bits));
+    uint32_t byte_sel[KS];   // v_perm selector replicating byte 2*ks + lg of the window
+#pragma unroll
+    for (int ks = 0; ks < KS; ++ks) byte_sel[ks] = 0x01010101u * static_cast<uint32_t>(2 * ks + lg);
+
+    // The fragments of step ks + 1 are requested before the MFMAs of step ks are issued.
+    typedef __attribute__((address_space(3))) unsigned char lds_byte_t;
+    const uint32_t lds_grp_addr = static_cast<uint32_t>(reinterpret_cast<uintptr_t>((lds_byte_t *)lds_grp));
+    auto read_frags = [&](Frag (&a)[kTM], uint32_t base, int ks) {
+        const uint32_t addr = base + a_rd[ks];
+        lds_read16<0 * 32 * kRowBytes>(a[0].q, addr);
+        lds_read16<1 * 32 * kRowBytes>(a[1].q, addr);
+        lds_read16<2 * 32 * kRowBytes>(a[2].q, addr);
+        lds_read16<3 * 32 * kRowBytes>(a[3].q, addr);
+    };
+    // Multiplies stage v (drain form: every step's operands are requested one step ahead, nothing
+    // is carried over from or into the neighbouring stages).
+    auto multiply_plain = [&](int32_t v) {
+        const uint32_t base = lds_grp_addr + static_cast<uint32_t>((v & (kNB - 1)) * kStageBytes);
+        Frag a[2][kTM];
+        read_frags(a[0], base, 0);
+#pragma unroll
+        for (int ks = 0; ks < KS; ++ks) {
+            if (ks + 1 < KS) read_frags(a[(ks + 1) & 1], base, ks + 1);
+            Frag b[kTN];
+#pragma unroll
+            for (int tn = 0; tn < kTN; ++tn)
+                expand_operand(win[tn][0], win[tn][WW - 1], byte_sel[ks], sign_mask, one_bits, b[tn]);
+            if (ks + 1 < KS) lds_wait<kTM>(a[ks & 1]); else lds_wait<0>(a[ks & 1]);
+#pragma unroll
+            for (int tm = 0; tm < kTM; ++tm)
+#pragma unroll
+                for (int tn = 0; tn < kTN; ++tn)
+                    acc[tm][tn] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[ks & 1][tm].v, b[tn].v, acc[tm][tn], 0, 0, 0);
+        }
+    };
+
+    // Steady-state round st (ring slot d = st % D).  On entry the operands of its first step are in
+    // pa[0] / pb[0], requested during the round before; stages st + 1 .. st + 3 lie inside K.
+    //   * the round opens with the meeting that makes stage st + 1 readable (its loads were issued two
+    //     rounds ago) and frees the buffer of stage st - 1 for the loads of stage st + 3;
+    //   * those loads are spread between the MFMAs, two per step, so that neither this wave nor the CU's
+    //     load path sees them as a burst;
+    //   * step ks requests the operands of step ks + 1, the last step those of stage st + 1's first
+    //     step; the tile windows of stage st + 1 are formed once step 3's operands exist.
+    Frag pa[2][kTM];
+    Frag pb[2][kTN];
+    auto steady_round = [&](int32_t st, int d) {
+        __builtin_amdgcn_s_waitcnt(vmcnt_imm(kVmPerStage));   // only the loads of stage st + 2 may be in flight
+        meet(false);
+        const uint32_t base = lds_grp_addr + static_cast<uint32_t>((st & (kNB - 1)) * kStageBytes);
+        const uint32_t base_next = lds_grp_addr + static_cast<uint32_t>(((st + 1) & (kNB - 1)) * kStageBytes);
+        const int32_t vl = st + D;
+        const int32_t k0 = (vl * kKG + grp) * BK;
+        const unsigned char *src = x_blk - kBias + static_cast<uint32_t>(k0) * 2u;   // wave-uniform
+        asm volatile("" : "+s"(src));   // one scalar base, so that the lane offset stays a 32-bit register
+        unsigned char *dst = lds_grp + (vl & (kNB - 1)) * kStageBytes + wn * (kStageBytes / 2);
+#pragma unroll
+        for (int ks = 0; ks < KS; ++ks) {
+            // One LDS read or wave-load after an MFMA: each of them holds the wave's instruction issue
+            // for about as long as an MFMA runs, so they must not come in runs.  The fences keep the
+            // compiler from regrouping them.
+            const int cur = ks & 1, nx = cur ^ 1;
+            const uint32_t rbase = (ks + 1 < KS ? base : base_next) + a_rd[(ks + 1) % KS];
+            const uint32_t sel = byte_sel[(ks + 1) % KS];
+            auto mfma = [&](int tm, int tn) {
+                acc[tm][tn] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(pa[cur][tm].v, pb[cur][tn].v, acc[tm][tn], 0, 0, 0);
+            };
+            lds_wait2<2>(pa[cur][0], pa[cur][1]);   // of the four reads of the step before, the first two are back
+            mfma(0, 0);
+            lds_read16<0 * 32 * kRowBytes>(pa[nx][0].q, rbase);
+            expand_operand_half(win[0][0], win[0][WW - 1], sel, sign_mask, one_bits, 0, pb[nx][0]);
+            __builtin_amdgcn_sched_barrier(0);
+            mfma(0, 1);
+            lds_read16<1 * 32 * kRowBytes>(pa[nx][1].q, rbase);
+            expand_operand_half(win[0][0], win[0][WW - 1], sel, sign_mask, one_bits, 1, pb[nx][0]);
+            __builtin_amdgcn_sched_barrier(0);
+            mfma(1, 0);
+            lds_read16<2 * 32 * kRowBytes>(pa[nx][2].q, rbase);
+            expand_operand_half(win[1][0], win[1][WW - 1], sel, sign_mask, one_bits, 0, pb[nx][1]);
+            __builtin_amdgcn_sched_barrier(0);
+            mfma(1, 1);
+            lds_read16<3 * 32 * kRowBytes>(pa[nx][3].q, rbase);
+            expand_operand_half(win[1][0], win[1][WW - 1], sel, sign_mask, one_bits, 1, pb[nx][1]);
+            __builtin_amdgcn_sched_barrier(0);
+            lds_wait2<4>(pa[cur][2], pa[cur][3]);   // the other two (the four new reads may be pending)
+            mfma(2, 0);
+            if (ks == 0) stage_load_one<0>(src, a_off, dst);
+            if (ks == 1) stage_load_one<2>(src, a_off, dst);
+            if (ks == 2) stage_load_one<4>(src, a_off, dst);
+            if (ks == 3) stage_load_one<6>(src, a_off, dst);
+            __builtin_amdgcn_sched_barrier(0);
+            mfma(2, 1);
+            __builtin_amdgcn_sched_barrier(0);
+            mfma(3, 0);
+            if (ks == 0) stage_load_one<1>(src, a_off, dst);
+            if (ks == 1) stage_load_one<3>(src, a_off, dst);
+            if (ks == 2) stage_load_one<5>(src, a_off, dst);
+            if (ks == 3) stage_load_one<7>(src, a_off, dst);
+            __builtin_amdgcn_sched_barrier(0);
+            mfma(3, 1);
+            if (ks == KS - 1) load_window<BK>(P, tile, pos, wreg[d], wpos[d]);
+            if (ks == KS - 2) form_window<BK>(P, wreg[(d + 1) % D], wpos[(d + 1) % D], head, win);   // stage st + 1
+            __builtin_amdgcn_sched_barrier(0);
+        }
+    };
+    static_assert(KS == 4 && kLoads == 8, "two wave-loads per MFMA step");
+
+    const int32_t n_stages = ((P.in + BK - 1) / BK + kKG - 1) / kKG;   // virtual stages per group
+    const int32_t n_full = P.in / (kKG * BK);                           // of which both groups' lie inside K
+#pragma unroll
+    for (int d = 0; d < D; ++d)
+        if (d < n_stages) load_stage_any(d, d);
+    __builtin_amdgcn_s_waitcnt(vmcnt_imm(0));
+    zero_tail(0);
+    form_window<BK>(P, wreg[0], wpos[0], head, win);
+    meet(true);   // stage 0 is readable
+
+    int32_t st0 = 0;
+    if (2 * D <= n_full) {   // the steady loop runs: request the first operands
+        read_frags(pa[0], lds_grp_addr, 0);
+#pragma unroll
+        for (int tn = 0; tn < kTN; ++tn)
+            expand_operand(win[tn][0], win[tn][WW - 1], byte_sel[0], sign_mask, one_bits, pb[0][tn]);
+    }
+    for (; st0 + 2 * D <= n_full; st0 += D) {
+#pragma unroll
+        for (int d = 0; d < D; ++d) steady_round(st0 + d, d);
+    }
+    // Drain: st0 is a multiple of D, so slot numbers stay static.  Every round opens with the meeting
+    // that makes stage st + 1 readable; `win` holds the windows of stage st on entry.
+    for (; st0 < n_stages; st0 += D) {
+#pragma unroll
+        for (int d = 0; d < D; ++d) {
+            const int32_t st = st0 + d;
+            if (st < n_stages) {   // uniform
+                if (st + 1 < n_stages) {
+                    if (st + 2 < n_stages) __builtin_amdgcn_s_waitcnt(vmcnt_imm(kVmPerStage));
+                    else __builtin_amdgcn_s_waitcnt(vmcnt_imm(0));
+                    zero_tail(st + 1);
+                    meet(true);
+                }
+                if (st + D < n_stages) load_stage_any(d, st + D);
+                multiply_plain(st);
+                if (st + 1 < n_stages) form_window<BK>(P, wreg[(d + 1) % D], wpos[(d + 1) % D], head, win);
+            }
+        }
+    }
+    static_assert(D == 3 && kNB == 4, "the wait counts are written for three stages in flight");
+
+    exchange_partials(acc, lds_raw, wave, lane);
+    write_output<uint16_t, RELU>(acc, P, y, alpha, m0, n0, grp, lg, b_col);
+}
+
+}  // namespace direct
+
+// =====================================================================================================
+// float32 activations: register ring, split into three bf16 planes on the way to LDS
+// =====================================================================================================
+namespace ring {
+
+constexpr int NP = 3;                          // exact split x = t0 + t1 + t2 into bf16 terms
+constexpr int BK = 32;                         // K elements per stage
+constexpr int KS = BK / 16;
+constexpr int WW = BK / 32;
+constexpr int D = 3;                           // stages in flight in registers
+constexpr int kPieces = BK / 8;                // 8-element pieces per row and stage
+constexpr int kRowsPerPass = kGroupThreads / kPieces;
+constexpr int kRowItems = kBM / kRowsPerPass;  // rows staged per thread and stage
+constexpr int RS = (BK + 8) * 2;               // LDS row stride in bytes (16 B of padding)
+constexpr int kPlaneBytes = kBM * RS;
+constexpr int kBufferBytes = NP * kPlaneBytes;
+constexpr int kLdsBytes = 2 * kKG * kBufferBytes > kExchangeBytes ? 2 * kKG * kBufferBytes : kExchangeBytes;
+
+template <bool RELU>
+__global__ __launch_bounds__(kThreads, 1) void linear_mfma_f32_kernel(const float *__restrict__ x,
+                                                                         float *__restrict__ y,
+                                                                         const uint32_t *__restrict__ tile,
+                                                                         const float *__restrict__ alpha, MfmaParams P) {
+    extern __shared__ __attribute__((aligned(16))) unsigned char lds_raw[];
+    const int tid = threadIdx.x;
+    const int lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int grp = wave >> 1;   // K group
+    const int wn = wave & 1;     // column half
+    const int gt = tid & (kGroupThreads - 1);
+    const int ln = lane & 31;    // column (B operand) / row (A operand) inside a 32 x 32 tile
+    const int lg = lane >> 5;    // K half of the operand registers
+    unsigned char *lds_grp = lds_raw + grp * 2 * kBufferBytes;
+
+    uint32_t tile_m, tile_n;
+    block_coords(P, tile_m, tile_n);
+    const int64_t m0 = int64_t(tile_m) * kBM;
+    const int64_t n0 = int64_t(tile_n) * kBN;
+
+    // ---- staging assignments ---------------------------------------------------------------
+    // A thread stages pieces of 8 consecutive K elements of kRowItems rows; the pieces of a row lie
+    // on adjacent threads.  Rows past M are clamped to row M-1 (their results are never written).
+    // Offsets are relative to the block's first row and fit 32 bits (the launcher checks).
+    const unsigned char *x_blk = reinterpret_cast<const unsigned char *>(x + m0 * P.in);
+    const int a_piece = gt % kPieces;
+    uint32_t a_row_off[kRowItems];   // bytes
+    int a_lds[kRowItems];            // bytes inside a plane
+#pragma unroll
+    for (int i = 0; i < kRowItems; ++i) {
+        const int r = gt / kPieces + i * kRowsPerPass;
+        const int64_t last = P.M - 1 - m0;
+        const uint32_t rr = static_cast<uint32_t>(r < last ? r : last);
+        a_row_off[i] = rr * static_cast<uint32_t>(P.in) * 4u;
+        a_lds[i] = r * RS + a_piece * 16;
+    }
+
+    const int b_col = wn * kWN + ln * kTN;   // + tn: a lane owns kTN adjacent columns of the block
+    uint32_t pos[kTN];
+    window_start<BK>(P, n0 + b_col, grp, pos);
+    uint32_t head[WW];
+#pragma unroll
+    for (int j = 0; j < WW; ++j) head[j] = tile[j];
+
+    u32x4_t areg[D][kRowItems][2];
+    uint32_t wreg[D][kTN][WW + 1];
+    uint32_t wpos[D][kTN];
+    uint32_t win[kTN][WW];
+
+    // Loads are unconditional (addresses are clamped into the tensors) so that they stay in flight
+    // across stages; what lies past the end of a row is zeroed when the stage is written to LDS.
+    // Virtual stage v of group g is stage v*kKG + g.  A group whose stage lies past the end of K
+    // still goes through the motions (the barriers are shared); its activations are zero.
+    auto load_stage = [&](int slot, int32_t v) {
+        const int32_t k0 = (v * kKG + grp) * BK;
+        int32_t c = k0 + a_piece * 8;
+        c = c < P.in - 8 ? c : P.in - 8;   // in % 8 == 0: a piece is entirely inside or outside the row
+        const uint32_t cb = static_cast<uint32_t>(c) * 4u;
+#pragma unroll
+        for (int i = 0; i < kRowItems; ++i)
+#pragma unroll
+            for (int h = 0; h < 2; ++h)
+                areg[slot][i][h] = *reinterpret_cast<const u32x4_t *>(x_blk + (a_row_off[i] + cb + 16u * h));
+        load_window<BK>(P, tile, pos, wreg[slot], wpos[slot]);
+    };
+    auto store_stage = [&](int slot, int buf, int32_t v) {
+        const int32_t k0 = (v * kKG + grp) * BK;
+        unsigned char *dst = lds_grp + buf * kBufferBytes;
+#pragma unroll
+        for (int i = 0; i < kRowItems; ++i) {
+            uint32_t o[3][4];
+#pragma unroll
+            for (int d = 0; d < 4; ++d) {
+                const u32x4_t &src = areg[slot][i][d >> 1];
+                uint32_t e0, e1, e2, f0, f1, f2;
+                split3(__uint_as_float(src[(d & 1) * 2]), e0, e1, e2);
+                split3(__uint_as_float(src[(d & 1) * 2 + 1]), f0, f1, f2);
+                o[0][d] = (e0 >> 16) | f0;
+                o[1][d] = (e1 >> 16) | f1;
+                o[2][d] = (e2 >> 16) | (f2 & 0xffff0000u);
+            }
+#pragma unroll
+            for (int pl = 0; pl < 3; ++pl)
+                *reinterpret_cast<u32x4_t *>(dst + pl * kPlaneBytes + a_lds[i]) =
+                    u32x4_t{o[pl][0], o[pl][1], o[pl][2], o[pl][3]};
+        }
+        if (k0 + BK > P.in) {   // uniform over the group: the last stages only
+            if (k0 + a_piece * 8 >= P.in) {   // overwrite what was loaded from the clamped address
+#pragma unroll
+                for (int i = 0; i < kRowItems; ++i)
+#pragma unroll
+                    for (int pl = 0; pl < NP; ++pl)
+                        *reinterpret_cast<u32x4_t *>(dst + pl * kPlaneBytes + a_lds[i]) = u32x4_t{0, 0, 0, 0};
+            }
+        }
+        form_window<BK>(P, wreg[slot], wpos[slot], head, win);
+    };
+
+    f32x16_t acc[kTM][kTN];
+#pragma unroll
+    for (int i = 0; i < kTM; ++i)
+#pragma unroll
+        for (int j = 0; j < kTN; ++j)
+#pragma unroll
+            for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.f;
+
+    // Accumulator index tm of group g works on row block (tm + 2g) % 4 (see exchange_partials).
+    int a_blk[kTM];
+#pragma unroll
+    for (int tm = 0; tm < kTM; ++tm) a_blk[tm] = (((tm + 2 * grp) & (kTM - 1)) * 32 + ln) * RS + lg * 16;
+
+    uint32_t sign_mask = 0x80008000u, one_bits = 0x3f803f80u;
+    asm volatile("" : "+v"(sign_mask), "+v"(one_bits));
+    uint32_t byte_sel[KS];
+#pragma unroll
+    for (int ks = 0; ks < KS; ++ks) byte_sel[ks] = 0x01010101u * static_cast<uint32_t>(2 * ks + lg);
+
+    auto multiply_stage = [&](int buf) {
+        const unsigned char *src = lds_grp + buf * kBufferBytes;
+#pragma unroll
+        for (int ks = 0; ks < KS; ++ks) {
+            Frag b[kTN];
+#pragma unroll
+            for (int tn = 0; tn < kTN; ++tn)
+                expand_operand(win[tn][0], win[tn][WW - 1], byte_sel[ks], sign_mask, one_bits, b[tn]);
+#pragma unroll
+            for (int pl = 0; pl < NP; ++pl) {
+                Frag a[kTM];
+#pragma unroll
+                for (int tm = 0; tm < kTM; ++tm)
+                    a[tm].q = *reinterpret_cast<const u32x4_t *>(src + pl * kPlaneBytes + a_blk[tm] + ks * 32);
+#pragma unroll
+                for (int tm = 0; tm < kTM; ++tm)
+#pragma unroll
+                    for (int tn = 0; tn < kTN; ++tn)
+                        acc[tm][tn] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[tm].v, b[tn].v, acc[tm][tn], 0, 0, 0);
+            }
+        }
+    };
+
+    const int32_t n_stages = ((P.in + BK - 1) / BK + kKG - 1) / kKG;   // virtual stages per group
+#pragma unroll
+    for (int d = 0; d < D; ++d)
+        if (d < n_stages) load_stage(d, d);
+    store_stage(0, 0, 0);
+    __syncthreads();
+
+    // Steady state: every sub-iteration issues the loads of stage st + D, multiplies stage st and
+    // moves stage st + 1 from registers to LDS.  No condition depends on the stage number here, so
+    // the compiler can count exactly how many younger loads may stay in flight at each wait.
+    int32_t st0 = 0;
+    for (; st0 + 2 * D <= n_stages; st0 += D) {
+#pragma unroll
+        for (int d = 0; d < D; ++d) {
+            const int32_t st = st0 + d;
+            const int buf = st & 1;
+            load_stage(d, st + D);
+            multiply_stage(buf);
+            store_stage((d + 1) % D, buf ^ 1, st + 1);
+            __syncthreads();
+        }
+    }
+    // Drain: at most 2*D - 1 stages are left; st0 is a multiple of D, so slot numbers stay static.
+    for (; st0 < n_stages; st0 += D) {
+#pragma unroll
+        for (int d = 0; d < D; ++d) {
+            const int32_t st = st0 + d;
+            if (st < n_stages) {   // uniform
+                const int buf = st & 1;
+                if (st + D < n_stages) load_stage(d, st + D);
+                multiply_stage(buf);
+                if (st + 1 < n_stages) {
+                    store_stage((d + 1) % D, buf ^ 1, st + 1);
+                    __syncthreads();
+                }
+            }
+        }
+    }
+
+    exchange_partials(acc, lds_raw, wave, lane);
+    write_output<float, RELU>(acc, P, y, alpha, m0, n0, grp, lg, b_col);
+}
+
+}  // namespace ring
+
+template <typename K>
+tbn_status set_lds_limit(K kernel, int lds, bool &done) {
+    if (done) return TBN_OK;   // dynamic LDS above the default limit has to be allowed once
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kernel), hipFuncAttributeMaxDynamicSharedMemorySize, lds);
+    if (e != hipSuccess) {
+        set_error("tbn_linear_forward: cannot reserve %d bytes of LDS: %s", lds, hipGetErrorString(e));
+        return TBN_ERR_DEVICE;
+    }
+    done = true;
+    return TBN_OK;
+}
+
+template <bool RELU>
+tbn_status launch_bf16(const LinearArgs &a, const MfmaParams &P, dim3 grid) {
+    static bool attr_set = false;
+    tbn_status st = set_lds_limit(&direct::linear_mfma_bf16_kernel<RELU>, direct::kLdsBytes, attr_set);
+    if (st != TBN_OK) return st;
+    hipLaunchKernelGGL((direct::linear_mfma_bf16_kernel<RELU>), grid, dim3(kThreads), direct::kLdsBytes, a.stream,
+                       static_cast<const uint16_t *>(a.x), static_cast<uint16_t *>(a.y), a.tile, a.alpha, P);
+    return check_launch("tbn_linear_forward (matrix-core kernel)");
+}
+
+template <bool RELU>
+tbn_status launch_f32(const LinearArgs &a, const MfmaParams &P, dim3 grid) {
+    static bool attr_set = false;
+    tbn_status st = set_lds_limit(&ring::linear_mfma_f32_kernel<RELU>, ring::kLdsBytes, attr_set);
+    if (st != TBN_OK) return st;
+    hipLaunchKernelGGL((ring::linear_mfma_f32_kernel<RELU>), grid, dim3(kThreads), ring::kLdsBytes, a.stream,
+                       static_cast<const float *>(a.x), static_cast<float *>(a.y), a.tile, a.alpha, P);
     return check_launch("tbn_linear_forward (matrix-core kernel)");
 }
 
 }  // namespace
 
 bool linear_mfma_supported(const LinearArgs &a) {
-    if (a.p < a.in || a.p < 64) return false;   // at most one tile end per row, windows never wrap twice
-    if (a.in % 8 != 0) return false;            // 16-byte (bf16) / 32-byte (f32) activation pieces
+    if (a.p < a.in || a.p < 128) return false;    // at most one tile end per row and per stage window
+    if (a.p >= (int64_t(1) << 31) - 256) return false;   // window positions are kept in 32 bits
+    if (a.in % 8 != 0) return false;              // 16-byte (bf16) / 32-byte (f32) activation pieces
+    if (a.in > (1 << 21) || a.out > (1 << 22)) return false;   // byte offsets inside a 128-row block fit 32 bits
+    if (a.M > (int64_t(1) << 36)) return false;   // row blocks are counted in 32 bits
     if (reinterpret_cast<uintptr_t>(a.x) & 15u) return false;
     if (a.M < 16) return false;
     return true;
@@ -429,27 +961,30 @@ bool linear_mfma_supported(const LinearArgs &a) {
 
 tbn_status launch_linear_mfma(const LinearArgs &a) {
     MfmaParams P;
-    P.M = a.M; P.in = a.in; P.out = a.out; P.p = a.p;
-    P.n_words = (a.p + 31) / 32;
+    P.M = a.M; P.out = a.out;
+    P.in = static_cast<int32_t>(a.in);
+    P.p = static_cast<int32_t>(a.p);
+    P.n_words = static_cast<int32_t>((a.p + 31) / 32);
     P.U = unique_rows(a.out, a.in, a.p);
     P.n_alpha = a.n_alpha;
-    P.relu = (a.flags & TBN_FLAG_RELU) ? 1 : 0;
     P.aligned = (a.p % a.in == 0) ? 1 : 0;
     const size_t esz = (a.dt == TBN_F32) ? 4 : 2;
     P.vec_store = (P.U % 2 == 0 && a.out % 2 == 0 && (reinterpret_cast<uintptr_t>(a.y) % (2 * esz)) == 0) ? 1 : 0;
-    P.tiles_m = (a.M + kBM - 1) / kBM;
+    P.reps_all = (a.out % P.U == 0 && a.out / P.U < (1 << 30)) ? static_cast<int32_t>(a.out / P.U) : 0;
+    P.tiles_m = static_cast<uint32_t>((a.M + kBM - 1) / kBM);
     P.tiles_n = static_cast<int>((P.U + kBN - 1) / kBN);
-    const int64_t blocks = P.tiles_m * P.tiles_n;
+    const int64_t blocks = int64_t(P.tiles_m) * P.tiles_n;
     if (blocks > 0x7fffffffLL) {
         set_error("tbn_linear_forward: problem too large for one launch");
         return TBN_ERR_UNSUPPORTED;
     }
     const dim3 grid(static_cast<unsigned>(blocks));
+    const bool relu = (a.flags & TBN_FLAG_RELU) != 0;
     tbn_status st;
     if (a.dt == TBN_F32)
-        st = P.relu ? launch_typed<float, true>(a, P, grid) : launch_typed<float, false>(a, P, grid);
+        st = relu ? launch_f32<true>(a, P, grid) : launch_f32<false>(a, P, grid);
     else
-        st = P.relu ? launch_typed<uint16_t, true>(a, P, grid) : launch_typed<uint16_t, false>(a, P, grid);
+        st = relu ? launch_bf16<true>(a, P, grid) : launch_bf16<false>(a, P, grid);
     if (st != TBN_OK) return st;
     // columns whose weight row straddles a tile end need two alphas
     if (a.n_alpha > 1 && !P.aligned) return launch_linear_rows_fixup(a);
