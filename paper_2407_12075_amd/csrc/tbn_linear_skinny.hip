@@ -5,9 +5,9 @@
 // At these sizes the layer moves a few hundred kilobytes, so the kernel is built for latency:
 //   * a workgroup owns 16 batch rows x 16 distinct columns and splits K among its 8 waves;
 //   * a wave multiplies with v_mfma_f32_16x16x32_bf16: activations go from global memory straight
-//     into the operand layout (a lane reads 64 contiguous bytes of its row per 128 columns of K,
-//     so a row is read in 256-byte runs), the sign operand is expanded in registers from one
-//     32-bit tile window per lane and 128 columns; nothing is staged in LDS;
+//     into the operand layout (the four lane groups of a row read 64 contiguous bytes per load
+//     instruction), the sign operand is expanded in registers from the 128-bit cyclic tile window
+//     of the lane's column, fetched with one wide load per 128 columns of K; nothing is staged in LDS;
 //   * float32 activations are split exactly into three bf16 terms in registers;
 //   * the 8 partial 16 x 16 blocks are summed through LDS in a fixed order and all replicas are
 //     written by the whole workgroup with lanes running along the columns of Y.
@@ -39,13 +39,26 @@ union Frag {
     u32x4_t q;
 };
 
-// +-1 bf16 operand (8 values) from 8 tile bits in natural order (bit 1 -> +1)
-__device__ __forceinline__ void expand_byte(Frag &f, uint32_t byte) {
-    const uint32_t nb = ~byte;
+// +-1 bf16 operand (8 values) from byte `sel / 0x01010101` of an inverted 32-bit tile window (bit 1 of the
+// tile is +1, i.e. sign bit clear): the byte is replicated into both halves, each half is shifted so that
+// bits 2v and 2v + 1 land on the two sign positions, and the pattern of 1.0 is merged in.
+__device__ __forceinline__ void expand_byte(Frag &f, uint32_t inv_window, uint32_t sel, uint32_t sign_mask, uint32_t one_bits) {
+    typedef uint16_t u16x2_t __attribute__((ext_vector_type(2)));
+    const uint32_t rep = __builtin_amdgcn_perm(inv_window, inv_window, sel);
+    const u16x2_t r2 = __builtin_bit_cast(u16x2_t, rep);
 #pragma unroll
-    for (int v = 0; v < 4; ++v)
-        f.u[v] = 0x3f803f80u | ((nb << (15 - 2 * v)) & 0x8000u) | ((nb << (30 - 2 * v)) & 0x80000000u);
+    for (int v = 0; v < 4; ++v) {
+        const u16x2_t sh = {static_cast<uint16_t>(15 - 2 * v), static_cast<uint16_t>(14 - 2 * v)};
+        f.u[v] = (__builtin_bit_cast(uint32_t, static_cast<u16x2_t>(r2 << sh)) & sign_mask) | one_bits;
+    }
 }
+
+// Four tile words fetched with one load (dword alignment is all the hardware asks for) and the word after them.
+struct WinWords {
+    typedef uint32_t vec4 __attribute__((ext_vector_type(4), aligned(4)));
+    vec4 q;
+    uint32_t tail;
+};
 
 template <typename XT> struct SkTraits;
 template <> struct SkTraits<uint16_t> {
@@ -100,47 +113,116 @@ __global__ __launch_bounds__(kThreads) void linear_skinny_kernel(const XT *__res
     const int64_t u0 = int64_t(blockIdx.x) * 16, m0 = int64_t(blockIdx.y) * 16;
 
     // operand rows of this lane (clamped: results of rows / columns past the end are dropped)
-    const int64_t m_l = (m0 + ln) < P.M ? (m0 + ln) : (P.M - 1);
+    const bool row_ok = (m0 + ln) < P.M;
+    const int64_t m_l = row_ok ? (m0 + ln) : (P.M - 1);
     const int64_t u_l = (u0 + ln) < P.U ? (u0 + ln) : (P.U - 1);
-    const XT *xrow = x + m_l * P.in;
-    const int64_t off = (u_l * P.in) % P.p;   // start bit of weight row u_l in the tile
-    const uint32_t tile_head = tile[0];
+    const unsigned char *xrow = reinterpret_cast<const unsigned char *>(x + m_l * P.in);
+    const uint32_t p32 = static_cast<uint32_t>(P.p), in32 = static_cast<uint32_t>(P.in);
+    // start bit of weight row u_l in the tile: (u_l * in) mod p, the product is below 2^53
+    uint32_t off;
+    {
+        const uint64_t prod = static_cast<uint64_t>(u_l) * in32;
+        const uint64_t q = static_cast<uint64_t>(static_cast<double>(prod) / static_cast<double>(p32));
+        int64_t r = static_cast<int64_t>(prod - q * p32);
+        if (r < 0) r += p32;
+        if (r >= static_cast<int64_t>(p32)) r -= p32;
+        off = static_cast<uint32_t>(r);
+    }
+    uint32_t head[5];   // start of the tile: continues a window that runs past the tile end (n_words >= 4)
+#pragma unroll
+    for (int j = 0; j < 5; ++j) head[j] = tile[j < P.n_words ? j : P.n_words - 1];
+
+    // alphas of this thread's first four replicas: requested now, used in the epilogue
+    const int u = tid & 15, m = (tid >> 4) & 15;
+    const int64_t reps = (P.out + P.U - 1) / P.U;
+    constexpr int kStep = kThreads / 256;   // replicas taken by one thread are kStep apart
+    auto alpha_of = [&](int64_t t) {
+        t = t < reps ? t : reps - 1;
+        int64_t o = u0 + u + t * P.U;
+        o = o < P.out ? o : P.out - 1;
+        return alpha[(P.n_alpha == 1) ? 0 : (P.aligned ? t : (o * P.in) / P.p)];
+    };
+    float al_first[4];
+#pragma unroll
+    for (int j = 0; j < 4; ++j) al_first[j] = alpha_of((tid >> 8) + j * kStep);
+
+    // operand constants kept in registers (two literals do not fit one instruction)
+    uint32_t sign_mask = 0x80008000u, one_bits = 0x3f803f80u;
+    asm volatile("" : "+v"(sign_mask), "+v"(one_bits));
+    const uint32_t byte_sel = 0x01010101u * static_cast<uint32_t>(lg);   // byte lg of a window word
 
     f32x4_t acc = {0.f, 0.f, 0.f, 0.f};
     const int n_blocks = static_cast<int>((P.in + kKBlock - 1) / kKBlock);
 
-    // K index of (block b, step s, lane group lg, element i) is 128*b + 32*lg + 8*s + i: a lane reads
-    // 64 contiguous bytes (bf16) of its batch row per block and one 32-bit tile window.
+    // K index of (block b, step s, lane group lg, element i) is 128*b + 32*s + 8*lg + i: per load
+    // instruction the four lane groups of a batch row read 64 contiguous bytes (bf16); a lane needs
+    // byte 4*s + lg of its column's 128-bit tile window of the block.
     constexpr int NB = T::blocks_in_flight;
     typename T::Piece pc[NB][4];
-    uint32_t w_lo[NB], w_hi[NB];
-    auto issue = [&](int b, typename T::Piece (&dst)[4], uint32_t &lo, uint32_t &hi) {
-        const int64_t kb = int64_t(b) * kKBlock + 32 * lg;
+    WinWords wraw[NB];
+    uint32_t wpos[NB];
+    auto issue = [&](int b, typename T::Piece (&dst)[4], WinWords &wr, uint32_t &wp) {
+        const uint32_t kb = static_cast<uint32_t>(b) * kKBlock + 8u * lg;
+        if (row_ok) {   // lanes of batch rows past M load nothing (at M = 1 that is 15 of 16 lanes)
 #pragma unroll
-        for (int s = 0; s < 4; ++s) {
-            int64_t k = kb + 8 * s;
-            k = k < P.in - 8 ? k : P.in - 8;   // in % 8 == 0; pieces past the end are zeroed when used
-            T::load(dst[s], xrow + k);
+            for (int s = 0; s < 4; ++s) {
+                uint32_t k = kb + 32u * s;
+                k = k < in32 - 8 ? k : in32 - 8;   // in % 8 == 0; pieces past the end are zeroed when used
+                T::load(dst[s], reinterpret_cast<const XT *>(xrow + k * static_cast<uint32_t>(sizeof(XT))));
+            }
+        } else {
+#pragma unroll
+            for (int s = 0; s < 4; ++s) T::zero(dst[s]);
         }
-        int64_t pos = off + (kb < P.in ? kb : 0);
-        if (pos >= P.p) pos -= P.p;
-        const int64_t w = pos >> 5;
-        lo = tile[w];
-        hi = tile[(w + 1 < P.n_words) ? (w + 1) : w];
+        uint32_t pos = off + static_cast<uint32_t>(b) * kKBlock;   // < 2p: b * 128 < in <= p
+        if (pos >= p32) pos -= p32;
+        const uint32_t w = pos >> 5;
+        const uint32_t last = static_cast<uint32_t>(P.n_words) - 4u;
+        const uint32_t wb = w < last ? w : last;   // the four-word load stays inside the tile
+        wr.q = *reinterpret_cast<const WinWords::vec4 *>(reinterpret_cast<const unsigned char *>(tile) + (wb << 2));
+        const uint32_t w4 = (wb + 4 < static_cast<uint32_t>(P.n_words)) ? wb + 4 : static_cast<uint32_t>(P.n_words) - 1;
+        wr.tail = tile[w4];
+        wp = pos;
     };
-    auto consume = [&](int b, typename T::Piece (&src)[4], uint32_t lo, uint32_t hi) {
-        const int64_t kb = int64_t(b) * kKBlock + 32 * lg;
-        int64_t pos = off + (kb < P.in ? kb : 0);
-        if (pos >= P.p) pos -= P.p;
-        const uint32_t hi_ok = ((pos >> 5) + 1 < P.n_words) ? hi : 0u;
-        uint32_t wbits = __funnelshift_r(lo, hi_ok, static_cast<uint32_t>(pos & 31));
-        const int64_t left = P.p - pos;   // bits before the tile end; the window continues at bit 0
-        if (left < 32) wbits = (wbits & ((1u << left) - 1u)) | (tile_head << left);
+    auto consume = [&](int b, typename T::Piece (&src)[4], const WinWords &wr, uint32_t pos) {
+        const uint32_t kb = static_cast<uint32_t>(b) * kKBlock + 8u * lg;
+        const uint32_t sh = pos & 31u;
+        const uint32_t last = static_cast<uint32_t>(P.n_words) - 4u;
+        uint32_t win[4];
+#pragma unroll
+        for (int j = 0; j < 4; ++j) win[j] = __funnelshift_r(wr.q[j], j < 3 ? wr.q[j + 1] : wr.tail, sh);
+        const uint32_t left = p32 - pos;   // bits before the tile end; the window continues at bit 0
+        if (__any((pos >> 5) > last || left < 128u)) {   // rare: near the tile end
+            const uint32_t skip = (pos >> 5) > last ? (pos >> 5) - last : 0u;   // words the load was moved back by
+            uint32_t t[9];
+#pragma unroll
+            for (int j = 0; j < 9; ++j) t[j] = j < 4 ? wr.q[j] : (j == 4 ? wr.tail : 0u);
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                uint32_t lo = 0, hi = 0;
+#pragma unroll
+                for (int i = 0; i < 4; ++i)
+                    if (skip == static_cast<uint32_t>(i)) { lo = t[j + i]; hi = t[j + i + 1]; }
+                uint32_t raw = __funnelshift_r(lo, hi, sh);
+                // bits of this word at or past `left` come from the tile start
+                const int32_t lj = static_cast<int32_t>(left) - 32 * j;
+                if (lj < 32) {
+                    const uint32_t hb = lj <= 0 ? static_cast<uint32_t>(-lj) : 0u;   // first head bit used
+                    uint32_t h0 = 0, h1 = 0;
+#pragma unroll
+                    for (int i = 0; i < 4; ++i)
+                        if ((hb >> 5) == static_cast<uint32_t>(i)) { h0 = head[i]; h1 = head[i + 1]; }
+                    const uint32_t hw = __funnelshift_r(h0, h1, hb & 31u);
+                    raw = lj <= 0 ? hw : ((raw & ((1u << lj) - 1u)) | (hw << lj));
+                }
+                win[j] = raw;
+            }
+        }
 #pragma unroll
         for (int s = 0; s < 4; ++s) {
-            if (kb + 8 * s >= P.in) T::zero(src[s]);
+            if (kb + 32u * s >= in32) T::zero(src[s]);
             Frag bw, a[NP];
-            expand_byte(bw, (wbits >> (8 * s)) & 0xffu);
+            expand_byte(bw, ~win[s], byte_sel, sign_mask, one_bits);
             T::planes_of(src[s], a);
 #pragma unroll
             for (int pl = 0; pl < NP; ++pl)
@@ -154,12 +236,12 @@ __global__ __launch_bounds__(kThreads) void linear_skinny_kernel(const XT *__res
 #pragma unroll
         for (int j = 0; j < NB; ++j) {
             const int b = b0 + j * kWaves;
-            issue(b < n_blocks ? b : b0, pc[j], w_lo[j], w_hi[j]);   // a repeated block is loaded but not used
+            issue(b < n_blocks ? b : b0, pc[j], wraw[j], wpos[j]);   // a repeated block is loaded but not used
         }
 #pragma unroll
         for (int j = 0; j < NB; ++j) {
             const int b = b0 + j * kWaves;
-            if (b < n_blocks) consume(b, pc[j], w_lo[j], w_hi[j]);
+            if (b < n_blocks) consume(b, pc[j], wraw[j], wpos[j]);
         }
     }
 
@@ -177,18 +259,23 @@ __global__ __launch_bounds__(kThreads) void linear_skinny_kernel(const XT *__res
     __syncthreads();
 
     // epilogue: thread -> (replica t, batch row m, column u); u runs fastest over the lanes
-    const int u = tid & 15, m = (tid >> 4) & 15;
-    const int64_t reps = (P.out + P.U - 1) / P.U;
     if (u0 + u < P.U && m0 + m < P.M) {
         const float z = zfin[m][u];
         XT *yrow = y + (m0 + m) * P.out;
-        for (int64_t t = tid >> 8; t < reps; t += kThreads / 256) {
-            const int64_t o = u0 + u + t * P.U;
-            if (o >= P.out) break;
-            const int64_t ai = (P.n_alpha == 1) ? 0 : (P.aligned ? t : (o * P.in) / P.p);
-            float v = alpha[ai] * z;
-            if (RELU) v = fmaxf(v, 0.f);
-            ElemIO<XT>::store(yrow + o, v);
+        for (int64_t t0 = tid >> 8; t0 < reps; t0 += 4 * kStep) {
+            float al[4];   // fetched up front: one memory round trip per four replicas
+#pragma unroll
+            for (int j = 0; j < 4; ++j) al[j] = (t0 == (tid >> 8)) ? al_first[j] : alpha_of(t0 + j * kStep);
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                const int64_t t = t0 + j * kStep;
+                const int64_t o = u0 + u + t * P.U;
+                if (t < reps && o < P.out) {
+                    float v = al[j] * z;
+                    if (RELU) v = fmaxf(v, 0.f);
+                    ElemIO<XT>::store(yrow + o, v);
+                }
+            }
         }
     }
 }
@@ -201,7 +288,8 @@ template <typename XT, bool RELU> void launch_sk(const LinearArgs &a, const Skin
 }  // namespace
 
 bool linear_skinny_supported(const LinearArgs &a) {
-    if (a.p < a.in || a.p < 64) return false;   // at most one tile end per row, windows never wrap twice
+    if (a.p < a.in || a.p < 160) return false;  // at most one tile end per row and window; five tile words exist
+    if (a.p >= (int64_t(1) << 31) - 256 || a.in > (1 << 21)) return false;   // positions and products in 32 / 53 bits
     if (a.in % 8 != 0) return false;            // 16-byte (bf16) / 32-byte (f32) activation pieces
     if (reinterpret_cast<uintptr_t>(a.x) & 15u) return false;
     return a.M <= 64;
