@@ -18,9 +18,12 @@
 //     LDS read at (pixel + tap offset); float32 inputs are split exactly into three bf16 planes
 //     (the weights are +-1, so products are exact; sums are float32 in the matrix pipe);
 //   * the filter bits are reordered once per workgroup from (channel, tap) to (tap, channel) order
-//     into LDS, 32 channels per word, even/odd bits separated so that a lane expands a word into
-//     a +-1 bf16 operand with one shift and one and-or per register;
-//   * the next chunk's input is prefetched into registers while the current one is multiplied.
+//     into LDS, 32 channels per word; a lane expands its byte of a word into a +-1 bf16 operand by
+//     replicating it (v_perm), shifting both halves so that two neighbouring bits land on the two sign
+//     positions (v_pk_lshlrev_b16) and merging with the pattern of 1.0;
+//   * the operand reads run several MFMAs ahead of their use (explicit waits); the next chunk's input
+//     is on its way from global memory while the current one is multiplied and is converted in the
+//     shadow of the last taps' MFMAs.
 #include "tbn_common.h"
 
 #include <type_traits>
@@ -56,15 +59,6 @@ struct ConvMfmaParams {
 template <typename XT> struct CTraits;
 template <> struct CTraits<float> { static constexpr int planes = 3; };
 template <> struct CTraits<uint16_t> { static constexpr int planes = 1; };
-
-__device__ __forceinline__ uint32_t unshuffle_bits32(uint32_t x) {
-    uint32_t t;
-    t = (x ^ (x >> 1)) & 0x22222222u; x ^= t ^ (t << 1);
-    t = (x ^ (x >> 2)) & 0x0c0c0c0cu; x ^= t ^ (t << 2);
-    t = (x ^ (x >> 4)) & 0x00f000f0u; x ^= t ^ (t << 4);
-    t = (x ^ (x >> 8)) & 0x0000ff00u; x ^= t ^ (t << 8);
-    return x;
-}
 
 // truncation split of a float into three bf16 terms (top 8 significand bits, next 8, the rest)
 __device__ __forceinline__ void split3(float x, uint32_t &t0, uint32_t &t1, uint32_t &t2) {
@@ -144,9 +138,9 @@ __global__ __launch_bounds__(kThreads, 2) void conv_mfma_kernel(const XT *__rest
 #pragma unroll
             for (int j = 0; j < 32; ++j) {
                 const int pos = j * T + tap;   // bit of channel j, this tap, inside the block
-                acc |= ((w[pos >> 5] >> (pos & 31)) & 1u) << j;
+                acc |= __builtin_amdgcn_ubfe(w[pos >> 5], pos & 31, 1) << j;   // bit extract, shift-or
             }
-            o[tap] = unshuffle_bits32(acc);
+            o[tap] = acc;   // bit j = channel j of the chunk
         }
 #pragma unroll
         for (int tap = 0; tap < T; ++tap) lds_bits[(chunk * T + tap) * kFB + u] = o[tap];
@@ -181,14 +175,27 @@ __global__ __launch_bounds__(kThreads, 2) void conv_mfma_kernel(const XT *__rest
     const int64_t plane_hw = P.H * P.W;
     const XT *x_img = x + img * P.C * plane_hw;
 
-    float st_a[kMaxItems], st_b[kMaxItems];   // the two channels of a pair
-    auto load_chunk = [&](int chunk) {
+    float st_a[1][kMaxItems], st_b[1][kMaxItems];   // the two channels of a pair
+    uint32_t st_pk[kMaxItems][NP];                  // ... split and packed, ready for LDS
+    auto load_chunk = [&](int chunk, int slot) {
         const XT *base = x_img + int64_t(chunk) * kCK * plane_hw;
 #pragma unroll
         for (int i = 0; i < kMaxItems; ++i) {
             const int32_t g = it_goff[i] < 0 ? 0 : it_goff[i];
-            st_a[i] = load_elem(base + g);
-            st_b[i] = load_elem(base + g + plane_hw);
+            st_a[slot][i] = load_elem(base + g);
+            st_b[slot][i] = load_elem(base + g + plane_hw);
+        }
+    };
+    auto pack_item = [&](int i, int slot) {   // VALU only
+        if (NP == 3) {
+            uint32_t a0, a1, a2, b0, b1, b2;
+            split3(st_a[slot][i], a0, a1, a2);
+            split3(st_b[slot][i], b0, b1, b2);
+            st_pk[i][0] = (a0 >> 16) | b0;
+            st_pk[i][NP > 1 ? 1 : 0] = (a1 >> 16) | b1;
+            st_pk[i][NP > 2 ? 2 : 0] = (a2 >> 16) | (b2 & 0xffff0000u);
+        } else {   // bf16 input: the float holds the exact value, its top half is the bf16 pattern
+            st_pk[i][0] = (__float_as_uint(st_a[slot][i]) >> 16) | (__float_as_uint(st_b[slot][i]) & 0xffff0000u);
         }
     };
     auto store_chunk = [&](int buf) {
@@ -196,17 +203,9 @@ __global__ __launch_bounds__(kThreads, 2) void conv_mfma_kernel(const XT *__rest
 #pragma unroll
         for (int i = 0; i < kMaxItems; ++i) {
             if (it_goff[i] < 0) continue;
-            if (NP == 3) {
-                uint32_t a0, a1, a2, b0, b1, b2;
-                split3(st_a[i], a0, a1, a2);
-                split3(st_b[i], b0, b1, b2);
-                *reinterpret_cast<uint32_t *>(dst + it_loff[i]) = (a0 >> 16) | b0;
-                *reinterpret_cast<uint32_t *>(dst + P.plane_bytes + it_loff[i]) = (a1 >> 16) | b1;
-                *reinterpret_cast<uint32_t *>(dst + 2 * P.plane_bytes + it_loff[i]) = (a2 >> 16) | (b2 & 0xffff0000u);
-            } else {   // bf16 input: the float holds the exact value, its top half is the bf16 pattern
-                *reinterpret_cast<uint32_t *>(dst + it_loff[i]) =
-                    (__float_as_uint(st_a[i]) >> 16) | (__float_as_uint(st_b[i]) & 0xffff0000u);
-            }
+#pragma unroll
+            for (int pl = 0; pl < NP; ++pl)
+                *reinterpret_cast<uint32_t *>(dst + pl * P.plane_bytes + it_loff[i]) = st_pk[i][pl];
         }
     };
 
@@ -234,45 +233,119 @@ __global__ __launch_bounds__(kThreads, 2) void conv_mfma_kernel(const XT *__rest
 #pragma unroll
     for (int tap = 0; tap < T; ++tap) tap_off[tap] = ((tap / P.kw) * P.PC + (tap % P.kw)) * kPixStride;
 
-    auto multiply_chunk = [&](int buf, int chunk) {
-        const unsigned char *src = lds_patch + buf * buf_bytes;
+    // operand constants kept in registers (two literals do not fit one instruction)
+    uint32_t sign_mask = 0x80008000u, one_bits = 0x3f803f80u;
+    asm volatile("" : "+v"(sign_mask), "+v"(one_bits));
+    const uint32_t byte_sel = 0x01010101u * static_cast<uint32_t>(lg);
+    typedef __attribute__((address_space(3))) unsigned char lds_byte_t;
+    const uint32_t patch_addr = static_cast<uint32_t>(reinterpret_cast<uintptr_t>((lds_byte_t *)lds_patch));
+
+    // One chunk of the product for a wave with J live pixel tiles.  The work is a chain of units
+    // (tap, pixel tile, plane): one 16-byte LDS read of the input operand, then one MFMA per filter
+    // tile.  The reads are written as inline assembly and run kDepth units ahead of their MFMAs, with
+    // explicit waits tied to the destination registers (LDS operations complete in order, so extra
+    // operations the compiler puts in between only make a wait more conservative).  The +-1 operands
+    // of the next tap and the conversion of the next chunk's staged input are computed in the shadow
+    // of the MFMAs.
+    auto multiply_chunk = [&](int buf, int chunk, bool stage_next, int next_slot, auto j_c) {
+        constexpr int J = decltype(j_c)::value;
+        constexpr int U = T * J * NP;
+        constexpr int kDepth = U < 6 ? U : 6;
+        const uint32_t src = patch_addr + static_cast<uint32_t>(buf * buf_bytes);
         const uint32_t *bits = lds_bits + chunk * T * kFB + ln;
+        uint32_t nw[T][2];   // inverted filter bits of the chunk (bit 1 of the tile is +1: sign bit clear)
 #pragma unroll
-        for (int tap = 0; tap < T; ++tap) {
-            Frag wf[2];
+        for (int tap = 0; tap < T; ++tap)
+#pragma unroll
+            for (int ft = 0; ft < 2; ++ft) nw[tap][ft] = ~bits[tap * kFB + ft * 16];
+        auto unit_addr = [&](int u) {
+            const int tap = u / (J * NP), j = (u / NP) % J, pl = u % NP;
+            return src + static_cast<uint32_t>(pix_off[j] + tap_off[tap] + pl * P.plane_bytes);
+        };
+        auto expand = [&](int tap, Frag (&wf)[2]) {
+            // lane group lg holds channels 8*lg .. 8*lg + 7 of the step: byte lg of the word; register v
+            // holds channels 2v and 2v + 1
+            typedef uint16_t u16x2_t __attribute__((ext_vector_type(2)));
 #pragma unroll
             for (int ft = 0; ft < 2; ++ft) {
-                const uint32_t nw = (~bits[tap * kFB + ft * 16]) >> (4 * lg);
+                const u16x2_t r2 = __builtin_bit_cast(u16x2_t, __builtin_amdgcn_perm(nw[tap][ft], nw[tap][ft], byte_sel));
 #pragma unroll
-                for (int v = 0; v < 4; ++v) wf[ft].u[v] = ((nw << (15 - v)) & 0x80008000u) | 0x3f803f80u;
-            }
-#pragma unroll
-            for (int j = 0; j < 2; ++j) {
-                if (!tile_live[j]) continue;   // uniform per wave
-#pragma unroll
-                for (int pl = 0; pl < NP; ++pl) {
-                    Frag xf;
-                    xf.q = *reinterpret_cast<const u32x4_t *>(src + pl * P.plane_bytes + pix_off[j] + tap_off[tap]);
-#pragma unroll
-                    for (int ft = 0; ft < 2; ++ft)
-                        acc[ft][j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(wf[ft].v, xf.v, acc[ft][j], 0, 0, 0);
+                for (int v = 0; v < 4; ++v) {
+                    const u16x2_t sh = {static_cast<uint16_t>(15 - 2 * v), static_cast<uint16_t>(14 - 2 * v)};
+                    wf[ft].u[v] = (__builtin_bit_cast(uint32_t, static_cast<u16x2_t>(r2 << sh)) & sign_mask) | one_bits;
                 }
             }
+        };
+        Frag xf[kDepth + 1];
+        Frag wf[2][2];
+#pragma unroll
+        for (int u = 0; u < kDepth; ++u) asm volatile("ds_read_b128 %0, %1" : "=v"(xf[u].q) : "v"(unit_addr(u)));
+        expand(0, wf[0]);
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            const int tap = u / (J * NP), j = (u / NP) % J;
+            if (u + kDepth < U)
+                asm volatile("ds_read_b128 %0, %1" : "=v"(xf[(u + kDepth) % (kDepth + 1)].q) : "v"(unit_addr(u + kDepth)));
+            if (u % (J * NP) == 0 && tap + 1 < T) expand(tap + 1, wf[(tap + 1) & 1]);
+            Frag &x = xf[u % (kDepth + 1)];
+            // younger reads in flight: min(kDepth, U - 1 - u)
+            if (U - 1 - u >= kDepth) asm volatile("s_waitcnt lgkmcnt(%1)" : "+v"(x.q) : "n"(kDepth));
+            else if (U - 1 - u == 5) asm volatile("s_waitcnt lgkmcnt(5)" : "+v"(x.q));
+            else if (U - 1 - u == 4) asm volatile("s_waitcnt lgkmcnt(4)" : "+v"(x.q));
+            else if (U - 1 - u == 3) asm volatile("s_waitcnt lgkmcnt(3)" : "+v"(x.q));
+            else if (U - 1 - u == 2) asm volatile("s_waitcnt lgkmcnt(2)" : "+v"(x.q));
+            else if (U - 1 - u == 1) asm volatile("s_waitcnt lgkmcnt(1)" : "+v"(x.q));
+            else asm volatile("s_waitcnt lgkmcnt(0)" : "+v"(x.q));
+#pragma unroll
+            for (int ft = 0; ft < 2; ++ft)
+                acc[ft][j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(wf[tap & 1][ft].v, x.v, acc[ft][j], 0, 0, 0);
+            // one staged item of the next chunk per tap
+            // conversion of the next chunk's staged input: late in the chunk (its loads were issued at the
+            // start), two items per tap over the last taps
+            if (u % (J * NP) == J * NP - 1 && stage_next) {
+                constexpr int kFirst = T > (kMaxItems + 1) / 2 ? T - (kMaxItems + 1) / 2 : 0;
+                if (tap >= kFirst) {
+                    const int i0 = 2 * (tap - kFirst);
+                    if (i0 < kMaxItems) pack_item(i0, next_slot);
+                    if (i0 + 1 < kMaxItems) pack_item(i0 + 1, next_slot);
+                }
+            }
+        }
+        if (stage_next) {
+            constexpr int kFirst = T > (kMaxItems + 1) / 2 ? T - (kMaxItems + 1) / 2 : 0;
+            constexpr int kDone = 2 * (T - kFirst) < kMaxItems ? 2 * (T - kFirst) : kMaxItems;
+#pragma unroll
+            for (int i = kDone; i < kMaxItems; ++i) pack_item(i, next_slot);
         }
     };
 
     // ---- main loop over channel chunks -----------------------------------------------------------------
-    load_chunk(0);
+    // Chunk c is multiplied from LDS buffer c % 2 while chunk c + 1 arrives in registers, is converted
+    // in the shadow of the MFMAs and written to the other buffer at the end.
+    load_chunk(0, 0);
+#pragma unroll
+    for (int i = 0; i < kMaxItems; ++i) pack_item(i, 0);
     __syncthreads();            // zero fill and filter bits are in place
     store_chunk(0);
     __syncthreads();
-    for (int chunk = 0; chunk < n_chunks; ++chunk) {
-        const int buf = chunk & 1;
-        if (chunk + 1 < n_chunks) load_chunk(chunk + 1);
-        multiply_chunk(buf, chunk);
-        if (chunk + 1 < n_chunks) store_chunk(buf ^ 1);
-        __syncthreads();
-    }
+    auto main_loop = [&](auto j_c) {
+        for (int chunk = 0; chunk < n_chunks; ++chunk) {
+            const int buf = chunk & 1;
+            const bool more = chunk + 1 < n_chunks;
+            if (more) load_chunk(chunk + 1, 0);
+            if constexpr (decltype(j_c)::value > 0) {
+                multiply_chunk(buf, chunk, more, 0, j_c);
+            } else if (more) {   // a wave without pixels of its own still stages its share of the input
+#pragma unroll
+                for (int i = 0; i < kMaxItems; ++i) pack_item(i, 0);
+            }
+            if (more) store_chunk(buf ^ 1);
+            __syncthreads();
+        }
+    };
+    if (tile_live[1]) main_loop(std::integral_constant<int, 2>{});
+    else if (tile_live[0]) main_loop(std::integral_constant<int, 1>{});
+    else main_loop(std::integral_constant<int, 0>{});
 
     // ---- epilogue: y[img, u + t*R, row0.., :] = alpha[t] * Z[u] ---------------------------------------------
     // lane holds pixel ln of its tiles and filters 4*lg + i of each filter tile
@@ -328,7 +401,11 @@ ConvPlan plan_conv(const ConvArgs &a) {
     // balanced row blocks of at most kMaxPix pixels whose valid input patch fits the staging budget
     int64_t rows = kMaxPix / a.Wo;
     if (rows > a.Ho) rows = a.Ho;
-    const int64_t nblk0 = (a.Ho + rows - 1) / rows;
+    int64_t nblk0 = (a.Ho + rows - 1) / rows;
+    // With fewer workgroups than CUs (256), halve the row blocks as long as a block keeps at least 3 rows.
+    const int64_t R = unique_rows(a.O, F, a.p);
+    const int64_t fblocks = (R + kFB - 1) / kFB;
+    while (nblk0 * a.N * fblocks < 256 && (a.Ho + 2 * nblk0 - 1) / (2 * nblk0) >= 3) nblk0 *= 2;
     rows = (a.Ho + nblk0 - 1) / nblk0;
     for (; rows >= 1; --rows) {
         const int64_t PR = (rows - 1) * a.sh + a.kh, PC = (a.Wo - 1) * a.sw + a.kw;
