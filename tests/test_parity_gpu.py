@@ -134,6 +134,18 @@ LINEAR_SMALL = [
     (48, 200, 90, 4, 4),       # small batch with tile ends inside rows
     (65, 1024, 512, 4, 4),     # smallest batch of the large-batch kernel
     (2, 4096, 40, 5, 5),       # 8 distinct rows only: a partly filled column tile
+    # K-split matrix-core kernels: stage counts, tails, window wraps
+    (130, 64, 256, 2, 2),      # one stage: the second K group only sees a stage past the end
+    (130, 192, 128, 2, 1),     # three stages: 2 + 1
+    (256, 904, 72, 3, 3),      # in % 64 = 8: a last stage with one valid piece
+    (140, 1000, 130, 5, 5),    # 26 distinct rows: a partly filled column block
+    (300, 1160, 58, 4, 4),     # p = 16820 = 14.5 rows: windows cross the tile end in many stages
+    (129, 2048, 192, 3, 3),    # long enough for the steady-state loop, second row block one row
+    (200, 1096, 220, 5, 5),    # steady-state loop, then a ragged last stage
+    (70, 8192, 80, 4, 4),      # 64 stages per K group
+    (257, 1544, 135, 5, 5),    # p = 41688 = 27 rows: odd number of distinct rows, p % 32 = 24
+    (4, 40, 16, 4, 1),         # p = 160: smallest tile the small-batch kernel takes
+    (3, 160, 9, 9, 9),         # p = in = 160
 ]
 
 
