@@ -69,6 +69,9 @@ __device__ __forceinline__ void split3(float x, uint32_t &t0, uint32_t &t1, uint
     t2 = __float_as_uint(r2);
 }
 
+// high halves of two words in one: (lo >> 16) | (hi & 0xffff0000), a single v_perm_b32
+__device__ __forceinline__ uint32_t pack_hi16(uint32_t lo, uint32_t hi) { return __builtin_amdgcn_perm(hi, lo, 0x07060302u); }
+
 __device__ __forceinline__ float load_elem(const float *p) { return *p; }
 __device__ __forceinline__ float load_elem(const uint16_t *p) { return bf16_bits_to_f32(*p); }
 
@@ -191,11 +194,11 @@ __global__ __launch_bounds__(kThreads, 2) void conv_mfma_kernel(const XT *__rest
             uint32_t a0, a1, a2, b0, b1, b2;
             split3(st_a[slot][i], a0, a1, a2);
             split3(st_b[slot][i], b0, b1, b2);
-            st_pk[i][0] = (a0 >> 16) | b0;
-            st_pk[i][NP > 1 ? 1 : 0] = (a1 >> 16) | b1;
-            st_pk[i][NP > 2 ? 2 : 0] = (a2 >> 16) | (b2 & 0xffff0000u);
+            st_pk[i][0] = pack_hi16(a0, b0);
+            st_pk[i][NP > 1 ? 1 : 0] = pack_hi16(a1, b1);
+            st_pk[i][NP > 2 ? 2 : 0] = pack_hi16(a2, b2);
         } else {   // bf16 input: the float holds the exact value, its top half is the bf16 pattern
-            st_pk[i][0] = (__float_as_uint(st_a[slot][i]) >> 16) | (__float_as_uint(st_b[slot][i]) & 0xffff0000u);
+            st_pk[i][0] = pack_hi16(__float_as_uint(st_a[slot][i]), __float_as_uint(st_b[slot][i]));
         }
     };
     auto store_chunk = [&](int buf) {

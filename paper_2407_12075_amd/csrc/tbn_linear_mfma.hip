@@ -91,6 +91,9 @@ __device__ __forceinline__ void split3(float x, uint32_t &t0, uint32_t &t1, uint
     t2 = __float_as_uint(r2);
 }
 
+// high halves of two words in one: (lo >> 16) | (hi & 0xffff0000), a single v_perm_b32
+__device__ __forceinline__ uint32_t pack_hi16(uint32_t lo, uint32_t hi) { return __builtin_amdgcn_perm(hi, lo, 0x07060302u); }
+
 template <typename OT> struct OutPack;
 template <> struct OutPack<uint16_t> {
     static __device__ __forceinline__ void store2(uint16_t *p, float a, float b) {
@@ -806,9 +809,9 @@ __global__ __launch_bounds__(kThreads, 1) void linear_mfma_f32_kernel(const floa
                 uint32_t e0, e1, e2, f0, f1, f2;
                 split3(__uint_as_float(src[(d & 1) * 2]), e0, e1, e2);
                 split3(__uint_as_float(src[(d & 1) * 2 + 1]), f0, f1, f2);
-                o[0][d] = (e0 >> 16) | f0;
-                o[1][d] = (e1 >> 16) | f1;
-                o[2][d] = (e2 >> 16) | (f2 & 0xffff0000u);
+                o[0][d] = pack_hi16(e0, f0);
+                o[1][d] = pack_hi16(e1, f1);
+                o[2][d] = pack_hi16(e2, f2);
             }
 #pragma unroll
             for (int pl = 0; pl < 3; ++pl)

@@ -94,7 +94,7 @@ template <> struct SkTraits<float> {
                 t[h][2] = __float_as_uint(r2) & 0xffff0000u;
             }
 #pragma unroll
-            for (int pl = 0; pl < 3; ++pl) a[pl].u[d] = (t[0][pl] >> 16) | t[1][pl];
+            for (int pl = 0; pl < 3; ++pl) a[pl].u[d] = __builtin_amdgcn_perm(t[1][pl], t[0][pl], 0x07060302u);   // high halves
         }
     }
 };
