@@ -117,6 +117,84 @@ __global__ __launch_bounds__(256) void conv_generic_kernel(const T *__restrict__
     }
 }
 
+// Repair pass behind the matrix-core conv kernel, which scales a channel by one alpha: the (at most k - 1)
+// output channels whose filter contains the start of a tile need two (Eq. 4-5: alpha changes where the
+// tile index returns to zero).  Requires p >= C*kh*kw, so a filter holds at most one tile start.
+// Workgroup = 64 output pixels of one (image, such channel); its four waves split the input channels,
+// each thread keeps the sums before and after the tile start apart, LDS adds the four slices.
+template <typename T, int TAPS>
+__global__ __launch_bounds__(256) void conv_tile_end_kernel(const T *__restrict__ x, T *__restrict__ y, int64_t C,
+                                                            int64_t H, int64_t W, int64_t O, int64_t Ho, int64_t Wo,
+                                                            int kh, int kw, int sh, int sw, int ph, int pw,
+                                                            const uint32_t *__restrict__ tile, int64_t p,
+                                                            const float *__restrict__ alpha, int relu) {
+    __shared__ float part[4][64][2];
+    const int64_t F = C * TAPS;
+    const int64_t c_idx = int64_t(blockIdx.y) + 1;   // tile number whose start is looked at
+    const int64_t f = c_idx * p;                     // flat index where it starts
+    if (f % F == 0) return;                          // it starts on a filter boundary: nothing to repair (whole block)
+    const int64_t o = f / F;
+    if (o >= O) return;
+    const int64_t b = blockIdx.z;
+    const int px = threadIdx.x & 63, slice = threadIdx.x >> 6;
+    const int64_t q = int64_t(blockIdx.x) * 64 + px;
+    const bool live = q < Ho * Wo;
+    const int64_t yo = live ? q / Wo : 0, xo = live ? q % Wo : 0;
+    // element offsets of the taps inside a channel plane, -1 where the tap falls into the padding
+    int32_t off[TAPS];
+#pragma unroll
+    for (int t = 0; t < TAPS; ++t) {
+        const int64_t yi = yo * sh - ph + t / kw, xi = xo * sw - pw + t % kw;
+        off[t] = (live && yi >= 0 && yi < H && xi >= 0 && xi < W) ? static_cast<int32_t>(yi * W + xi) : -1;
+    }
+    const int32_t cs = static_cast<int32_t>((C + 3) / 4);
+    const int32_t c_lo = slice * cs, c_hi = (c_lo + cs) < C ? (c_lo + cs) : static_cast<int32_t>(C);
+    const int64_t g0 = o * F + int64_t(c_lo) * TAPS;   // flat index of this slice's first weight
+    int64_t ti = g0 % p;                               // its tile position
+    int64_t before = f - g0;                           // weights of this slice before the tile start (may be <= 0)
+    const int64_t n_words = (p + 31) / 32;
+    float seg_a = 0.f, seg_b = 0.f;                    // sums over weights before / from the tile start
+    const T *xc = x + (b * C + c_lo) * H * W;
+    for (int32_t c = c_lo; c < c_hi; ++c, xc += H * W, before -= TAPS) {
+        float xv[TAPS];
+#pragma unroll
+        for (int t = 0; t < TAPS; ++t) xv[t] = off[t] >= 0 ? ElemIO<T>::load(xc + off[t]) : 0.f;
+        // the channel's TAPS tile bits: a window from ti on; the tile start may lie inside it
+        uint32_t bits;
+        if (ti + TAPS <= p) {
+            const int64_t w = ti >> 5;
+            const uint32_t lo = tile[w], hi = tile[(w + 1 < n_words) ? (w + 1) : w];
+            bits = __funnelshift_r(lo, hi, static_cast<uint32_t>(ti & 31));
+            ti += TAPS;
+            if (ti == p) ti = 0;
+        } else {   // once per tile
+            bits = 0;
+            for (int t = 0; t < TAPS; ++t) {
+                bits |= ((tile[ti >> 5] >> (ti & 31)) & 1u) << t;
+                if (++ti == p) ti = 0;
+            }
+        }
+        float sa = 0.f, sb = 0.f;
+#pragma unroll
+        for (int t = 0; t < TAPS; ++t) {
+            const float sv = ((bits >> t) & 1u) ? xv[t] : -xv[t];
+            if (t < before) sa += sv; else sb += sv;
+        }
+        seg_a += sa;
+        seg_b += sb;
+    }
+    part[slice][px][0] = seg_a;
+    part[slice][px][1] = seg_b;
+    __syncthreads();
+    if (slice == 0 && live) {
+        const float sa = (part[0][px][0] + part[1][px][0]) + (part[2][px][0] + part[3][px][0]);
+        const float sb = (part[0][px][1] + part[1][px][1]) + (part[2][px][1] + part[3][px][1]);
+        float v = alpha[c_idx - 1] * sa + alpha[c_idx] * sb;
+        if (relu) v = fmaxf(v, 0.f);
+        ElemIO<T>::store(y + ((b * O + o) * Ho + yo) * Wo + xo, v);
+    }
+}
+
 static tbn_status launch_conv_generic_impl(const ConvArgs &a, int32_t ends) {
     const int relu = (a.flags & TBN_FLAG_RELU) ? 1 : 0;
     const int64_t total = a.N * (ends > 0 ? ends : a.O) * a.Ho * a.Wo;
@@ -137,6 +215,29 @@ static tbn_status launch_conv_generic_impl(const ConvArgs &a, int32_t ends) {
 
 tbn_status launch_conv_generic(const ConvArgs &a) { return launch_conv_generic_impl(a, 0); }
 
-tbn_status launch_conv_generic_tile_ends(const ConvArgs &a) { return launch_conv_generic_impl(a, a.k - 1); }
+template <typename T, int TAPS>
+static void launch_tile_end(const ConvArgs &a, dim3 grid, int relu) {
+    hipLaunchKernelGGL((conv_tile_end_kernel<T, TAPS>), grid, dim3(256), 0, a.stream, static_cast<const T *>(a.x),
+                       static_cast<T *>(a.y), a.C, a.H, a.W, a.O, a.Ho, a.Wo, a.kh, a.kw, a.sh, a.sw, a.ph, a.pw, a.tile,
+                       a.p, a.alpha, relu);
+}
+
+tbn_status launch_conv_generic_tile_ends(const ConvArgs &a) {
+    const int64_t F = a.C * a.kh * a.kw;
+    const int taps = a.kh * a.kw;
+    const int64_t pix_blocks = (a.Ho * a.Wo + 63) / 64;
+    if (a.n_alpha != a.k || a.p < F || (taps != 1 && taps != 9) || a.H * a.W >= (int64_t(1) << 31) || a.k - 1 > 65535 ||
+        a.N > 65535 || pix_blocks > 0x7fffffffLL)
+        return launch_conv_generic_impl(a, a.k - 1);   // shapes the repair kernel does not take
+    if (a.k < 2 || a.N == 0 || pix_blocks == 0) return TBN_OK;
+    const int relu = (a.flags & TBN_FLAG_RELU) ? 1 : 0;
+    const dim3 grid(static_cast<unsigned>(pix_blocks), static_cast<unsigned>(a.k - 1), static_cast<unsigned>(a.N));
+    if (a.dt == TBN_F32) {
+        if (taps == 1) launch_tile_end<float, 1>(a, grid, relu); else launch_tile_end<float, 9>(a, grid, relu);
+    } else {
+        if (taps == 1) launch_tile_end<uint16_t, 1>(a, grid, relu); else launch_tile_end<uint16_t, 9>(a, grid, relu);
+    }
+    return check_launch("tbn_conv2d_forward (tile-end repair kernel)");
+}
 
 }  // namespace tbn
