@@ -56,6 +56,7 @@ tbn_status launch_linear_skinny(const LinearArgs &a);
 bool linear_rows_supported(const LinearArgs &a);   // wave-per-row kernel (also repairs tile-end columns)
 tbn_status launch_linear_rows(const LinearArgs &a);
 tbn_status launch_linear_rows_fixup(const LinearArgs &a);  // recompute the columns whose row holds a tile end
+tbn_status launch_linear_tile_ends(const LinearArgs &a);   // the same in one pass over X (falls back to the above)
 bool linear_mfma_supported(const LinearArgs &a);   // matrix-core kernel
 tbn_status launch_linear_mfma(const LinearArgs &a);
 

@@ -990,7 +990,7 @@ tbn_status launch_linear_mfma(const LinearArgs &a) {
         st = relu ? launch_bf16<true>(a, P, grid) : launch_bf16<false>(a, P, grid);
     if (st != TBN_OK) return st;
     // columns whose weight row straddles a tile end need two alphas
-    if (a.n_alpha > 1 && !P.aligned) return launch_linear_rows_fixup(a);
+    if (a.n_alpha > 1 && !P.aligned) return launch_linear_tile_ends(a);
     return TBN_OK;
 }
 

@@ -11,8 +11,11 @@
 //   * float32 activations are split exactly into three bf16 terms in registers;
 //   * the 8 partial 16 x 16 blocks are summed through LDS in a fixed order and all replicas are
 //     written by the whole workgroup with lanes running along the columns of Y.
-// Columns whose weight row contains a tile end (two alphas) are recomputed afterwards by the row
-// kernel, as for the large-batch kernel.
+// Columns whose weight row contains a tile start (two alphas) are recomputed afterwards, here and
+// after the large-batch kernel, by the same kernel in its FIXUP form at any batch size: the "columns"
+// of a workgroup are then the up to k - 1 such rows, the sums before and from the tile start are kept
+// in two accumulators (operand elements of the other part are zeroed), and X is read once for all
+// of them.
 #include "tbn_common.h"
 
 namespace tbn {
@@ -31,6 +34,7 @@ struct SkinnyParams {
     int64_t M, in, out, p, n_words, U;
     int32_t n_alpha;
     int aligned;
+    int32_t k;   // tile repeats (FIXUP form: tile starts 1 .. k - 1 are looked at)
 };
 
 union Frag {
@@ -99,14 +103,27 @@ template <> struct SkTraits<float> {
     }
 };
 
-template <typename XT, bool RELU>
+// Row of the weight that contains the start of tile number c (FIXUP form), j_e = the start's position in it
+// (0: the tile starts with the row, nothing to repair).
+__device__ __forceinline__ void tile_start_row(const SkinnyParams &P, int64_t c, int64_t &o_c, uint32_t &j_e) {
+    const uint64_t prod = static_cast<uint64_t>(c) * static_cast<uint64_t>(P.p);   // < 2^47
+    uint64_t q = static_cast<uint64_t>(static_cast<double>(prod) / static_cast<double>(P.in));
+    int64_t r = static_cast<int64_t>(prod - q * static_cast<uint64_t>(P.in));
+    if (r < 0) { r += P.in; --q; }
+    if (r >= P.in) { r -= P.in; ++q; }
+    o_c = static_cast<int64_t>(q);
+    j_e = static_cast<uint32_t>(r);
+}
+
+template <typename XT, bool RELU, bool FIXUP>
 __global__ __launch_bounds__(kThreads) void linear_skinny_kernel(const XT *__restrict__ x, XT *__restrict__ y,
                                                                  const uint32_t *__restrict__ tile,
                                                                  const float *__restrict__ alpha, SkinnyParams P) {
     using T = SkTraits<XT>;
     constexpr int NP = T::planes;
-    __shared__ float part[kWaves][16][17];   // partial blocks [wave][batch row][column], padded
-    __shared__ float zfin[16][17];
+    constexpr int NA = FIXUP ? 2 : 1;              // accumulators: FIXUP keeps the two alpha segments apart
+    __shared__ float part[NA][kWaves][16][17];     // partial blocks [wave][batch row][column], padded
+    __shared__ float zfin[NA][16][17];
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int ln = lane & 15, lg = lane >> 4;
@@ -118,9 +135,18 @@ __global__ __launch_bounds__(kThreads) void linear_skinny_kernel(const XT *__res
     const int64_t u_l = (u0 + ln) < P.U ? (u0 + ln) : (P.U - 1);
     const unsigned char *xrow = reinterpret_cast<const unsigned char *>(x + m_l * P.in);
     const uint32_t p32 = static_cast<uint32_t>(P.p), in32 = static_cast<uint32_t>(P.in);
-    // start bit of weight row u_l in the tile: (u_l * in) mod p, the product is below 2^53
+    // start bit of the lane's weight row in the tile
     uint32_t off;
-    {
+    uint32_t j_e = 0;   // FIXUP: elements before j_e belong to the first alpha segment
+    if (FIXUP) {
+        // the lane's row is the one that holds the start of tile u0 + ln + 1; its first weight is
+        // tile bit p - j_e (lanes past k - 1, or whose tile starts with a row, compute a result nobody reads)
+        int64_t c = u0 + ln + 1;
+        c = c < P.k ? c : 1;
+        int64_t o_c;
+        tile_start_row(P, c, o_c, j_e);
+        off = j_e == 0 ? 0u : p32 - j_e;
+    } else {   // (u_l * in) mod p, the product is below 2^53
         const uint64_t prod = static_cast<uint64_t>(u_l) * in32;
         const uint64_t q = static_cast<uint64_t>(static_cast<double>(prod) / static_cast<double>(p32));
         int64_t r = static_cast<int64_t>(prod - q * p32);
@@ -142,16 +168,20 @@ __global__ __launch_bounds__(kThreads) void linear_skinny_kernel(const XT *__res
         o = o < P.out ? o : P.out - 1;
         return alpha[(P.n_alpha == 1) ? 0 : (P.aligned ? t : (o * P.in) / P.p)];
     };
-    float al_first[4];
+    float al_first[4] = {0.f, 0.f, 0.f, 0.f};
+    if (!FIXUP) {
 #pragma unroll
-    for (int j = 0; j < 4; ++j) al_first[j] = alpha_of((tid >> 8) + j * kStep);
+        for (int j = 0; j < 4; ++j) al_first[j] = alpha_of((tid >> 8) + j * kStep);
+    }
 
     // operand constants kept in registers (two literals do not fit one instruction)
     uint32_t sign_mask = 0x80008000u, one_bits = 0x3f803f80u;
     asm volatile("" : "+v"(sign_mask), "+v"(one_bits));
     const uint32_t byte_sel = 0x01010101u * static_cast<uint32_t>(lg);   // byte lg of a window word
 
-    f32x4_t acc = {0.f, 0.f, 0.f, 0.f};
+    f32x4_t acc[NA];
+#pragma unroll
+    for (int h = 0; h < NA; ++h) acc[h] = f32x4_t{0.f, 0.f, 0.f, 0.f};
     const int n_blocks = static_cast<int>((P.in + kKBlock - 1) / kKBlock);
 
     // K index of (block b, step s, lane group lg, element i) is 128*b + 32*s + 8*lg + i: per load
@@ -224,9 +254,27 @@ __global__ __launch_bounds__(kThreads) void linear_skinny_kernel(const XT *__res
             Frag bw, a[NP];
             expand_byte(bw, ~win[s], byte_sel, sign_mask, one_bits);
             T::planes_of(src[s], a);
+            if (FIXUP) {
+                // elements kb + 32 s + i with i < na lie before the tile start: keep them in the first
+                // operand, the others in the second (0.0 elsewhere)
+                const int32_t na = static_cast<int32_t>(j_e) - static_cast<int32_t>(kb + 32u * s);
+                Frag bw2;
 #pragma unroll
-            for (int pl = 0; pl < NP; ++pl)
-                acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a[pl].v, bw.v, acc, 0, 0, 0);
+                for (int v = 0; v < 4; ++v) {
+                    const uint32_t keep = (na > 2 * v ? 0x0000ffffu : 0u) | (na > 2 * v + 1 ? 0xffff0000u : 0u);
+                    bw2.u[v] = bw.u[v] & ~keep;
+                    bw.u[v] &= keep;
+                }
+#pragma unroll
+                for (int pl = 0; pl < NP; ++pl) {
+                    acc[0] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a[pl].v, bw.v, acc[0], 0, 0, 0);
+                    acc[NA - 1] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a[pl].v, bw2.v, acc[NA - 1], 0, 0, 0);
+                }
+            } else {
+#pragma unroll
+                for (int pl = 0; pl < NP; ++pl)
+                    acc[0] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a[pl].v, bw.v, acc[0], 0, 0, 0);
+            }
         }
     };
 
@@ -247,20 +295,40 @@ __global__ __launch_bounds__(kThreads) void linear_skinny_kernel(const XT *__res
 
     // accumulator layout: lane holds column ln, batch rows 4*lg + i
 #pragma unroll
-    for (int i = 0; i < 4; ++i) part[wave][4 * lg + i][ln] = acc[i];
+    for (int h = 0; h < NA; ++h)
+#pragma unroll
+        for (int i = 0; i < 4; ++i) part[h][wave][4 * lg + i][ln] = acc[h][i];
     __syncthreads();
     if (tid < 256) {
-        const int m = tid >> 4, u = tid & 15;
-        float s = 0.f;
+        const int mm = tid >> 4, uu = tid & 15;
 #pragma unroll
-        for (int w = 0; w < kWaves; ++w) s += part[w][m][u];
-        zfin[m][u] = s;
+        for (int h = 0; h < NA; ++h) {
+            float s = 0.f;
+#pragma unroll
+            for (int w = 0; w < kWaves; ++w) s += part[h][w][mm][uu];
+            zfin[h][mm][uu] = s;
+        }
     }
     __syncthreads();
 
+    if (FIXUP) {   // one column per (tile start, batch row): y = alpha[c-1] * (sum before) + alpha[c] * (sum from)
+        const int64_t c = u0 + u + 1;
+        if (tid < 256 && c < P.k && m0 + m < P.M) {
+            int64_t o_c;
+            uint32_t je;
+            tile_start_row(P, c, o_c, je);
+            if (je != 0 && o_c < P.out) {
+                float v = alpha[c - 1] * zfin[0][m][u] + alpha[c] * zfin[NA - 1][m][u];
+                if (RELU) v = fmaxf(v, 0.f);
+                ElemIO<XT>::store(y + (m0 + m) * P.out + o_c, v);
+            }
+        }
+        return;
+    }
+
     // epilogue: thread -> (replica t, batch row m, column u); u runs fastest over the lanes
     if (u0 + u < P.U && m0 + m < P.M) {
-        const float z = zfin[m][u];
+        const float z = zfin[0][m][u];
         XT *yrow = y + (m0 + m) * P.out;
         for (int64_t t0 = tid >> 8; t0 < reps; t0 += 4 * kStep) {
             float al[4];   // fetched up front: one memory round trip per four replicas
@@ -280,44 +348,65 @@ __global__ __launch_bounds__(kThreads) void linear_skinny_kernel(const XT *__res
     }
 }
 
-template <typename XT, bool RELU> void launch_sk(const LinearArgs &a, const SkinnyParams &P, dim3 grid) {
-    hipLaunchKernelGGL((linear_skinny_kernel<XT, RELU>), grid, dim3(kThreads), 0, a.stream,
+template <typename XT, bool RELU, bool FIXUP> void launch_sk(const LinearArgs &a, const SkinnyParams &P, dim3 grid) {
+    hipLaunchKernelGGL((linear_skinny_kernel<XT, RELU, FIXUP>), grid, dim3(kThreads), 0, a.stream,
                        static_cast<const XT *>(a.x), static_cast<XT *>(a.y), a.tile, a.alpha, P);
 }
 
-}  // namespace
+template <bool FIXUP> void launch_sk_any(const LinearArgs &a, const SkinnyParams &P, dim3 grid) {
+    const bool relu = (a.flags & TBN_FLAG_RELU) != 0;
+    if (a.dt == TBN_F32) {
+        if (relu) launch_sk<float, true, FIXUP>(a, P, grid); else launch_sk<float, false, FIXUP>(a, P, grid);
+    } else {
+        if (relu) launch_sk<uint16_t, true, FIXUP>(a, P, grid); else launch_sk<uint16_t, false, FIXUP>(a, P, grid);
+    }
+}
 
-bool linear_skinny_supported(const LinearArgs &a) {
+bool shape_ok(const LinearArgs &a) {
     if (a.p < a.in || a.p < 160) return false;  // at most one tile end per row and window; five tile words exist
     if (a.p >= (int64_t(1) << 31) - 256 || a.in > (1 << 21)) return false;   // positions and products in 32 / 53 bits
     if (a.in % 8 != 0) return false;            // 16-byte (bf16) / 32-byte (f32) activation pieces
     if (reinterpret_cast<uintptr_t>(a.x) & 15u) return false;
-    return a.M <= 64;
+    return true;
 }
 
-tbn_status launch_linear_skinny(const LinearArgs &a) {
+SkinnyParams make_params(const LinearArgs &a) {
     SkinnyParams P;
     P.M = a.M; P.in = a.in; P.out = a.out; P.p = a.p;
     P.n_words = (a.p + 31) / 32;
     P.U = unique_rows(a.out, a.in, a.p);
     P.n_alpha = a.n_alpha;
     P.aligned = (a.p % a.in == 0) ? 1 : 0;
+    P.k = a.k;
+    return P;
+}
+
+}  // namespace
+
+bool linear_skinny_supported(const LinearArgs &a) { return shape_ok(a) && a.M <= 64; }
+
+// Recomputes the columns whose weight row holds a tile start (two alphas), at any batch size.
+tbn_status launch_linear_tile_ends(const LinearArgs &a) {
+    const int64_t gy = (a.M + 15) / 16, gx = (int64_t(a.k) - 1 + 15) / 16;
+    if (!shape_ok(a) || a.n_alpha != a.k || gy > 65535 || gx > 65535) return launch_linear_rows_fixup(a);
+    if (a.k < 2 || a.M == 0) return TBN_OK;
+    const SkinnyParams P = make_params(a);
+    launch_sk_any<true>(a, P, dim3(static_cast<unsigned>(gx), static_cast<unsigned>(gy)));
+    return check_launch("tbn_linear_forward (tile-start repair kernel)");
+}
+
+tbn_status launch_linear_skinny(const LinearArgs &a) {
+    const SkinnyParams P = make_params(a);
     const int64_t gx = (P.U + 15) / 16, gy = (a.M + 15) / 16;
     if (gx > 0x7fffffffLL) {
         set_error("tbn_linear_forward: too many distinct rows for one launch");
         return TBN_ERR_UNSUPPORTED;
     }
-    const dim3 grid(static_cast<unsigned>(gx), static_cast<unsigned>(gy));
-    const bool relu = (a.flags & TBN_FLAG_RELU) != 0;
-    if (a.dt == TBN_F32) {
-        if (relu) launch_sk<float, true>(a, P, grid); else launch_sk<float, false>(a, P, grid);
-    } else {
-        if (relu) launch_sk<uint16_t, true>(a, P, grid); else launch_sk<uint16_t, false>(a, P, grid);
-    }
+    launch_sk_any<false>(a, P, dim3(static_cast<unsigned>(gx), static_cast<unsigned>(gy)));
     tbn_status st = check_launch("tbn_linear_forward (small-batch kernel)");
     if (st != TBN_OK) return st;
     // columns whose weight row straddles a tile end need two alphas
-    if (a.n_alpha > 1 && !P.aligned) return launch_linear_rows_fixup(a);
+    if (a.n_alpha > 1 && !P.aligned) return launch_linear_tile_ends(a);
     return TBN_OK;
 }
 
