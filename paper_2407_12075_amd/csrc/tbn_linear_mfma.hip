@@ -686,6 +686,9 @@ __global__ __launch_bounds__(kThreads, 1) void linear_mfma_bf16_kernel(const uin
 #pragma unroll
         for (int d = 0; d < D; ++d) steady_round(st0 + d, d);
     }
+    // The last steady round has requested operands nobody will use: let them land before their
+    // registers can be given to anything else.
+    if (st0 > 0) lds_wait<0>(pa[0]);
     // Drain: st0 is a multiple of D, so slot numbers stay static.  Every round opens with the meeting
     // that makes stage st + 1 readable; `win` holds the windows of stage st on entry.
     for (; st0 < n_stages; st0 += D) {
