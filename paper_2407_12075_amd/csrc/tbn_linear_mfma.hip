@@ -153,81 +153,80 @@ template <> struct WordVec<3> { typedef uint32_t type __attribute__((ext_vector_
 
 // Issues the load of the WW + 1 tile words that hold the BK window bits from pos on, and moves pos to
 // the group's next stage.  Near the tile end the load starts earlier so that it stays inside the tile
-// (n_words >= WW + 1); wpos keeps the window's cyclic position, wofs its bit offset in the loaded words.
+// (n_words >= WW + 1); wpos keeps the window's cyclic position.
+template <int BK>
+__device__ __forceinline__ void load_window_one(const MfmaParams &P, const uint32_t *__restrict__ tile, uint32_t &pos,
+                                                uint32_t (&wreg)[BK / 32 + 1], uint32_t &wpos) {
+    constexpr int NW = BK / 32 + 1;
+    const uint32_t w = pos >> 5;
+    const uint32_t last = static_cast<uint32_t>(P.n_words - NW);
+    const uint32_t wb = w < last ? w : last;
+    const typename WordVec<NW>::type v = *reinterpret_cast<const typename WordVec<NW>::type *>(
+        reinterpret_cast<const unsigned char *>(tile) + (wb << 2));
+#pragma unroll
+    for (int j = 0; j < NW; ++j) wreg[j] = v[j];
+    wpos = pos;
+    pos += kKG * BK;   // p >= kKG * BK
+    if (pos >= static_cast<uint32_t>(P.p)) pos -= static_cast<uint32_t>(P.p);
+}
 template <int BK>
 __device__ __forceinline__ void load_window(const MfmaParams &P, const uint32_t *__restrict__ tile, uint32_t (&pos)[kTN],
                                             uint32_t (&wreg)[kTN][BK / 32 + 1], uint32_t (&wpos)[kTN]) {
-    constexpr int NW = BK / 32 + 1;
 #pragma unroll
-    for (int tn = 0; tn < kTN; ++tn) {
-        const uint32_t w = pos[tn] >> 5;
-        const uint32_t last = static_cast<uint32_t>(P.n_words - NW);
-        const uint32_t wb = w < last ? w : last;
-        const typename WordVec<NW>::type v = *reinterpret_cast<const typename WordVec<NW>::type *>(
-            reinterpret_cast<const unsigned char *>(tile) + (wb << 2));
-#pragma unroll
-        for (int j = 0; j < NW; ++j) wreg[tn][j] = v[j];
-        wpos[tn] = pos[tn];
-        pos[tn] += kKG * BK;   // p >= kKG * BK
-        if (pos[tn] >= static_cast<uint32_t>(P.p)) pos[tn] -= static_cast<uint32_t>(P.p);
-    }
+    for (int tn = 0; tn < kTN; ++tn) load_window_one<BK>(P, tile, pos[tn], wreg[tn], wpos[tn]);
 }
 
-// BK window bits from the cyclic position on (bits past the tile end come from its start), inverted:
-// bit 1 is weight +1, i.e. sign bit clear.
+// BK window bits of one column from the cyclic position on (bits past the tile end come from its
+// start), inverted: bit 1 is weight +1, i.e. sign bit clear.
 template <int BK>
-__device__ __forceinline__ void form_window(const MfmaParams &P, const uint32_t (&wreg)[kTN][BK / 32 + 1],
-                                            const uint32_t (&wpos)[kTN], const uint32_t (&head)[BK / 32],
-                                            uint32_t (&win)[kTN][BK / 32]) {
+__device__ __forceinline__ void form_window_one(const MfmaParams &P, const uint32_t (&wreg)[BK / 32 + 1], uint32_t wpos,
+                                                const uint32_t (&head)[BK / 32], uint32_t (&win)[BK / 32]) {
     constexpr int WW = BK / 32;
     constexpr int NW = WW + 1;
-    bool special = false;   // the load was moved back, or the window runs past the tile end
-    const uint32_t last = static_cast<uint32_t>(P.n_words - NW);
+    const uint32_t sh = wpos & 31u;
 #pragma unroll
-    for (int tn = 0; tn < kTN; ++tn) {
-        const uint32_t sh = wpos[tn] & 31u;
+    for (int j = 0; j < WW; ++j) win[j] = __funnelshift_r(wreg[j], wreg[j + 1], sh);
+    // One test covers both special cases: the load was moved back (pos >= 32 * n_words - BK >= p - BK) and
+    // the window runs past the tile end (pos + BK > p).
+    if (__any(wpos + static_cast<uint32_t>(BK) >= static_cast<uint32_t>(P.p))) {   // rare
+        const uint32_t last = static_cast<uint32_t>(P.n_words - NW);
+        const uint32_t w = wpos >> 5;
+        if (w > last) {   // the words were loaded from `last` on: skip w - last of them (zeros follow)
+            const uint32_t skip = w - last;   // 1 .. NW - 1
+            uint32_t t[NW + 1];
 #pragma unroll
-        for (int j = 0; j < WW; ++j) win[tn][j] = __funnelshift_r(wreg[tn][j], wreg[tn][j + 1], sh);
-        special = special || ((wpos[tn] >> 5) > last) ||
-                  (static_cast<uint32_t>(P.p) - wpos[tn] < static_cast<uint32_t>(BK));
-    }
-    if (__any(special)) {   // rare
+            for (int j = 0; j <= NW; ++j) {
+                uint32_t x = 0;
 #pragma unroll
-        for (int tn = 0; tn < kTN; ++tn) {
-            const uint32_t w = wpos[tn] >> 5;
-            if (w > last) {   // the words were loaded from `last` on: skip w - last of them (zeros follow)
-                const uint32_t skip = w - last;   // 1 .. NW - 1
-                const uint32_t sh = wpos[tn] & 31u;
-                uint32_t t[NW + 1];
-#pragma unroll
-                for (int j = 0; j <= NW; ++j) {
-                    uint32_t x = 0;
-#pragma unroll
-                    for (int i = 1; i < NW; ++i)
-                        if (skip == static_cast<uint32_t>(i) && j + i < NW) x = wreg[tn][j + i];
-                    t[j] = x;
-                }
-#pragma unroll
-                for (int j = 0; j < WW; ++j) win[tn][j] = __funnelshift_r(t[j], t[j + 1], sh);
+                for (int i = 1; i < NW; ++i)
+                    if (skip == static_cast<uint32_t>(i) && j + i < NW) x = wreg[j + i];
+                t[j] = x;
             }
-            const uint32_t left = static_cast<uint32_t>(P.p) - wpos[tn];   // >= 1
-            if (left < static_cast<uint32_t>(BK)) {
-                if (WW == 2) {
-                    const uint64_t raw = (uint64_t(win[tn][WW - 1]) << 32) | win[tn][0];
-                    const uint64_t hd = (uint64_t(head[WW - 1]) << 32) | head[0];
-                    const uint64_t r = (raw & ((uint64_t(1) << left) - 1)) | (hd << left);
-                    win[tn][0] = static_cast<uint32_t>(r);
-                    win[tn][WW - 1] = static_cast<uint32_t>(r >> 32);
-                } else {
-                    win[tn][0] = (win[tn][0] & ((1u << left) - 1u)) | (head[0] << left);
-                }
+#pragma unroll
+            for (int j = 0; j < WW; ++j) win[j] = __funnelshift_r(t[j], t[j + 1], sh);
+        }
+        const uint32_t left = static_cast<uint32_t>(P.p) - wpos;   // >= 1
+        if (left < static_cast<uint32_t>(BK)) {
+            if (WW == 2) {
+                const uint64_t raw = (uint64_t(win[WW - 1]) << 32) | win[0];
+                const uint64_t hd = (uint64_t(head[WW - 1]) << 32) | head[0];
+                const uint64_t r = (raw & ((uint64_t(1) << left) - 1)) | (hd << left);
+                win[0] = static_cast<uint32_t>(r);
+                win[WW - 1] = static_cast<uint32_t>(r >> 32);
+            } else {
+                win[0] = (win[0] & ((1u << left) - 1u)) | (head[0] << left);
             }
         }
     }
 #pragma unroll
-    for (int tn = 0; tn < kTN; ++tn)
+    for (int j = 0; j < WW; ++j) win[j] = ~win[j];
+}
+template <int BK>
+__device__ __forceinline__ void form_window(const MfmaParams &P, const uint32_t (&wreg)[kTN][BK / 32 + 1],
+                                            const uint32_t (&wpos)[kTN], const uint32_t (&head)[BK / 32],
+                                            uint32_t (&win)[kTN][BK / 32]) {
 #pragma unroll
-        for (int j = 0; j < WW; ++j) win[tn][j] = ~win[tn][j];
+    for (int tn = 0; tn < kTN; ++tn) form_window_one<BK>(P, wreg[tn], wpos[tn], head, win[tn]);
 }
 
 // The +-1 operand of MFMA step ks: lane group lg supplies K elements 16*ks + 8*lg .. + 7, i.e. byte
@@ -650,6 +649,10 @@ __global__ __launch_bounds__(kThreads, 1) void linear_mfma_bf16_kernel(const uin
             if (ks == 3) stage_load_one<6>(src, a_off, dst);
             __builtin_amdgcn_sched_barrier(0);
             mfma(2, 1);
+            // the windows of stage st + 1 (this stage's last operands were expanded in step 2) and the
+            // window loads of stage st + 3: one column here, the other after the step's last MFMA
+            if (ks == KS - 2) form_window_one<BK>(P, wreg[(d + 1) % D][0], wpos[(d + 1) % D][0], head, win[0]);
+            if (ks == KS - 1) load_window_one<BK>(P, tile, pos[0], wreg[d][0], wpos[d][0]);
             __builtin_amdgcn_sched_barrier(0);
             mfma(3, 0);
             if (ks == 0) stage_load_one<1>(src, a_off, dst);
@@ -658,8 +661,8 @@ __global__ __launch_bounds__(kThreads, 1) void linear_mfma_bf16_kernel(const uin
             if (ks == 3) stage_load_one<7>(src, a_off, dst);
             __builtin_amdgcn_sched_barrier(0);
             mfma(3, 1);
-            if (ks == KS - 1) load_window<BK>(P, tile, pos, wreg[d], wpos[d]);
-            if (ks == KS - 2) form_window<BK>(P, wreg[(d + 1) % D], wpos[(d + 1) % D], head, win);   // stage st + 1
+            if (ks == KS - 2) form_window_one<BK>(P, wreg[(d + 1) % D][1], wpos[(d + 1) % D][1], head, win[1]);
+            if (ks == KS - 1) load_window_one<BK>(P, tile, pos[1], wreg[d][1], wpos[d][1]);
             __builtin_amdgcn_sched_barrier(0);
         }
     };
