@@ -188,7 +188,7 @@ __device__ __forceinline__ void form_window_one(const MfmaParams &P, const uint3
     for (int j = 0; j < WW; ++j) win[j] = __funnelshift_r(wreg[j], wreg[j + 1], sh);
     // One test covers both special cases: the load was moved back (pos >= 32 * n_words - BK >= p - BK) and
     // the window runs past the tile end (pos + BK > p).
-    if (__any(wpos + static_cast<uint32_t>(BK) >= static_cast<uint32_t>(P.p))) {   // rare
+    if (__builtin_expect(__any(wpos + static_cast<uint32_t>(BK) >= static_cast<uint32_t>(P.p)), 0)) {   // rare
         const uint32_t last = static_cast<uint32_t>(P.n_words - NW);
         const uint32_t w = wpos >> 5;
         if (w > last) {   // the words were loaded from `last` on: skip w - last of them (zeros follow)
@@ -229,6 +229,20 @@ __device__ __forceinline__ void form_window(const MfmaParams &P, const uint32_t 
     for (int tn = 0; tn < kTN; ++tn) form_window_one<BK>(P, wreg[tn], wpos[tn], head, win[tn]);
 }
 
+// The two lane halves (lg = 0 / 1) need the same two windows.  Each half loads and forms the window of
+// one column (lg = 0 the first, lg = 1 the second) and the halves trade: v_permlane32_swap of a register
+// with itself returns the lower half's value in every lane and the upper half's value in every lane.
+template <int BK>
+__device__ __forceinline__ void share_window(const uint32_t (&own)[BK / 32], uint32_t (&win)[kTN][BK / 32]) {
+    static_assert(kTN == 2, "one column per lane half");
+#pragma unroll
+    for (int j = 0; j < BK / 32; ++j) {
+        const auto r = __builtin_amdgcn_permlane32_swap(own[j], own[j], false, false);
+        win[0][j] = r[0];
+        win[1][j] = r[1];
+    }
+}
+
 // The +-1 operand of MFMA step ks: lane group lg supplies K elements 16*ks + 8*lg .. + 7, i.e. byte
 // 2*ks + lg of the (inverted) window; register v holds elements 2v and 2v + 1.
 __device__ __forceinline__ void expand_operand(uint32_t win_lo, uint32_t win_hi, uint32_t byte_sel, uint32_t sign_mask,
@@ -252,7 +266,9 @@ __device__ __forceinline__ void expand_operand_half(uint32_t win_lo, uint32_t wi
     for (int v = 2 * h; v < 2 * h + 2; ++v) {
         const u16x2_t sh = {static_cast<uint16_t>(15 - 2 * v), static_cast<uint16_t>(14 - 2 * v)};
         const uint32_t s = __builtin_bit_cast(uint32_t, static_cast<u16x2_t>(r2 << sh));
-        b.q[v] = (s & sign_mask) | one_bits;
+        uint32_t r = (s & sign_mask) | one_bits;
+        asm volatile("" : "+v"(r));   // computed here, between these MFMAs, not wherever its first use is
+        b.q[v] = r;
     }
 }
 
@@ -405,7 +421,7 @@ constexpr int kNB = 4;                         // LDS stage buffers per K group
 constexpr int kRowBytes = BK * 2;              // 128, unpadded
 constexpr int kStageBytes = kBM * kRowBytes;   // 16 KiB
 constexpr int kLoads = kStageBytes / (kGroupThreads / 64) / 1024;   // 1 KiB wave-loads per wave and stage: 8
-constexpr int kVmPerStage = kLoads + kTN;                           // vector-memory instructions per stage
+constexpr int kVmPerStage = kLoads + 1;                           // vector-memory instructions per stage
 constexpr int kLdsBytes = kKG * kNB * kStageBytes;                   // 128 KiB
 static_assert(kLdsBytes >= kExchangeBytes, "the exchange reuses the stage buffers");
 constexpr int kBias = 3 * 1024;                // keeps the lane offsets non-negative, see below
@@ -486,16 +502,22 @@ __global__ __launch_bounds__(kThreads, 1) void linear_mfma_bf16_kernel(const uin
 
     // ---- tile windows of this lane's two columns ------------------------------------------------
     const int b_col = wn * kWN + ln * kTN;   // + tn: a lane owns kTN adjacent columns of the block
-    uint32_t pos[kTN];
-    window_start<BK>(P, n0 + b_col, grp, pos);
+    uint32_t pos2[kTN];
+    window_start<BK>(P, n0 + b_col, grp, pos2);
+    uint32_t pos = lg ? pos2[1] : pos2[0];   // a lane looks after the window of column b_col + lg, see share_window
     uint32_t head[WW];   // start of the tile: continues a window that runs past the tile end
 #pragma unroll
     for (int j = 0; j < WW; ++j) head[j] = tile[j];
 
     constexpr int D = kNB - 1;   // stages in flight
-    uint32_t wreg[D][kTN][WW + 1];
-    uint32_t wpos[D][kTN];
+    uint32_t wreg[D][WW + 1];
+    uint32_t wpos[D];
     uint32_t win[kTN][WW];
+    auto form_windows = [&](int slot) {
+        uint32_t own[WW];
+        form_window_one<BK>(P, wreg[slot], wpos[slot], head, own);
+        share_window<BK>(own, win);
+    };
 
     // Virtual stage v of group g is stage v*kKG + g.  A group whose stage lies past the end of K
     // still goes through the motions (the barriers are shared); its activations are zeroed.
@@ -505,7 +527,7 @@ __global__ __launch_bounds__(kThreads, 1) void linear_mfma_bf16_kernel(const uin
         asm volatile("" : "+s"(src));   // one scalar base, so that the lane offset stays a 32-bit register
         unsigned char *dst = lds_grp + (v & (kNB - 1)) * kStageBytes + wn * (kStageBytes / 2);
         stage_load<0>(src, a_off, dst);
-        load_window<BK>(P, tile, pos, wreg[slot], wpos[slot]);
+        load_window_one<BK>(P, tile, pos, wreg[slot], wpos[slot]);
     };
     auto load_stage_any = [&](int slot, int32_t v) {
         const int32_t k0 = (v * kKG + grp) * BK;
@@ -521,7 +543,7 @@ __global__ __launch_bounds__(kThreads, 1) void linear_mfma_bf16_kernel(const uin
             c = c < P.in - 8 ? c : P.in - 8;
             __builtin_amdgcn_global_load_lds(x_blk + (a_row[j] + static_cast<uint32_t>(c) * 2u), dst + j * 1024, 16, 0, 0);
         }
-        load_window<BK>(P, tile, pos, wreg[slot], wpos[slot]);
+        load_window_one<BK>(P, tile, pos, wreg[slot], wpos[slot]);
     };
     // Zeroes the part of stage v that lies past the end of K (its loads are waited for first).
     auto zero_tail = [&](int32_t v) {
@@ -613,11 +635,12 @@ __global__ __launch_bounds__(kThreads, 1) void linear_mfma_bf16_kernel(const uin
         const unsigned char *src = x_blk - kBias + static_cast<uint32_t>(k0) * 2u;   // wave-uniform
         asm volatile("" : "+s"(src));   // one scalar base, so that the lane offset stays a 32-bit register
         unsigned char *dst = lds_grp + (vl & (kNB - 1)) * kStageBytes + wn * (kStageBytes / 2);
+        uint32_t own[WW];   // this lane half's window of stage st + 1, before the halves trade
 #pragma unroll
         for (int ks = 0; ks < KS; ++ks) {
-            // One LDS read or wave-load after an MFMA: each of them holds the wave's instruction issue
-            // for about as long as an MFMA runs, so they must not come in runs.  The fences keep the
-            // compiler from regrouping them.
+            // A wave issues one instruction every four cycles at best, an MFMA runs for 32: between two
+            // MFMAs there is room for a handful of other instructions, and LDS reads and wave-loads must
+            // not come in runs.  The fences keep the compiler from regrouping the work.
             const int cur = ks & 1, nx = cur ^ 1;
             const uint32_t rbase = (ks + 1 < KS ? base : base_next) + a_rd[(ks + 1) % KS];
             const uint32_t sel = byte_sel[(ks + 1) % KS];
@@ -649,10 +672,11 @@ __global__ __launch_bounds__(kThreads, 1) void linear_mfma_bf16_kernel(const uin
             if (ks == 3) stage_load_one<6>(src, a_off, dst);
             __builtin_amdgcn_sched_barrier(0);
             mfma(2, 1);
-            // the windows of stage st + 1 (this stage's last operands were expanded in step 2) and the
-            // window loads of stage st + 3: one column here, the other after the step's last MFMA
-            if (ks == KS - 2) form_window_one<BK>(P, wreg[(d + 1) % D][0], wpos[(d + 1) % D][0], head, win[0]);
-            if (ks == KS - 1) load_window_one<BK>(P, tile, pos[0], wreg[d][0], wpos[d][0]);
+            // the window of stage st + 1 (this stage's last operands were expanded in step 2): this lane
+            // half's column here, the trade with the other half after the step's last MFMA; in the last
+            // step the window load of stage st + 3
+            if (ks == KS - 2) form_window_one<BK>(P, wreg[(d + 1) % D], wpos[(d + 1) % D], head, own);
+            if (ks == KS - 1) load_window_one<BK>(P, tile, pos, wreg[d], wpos[d]);
             __builtin_amdgcn_sched_barrier(0);
             mfma(3, 0);
             if (ks == 0) stage_load_one<1>(src, a_off, dst);
@@ -661,8 +685,7 @@ __global__ __launch_bounds__(kThreads, 1) void linear_mfma_bf16_kernel(const uin
             if (ks == 3) stage_load_one<7>(src, a_off, dst);
             __builtin_amdgcn_sched_barrier(0);
             mfma(3, 1);
-            if (ks == KS - 2) form_window_one<BK>(P, wreg[(d + 1) % D][1], wpos[(d + 1) % D][1], head, win[1]);
-            if (ks == KS - 1) load_window_one<BK>(P, tile, pos[1], wreg[d][1], wpos[d][1]);
+            if (ks == KS - 2) share_window<BK>(own, win);
             __builtin_amdgcn_sched_barrier(0);
         }
     };
@@ -675,7 +698,7 @@ __global__ __launch_bounds__(kThreads, 1) void linear_mfma_bf16_kernel(const uin
         if (d < n_stages) load_stage_any(d, d);
     __builtin_amdgcn_s_waitcnt(vmcnt_imm(0));
     zero_tail(0);
-    form_window<BK>(P, wreg[0], wpos[0], head, win);
+    form_windows(0);
     meet(true);   // stage 0 is readable
 
     int32_t st0 = 0;
@@ -707,7 +730,7 @@ __global__ __launch_bounds__(kThreads, 1) void linear_mfma_bf16_kernel(const uin
                 }
                 if (st + D < n_stages) load_stage_any(d, st + D);
                 multiply_plain(st);
-                if (st + 1 < n_stages) form_window<BK>(P, wreg[(d + 1) % D], wpos[(d + 1) % D], head, win);
+                if (st + 1 < n_stages) form_windows((d + 1) % D);
             }
         }
     }
