@@ -257,19 +257,25 @@ __device__ __forceinline__ void expand_operand(uint32_t win_lo, uint32_t win_hi,
     }
 }
 
-// Registers 2h and 2h + 1 of the same operand (so that the work can be spread between MFMAs).
-__device__ __forceinline__ void expand_operand_half(uint32_t win_lo, uint32_t win_hi, uint32_t byte_sel, uint32_t sign_mask,
-                                                    uint32_t one_bits, int h, Frag &b) {
-    const uint32_t rep = __builtin_amdgcn_perm(win_hi, win_lo, byte_sel);
+// The byte of the (inverted) window that a lane expands in one MFMA step, four times.
+__device__ __forceinline__ uint32_t window_byte(uint32_t win_lo, uint32_t win_hi, uint32_t byte_sel) {
+    return __builtin_amdgcn_perm(win_hi, win_lo, byte_sel);
+}
+// Registers 2h and 2h + 1 of the operand (so that the work can be spread between MFMAs).  Both shifts
+// come before both merges: the result of a packed shift cannot be read by the very next instruction.
+__device__ __forceinline__ void expand_operand_half(uint32_t rep, uint32_t sign_mask, uint32_t one_bits, int h, Frag &b) {
     const u16x2_t r2 = __builtin_bit_cast(u16x2_t, rep);
+    uint32_t s[2];
 #pragma unroll
-    for (int v = 2 * h; v < 2 * h + 2; ++v) {
+    for (int i = 0; i < 2; ++i) {
+        const int v = 2 * h + i;
         const u16x2_t sh = {static_cast<uint16_t>(15 - 2 * v), static_cast<uint16_t>(14 - 2 * v)};
-        const uint32_t s = __builtin_bit_cast(uint32_t, static_cast<u16x2_t>(r2 << sh));
-        uint32_t r = (s & sign_mask) | one_bits;
-        asm volatile("" : "+v"(r));   // computed here, between these MFMAs, not wherever its first use is
-        b.q[v] = r;
+        s[i] = __builtin_bit_cast(uint32_t, static_cast<u16x2_t>(r2 << sh));
     }
+    uint32_t r0 = (s[0] & sign_mask) | one_bits, r1 = (s[1] & sign_mask) | one_bits;
+    asm volatile("" : "+v"(r0), "+v"(r1));   // computed here, between these MFMAs, not wherever the first use is
+    b.q[2 * h] = r0;
+    b.q[2 * h + 1] = r1;
 }
 
 // Adds the other K group's partial sums: accumulator index tm of group g stands for row block
@@ -433,6 +439,13 @@ template <int OFF>
 __device__ __forceinline__ void lds_read16(u32x4_t &dst, uint32_t addr) {
     asm volatile("ds_read_b128 %0, %1 offset:%2" : "=v"(dst) : "v"(addr), "n"(OFF));
 }
+// The same, and `after` is handed through: what is computed from it comes after the read.  (The compiler
+// pads its own hazard waits around every assembly statement, so the statement goes first and the
+// arithmetic follows in one run.)
+template <int OFF>
+__device__ __forceinline__ void lds_read16_then(u32x4_t &dst, uint32_t addr, uint32_t &after) {
+    asm volatile("ds_read_b128 %0, %2 offset:%3" : "=v"(dst), "+v"(after) : "v"(addr), "n"(OFF));
+}
 template <int N>
 __device__ __forceinline__ void lds_wait(Frag (&a)[kTM]) {   // at most N younger LDS operations pending
     static_assert(kTM == 4, "four operand fragments");
@@ -510,8 +523,8 @@ __global__ __launch_bounds__(kThreads, 1) void linear_mfma_bf16_kernel(const uin
     for (int j = 0; j < WW; ++j) head[j] = tile[j];
 
     constexpr int D = kNB - 1;   // stages in flight
-    uint32_t wreg[D][WW + 1];
-    uint32_t wpos[D];
+    uint32_t wreg[kNB][WW + 1];   // slot = stage % kNB, like the LDS buffers
+    uint32_t wpos[kNB];
     uint32_t win[kTN][WW];
     auto form_windows = [&](int slot) {
         uint32_t own[WW];
@@ -615,79 +628,90 @@ __global__ __launch_bounds__(kThreads, 1) void linear_mfma_bf16_kernel(const uin
         }
     };
 
-    // Steady-state round st (ring slot d = st % D).  On entry the operands of its first step are in
-    // pa[0] / pb[0], requested during the round before; stages st + 1 .. st + 3 lie inside K.
+    // Steady-state round st; D_ = st % kNB names its LDS buffer and ring slot.  On entry the operands of
+    // its first step are in pa[0] / pb[0], requested during the round before; stages st + 1 .. st + 3 lie
+    // inside K.
     //   * the round opens with the meeting that makes stage st + 1 readable (its loads were issued two
     //     rounds ago) and frees the buffer of stage st - 1 for the loads of stage st + 3;
     //   * those loads are spread between the MFMAs, two per step, so that neither this wave nor the CU's
     //     load path sees them as a burst;
     //   * step ks requests the operands of step ks + 1, the last step those of stage st + 1's first
     //     step; the tile windows of stage st + 1 are formed once step 3's operands exist.
+    // Buffer numbers and steps are compile-time constants, so every LDS address is a register that
+    // never changes plus an immediate offset.
     Frag pa[2][kTM];
     Frag pb[2][kTN];
-    auto steady_round = [&](int32_t st, int d) {
+    uint32_t a_rdg[KS];   // operand read addresses inside the group's first buffer
+#pragma unroll
+    for (int ks = 0; ks < KS; ++ks) a_rdg[ks] = lds_grp_addr + a_rd[ks];
+    unsigned char *lds_wave = lds_grp + wn * (kStageBytes / 2);   // where this wave's loads of buffer 0 go
+    auto steady_round = [&](auto d_c, int32_t st) {
+        constexpr int D_ = decltype(d_c)::value;
+        constexpr int kBufNext = (D_ + 1) & (kNB - 1), kBufLoad = (D_ + D) & (kNB - 1);
         __builtin_amdgcn_s_waitcnt(vmcnt_imm(kVmPerStage));   // only the loads of stage st + 2 may be in flight
         meet(false);
-        const uint32_t base = lds_grp_addr + static_cast<uint32_t>((st & (kNB - 1)) * kStageBytes);
-        const uint32_t base_next = lds_grp_addr + static_cast<uint32_t>(((st + 1) & (kNB - 1)) * kStageBytes);
-        const int32_t vl = st + D;
-        const int32_t k0 = (vl * kKG + grp) * BK;
+        const int32_t k0 = ((st + D) * kKG + grp) * BK;
         const unsigned char *src = x_blk - kBias + static_cast<uint32_t>(k0) * 2u;   // wave-uniform
-        asm volatile("" : "+s"(src));   // one scalar base, so that the lane offset stays a 32-bit register
-        unsigned char *dst = lds_grp + (vl & (kNB - 1)) * kStageBytes + wn * (kStageBytes / 2);
+        asm volatile("" : "+s"(src));   // one scalar base
+        unsigned char *dst = lds_wave + kBufLoad * kStageBytes;
+        // The lane offsets are widened to 64 bits inside the round (not once, outside the loop), which lets
+        // the wave-loads take them as 32-bit offsets to the scalar base.
+        asm volatile("" : "+v"(a_off[0]), "+v"(a_off[1]), "+v"(a_off[2]), "+v"(a_off[3]), "+v"(a_off[4]), "+v"(a_off[5]),
+                          "+v"(a_off[6]), "+v"(a_off[7]));
         uint32_t own[WW];   // this lane half's window of stage st + 1, before the halves trade
-#pragma unroll
-        for (int ks = 0; ks < KS; ++ks) {
+        auto step = [&](auto ks_c) {
             // A wave issues one instruction every four cycles at best, an MFMA runs for 32: between two
             // MFMAs there is room for a handful of other instructions, and LDS reads and wave-loads must
             // not come in runs.  The fences keep the compiler from regrouping the work.
-            const int cur = ks & 1, nx = cur ^ 1;
-            const uint32_t rbase = (ks + 1 < KS ? base : base_next) + a_rd[(ks + 1) % KS];
-            const uint32_t sel = byte_sel[(ks + 1) % KS];
+            constexpr int ks = decltype(ks_c)::value;
+            constexpr int cur = ks & 1, nx = cur ^ 1, ksn = (ks + 1) % KS;
+            constexpr int kRd = (ks + 1 < KS ? D_ : kBufNext) * kStageBytes;   // buffer of the operands requested here
+            const uint32_t raddr = a_rdg[ksn];
+            uint32_t rep;
             auto mfma = [&](int tm, int tn) {
                 acc[tm][tn] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(pa[cur][tm].v, pb[cur][tn].v, acc[tm][tn], 0, 0, 0);
             };
             lds_wait2<2>(pa[cur][0], pa[cur][1]);   // of the four reads of the step before, the first two are back
             mfma(0, 0);
-            lds_read16<0 * 32 * kRowBytes>(pa[nx][0].q, rbase);
-            expand_operand_half(win[0][0], win[0][WW - 1], sel, sign_mask, one_bits, 0, pb[nx][0]);
+            lds_read16_then<kRd + 0 * 32 * kRowBytes>(pa[nx][0].q, raddr, byte_sel[ksn]);
+            rep = window_byte(win[0][0], win[0][WW - 1], byte_sel[ksn]);
+            expand_operand_half(rep, sign_mask, one_bits, 0, pb[nx][0]);
             __builtin_amdgcn_sched_barrier(0);
             mfma(0, 1);
-            lds_read16<1 * 32 * kRowBytes>(pa[nx][1].q, rbase);
-            expand_operand_half(win[0][0], win[0][WW - 1], sel, sign_mask, one_bits, 1, pb[nx][0]);
+            lds_read16<kRd + 1 * 32 * kRowBytes>(pa[nx][1].q, raddr);
+            expand_operand_half(rep, sign_mask, one_bits, 1, pb[nx][0]);
             __builtin_amdgcn_sched_barrier(0);
             mfma(1, 0);
-            lds_read16<2 * 32 * kRowBytes>(pa[nx][2].q, rbase);
-            expand_operand_half(win[1][0], win[1][WW - 1], sel, sign_mask, one_bits, 0, pb[nx][1]);
+            lds_read16_then<kRd + 2 * 32 * kRowBytes>(pa[nx][2].q, raddr, byte_sel[ksn]);
+            rep = window_byte(win[1][0], win[1][WW - 1], byte_sel[ksn]);
+            expand_operand_half(rep, sign_mask, one_bits, 0, pb[nx][1]);
             __builtin_amdgcn_sched_barrier(0);
             mfma(1, 1);
-            lds_read16<3 * 32 * kRowBytes>(pa[nx][3].q, rbase);
-            expand_operand_half(win[1][0], win[1][WW - 1], sel, sign_mask, one_bits, 1, pb[nx][1]);
+            lds_read16<kRd + 3 * 32 * kRowBytes>(pa[nx][3].q, raddr);
+            expand_operand_half(rep, sign_mask, one_bits, 1, pb[nx][1]);
             __builtin_amdgcn_sched_barrier(0);
             lds_wait2<4>(pa[cur][2], pa[cur][3]);   // the other two (the four new reads may be pending)
             mfma(2, 0);
-            if (ks == 0) stage_load_one<0>(src, a_off, dst);
-            if (ks == 1) stage_load_one<2>(src, a_off, dst);
-            if (ks == 2) stage_load_one<4>(src, a_off, dst);
-            if (ks == 3) stage_load_one<6>(src, a_off, dst);
+            stage_load_one<2 * ks>(src, a_off, dst);
             __builtin_amdgcn_sched_barrier(0);
             mfma(2, 1);
             // the window of stage st + 1 (this stage's last operands were expanded in step 2): this lane
             // half's column here, the trade with the other half after the step's last MFMA; in the last
             // step the window load of stage st + 3
-            if (ks == KS - 2) form_window_one<BK>(P, wreg[(d + 1) % D], wpos[(d + 1) % D], head, own);
-            if (ks == KS - 1) load_window_one<BK>(P, tile, pos, wreg[d], wpos[d]);
+            if constexpr (ks == KS - 2) form_window_one<BK>(P, wreg[kBufNext], wpos[kBufNext], head, own);
+            if constexpr (ks == KS - 1) load_window_one<BK>(P, tile, pos, wreg[kBufLoad], wpos[kBufLoad]);
             __builtin_amdgcn_sched_barrier(0);
             mfma(3, 0);
-            if (ks == 0) stage_load_one<1>(src, a_off, dst);
-            if (ks == 1) stage_load_one<3>(src, a_off, dst);
-            if (ks == 2) stage_load_one<5>(src, a_off, dst);
-            if (ks == 3) stage_load_one<7>(src, a_off, dst);
+            stage_load_one<2 * ks + 1>(src, a_off, dst);
             __builtin_amdgcn_sched_barrier(0);
             mfma(3, 1);
-            if (ks == KS - 2) share_window<BK>(own, win);
+            if constexpr (ks == KS - 2) share_window<BK>(own, win);
             __builtin_amdgcn_sched_barrier(0);
-        }
+        };
+        step(std::integral_constant<int, 0>{});
+        step(std::integral_constant<int, 1>{});
+        step(std::integral_constant<int, 2>{});
+        step(std::integral_constant<int, 3>{});
     };
     static_assert(KS == 4 && kLoads == 8, "two wave-loads per MFMA step");
 
@@ -702,24 +726,26 @@ __global__ __launch_bounds__(kThreads, 1) void linear_mfma_bf16_kernel(const uin
     meet(true);   // stage 0 is readable
 
     int32_t st0 = 0;
-    if (2 * D <= n_full) {   // the steady loop runs: request the first operands
+    if (kNB + D <= n_full) {   // the steady loop runs: request the first operands
         read_frags(pa[0], lds_grp_addr, 0);
 #pragma unroll
         for (int tn = 0; tn < kTN; ++tn)
             expand_operand(win[tn][0], win[tn][WW - 1], byte_sel[0], sign_mask, one_bits, pb[0][tn]);
     }
-    for (; st0 + 2 * D <= n_full; st0 += D) {
-#pragma unroll
-        for (int d = 0; d < D; ++d) steady_round(st0 + d, d);
+    for (; st0 + kNB + D <= n_full; st0 += kNB) {
+        steady_round(std::integral_constant<int, 0>{}, st0);
+        steady_round(std::integral_constant<int, 1>{}, st0 + 1);
+        steady_round(std::integral_constant<int, 2>{}, st0 + 2);
+        steady_round(std::integral_constant<int, 3>{}, st0 + 3);
     }
     // The last steady round has requested operands nobody will use: let them land before their
     // registers can be given to anything else.
     if (st0 > 0) lds_wait<0>(pa[0]);
-    // Drain: st0 is a multiple of D, so slot numbers stay static.  Every round opens with the meeting
+    // Drain: st0 is a multiple of kNB, so slot numbers stay static.  Every round opens with the meeting
     // that makes stage st + 1 readable; `win` holds the windows of stage st on entry.
-    for (; st0 < n_stages; st0 += D) {
+    for (; st0 < n_stages; st0 += kNB) {
 #pragma unroll
-        for (int d = 0; d < D; ++d) {
+        for (int d = 0; d < kNB; ++d) {
             const int32_t st = st0 + d;
             if (st < n_stages) {   // uniform
                 if (st + 1 < n_stages) {
@@ -728,9 +754,9 @@ __global__ __launch_bounds__(kThreads, 1) void linear_mfma_bf16_kernel(const uin
                     zero_tail(st + 1);
                     meet(true);
                 }
-                if (st + D < n_stages) load_stage_any(d, st + D);
+                if (st + D < n_stages) load_stage_any((d + D) & (kNB - 1), st + D);
                 multiply_plain(st);
-                if (st + 1 < n_stages) form_windows((d + 1) % D);
+                if (st + 1 < n_stages) form_windows((d + 1) & (kNB - 1));
             }
         }
     }
