@@ -671,7 +671,7 @@ __global__ __launch_bounds__(kThreads, 1) void linear_mfma_bf16_kernel(const uin
             auto mfma = [&](int tm, int tn) {
                 acc[tm][tn] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(pa[cur][tm].v, pb[cur][tn].v, acc[tm][tn], 0, 0, 0);
             };
-            lds_wait2<2>(pa[cur][0], pa[cur][1]);   // of the four reads of the step before, the first two are back
+            lds_wait<0>(pa[cur]);   // the four reads of the step before (the last was issued five MFMAs ago)
             mfma(0, 0);
             lds_read16_then<kRd + 0 * 32 * kRowBytes>(pa[nx][0].q, raddr, byte_sel[ksn]);
             rep = window_byte(win[0][0], win[0][WW - 1], byte_sel[ksn]);
@@ -690,7 +690,6 @@ __global__ __launch_bounds__(kThreads, 1) void linear_mfma_bf16_kernel(const uin
             lds_read16<kRd + 3 * 32 * kRowBytes>(pa[nx][3].q, raddr);
             expand_operand_half(rep, sign_mask, one_bits, 1, pb[nx][1]);
             __builtin_amdgcn_sched_barrier(0);
-            lds_wait2<4>(pa[cur][2], pa[cur][3]);   // the other two (the four new reads may be pending)
             mfma(2, 0);
             stage_load_one<2 * ks>(src, a_off, dst);
             __builtin_amdgcn_sched_barrier(0);
