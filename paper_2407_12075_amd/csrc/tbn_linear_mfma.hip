@@ -154,7 +154,7 @@ template <> struct WordVec<3> { typedef uint32_t type __attribute__((ext_vector_
 // Issues the load of the WW + 1 tile words that hold the BK window bits from pos on, and moves pos to
 // the group's next stage.  Near the tile end the load starts earlier so that it stays inside the tile
 // (n_words >= WW + 1); wpos keeps the window's cyclic position.
-template <int BK>
+template <int BK, int STEP = kKG * BK>
 __device__ __forceinline__ void load_window_one(const MfmaParams &P, const uint32_t *__restrict__ tile, uint32_t &pos,
                                                 uint32_t (&wreg)[BK / 32 + 1], uint32_t &wpos) {
     constexpr int NW = BK / 32 + 1;
@@ -166,7 +166,7 @@ __device__ __forceinline__ void load_window_one(const MfmaParams &P, const uint3
 #pragma unroll
     for (int j = 0; j < NW; ++j) wreg[j] = v[j];
     wpos = pos;
-    pos += kKG * BK;   // p >= kKG * BK
+    pos += STEP;   // the group's next stage; p >= STEP
     if (pos >= static_cast<uint32_t>(P.p)) pos -= static_cast<uint32_t>(P.p);
 }
 template <int BK>
@@ -278,28 +278,28 @@ __device__ __forceinline__ void expand_operand_half(uint32_t rep, uint32_t sign_
     b.q[2 * h + 1] = r1;
 }
 
-// Adds the other K group's partial sums: accumulator index tm of group g stands for row block
-// (tm + 2g) % 4, so both groups keep acc[0..1] and hand over acc[2..3] with the same register
-// indices; afterwards acc[0..1] of wave (g, h) hold rows 64g .. 64g + 63 of column half h.
-__device__ __forceinline__ void exchange_partials(f32x16_t (&acc)[kTM][kTN], unsigned char *lds_raw, int wave, int lane) {
-    __syncthreads();   // all waves are done with the staging buffers
-    float *red = reinterpret_cast<float *>(lds_raw);
-    constexpr int kSlotFloats = kTmOut * kTN * 16 * 64;   // per wave
-    float *dst = red + (wave ^ 2) * kSlotFloats + lane * 4;    // the partner's slot
+// Adds up the K groups' partial sums through LDS.  Accumulator index tm of group g stands for row block
+// (tm + (4/KG)*g) % 4, so every group ends up with the finished sums of its row blocks in its first
+// accumulators.  Two groups: each hands acc[2..3] to the other.  Four groups: first g and g ^ 2 trade
+// acc[2..3] (added to the partner's acc[0..1]), then g hands acc[1] to g + 1 (added to its acc[0]).
+template <int NT>
+__device__ __forceinline__ void hand_over(f32x16_t (&acc)[kTM][kTN], float *red, int from_tm, int to_wave, int wave, int lane) {
+    constexpr int kSlotFloats = NT * kTN * 16 * 64;   // per wave
+    float *dst = red + to_wave * kSlotFloats + lane * 4;
 #pragma unroll
-    for (int tm = 0; tm < kTmOut; ++tm)
+    for (int tm = 0; tm < NT; ++tm)
 #pragma unroll
         for (int tn = 0; tn < kTN; ++tn)
 #pragma unroll
             for (int q = 0; q < 4; ++q) {
-                const f32x16_t &s = acc[kTmOut + tm][tn];
+                const f32x16_t &s = acc[from_tm + tm][tn];
                 *reinterpret_cast<f32x4_t *>(dst + ((tm * kTN + tn) * 4 + q) * 256) =
                     f32x4_t{s[4 * q], s[4 * q + 1], s[4 * q + 2], s[4 * q + 3]};
             }
     __syncthreads();
     const float *src = red + wave * kSlotFloats + lane * 4;
 #pragma unroll
-    for (int tm = 0; tm < kTmOut; ++tm)
+    for (int tm = 0; tm < NT; ++tm)
 #pragma unroll
         for (int tn = 0; tn < kTN; ++tn)
 #pragma unroll
@@ -311,10 +311,22 @@ __device__ __forceinline__ void exchange_partials(f32x16_t (&acc)[kTM][kTN], uns
                 acc[tm][tn][4 * q + 3] += v[3];
             }
 }
+template <int KG>
+__device__ __forceinline__ void exchange_partials(f32x16_t (&acc)[kTM][kTN], unsigned char *lds_raw, int wave, int lane) {
+    float *red = reinterpret_cast<float *>(lds_raw);
+    __syncthreads();   // all waves are done with the staging buffers
+    if constexpr (KG == 2) {
+        hand_over<2>(acc, red, 2, wave ^ 2, wave, lane);
+    } else {
+        hand_over<2>(acc, red, 2, wave ^ 4, wave, lane);
+        __syncthreads();   // everybody has read its slot
+        hand_over<1>(acc, red, 1, (wave + 2) & 7, wave, lane);
+    }
+}
 
-// Epilogue: y[m, u + t*U] = alpha(u + t*U) * Z[m, u] from acc[0..1] (rows 64*grp + 32*tm + 8*(e/4) +
-// 4*lg + e%4 of the block, columns b_col, b_col + 1).
-template <typename XT, bool RELU>
+// Epilogue: y[m, u + t*U] = alpha(u + t*U) * Z[m, u] from acc[0..TMOUT-1] (rows 32*TMOUT*grp + 32*tm +
+// 8*(e/4) + 4*lg + e%4 of the block, columns b_col, b_col + 1).
+template <typename XT, bool RELU, int TMOUT>
 __device__ __forceinline__ void write_output(const f32x16_t (&acc)[kTM][kTN], const MfmaParams &P, XT *__restrict__ y,
                                              const float *__restrict__ alpha, int64_t m0, int64_t n0, int grp, int lg,
                                              int b_col) {
@@ -344,10 +356,10 @@ __device__ __forceinline__ void write_output(const f32x16_t (&acc)[kTM][kTN], co
                 }
                 const int n_here = (reps_all - t0) < kChunk ? (reps_all - t0) : kChunk;
 #pragma unroll
-                for (int tm = 0; tm < kTmOut; ++tm) {
+                for (int tm = 0; tm < TMOUT; ++tm) {
 #pragma unroll
                     for (int e = 0; e < 16; ++e) {
-                        const int row = grp * kTmOut * 32 + tm * 32 + 8 * (e >> 2) + (e & 3);   // + 4*lg
+                        const int row = grp * TMOUT * 32 + tm * 32 + 8 * (e >> 2) + (e & 3);   // + 4*lg
                         if (!FULL && row + 4 * lg >= rows_left) continue;
                         unsigned char *dst =
                             y_blk + (int64_t(row) * P.out + int64_t(t0) * P.U) * static_cast<int64_t>(sizeof(XT));
@@ -379,7 +391,7 @@ __device__ __forceinline__ void write_output(const f32x16_t (&acc)[kTM][kTN], co
     }
     if (u_base >= P.U) return;
     const bool pair_ok = (u_base + 1 < P.U);
-    const int64_t m_wave = m0 + grp * kTmOut * 32 + 4 * lg;
+    const int64_t m_wave = m0 + grp * TMOUT * 32 + 4 * lg;
     const int64_t reps = (P.out - u_base + P.U - 1) / P.U;   // replicas of column u_base
 
     // general case (odd sizes, or tile ends inside rows so that alpha(o) = alpha[(o*in) / p] differs
@@ -395,7 +407,7 @@ __device__ __forceinline__ void write_output(const f32x16_t (&acc)[kTM][kTN], co
             al1 = ok1 ? alpha[(o1 * P.in) / P.p] : 0.f;
         }
 #pragma unroll
-        for (int tm = 0; tm < kTmOut; ++tm) {
+        for (int tm = 0; tm < TMOUT; ++tm) {
 #pragma unroll
             for (int e = 0; e < 16; ++e) {
                 const int64_t m = m_wave + tm * 32 + 8 * (e >> 2) + (e & 3);
@@ -420,17 +432,37 @@ __device__ __forceinline__ void write_output(const f32x16_t (&acc)[kTM][kTN], co
 // =====================================================================================================
 namespace direct {
 
-constexpr int BK = 64;                         // K elements per stage
-constexpr int KS = BK / 16;                    // MFMA steps per stage
-constexpr int WW = BK / 32;                    // 32-bit window words per stage
 constexpr int kNB = 4;                         // LDS stage buffers per K group
-constexpr int kRowBytes = BK * 2;              // 128, unpadded
-constexpr int kStageBytes = kBM * kRowBytes;   // 16 KiB
-constexpr int kLoads = kStageBytes / (kGroupThreads / 64) / 1024;   // 1 KiB wave-loads per wave and stage: 8
-constexpr int kVmPerStage = kLoads + 1;                           // vector-memory instructions per stage
-constexpr int kLdsBytes = kKG * kNB * kStageBytes;                   // 128 KiB
-static_assert(kLdsBytes >= kExchangeBytes, "the exchange reuses the stage buffers");
 constexpr int kBias = 3 * 1024;                // keeps the lane offsets non-negative, see below
+
+// The kernel exists with two K groups of two waves (one wave per SIMD) and with four K groups of two
+// waves (two waves per SIMD, which hides one wave's instruction issue and waits behind the other's
+// MFMAs).  A stage of a group is 128 / KG elements of K, so that both forms move through K at the same
+// pace and use the same 128 KiB of LDS.
+template <int KG>
+struct Cfg {
+    static constexpr int kThreads = KG * 128;
+    static constexpr int BK = 128 / KG;                  // K elements per stage
+    static constexpr int KS = BK / 16;                   // MFMA steps per stage
+    static constexpr int WW = (BK + 31) / 32;            // 32-bit window words per stage
+    static constexpr int kRowBytes = BK * 2;             // unpadded
+    static constexpr int kSwz = kRowBytes / 16 - 1;      // chunk swizzle mask
+    static constexpr int kSwzShift = KG == 2 ? 1 : 2;    // row bits that drive the swizzle start here
+    // With 64-byte rows two row slots share the 32 banks.  The LDS serves the even and the odd lanes of
+    // 16 in turn, so rows 2i and 2i + 2 must not sit in the same half: row slots trade their two lowest
+    // row bits.
+    static __device__ __host__ constexpr int row_slot(int r) { return KG == 2 ? r : ((r & ~3) | ((r & 1) << 1) | ((r >> 1) & 1)); }
+    static constexpr int kStageBytes = kBM * kRowBytes;
+    static constexpr int kLoads = kStageBytes / 2 / 1024;   // 1 KiB wave-loads per wave and stage
+    static constexpr int kRowsPerLoad = 1024 / kRowBytes;
+    static constexpr int kLanesPerRow = kRowBytes / 16;
+    static constexpr int kVmPerStage = kLoads + 1;       // vector-memory instructions per stage
+    static constexpr int kLdsBytes = KG * kNB * kStageBytes;   // 128 KiB
+    static constexpr int kRot = kTM / KG;                // row blocks a group keeps at the end
+    static_assert(KG == 2 || KG == 4, "two or four K groups");
+    static_assert(kLoads == 2 * KS, "two wave-loads per MFMA step");
+    static_assert(kLdsBytes == 131072, "LDS budget");
+};
 
 // Operand reads are written as inline assembly so that the compiler does not see LDS reads next to the
 // asynchronous global -> LDS loads (it would make every read wait for all of those loads).  The
@@ -457,22 +489,24 @@ __device__ __forceinline__ void lds_wait2(Frag &a0, Frag &a1) {   // at most N y
     asm volatile("s_waitcnt lgkmcnt(%2)" : "+v"(a0.q), "+v"(a1.q) : "n"(N));
 }
 
+// One 16-byte-per-lane load from global memory straight into LDS (lane i's bytes land at lds + 16*i).
+__device__ __forceinline__ void load_to_lds16(const unsigned char *gptr, unsigned char *lds) {
+    __builtin_amdgcn_global_load_lds(gptr, lds, 16, 0, 0);
+}
 // Wave-load J of a stage (the immediate offset has to be a compile-time constant).
 template <int J>
-__device__ __forceinline__ void stage_load_one(const unsigned char *src, const uint32_t (&a_off)[kLoads], unsigned char *dst) {
-    __builtin_amdgcn_global_load_lds(src + a_off[J], dst + (J >> 2) * 4096, 16, (J & 3) * 1024, 0);
-}
-template <int J>
-__device__ __forceinline__ void stage_load(const unsigned char *src, const uint32_t (&a_off)[kLoads], unsigned char *dst) {
-    stage_load_one<J>(src, a_off, dst);
-    if constexpr (J + 1 < kLoads) stage_load<J + 1>(src, a_off, dst);
+__device__ __forceinline__ void stage_load_one(const unsigned char *src, uint32_t off, unsigned char *dst) {
+    __builtin_amdgcn_global_load_lds(src + off, dst + (J >> 2) * 4096, 16, (J & 3) * 1024, 0);
 }
 
-template <bool RELU>
-__global__ __launch_bounds__(kThreads, 1) void linear_mfma_bf16_kernel(const uint16_t *__restrict__ x,
+template <int KG, bool RELU>
+__global__ __launch_bounds__(Cfg<KG>::kThreads, 1) void linear_mfma_bf16_kernel(const uint16_t *__restrict__ x,
                                                                           uint16_t *__restrict__ y,
                                                                           const uint32_t *__restrict__ tile,
                                                                           const float *__restrict__ alpha, MfmaParams P) {
+    typedef Cfg<KG> C;
+    constexpr int BK = C::BK, KS = C::KS, WW = C::WW, kRowBytes = C::kRowBytes, kStageBytes = C::kStageBytes;
+    constexpr int kLoads = C::kLoads, kVmPerStage = C::kVmPerStage, kKG = KG;
     extern __shared__ __attribute__((aligned(1024))) unsigned char lds_raw[];
     const int tid = threadIdx.x;
     const int lane = tid & 63;
@@ -489,12 +523,12 @@ __global__ __launch_bounds__(kThreads, 1) void linear_mfma_bf16_kernel(const uin
     const int64_t n0 = int64_t(tile_n) * kBN;
 
     // ---- activation loads ---------------------------------------------------------------------------
-    // Wave-load j of a wave fills the 1 KiB of LDS that holds row slots 8q .. 8q + 7 (q = 8*wn + j) of
-    // the stage: lane i writes bytes 16*i .. 16*i + 15 of it, i.e. row slot sr = 8q + i/8, chunk slot
-    // i%8.  Row slot block sr/32 holds row block (sr/32 + 2*grp) % 4 of X (both K groups then keep
-    // accumulators 0..1 at the end), and chunk slot s of row slot sr holds 16-byte chunk
-    // s ^ ((sr >> 1) & 7) of the stage's 128 bytes of that row.  Rows past M are clamped to row M-1
-    // (their results are never written).
+    // Wave-load j of a wave fills 1 KiB of LDS, piece q = kLoads*wn + j of the stage: lane i writes bytes
+    // 16*i .. 16*i + 15 of it, i.e. row slot sr = kRowsPerLoad*q + i/kLanesPerRow, chunk slot
+    // i%kLanesPerRow.  Row slot block sr/32 holds row block (sr/32 + kRot*grp) % 4 of X (every K group then
+    // keeps its first accumulators at the end), and chunk slot s of row slot sr holds 16-byte chunk
+    // s ^ ((sr >> kSwzShift) & kSwz) of the stage's bytes of that row, which keeps the operand reads free of
+    // bank conflicts (with 64-byte rows the row slots are permuted as well, see Cfg::row_slot).  Rows past M are clamped to row M-1 (their results are never written).
     // The instruction's immediate offset is added to the LDS address and to the global address alike;
     // loads j = 0..3 and 4..7 share an LDS base and differ in that offset, which the per-lane global
     // offset takes back out; kBias, subtracted from the scalar base instead, keeps it non-negative.
@@ -504,11 +538,11 @@ __global__ __launch_bounds__(kThreads, 1) void linear_mfma_bf16_kernel(const uin
     int a_chunk[kLoads];
 #pragma unroll
     for (int j = 0; j < kLoads; ++j) {
-        const int sr = 8 * (8 * wn + j) + (lane >> 3);
-        const int r = ((((sr >> 5) + 2 * grp) & 3) << 5) + (sr & 31);
+        const int sr = C::kRowsPerLoad * (kLoads * wn + j) + lane / C::kLanesPerRow;
+        const int r = ((((sr >> 5) + C::kRot * grp) & 3) << 5) + C::row_slot(sr & 31);   // row_slot is its own inverse
         const int64_t last = P.M - 1 - m0;
         const uint32_t rr = static_cast<uint32_t>(r < last ? r : last);
-        a_chunk[j] = (lane & 7) ^ ((sr >> 1) & 7);
+        a_chunk[j] = (lane % C::kLanesPerRow) ^ ((sr >> C::kSwzShift) & C::kSwz);
         a_row[j] = rr * static_cast<uint32_t>(P.in) * 2u;
         a_off[j] = a_row[j] + static_cast<uint32_t>(a_chunk[j]) * 16u + kBias - static_cast<uint32_t>((j & 3) * 1024);
     }
@@ -539,8 +573,17 @@ __global__ __launch_bounds__(kThreads, 1) void linear_mfma_bf16_kernel(const uin
         const unsigned char *src = x_blk - kBias + static_cast<uint32_t>(k0) * 2u;   // wave-uniform
         asm volatile("" : "+s"(src));   // one scalar base, so that the lane offset stays a 32-bit register
         unsigned char *dst = lds_grp + (v & (kNB - 1)) * kStageBytes + wn * (kStageBytes / 2);
-        stage_load<0>(src, a_off, dst);
-        load_window_one<BK>(P, tile, pos, wreg[slot], wpos[slot]);
+        stage_load_one<0>(src, a_off[0], dst);
+        stage_load_one<1>(src, a_off[1], dst);
+        stage_load_one<2>(src, a_off[2], dst);
+        stage_load_one<3>(src, a_off[3], dst);
+        if constexpr (kLoads == 8) {
+            stage_load_one<4>(src, a_off[4], dst);
+            stage_load_one<5>(src, a_off[5], dst);
+            stage_load_one<6>(src, a_off[6], dst);
+            stage_load_one<7>(src, a_off[7], dst);
+        }
+        load_window_one<BK, 128>(P, tile, pos, wreg[slot], wpos[slot]);
     };
     auto load_stage_any = [&](int slot, int32_t v) {
         const int32_t k0 = (v * kKG + grp) * BK;
@@ -554,9 +597,9 @@ __global__ __launch_bounds__(kThreads, 1) void linear_mfma_bf16_kernel(const uin
         for (int j = 0; j < kLoads; ++j) {
             int32_t c = k0 + a_chunk[j] * 8;
             c = c < P.in - 8 ? c : P.in - 8;
-            __builtin_amdgcn_global_load_lds(x_blk + (a_row[j] + static_cast<uint32_t>(c) * 2u), dst + j * 1024, 16, 0, 0);
+            load_to_lds16(x_blk + (a_row[j] + static_cast<uint32_t>(c) * 2u), dst + j * 1024);
         }
-        load_window_one<BK>(P, tile, pos, wreg[slot], wpos[slot]);
+        load_window_one<BK, 128>(P, tile, pos, wreg[slot], wpos[slot]);
     };
     // Zeroes the part of stage v that lies past the end of K (its loads are waited for first).
     auto zero_tail = [&](int32_t v) {
@@ -584,10 +627,10 @@ __global__ __launch_bounds__(kThreads, 1) void linear_mfma_bf16_kernel(const uin
 #pragma unroll
             for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.f;
 
-    // operand reads: row slot 32*tm + ln, chunk 2*ks + lg at chunk slot (2*ks + lg) ^ ((ln >> 1) & 7)
+    // operand reads: row 32*tm + ln at its row slot, chunk 2*ks + lg at chunk slot (2*ks + lg) ^ ((ln >> kSwzShift) & kSwz)
     uint32_t a_rd[KS];
 #pragma unroll
-    for (int ks = 0; ks < KS; ++ks) a_rd[ks] = static_cast<uint32_t>(ln * kRowBytes + (((2 * ks + lg) ^ ((ln >> 1) & 7)) << 4));
+    for (int ks = 0; ks < KS; ++ks) a_rd[ks] = static_cast<uint32_t>(C::row_slot(ln) * kRowBytes + (((2 * ks + lg) ^ ((ln >> C::kSwzShift) & C::kSwz)) << 4));
 
     // Operand constants kept in registers (two literals do not fit one instruction).
     uint32_t sign_mask = 0x80008000u, one_bits = 0x3f803f80u;
@@ -636,7 +679,7 @@ __global__ __launch_bounds__(kThreads, 1) void linear_mfma_bf16_kernel(const uin
     //   * those loads are spread between the MFMAs, two per step, so that neither this wave nor the CU's
     //     load path sees them as a burst;
     //   * step ks requests the operands of step ks + 1, the last step those of stage st + 1's first
-    //     step; the tile windows of stage st + 1 are formed once step 3's operands exist.
+    //     step; the tile windows of stage st + 1 are formed once the last step's operands exist.
     // Buffer numbers and steps are compile-time constants, so every LDS address is a register that
     // never changes plus an immediate offset.
     Frag pa[2][kTM];
@@ -656,8 +699,8 @@ __global__ __launch_bounds__(kThreads, 1) void linear_mfma_bf16_kernel(const uin
         unsigned char *dst = lds_wave + kBufLoad * kStageBytes;
         // The lane offsets are widened to 64 bits inside the round (not once, outside the loop), which lets
         // the wave-loads take them as 32-bit offsets to the scalar base.
-        asm volatile("" : "+v"(a_off[0]), "+v"(a_off[1]), "+v"(a_off[2]), "+v"(a_off[3]), "+v"(a_off[4]), "+v"(a_off[5]),
-                          "+v"(a_off[6]), "+v"(a_off[7]));
+        asm volatile("" : "+v"(a_off[0]), "+v"(a_off[1]), "+v"(a_off[2]), "+v"(a_off[3]));
+        if constexpr (kLoads == 8) asm volatile("" : "+v"(a_off[4]), "+v"(a_off[5]), "+v"(a_off[6]), "+v"(a_off[7]));
         uint32_t own[WW];   // this lane half's window of stage st + 1, before the halves trade
         auto step = [&](auto ks_c) {
             // A wave issues one instruction every four cycles at best, an MFMA runs for 32: between two
@@ -691,17 +734,17 @@ __global__ __launch_bounds__(kThreads, 1) void linear_mfma_bf16_kernel(const uin
             expand_operand_half(rep, sign_mask, one_bits, 1, pb[nx][1]);
             __builtin_amdgcn_sched_barrier(0);
             mfma(2, 0);
-            stage_load_one<2 * ks>(src, a_off, dst);
+            stage_load_one<2 * ks>(src, a_off[2 * ks], dst);
             __builtin_amdgcn_sched_barrier(0);
             mfma(2, 1);
-            // the window of stage st + 1 (this stage's last operands were expanded in step 2): this lane
+            // the window of stage st + 1 (this stage's last operands were expanded in this step): this lane
             // half's column here, the trade with the other half after the step's last MFMA; in the last
             // step the window load of stage st + 3
             if constexpr (ks == KS - 2) form_window_one<BK>(P, wreg[kBufNext], wpos[kBufNext], head, own);
-            if constexpr (ks == KS - 1) load_window_one<BK>(P, tile, pos, wreg[kBufLoad], wpos[kBufLoad]);
+            if constexpr (ks == KS - 1) load_window_one<BK, 128>(P, tile, pos, wreg[kBufLoad], wpos[kBufLoad]);
             __builtin_amdgcn_sched_barrier(0);
             mfma(3, 0);
-            stage_load_one<2 * ks + 1>(src, a_off, dst);
+            stage_load_one<2 * ks + 1>(src, a_off[2 * ks + 1], dst);
             __builtin_amdgcn_sched_barrier(0);
             mfma(3, 1);
             if constexpr (ks == KS - 2) share_window<BK>(own, win);
@@ -709,10 +752,11 @@ __global__ __launch_bounds__(kThreads, 1) void linear_mfma_bf16_kernel(const uin
         };
         step(std::integral_constant<int, 0>{});
         step(std::integral_constant<int, 1>{});
-        step(std::integral_constant<int, 2>{});
-        step(std::integral_constant<int, 3>{});
+        if constexpr (KS == 4) {
+            step(std::integral_constant<int, 2>{});
+            step(std::integral_constant<int, 3>{});
+        }
     };
-    static_assert(KS == 4 && kLoads == 8, "two wave-loads per MFMA step");
 
     const int32_t n_stages = ((P.in + BK - 1) / BK + kKG - 1) / kKG;   // virtual stages per group
     const int32_t n_full = P.in / (kKG * BK);                           // of which both groups' lie inside K
@@ -761,8 +805,8 @@ __global__ __launch_bounds__(kThreads, 1) void linear_mfma_bf16_kernel(const uin
     }
     static_assert(D == 3 && kNB == 4, "the wait counts are written for three stages in flight");
 
-    exchange_partials(acc, lds_raw, wave, lane);
-    write_output<uint16_t, RELU>(acc, P, y, alpha, m0, n0, grp, lg, b_col);
+    exchange_partials<KG>(acc, lds_raw, wave, lane);
+    write_output<uint16_t, RELU, C::kRot>(acc, P, y, alpha, m0, n0, grp, lg, b_col);
 }
 
 }  // namespace direct
@@ -965,8 +1009,8 @@ __global__ __launch_bounds__(kThreads, 1) void linear_mfma_f32_kernel(const floa
         }
     }
 
-    exchange_partials(acc, lds_raw, wave, lane);
-    write_output<float, RELU>(acc, P, y, alpha, m0, n0, grp, lg, b_col);
+    exchange_partials<2>(acc, lds_raw, wave, lane);
+    write_output<float, RELU, kTmOut>(acc, P, y, alpha, m0, n0, grp, lg, b_col);
 }
 
 }  // namespace ring
@@ -983,13 +1027,21 @@ tbn_status set_lds_limit(K kernel, int lds, bool &done) {
     return TBN_OK;
 }
 
-template <bool RELU>
+// K groups of the bf16 kernel.  Four groups (two waves per SIMD) pass the same tests but measure about
+// 12 % slower in the main loop: the two waves of a SIMD do not alternate on the matrix pipe.
+#ifndef TBN_BF16_GROUPS
+#define TBN_BF16_GROUPS 2
+#endif
+constexpr int kBf16Groups = TBN_BF16_GROUPS;
+
+template <int KG, bool RELU>
 tbn_status launch_bf16(const LinearArgs &a, const MfmaParams &P, dim3 grid) {
     static bool attr_set = false;
-    tbn_status st = set_lds_limit(&direct::linear_mfma_bf16_kernel<RELU>, direct::kLdsBytes, attr_set);
+    tbn_status st = set_lds_limit(&direct::linear_mfma_bf16_kernel<KG, RELU>, direct::Cfg<KG>::kLdsBytes, attr_set);
     if (st != TBN_OK) return st;
-    hipLaunchKernelGGL((direct::linear_mfma_bf16_kernel<RELU>), grid, dim3(kThreads), direct::kLdsBytes, a.stream,
-                       static_cast<const uint16_t *>(a.x), static_cast<uint16_t *>(a.y), a.tile, a.alpha, P);
+    hipLaunchKernelGGL((direct::linear_mfma_bf16_kernel<KG, RELU>), grid, dim3(direct::Cfg<KG>::kThreads),
+                       direct::Cfg<KG>::kLdsBytes, a.stream, static_cast<const uint16_t *>(a.x),
+                       static_cast<uint16_t *>(a.y), a.tile, a.alpha, P);
     return check_launch("tbn_linear_forward (matrix-core kernel)");
 }
 
@@ -1041,7 +1093,7 @@ tbn_status launch_linear_mfma(const LinearArgs &a) {
     if (a.dt == TBN_F32)
         st = relu ? launch_f32<true>(a, P, grid) : launch_f32<false>(a, P, grid);
     else
-        st = relu ? launch_bf16<true>(a, P, grid) : launch_bf16<false>(a, P, grid);
+        st = relu ? launch_bf16<kBf16Groups, true>(a, P, grid) : launch_bf16<kBf16Groups, false>(a, P, grid);
     if (st != TBN_OK) return st;
     // columns whose weight row straddles a tile end need two alphas
     if (a.n_alpha > 1 && !P.aligned) return launch_linear_tile_ends(a);
