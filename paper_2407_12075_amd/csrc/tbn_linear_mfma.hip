@@ -67,7 +67,7 @@ struct MfmaParams {
     int32_t in, p, n_words;
     int32_t n_alpha;
     int aligned;      // p % in == 0: alpha index of column o is o / U
-    int vec_store;    // adjacent column pairs can be written with one aligned vector store
+    int vec_store;    // groups of eight adjacent columns can be written with aligned 16-byte stores
     int tiles_n;      // column blocks of U
     uint32_t tiles_m;
     int32_t reps_all; // out / U when U divides out, else 0
@@ -94,17 +94,28 @@ __device__ __forceinline__ void split3(float x, uint32_t &t0, uint32_t &t1, uint
 // high halves of two words in one: (lo >> 16) | (hi & 0xffff0000), a single v_perm_b32
 __device__ __forceinline__ uint32_t pack_hi16(uint32_t lo, uint32_t hi) { return __builtin_amdgcn_perm(hi, lo, 0x07060302u); }
 
+// Stores of four adjacent outputs (8-byte aligned bf16, 16-byte aligned float32).
 template <typename OT> struct OutPack;
 template <> struct OutPack<uint16_t> {
-    static __device__ __forceinline__ void store2(uint16_t *p, float a, float b) {
+    static __device__ __forceinline__ uint32_t pack2(float a, float b) {
         const f32x2_t f = {a, b};
-        const bf16x2_t h = __builtin_convertvector(f, bf16x2_t);   // round to nearest even in hardware
-        *reinterpret_cast<bf16x2_t *>(p) = h;
+        return __builtin_bit_cast(uint32_t, __builtin_convertvector(f, bf16x2_t));   // round to nearest even in hardware
+    }
+    static __device__ __forceinline__ void store4(uint16_t *p, const float (&v)[4]) {
+        typedef uint32_t u32x2_t __attribute__((ext_vector_type(2)));
+        *reinterpret_cast<u32x2_t *>(p) = u32x2_t{pack2(v[0], v[1]), pack2(v[2], v[3])};
+    }
+    static __device__ __forceinline__ void store8(uint16_t *p, const float (&v)[8]) {   // 16-byte aligned
+        *reinterpret_cast<u32x4_t *>(p) = u32x4_t{pack2(v[0], v[1]), pack2(v[2], v[3]), pack2(v[4], v[5]), pack2(v[6], v[7])};
     }
 };
 template <> struct OutPack<float> {
-    static __device__ __forceinline__ void store2(float *p, float a, float b) {
-        *reinterpret_cast<f32x2_t *>(p) = f32x2_t{a, b};
+    static __device__ __forceinline__ void store4(float *p, const float (&v)[4]) {
+        *reinterpret_cast<f32x4_t *>(p) = f32x4_t{v[0], v[1], v[2], v[3]};
+    }
+    static __device__ __forceinline__ void store8(float *p, const float (&v)[8]) {   // 16-byte aligned
+        *reinterpret_cast<f32x4_t *>(p) = f32x4_t{v[0], v[1], v[2], v[3]};
+        *reinterpret_cast<f32x4_t *>(p + 4) = f32x4_t{v[4], v[5], v[6], v[7]};
     }
 };
 
@@ -131,19 +142,19 @@ __device__ __forceinline__ void block_coords(const MfmaParams &P, uint32_t &tile
     }
 }
 
-// Cyclic bit positions, at the K group's first stage, of the tile windows of a lane's two adjacent columns.
-template <int BK>
-__device__ __forceinline__ void window_start(const MfmaParams &P, int64_t col0, int grp, uint32_t (&pos)[kTN]) {
-    static_assert(kTN == 2, "two adjacent columns per lane");
-    int64_t u0 = col0;
-    u0 = u0 < P.U ? u0 : P.U - 1;   // columns past U repeat the last one; they are never written
-    pos[0] = mod_u53(static_cast<uint64_t>(u0) * static_cast<uint32_t>(P.in) + static_cast<uint32_t>(grp * BK),
-                     static_cast<uint32_t>(P.p));
-    pos[1] = pos[0];
-    if (u0 + 1 < P.U) {   // the next row starts `in` bits further on (in <= p)
-        pos[1] += static_cast<uint32_t>(P.in);
-        if (pos[1] >= static_cast<uint32_t>(P.p)) pos[1] -= static_cast<uint32_t>(P.p);
-    }
+// The +-1 operand goes into the MFMA as the row operand and the activations as the column operand:
+// a lane then holds, for one row of Y, sixteen columns per 32 x 32 tile (accumulator register e is
+// operand lane 8*(e/4) + 4*lg + e%4).  Operand lane l of tile tn is given column
+// 16*(l/8) + 8*((l/4)%2) + 4*tn + l%4 of the wave's 64, so that registers 4q .. 4q + 3 of the two tiles
+// are the eight adjacent columns 16*q + 8*lg .. + 7: one 16-byte store of bf16 (two of float32).
+__device__ __forceinline__ int wave_col(int l, int tn) { return 16 * (l >> 3) + 8 * ((l >> 2) & 1) + 4 * tn + (l & 3); }
+
+// Cyclic bit position of the tile window of distinct row `col` at K offset k_off (columns past U
+// repeat the last one; they are never written).
+__device__ __forceinline__ uint32_t window_start(const MfmaParams &P, int64_t col, int k_off) {
+    const int64_t u = col < P.U ? col : P.U - 1;
+    return mod_u53(static_cast<uint64_t>(u) * static_cast<uint32_t>(P.in) + static_cast<uint32_t>(k_off),
+                   static_cast<uint32_t>(P.p));
 }
 
 // WW + 1 tile words with one load instruction (dword alignment is all the hardware asks for).
@@ -324,29 +335,78 @@ __device__ __forceinline__ void exchange_partials(f32x16_t (&acc)[kTM][kTN], uns
     }
 }
 
-// Epilogue: y[m, u + t*U] = alpha(u + t*U) * Z[m, u] from acc[0..TMOUT-1] (rows 32*TMOUT*grp + 32*tm +
-// 8*(e/4) + 4*lg + e%4 of the block, columns b_col, b_col + 1).
+// The slot of the last hand-over that only this wave has read: free for the wave's own use afterwards
+// (16 KiB with two K groups, 8 KiB with four).
+template <int KG>
+__device__ __forceinline__ float *stage_slot(unsigned char *lds_raw, int wave) {
+    constexpr int kSlotFloats = (KG == 2 ? 2 : 1) * kTN * 16 * 64;
+    return reinterpret_cast<float *>(lds_raw) + wave * kSlotFloats;
+}
+
+// Epilogue: y[m, u + t*U] = alpha(u + t*U) * Z[m, u] from acc[0..TMOUT-1].  The lane holds row
+// 32*TMOUT*grp + 32*tm + ln of the block and, in registers 4q .. 4q + 3 of tiles 0 and 1, columns
+// 16*q + 8*lg .. + 7 of the wave's 64 (n_wave is the wave's first distinct row).
 template <typename XT, bool RELU, int TMOUT>
 __device__ __forceinline__ void write_output(const f32x16_t (&acc)[kTM][kTN], const MfmaParams &P, XT *__restrict__ y,
-                                             const float *__restrict__ alpha, int64_t m0, int64_t n0, int grp, int lg,
-                                             int b_col) {
-    static_assert(kTN == 2, "the epilogue writes column pairs");
-    const int64_t u_base = n0 + b_col;   // first of this lane's two adjacent unique columns
+                                             const float *__restrict__ alpha, int64_t m0, int64_t n_wave, int grp, int lane,
+                                             float *stage_area) {
+    static_assert(kTN == 2, "eight adjacent columns come from two tiles");
+    const int ln = lane & 31, lg = lane >> 5;
+    const int row0 = grp * TMOUT * 32 + ln;   // + 32*tm
+    const int64_t rows_left = P.M - m0;        // >= 1
     if (P.reps_all > 0 && (P.n_alpha == 1 || P.aligned) && P.vec_store) {
-        // Every column has the same number of replicas, alpha depends on the replica only and every
-        // replica is a whole, aligned column pair.  Row and replica addresses are wave-uniform (scalar
-        // registers), the lane adds a fixed 32-bit offset; replicas are taken in chunks whose alphas
-        // are fetched up front, rows outermost inside a chunk, so that the stores of one row of Y are
-        // issued back to back.
-        constexpr int kChunk = 4;
+        // Every column has the same number of replicas, alpha depends on the replica only, U is a multiple
+        // of 8 and every group of eight is 16-byte aligned.  The wave turns its sums round through LDS, 32
+        // rows at a time, so that eight lanes hold one row's 64 columns: a store instruction then writes
+        // whole 128-byte lines of bf16 (eight rows of them), and few enough stores are issued that the
+        // wave never runs into the limit of stores in flight.
+        //   LDS row r of the 32 is 256 bytes; the 16-byte chunk ch of it (columns 4*ch .. 4*ch + 3) sits
+        //   at chunk position ch ^ s(r), s(r) = ((r >> 1) & 7) ^ (2 * (r & 1)): the writes (lanes = rows,
+        //   served even lanes first) and the reads (eight lanes per row; a lane reads chunks 2g and
+        //   2g + 1, the upper four lanes in the other order) are then free of bank conflicts.
+        float *stage = stage_area;   // 8 KiB that only this wave touches
+        const int g = lane & 7, rr = lane >> 3;
+        const int ch_a = 2 * g + (g >> 2), ch_b = 2 * g + 1 - (g >> 2);
         const int reps_all = P.reps_all;
-        const uint32_t lane_off =
-            (static_cast<uint32_t>(4 * lg) * static_cast<uint32_t>(P.out) + static_cast<uint32_t>(b_col)) *
-            static_cast<uint32_t>(sizeof(XT));
-        unsigned char *y_blk = reinterpret_cast<unsigned char *>(y + m0 * P.out + n0);
-        const int64_t rows_left = P.M - m0;   // >= 1
-        auto write_all = [&](auto full_c) {
-            constexpr bool FULL = decltype(full_c)::value;
+        const uint32_t lane_off = (static_cast<uint32_t>(rr) * static_cast<uint32_t>(P.out) + static_cast<uint32_t>(8 * g)) *
+                                  static_cast<uint32_t>(sizeof(XT));
+        const int64_t cols_left = P.U - n_wave;   // a multiple of 8; <= 0 if the wave has no columns
+        const bool col_ok = 8 * g < cols_left;
+#pragma unroll
+        for (int tm = 0; tm < TMOUT; ++tm) {
+            {
+                const int s_w = ((ln >> 1) & 7) ^ (2 * (ln & 1));
+#pragma unroll
+                for (int q = 0; q < 4; ++q)
+#pragma unroll
+                    for (int tn = 0; tn < kTN; ++tn) {
+                        const int ch = 4 * q + 2 * lg + tn;
+                        const f32x16_t &z = acc[tm][tn];
+                        *reinterpret_cast<f32x4_t *>(stage + ln * 64 + ((ch ^ s_w) << 2)) =
+                            f32x4_t{z[4 * q], z[4 * q + 1], z[4 * q + 2], z[4 * q + 3]};
+                    }
+            }
+            __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+            __builtin_amdgcn_wave_barrier();
+            __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+            float zr[4][8];   // rows rr + 8*i of the 32, columns 8*g .. 8*g + 7
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                const int r = rr + 8 * i;
+                const int s_r = ((r >> 1) & 7) ^ (2 * (r & 1));
+                const f32x4_t za = *reinterpret_cast<const f32x4_t *>(stage + r * 64 + ((ch_a ^ s_r) << 2));
+                const f32x4_t zb = *reinterpret_cast<const f32x4_t *>(stage + r * 64 + ((ch_b ^ s_r) << 2));
+#pragma unroll
+                for (int e = 0; e < 4; ++e) {
+                    zr[i][e] = g < 4 ? za[e] : zb[e];
+                    zr[i][4 + e] = g < 4 ? zb[e] : za[e];
+                }
+            }
+            __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+            __builtin_amdgcn_wave_barrier();   // the next 32 rows overwrite the staging area
+            const int row_base = (grp * TMOUT + tm) * 32;
+            unsigned char *y_blk = reinterpret_cast<unsigned char *>(y + (m0 + row_base) * P.out + n_wave);
+            constexpr int kChunk = 4;   // replicas whose alphas are fetched together
             for (int t0 = 0; t0 < reps_all; t0 += kChunk) {
                 float al[kChunk];
 #pragma unroll
@@ -354,73 +414,62 @@ __device__ __forceinline__ void write_output(const f32x16_t (&acc)[kTM][kTN], co
                     const int t = (t0 + j < reps_all) ? (t0 + j) : (reps_all - 1);
                     al[j] = alpha[P.n_alpha == 1 ? 0 : t];
                 }
-                const int n_here = (reps_all - t0) < kChunk ? (reps_all - t0) : kChunk;
 #pragma unroll
-                for (int tm = 0; tm < TMOUT; ++tm) {
+                for (int j = 0; j < kChunk; ++j) {
+                    if (t0 + j >= reps_all) break;
+                    unsigned char *dst_t = y_blk + int64_t(t0 + j) * P.U * static_cast<int64_t>(sizeof(XT));
 #pragma unroll
-                    for (int e = 0; e < 16; ++e) {
-                        const int row = grp * TMOUT * 32 + tm * 32 + 8 * (e >> 2) + (e & 3);   // + 4*lg
-                        if (!FULL && row + 4 * lg >= rows_left) continue;
-                        unsigned char *dst =
-                            y_blk + (int64_t(row) * P.out + int64_t(t0) * P.U) * static_cast<int64_t>(sizeof(XT));
-                        const float z0 = acc[tm][0][e], z1 = acc[tm][1][e];
-                        if (n_here == kChunk) {
+                    for (int i = 0; i < 4; ++i) {
+                        if (!col_ok || row_base + rr + 8 * i >= rows_left) continue;
+                        float v[8];
 #pragma unroll
-                            for (int j = 0; j < kChunk; ++j) {
-                                float v0 = al[j] * z0, v1 = al[j] * z1;
-                                if (RELU) { v0 = fmaxf(v0, 0.f); v1 = fmaxf(v1, 0.f); }
-                                OutPack<XT>::store2(
-                                    reinterpret_cast<XT *>(dst + int64_t(j) * P.U * sizeof(XT) + lane_off), v0, v1);
-                            }
-                        } else {
-                            for (int j = 0; j < n_here; ++j) {
-                                float v0 = al[j] * z0, v1 = al[j] * z1;
-                                if (RELU) { v0 = fmaxf(v0, 0.f); v1 = fmaxf(v1, 0.f); }
-                                OutPack<XT>::store2(
-                                    reinterpret_cast<XT *>(dst + int64_t(j) * P.U * sizeof(XT) + lane_off), v0, v1);
-                            }
+                        for (int e = 0; e < 8; ++e) {
+                            v[e] = al[j] * zr[i][e];
+                            if (RELU) v[e] = fmaxf(v[e], 0.f);
                         }
+                        OutPack<XT>::store8(reinterpret_cast<XT *>(dst_t + int64_t(8 * i) * P.out * sizeof(XT) + lane_off), v);
                     }
                 }
             }
-        };
-        if (u_base < P.U) {   // U is even here, so the lane's second column exists as well
-            if (rows_left >= kBM) write_all(std::true_type{}); else write_all(std::false_type{});
         }
         return;
     }
-    if (u_base >= P.U) return;
-    const bool pair_ok = (u_base + 1 < P.U);
-    const int64_t m_wave = m0 + grp * TMOUT * 32 + 4 * lg;
-    const int64_t reps = (P.out - u_base + P.U - 1) / P.U;   // replicas of column u_base
 
-    // general case (odd sizes, or tile ends inside rows so that alpha(o) = alpha[(o*in) / p] differs
-    // per lane): replicas outermost
-    for (int64_t t = 0; t < reps; ++t) {
-        const int64_t o0 = u_base + t * P.U, o1 = o0 + 1;
-        const bool ok1 = pair_ok && (o1 < P.out);
-        float al0, al1;
-        if (P.n_alpha == 1) {
-            al0 = al1 = alpha[0];
-        } else {
-            al0 = alpha[(o0 * P.in) / P.p];
-            al1 = ok1 ? alpha[(o1 * P.in) / P.p] : 0.f;
-        }
+    // General case (odd sizes, or tile ends inside rows so that alpha(o) = alpha[(o*in) / p] differs from
+    // column to column): groups of four adjacent columns, one store each where alignment allows.
+    const bool vec4 = P.U % 4 == 0 && P.out % 4 == 0 && (reinterpret_cast<uintptr_t>(y) % (4 * sizeof(XT))) == 0;
 #pragma unroll
-        for (int tm = 0; tm < TMOUT; ++tm) {
+    for (int tn = 0; tn < kTN; ++tn) {
 #pragma unroll
-            for (int e = 0; e < 16; ++e) {
-                const int64_t m = m_wave + tm * 32 + 8 * (e >> 2) + (e & 3);
-                if (m >= P.M) continue;
-                float v0 = al0 * acc[tm][0][e];
-                float v1 = al1 * acc[tm][1][e];
-                if (RELU) { v0 = fmaxf(v0, 0.f); v1 = fmaxf(v1, 0.f); }
-                XT *dst = y + m * P.out + o0;
-                if (P.vec_store && ok1) {
-                    OutPack<XT>::store2(dst, v0, v1);
-                } else {
-                    ElemIO<XT>::store(dst, v0);
-                    if (ok1) ElemIO<XT>::store(dst + 1, v1);
+        for (int q = 0; q < 4; ++q) {
+            const int64_t u0 = n_wave + 16 * q + 8 * lg + 4 * tn;   // first of four adjacent distinct rows
+            if (u0 >= P.U) continue;
+            const int n_cols = (P.U - u0) < 4 ? static_cast<int>(P.U - u0) : 4;
+            for (int64_t o0 = u0; o0 < P.out; o0 += P.U) {   // replicas
+                float al[4];
+#pragma unroll
+                for (int i = 0; i < 4; ++i) {
+                    const int64_t o = o0 + i;
+                    al[i] = (i < n_cols && o < P.out) ? alpha[P.n_alpha == 1 ? 0 : (o * P.in) / P.p] : 0.f;
+                }
+#pragma unroll
+                for (int tm = 0; tm < TMOUT; ++tm) {
+                    const int row = row0 + 32 * tm;
+                    if (row >= rows_left) continue;
+                    float v[4];
+#pragma unroll
+                    for (int i = 0; i < 4; ++i) {
+                        v[i] = al[i] * acc[tm][tn][4 * q + i];
+                        if (RELU) v[i] = fmaxf(v[i], 0.f);
+                    }
+                    XT *dst = y + (m0 + row) * P.out + o0;
+                    if (vec4) {   // then n_cols == 4 and o0 + 3 < out
+                        OutPack<XT>::store4(dst, v);
+                    } else {
+#pragma unroll
+                        for (int i = 0; i < 4; ++i)
+                            if (i < n_cols && o0 + i < P.out) ElemIO<XT>::store(dst + i, v[i]);
+                    }
                 }
             }
         }
@@ -547,11 +596,10 @@ __global__ __launch_bounds__(Cfg<KG>::kThreads, 1) void linear_mfma_bf16_kernel(
         a_off[j] = a_row[j] + static_cast<uint32_t>(a_chunk[j]) * 16u + kBias - static_cast<uint32_t>((j & 3) * 1024);
     }
 
-    // ---- tile windows of this lane's two columns ------------------------------------------------
-    const int b_col = wn * kWN + ln * kTN;   // + tn: a lane owns kTN adjacent columns of the block
-    uint32_t pos2[kTN];
-    window_start<BK>(P, n0 + b_col, grp, pos2);
-    uint32_t pos = lg ? pos2[1] : pos2[0];   // a lane looks after the window of column b_col + lg, see share_window
+    // ---- tile windows ---------------------------------------------------------------------------
+    // Operand lane ln supplies columns wave_col(ln, 0) and wave_col(ln, 1) of the wave's 64; this lane
+    // looks after the window of the one with tn = lg (see share_window).
+    uint32_t pos = window_start(P, n0 + wn * kWN + wave_col(ln, lg), grp * BK);
     uint32_t head[WW];   // start of the tile: continues a window that runs past the tile end
 #pragma unroll
     for (int j = 0; j < WW; ++j) head[j] = tile[j];
@@ -667,7 +715,7 @@ __global__ __launch_bounds__(Cfg<KG>::kThreads, 1) void linear_mfma_bf16_kernel(
             for (int tm = 0; tm < kTM; ++tm)
 #pragma unroll
                 for (int tn = 0; tn < kTN; ++tn)
-                    acc[tm][tn] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[ks & 1][tm].v, b[tn].v, acc[tm][tn], 0, 0, 0);
+                    acc[tm][tn] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(b[tn].v, a[ks & 1][tm].v, acc[tm][tn], 0, 0, 0);
         }
     };
 
@@ -712,7 +760,7 @@ __global__ __launch_bounds__(Cfg<KG>::kThreads, 1) void linear_mfma_bf16_kernel(
             const uint32_t raddr = a_rdg[ksn];
             uint32_t rep;
             auto mfma = [&](int tm, int tn) {
-                acc[tm][tn] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(pa[cur][tm].v, pb[cur][tn].v, acc[tm][tn], 0, 0, 0);
+                acc[tm][tn] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(pb[cur][tn].v, pa[cur][tm].v, acc[tm][tn], 0, 0, 0);
             };
             lds_wait<0>(pa[cur]);   // the four reads of the step before (the last was issued five MFMAs ago)
             mfma(0, 0);
@@ -806,7 +854,7 @@ __global__ __launch_bounds__(Cfg<KG>::kThreads, 1) void linear_mfma_bf16_kernel(
     static_assert(D == 3 && kNB == 4, "the wait counts are written for three stages in flight");
 
     exchange_partials<KG>(acc, lds_raw, wave, lane);
-    write_output<uint16_t, RELU, C::kRot>(acc, P, y, alpha, m0, n0, grp, lg, b_col);
+    write_output<uint16_t, RELU, C::kRot>(acc, P, y, alpha, m0, n0 + wn * kWN, grp, lane, stage_slot<KG>(lds_raw, wave));
 }
 
 }  // namespace direct
@@ -867,9 +915,9 @@ __global__ __launch_bounds__(kThreads, 1) void linear_mfma_f32_kernel(const floa
         a_lds[i] = r * RS + a_piece * 16;
     }
 
-    const int b_col = wn * kWN + ln * kTN;   // + tn: a lane owns kTN adjacent columns of the block
-    uint32_t pos[kTN];
-    window_start<BK>(P, n0 + b_col, grp, pos);
+    uint32_t pos[kTN];   // operand lane ln supplies columns wave_col(ln, tn) of the wave's 64
+#pragma unroll
+    for (int tn = 0; tn < kTN; ++tn) pos[tn] = window_start(P, n0 + wn * kWN + wave_col(ln, tn), grp * BK);
     uint32_t head[WW];
 #pragma unroll
     for (int j = 0; j < WW; ++j) head[j] = tile[j];
@@ -965,7 +1013,7 @@ __global__ __launch_bounds__(kThreads, 1) void linear_mfma_f32_kernel(const floa
                 for (int tm = 0; tm < kTM; ++tm)
 #pragma unroll
                     for (int tn = 0; tn < kTN; ++tn)
-                        acc[tm][tn] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[tm].v, b[tn].v, acc[tm][tn], 0, 0, 0);
+                        acc[tm][tn] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(b[tn].v, a[tm].v, acc[tm][tn], 0, 0, 0);
             }
         }
     };
@@ -1010,7 +1058,7 @@ __global__ __launch_bounds__(kThreads, 1) void linear_mfma_f32_kernel(const floa
     }
 
     exchange_partials<2>(acc, lds_raw, wave, lane);
-    write_output<float, RELU, kTmOut>(acc, P, y, alpha, m0, n0, grp, lg, b_col);
+    write_output<float, RELU, kTmOut>(acc, P, y, alpha, m0, n0 + wn * kWN, grp, lane, stage_slot<2>(lds_raw, wave));
 }
 
 }  // namespace ring
@@ -1077,8 +1125,7 @@ tbn_status launch_linear_mfma(const LinearArgs &a) {
     P.U = unique_rows(a.out, a.in, a.p);
     P.n_alpha = a.n_alpha;
     P.aligned = (a.p % a.in == 0) ? 1 : 0;
-    const size_t esz = (a.dt == TBN_F32) ? 4 : 2;
-    P.vec_store = (P.U % 2 == 0 && a.out % 2 == 0 && (reinterpret_cast<uintptr_t>(a.y) % (2 * esz)) == 0) ? 1 : 0;
+    P.vec_store = (P.U % 8 == 0 && a.out % 8 == 0 && (reinterpret_cast<uintptr_t>(a.y) % 16) == 0) ? 1 : 0;
     P.reps_all = (a.out % P.U == 0 && a.out / P.U < (1 << 30)) ? static_cast<int32_t>(a.out / P.U) : 0;
     P.tiles_m = static_cast<uint32_t>((a.M + kBM - 1) / kBM);
     P.tiles_n = static_cast<int>((P.U + kBN - 1) / kBN);
