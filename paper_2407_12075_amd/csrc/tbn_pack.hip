@@ -118,22 +118,31 @@ __global__ __launch_bounds__(kPackThreads) void pack_kernel(const float *__restr
 __global__ __launch_bounds__(256) void pack_alpha_kernel(const double *__restrict__ partial, int64_t n_part,
                                                          int32_t k, int32_t n_alpha, int64_t p,
                                                          float *__restrict__ alpha_out) {
-    __shared__ double red[256];
+    __shared__ double red[256 / kWave];
     const int tid = threadIdx.x;
     const int32_t r_begin = (n_alpha == 1) ? 0 : blockIdx.x;
     const int32_t r_end = (n_alpha == 1) ? k : blockIdx.x + 1;
     double acc = 0.0;
-    for (int32_t r = r_begin; r < r_end; ++r)
-        for (int64_t i = tid; i < n_part; i += 256) acc += partial[i * k + r];
-    red[tid] = acc;
-    __syncthreads();
-    for (int s = 128; s > 0; s >>= 1) {
-        if (tid < s) red[tid] += red[tid + s];
-        __syncthreads();
+    for (int32_t r = r_begin; r < r_end; ++r) {
+        int64_t i = tid;
+        for (; i + 7 * 256 < n_part; i += 8 * 256) {   // eight independent loads in flight
+            double t[8];
+#pragma unroll
+            for (int j = 0; j < 8; ++j) t[j] = partial[(i + j * 256) * k + r];
+#pragma unroll
+            for (int j = 0; j < 8; ++j) acc += t[j];
+        }
+        for (; i < n_part; i += 256) acc += partial[i * k + r];
     }
+    acc = wave_sum_f64(acc);
+    if ((tid & (kWave - 1)) == 0) red[tid / kWave] = acc;
+    __syncthreads();
     if (tid == 0) {
+        double total = 0.0;
+#pragma unroll
+        for (int wv = 0; wv < 256 / kWave; ++wv) total += red[wv];
         const double denom = (n_alpha == 1) ? static_cast<double>(p) * static_cast<double>(k) : static_cast<double>(p);
-        alpha_out[blockIdx.x] = static_cast<float>(red[0] / denom);
+        alpha_out[blockIdx.x] = static_cast<float>(total / denom);
     }
 }
 
