@@ -82,6 +82,15 @@ __device__ __forceinline__ uint32_t mod_u53(uint64_t x, uint32_t p) {
     return static_cast<uint32_t>(r);
 }
 
+// floor(x / p) for x < 2^53 and p < 2^31, by the same float64 quotient.
+__device__ __forceinline__ uint32_t div_u53(uint64_t x, uint32_t p) {
+    uint64_t q = static_cast<uint64_t>(static_cast<double>(x) / static_cast<double>(p));
+    const int64_t r = static_cast<int64_t>(x - q * p);
+    if (r < 0) --q;
+    if (r >= static_cast<int64_t>(p)) ++q;
+    return static_cast<uint32_t>(q);
+}
+
 // truncation split: t0 = top 8 significand bits, t1 = next 8, t2 = the rest (at most 8 bits)
 __device__ __forceinline__ void split3(float x, uint32_t &t0, uint32_t &t1, uint32_t &t2) {
     t0 = __float_as_uint(x) & 0xffff0000u;
@@ -343,70 +352,71 @@ __device__ __forceinline__ float *stage_slot(unsigned char *lds_raw, int wave) {
     return reinterpret_cast<float *>(lds_raw) + wave * kSlotFloats;
 }
 
-// Epilogue: y[m, u + t*U] = alpha(u + t*U) * Z[m, u] from acc[0..TMOUT-1].  The lane holds row
+// Epilogue: y[m, u + t*U] = alpha(u + t*U) * Z[m, u] from acc[0..TMOUT-1].  On entry the lane holds row
 // 32*TMOUT*grp + 32*tm + ln of the block and, in registers 4q .. 4q + 3 of tiles 0 and 1, columns
-// 16*q + 8*lg .. + 7 of the wave's 64 (n_wave is the wave's first distinct row).
+// 16*q + 8*lg .. + 7 of the wave's 64 (n_wave is the wave's first distinct row).  The wave turns its sums
+// round through LDS, 32 rows at a time, so that eight lanes hold one row's 64 columns: a store
+// instruction then writes whole 128-byte lines of bf16 (eight rows of them), and few enough stores are
+// issued that the wave never runs into the limit of stores in flight.
+//   LDS row r of the 32 is 256 bytes; the 16-byte chunk ch of it (columns 4*ch .. 4*ch + 3) sits at chunk
+//   position ch ^ s(r), s(r) = ((r >> 1) & 7) ^ (2 * (r & 1)): the writes (lanes = rows, served even lanes
+//   first) and the reads (eight lanes per row; a lane reads chunks 2g and 2g + 1, the upper four lanes
+//   in the other order) are then free of bank conflicts.
 template <typename XT, bool RELU, int TMOUT>
 __device__ __forceinline__ void write_output(const f32x16_t (&acc)[kTM][kTN], const MfmaParams &P, XT *__restrict__ y,
                                              const float *__restrict__ alpha, int64_t m0, int64_t n_wave, int grp, int lane,
-                                             float *stage_area) {
+                                             float *stage) {   // stage: 8 KiB of LDS that only this wave touches
     static_assert(kTN == 2, "eight adjacent columns come from two tiles");
     const int ln = lane & 31, lg = lane >> 5;
-    const int row0 = grp * TMOUT * 32 + ln;   // + 32*tm
+    const int g = lane & 7, rr = lane >> 3;
+    const int ch_a = 2 * g + (g >> 2), ch_b = 2 * g + 1 - (g >> 2);
     const int64_t rows_left = P.M - m0;        // >= 1
-    if (P.reps_all > 0 && (P.n_alpha == 1 || P.aligned) && P.vec_store) {
-        // Every column has the same number of replicas, alpha depends on the replica only, U is a multiple
-        // of 8 and every group of eight is 16-byte aligned.  The wave turns its sums round through LDS, 32
-        // rows at a time, so that eight lanes hold one row's 64 columns: a store instruction then writes
-        // whole 128-byte lines of bf16 (eight rows of them), and few enough stores are issued that the
-        // wave never runs into the limit of stores in flight.
-        //   LDS row r of the 32 is 256 bytes; the 16-byte chunk ch of it (columns 4*ch .. 4*ch + 3) sits
-        //   at chunk position ch ^ s(r), s(r) = ((r >> 1) & 7) ^ (2 * (r & 1)): the writes (lanes = rows,
-        //   served even lanes first) and the reads (eight lanes per row; a lane reads chunks 2g and
-        //   2g + 1, the upper four lanes in the other order) are then free of bank conflicts.
-        float *stage = stage_area;   // 8 KiB that only this wave touches
-        const int g = lane & 7, rr = lane >> 3;
-        const int ch_a = 2 * g + (g >> 2), ch_b = 2 * g + 1 - (g >> 2);
-        const int reps_all = P.reps_all;
-        const uint32_t lane_off = (static_cast<uint32_t>(rr) * static_cast<uint32_t>(P.out) + static_cast<uint32_t>(8 * g)) *
-                                  static_cast<uint32_t>(sizeof(XT));
-        const int64_t cols_left = P.U - n_wave;   // a multiple of 8; <= 0 if the wave has no columns
-        const bool col_ok = 8 * g < cols_left;
+    const int64_t u0 = n_wave + 8 * g;         // first of this lane's eight adjacent distinct rows
+    const int64_t cols_left = P.U - u0;        // <= 0: nothing to write
+    const uint32_t lane_off = (static_cast<uint32_t>(rr) * static_cast<uint32_t>(P.out) + static_cast<uint32_t>(8 * g)) *
+                              static_cast<uint32_t>(sizeof(XT));
+    // every column has the same number of replicas and alpha depends on the replica only
+    const bool uniform_alpha = P.reps_all > 0 && (P.n_alpha == 1 || P.aligned);
 #pragma unroll
-        for (int tm = 0; tm < TMOUT; ++tm) {
-            {
-                const int s_w = ((ln >> 1) & 7) ^ (2 * (ln & 1));
+    for (int tm = 0; tm < TMOUT; ++tm) {
+        {
+            const int s_w = ((ln >> 1) & 7) ^ (2 * (ln & 1));
 #pragma unroll
-                for (int q = 0; q < 4; ++q)
+            for (int q = 0; q < 4; ++q)
 #pragma unroll
-                    for (int tn = 0; tn < kTN; ++tn) {
-                        const int ch = 4 * q + 2 * lg + tn;
-                        const f32x16_t &z = acc[tm][tn];
-                        *reinterpret_cast<f32x4_t *>(stage + ln * 64 + ((ch ^ s_w) << 2)) =
-                            f32x4_t{z[4 * q], z[4 * q + 1], z[4 * q + 2], z[4 * q + 3]};
-                    }
-            }
-            __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
-            __builtin_amdgcn_wave_barrier();
-            __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
-            float zr[4][8];   // rows rr + 8*i of the 32, columns 8*g .. 8*g + 7
-#pragma unroll
-            for (int i = 0; i < 4; ++i) {
-                const int r = rr + 8 * i;
-                const int s_r = ((r >> 1) & 7) ^ (2 * (r & 1));
-                const f32x4_t za = *reinterpret_cast<const f32x4_t *>(stage + r * 64 + ((ch_a ^ s_r) << 2));
-                const f32x4_t zb = *reinterpret_cast<const f32x4_t *>(stage + r * 64 + ((ch_b ^ s_r) << 2));
-#pragma unroll
-                for (int e = 0; e < 4; ++e) {
-                    zr[i][e] = g < 4 ? za[e] : zb[e];
-                    zr[i][4 + e] = g < 4 ? zb[e] : za[e];
+                for (int tn = 0; tn < kTN; ++tn) {
+                    const int ch = 4 * q + 2 * lg + tn;
+                    const f32x16_t &z = acc[tm][tn];
+                    *reinterpret_cast<f32x4_t *>(stage + ln * 64 + ((ch ^ s_w) << 2)) =
+                        f32x4_t{z[4 * q], z[4 * q + 1], z[4 * q + 2], z[4 * q + 3]};
                 }
+        }
+        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+        __builtin_amdgcn_wave_barrier();
+        __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+        float zr[4][8];   // rows rr + 8*i of the 32, columns 8*g .. 8*g + 7
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            const int r = rr + 8 * i;
+            const int s_r = ((r >> 1) & 7) ^ (2 * (r & 1));
+            const f32x4_t za = *reinterpret_cast<const f32x4_t *>(stage + r * 64 + ((ch_a ^ s_r) << 2));
+            const f32x4_t zb = *reinterpret_cast<const f32x4_t *>(stage + r * 64 + ((ch_b ^ s_r) << 2));
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                zr[i][e] = g < 4 ? za[e] : zb[e];
+                zr[i][4 + e] = g < 4 ? zb[e] : za[e];
             }
-            __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
-            __builtin_amdgcn_wave_barrier();   // the next 32 rows overwrite the staging area
-            const int row_base = (grp * TMOUT + tm) * 32;
-            unsigned char *y_blk = reinterpret_cast<unsigned char *>(y + (m0 + row_base) * P.out + n_wave);
-            constexpr int kChunk = 4;   // replicas whose alphas are fetched together
+        }
+        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+        __builtin_amdgcn_wave_barrier();   // the next 32 rows overwrite the staging area
+
+        const int row_base = (grp * TMOUT + tm) * 32;
+        unsigned char *y_blk = reinterpret_cast<unsigned char *>(y + (m0 + row_base) * P.out + n_wave);
+        if (uniform_alpha && P.vec_store) {
+            // U is a multiple of 8 and every group of eight is 16-byte aligned; the alphas of four replicas
+            // are fetched together
+            constexpr int kChunk = 4;
+            const int reps_all = P.reps_all;
             for (int t0 = 0; t0 < reps_all; t0 += kChunk) {
                 float al[kChunk];
 #pragma unroll
@@ -420,7 +430,7 @@ __device__ __forceinline__ void write_output(const f32x16_t (&acc)[kTM][kTN], co
                     unsigned char *dst_t = y_blk + int64_t(t0 + j) * P.U * static_cast<int64_t>(sizeof(XT));
 #pragma unroll
                     for (int i = 0; i < 4; ++i) {
-                        if (!col_ok || row_base + rr + 8 * i >= rows_left) continue;
+                        if (cols_left <= 0 || row_base + rr + 8 * i >= rows_left) continue;
                         float v[8];
 #pragma unroll
                         for (int e = 0; e < 8; ++e) {
@@ -431,45 +441,46 @@ __device__ __forceinline__ void write_output(const f32x16_t (&acc)[kTM][kTN], co
                     }
                 }
             }
+            continue;
         }
-        return;
-    }
-
-    // General case (odd sizes, or tile ends inside rows so that alpha(o) = alpha[(o*in) / p] differs from
-    // column to column): groups of four adjacent columns, one store each where alignment allows.
-    const bool vec4 = P.U % 4 == 0 && P.out % 4 == 0 && (reinterpret_cast<uintptr_t>(y) % (4 * sizeof(XT))) == 0;
+        // General case: odd sizes, or tile ends inside rows so that alpha(o) = alpha[(o*in) / p] differs
+        // from column to column (the index is divided out for the lane's first column and stepped on).
+        if (cols_left <= 0) continue;
+        const int n_cols = cols_left < 8 ? static_cast<int>(cols_left) : 8;
+        for (int64_t o0 = u0; o0 < P.out; o0 += P.U) {   // replicas
+            float al[8];
+            if (P.n_alpha == 1) {
+                const float a0 = alpha[0];
 #pragma unroll
-    for (int tn = 0; tn < kTN; ++tn) {
+                for (int e = 0; e < 8; ++e) al[e] = a0;
+            } else {
+                const uint64_t f = static_cast<uint64_t>(o0) * static_cast<uint32_t>(P.in);
+                uint32_t idx = div_u53(f, static_cast<uint32_t>(P.p));
+                uint32_t rem = static_cast<uint32_t>(f - static_cast<uint64_t>(idx) * static_cast<uint32_t>(P.p));
 #pragma unroll
-        for (int q = 0; q < 4; ++q) {
-            const int64_t u0 = n_wave + 16 * q + 8 * lg + 4 * tn;   // first of four adjacent distinct rows
-            if (u0 >= P.U) continue;
-            const int n_cols = (P.U - u0) < 4 ? static_cast<int>(P.U - u0) : 4;
-            for (int64_t o0 = u0; o0 < P.out; o0 += P.U) {   // replicas
-                float al[4];
-#pragma unroll
-                for (int i = 0; i < 4; ++i) {
-                    const int64_t o = o0 + i;
-                    al[i] = (i < n_cols && o < P.out) ? alpha[P.n_alpha == 1 ? 0 : (o * P.in) / P.p] : 0.f;
+                for (int e = 0; e < 8; ++e) {
+                    al[e] = alpha[idx < static_cast<uint32_t>(P.n_alpha) ? idx : static_cast<uint32_t>(P.n_alpha) - 1];
+                    rem += static_cast<uint32_t>(P.in);   // in <= p < 2^31
+                    if (rem >= static_cast<uint32_t>(P.p)) { rem -= static_cast<uint32_t>(P.p); ++idx; }
                 }
+            }
 #pragma unroll
-                for (int tm = 0; tm < TMOUT; ++tm) {
-                    const int row = row0 + 32 * tm;
-                    if (row >= rows_left) continue;
-                    float v[4];
+            for (int i = 0; i < 4; ++i) {
+                const int row = row_base + rr + 8 * i;
+                if (row >= rows_left) continue;
+                float v[8];
 #pragma unroll
-                    for (int i = 0; i < 4; ++i) {
-                        v[i] = al[i] * acc[tm][tn][4 * q + i];
-                        if (RELU) v[i] = fmaxf(v[i], 0.f);
-                    }
-                    XT *dst = y + (m0 + row) * P.out + o0;
-                    if (vec4) {   // then n_cols == 4 and o0 + 3 < out
-                        OutPack<XT>::store4(dst, v);
-                    } else {
+                for (int e = 0; e < 8; ++e) {
+                    v[e] = al[e] * zr[i][e];
+                    if (RELU) v[e] = fmaxf(v[e], 0.f);
+                }
+                XT *dst = y + (m0 + row) * P.out + o0;
+                if (P.vec_store) {   // then n_cols == 8 and o0 + 7 < out
+                    OutPack<XT>::store8(dst, v);
+                } else {
 #pragma unroll
-                        for (int i = 0; i < 4; ++i)
-                            if (i < n_cols && o0 + i < P.out) ElemIO<XT>::store(dst + i, v[i]);
-                    }
+                    for (int e = 0; e < 8; ++e)
+                        if (e < n_cols && o0 + e < P.out) ElemIO<XT>::store(dst + e, v[e]);
                 }
             }
         }
