@@ -144,6 +144,8 @@ LINEAR_SMALL = [
     (200, 1096, 220, 5, 5),    # steady-state loop, then a ragged last stage
     (70, 8192, 80, 4, 4),      # 64 stages per K group
     (257, 1544, 135, 5, 5),    # p = 41688 = 27 rows: odd number of distinct rows, p % 32 = 24
+    (140, 600, 1024, 6, 6),    # tile ends inside rows with 16-byte stores: 512 distinct rows, 2 replicas, alpha steps inside a lane's 8 columns
+    (150, 1024, 256, 2, 2),    # aligned, 128 distinct rows: one column block, 16-byte stores, second row block partly filled
     (4, 40, 16, 4, 1),         # p = 160: smallest tile the small-batch kernel takes
     (3, 160, 9, 9, 9),         # p = in = 160
 ]
@@ -246,6 +248,29 @@ def test_config5_ffn(tbn, c):
 @pytest.mark.parametrize("c", wl.EXTRA, ids=lambda c: c.name)
 def test_extra_paper_shapes(tbn, c):
     _linear_full(tbn, c, full=True)
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_linear_output_pointer_not_16_byte_aligned(tbn, dtype):
+    # the 16-byte store form needs an aligned y; one element further on the element-wise form has to take over
+    M, cin, cout, k, n_alpha = 200, 512, 512, 4, 4
+    rng = np.random.default_rng(77)
+    w = (0.02 * rng.standard_normal(cin * cout)).astype(np.float32)
+    x = rng.standard_normal((M, cin)).astype(np.float32)
+    bits = None
+    if dtype == "bf16":
+        bits = wl.f32_to_bf16_bits(x)
+        x = wl.bf16_bits_to_f32(bits).reshape(M, cin)
+        bits = bits.reshape(M, cin)
+    tile_ref, alpha_ref = orc.pack_tile(w, k, n_alpha)
+    ref = orc.linear_forward(x, tile_ref, alpha_ref, cout, k)
+    xd = x_to_device(x, bits)
+    big = torch.zeros(M * cout + 8, dtype=xd.dtype, device="cuda")
+    y = big[1:1 + M * cout].view(M, cout)
+    tbn.tbn_linear_forward(xd, dev(tile_ref.view(np.int32)), dev(alpha_ref), cout, k, y=y)
+    torch.cuda.synchronize()
+    assert_close(y_to_numpy(y), ref, dtype, f"linear with y offset by one element, {dtype}")
+    assert float(big[0]) == 0.0 and float(big[1 + M * cout:].abs().max()) == 0.0   # nothing written outside y
 
 
 def test_aligned_output_blocks_are_scaled_copies_at_full_size(tbn):
