@@ -8,14 +8,15 @@
 // column o = u + t*U as alpha(o) * Z[:, u].
 //
 // gfx950 mapping, chosen from measurements on the chip: one v_mfma_f32_32x32x16_bf16 keeps a SIMD's
-// matrix pipe busy for 32 cycles, and the wave that issued it can slip in about five independent
-// VALU / LDS / memory instructions meanwhile; every instruction beyond that costs issue time.  Turning
-// tile bits into a +-1 bf16 operand costs 9 VALU instructions per operand, so an operand has to feed
-// four MFMAs, i.e. a wave needs a 128-row block.  With only U/64 column strips that would leave most
-// SIMDs idle for a small U, so K is split instead:
+// matrix pipe busy for 32 cycles, a wave issues at most one instruction every four cycles, so about five
+// independent VALU / LDS / memory instructions fit in an MFMA's shadow and every further one costs issue
+// time.  Turning tile bits into a +-1 bf16 operand costs 9 VALU instructions per operand, so an operand
+// has to feed four MFMAs, i.e. a wave needs a 128-row block.  With only U/64 column strips that would
+// leave most SIMDs idle for a small U, so K is split instead:
 //   * a workgroup (4 waves) owns a 128 x 128 block of Z; wave (g, h) multiplies all 128 rows with
 //     column half h over the stages of K congruent to g mod 2 (128 accumulator registers); the two
-//     partial blocks are added through LDS at the end and every wave writes 64 rows x 64 columns;
+//     partial blocks are added through LDS at the end and every wave writes 64 rows x 64 columns
+//     (the bf16 kernel is written for two or four K groups; two is what the launcher builds);
 //   * bf16 activations go from global memory straight into LDS (global_load_lds_dwordx4, four stage
 //     buffers per K group, no staging registers, no LDS stores); rows are unpadded and their
 //     16-byte chunks are XOR-swizzled by choosing which chunk each lane fetches, so that the
@@ -23,14 +24,17 @@
 //   * float32 activations are loaded into a register ring and split exactly into three bf16 terms
 //     when they are written to LDS (8 + 8 + 8 significand bits; the weights are +-1, so every product
 //     is exact and the sums are float32 accumulations in the matrix pipe);
-//   * the +-1 operand never exists in memory, nor the tile bits in LDS: every lane fetches the
-//     words of its own column's cyclic tile window (they stay in L1 / L2), and per MFMA step
-//     replicates its byte (v_perm), shifts both 16-bit halves so that two neighbouring bits land
-//     on the two sign positions (v_pk_lshlrev_b16), and merges with the pattern of 1.0;
-//   * the epilogue scales by alpha and writes the replicated column blocks straight from the
-//     accumulators; a lane owns two adjacent columns so that a half-wave writes a contiguous run.
+//   * the +-1 operand never exists in memory, nor the tile bits in LDS: lanes fetch the words of
+//     their columns' cyclic tile windows (they stay in L1 / L2), and per MFMA step replicate a
+//     byte (v_perm), shift both 16-bit halves so that two neighbouring bits land on the two sign
+//     positions (v_pk_lshlrev_b16), and merge with the pattern of 1.0;
+//   * the +-1 operand is the MFMA's row operand and the activations its column operand, with the
+//     operand lanes numbered so that a lane ends up with eight adjacent columns of one row of Y; the
+//     epilogue scales by alpha, turns the block round through LDS so that eight lanes hold a whole
+//     row of the wave's 64 columns, and writes the replicated column blocks with 16-byte stores.
 // Rows whose weights straddle a tile end use two different alphas when one alpha per tile is
-// given; those few columns are recomputed afterwards by the row kernel (see tbn_linear_rows.hip).
+// given; those few columns are recomputed afterwards in one pass over X (see tbn_linear_skinny.hip,
+// launch_linear_tile_ends).
 #include "tbn_common.h"
 
 #include <type_traits>
