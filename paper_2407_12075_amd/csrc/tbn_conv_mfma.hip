@@ -40,7 +40,8 @@ constexpr int kThreads = 256;
 constexpr int kFB = 32;            // distinct filters per workgroup (2 MFMA row tiles)
 constexpr int kCK = 32;            // input channels per chunk (one MFMA step per tap)
 constexpr int kMaxPix = 128;       // output pixels per workgroup (8 MFMA column tiles)
-constexpr int kMaxItems = 10;      // staged (channel pair, pixel) items per thread and chunk
+constexpr int kItemsSmall = 10;     // staged (channel pair, pixel) items per thread and chunk: patches up to 160 pixels
+constexpr int kItemsLarge = 12;     // ... up to 192 pixels (one output row of a 56- to 62-wide image with its 3x3 halo)
 constexpr int kPixStride = kCK * 2 + 16;   // bytes per patch pixel in LDS: 32 bf16 channels + 16 B padding
 
 struct ConvMfmaParams {
@@ -75,7 +76,7 @@ __device__ __forceinline__ uint32_t pack_hi16(uint32_t lo, uint32_t hi) { return
 __device__ __forceinline__ float load_elem(const float *p) { return *p; }
 __device__ __forceinline__ float load_elem(const uint16_t *p) { return bf16_bits_to_f32(*p); }
 
-template <typename XT, int T, bool RELU>
+template <typename XT, int T, bool RELU, int kMaxItems>
 __global__ __launch_bounds__(kThreads, 2) void conv_mfma_kernel(const XT *__restrict__ x, XT *__restrict__ y,
                                                                   const uint32_t *__restrict__ tile,
                                                                   const float *__restrict__ alpha, ConvMfmaParams P) {
@@ -387,10 +388,11 @@ struct ConvPlan {
     bool ok;
     int rows_per_blk, PR, PC, nblk;
     size_t lds;
+    int items;   // kItemsSmall or kItemsLarge
 };
 
 ConvPlan plan_conv(const ConvArgs &a) {
-    ConvPlan pl{false, 0, 0, 0, 0, 0};
+    ConvPlan pl{false, 0, 0, 0, 0, 0, kItemsSmall};
     const int64_t F = a.C * a.kh * a.kw;
     const int T = a.kh * a.kw;
     if (T != 1 && T != 9) return pl;                     // instantiated tap counts: 1x1 and 3x3
@@ -410,28 +412,32 @@ ConvPlan plan_conv(const ConvArgs &a) {
     const int64_t fblocks = (R + kFB - 1) / kFB;
     while (nblk0 * a.N * fblocks < 256 && (a.Ho + 2 * nblk0 - 1) / (2 * nblk0) >= 3) nblk0 *= 2;
     rows = (a.Ho + nblk0 - 1) / nblk0;
-    for (; rows >= 1; --rows) {
-        const int64_t PR = (rows - 1) * a.sh + a.kh, PC = (a.Wo - 1) * a.sw + a.kw;
-        const int64_t vrows = PR < a.H ? PR : a.H, vcols = PC < a.W ? PC : a.W;
-        const size_t lds = 2 * size_t(planes) * PR * PC * kPixStride + bits_bytes;
-        if (vrows * vcols * (kCK / 2) <= int64_t(kMaxItems) * kThreads && lds <= 150 * 1024) {
-            pl.ok = true;
-            pl.rows_per_blk = static_cast<int>(rows);
-            pl.PR = static_cast<int>(PR);
-            pl.PC = static_cast<int>(PC);
-            pl.nblk = static_cast<int>((a.Ho + rows - 1) / rows);
-            pl.lds = lds;
-            return pl;
+    // the smaller staging budget first (less work per thread for the patches it covers)
+    for (int items : {kItemsSmall, kItemsLarge}) {
+        for (int64_t r = rows; r >= 1; --r) {
+            const int64_t PR = (r - 1) * a.sh + a.kh, PC = (a.Wo - 1) * a.sw + a.kw;
+            const int64_t vrows = PR < a.H ? PR : a.H, vcols = PC < a.W ? PC : a.W;
+            const size_t lds = 2 * size_t(planes) * PR * PC * kPixStride + bits_bytes;
+            if (vrows * vcols * (kCK / 2) <= int64_t(items) * kThreads && lds <= 150 * 1024) {
+                pl.ok = true;
+                pl.rows_per_blk = static_cast<int>(r);
+                pl.PR = static_cast<int>(PR);
+                pl.PC = static_cast<int>(PC);
+                pl.nblk = static_cast<int>((a.Ho + r - 1) / r);
+                pl.lds = lds;
+                pl.items = items;
+                return pl;
+            }
         }
     }
     return pl;
 }
 
-template <typename XT, int T, bool RELU>
+template <typename XT, int T, bool RELU, int ITEMS>
 tbn_status launch_conv_typed(const ConvArgs &a, const ConvMfmaParams &P, const ConvPlan &pl, dim3 grid) {
     static size_t attr_bytes = 0;   // largest dynamic LDS size allowed so far for this instantiation
     if (pl.lds > attr_bytes) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(&conv_mfma_kernel<XT, T, RELU>),
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(&conv_mfma_kernel<XT, T, RELU, ITEMS>),
                                            hipFuncAttributeMaxDynamicSharedMemorySize, static_cast<int>(pl.lds));
         if (e != hipSuccess) {
             set_error("tbn_conv2d_forward: cannot reserve %zu bytes of LDS: %s", pl.lds, hipGetErrorString(e));
@@ -439,15 +445,21 @@ tbn_status launch_conv_typed(const ConvArgs &a, const ConvMfmaParams &P, const C
         }
         attr_bytes = pl.lds;
     }
-    hipLaunchKernelGGL((conv_mfma_kernel<XT, T, RELU>), grid, dim3(kThreads), pl.lds, a.stream,
+    hipLaunchKernelGGL((conv_mfma_kernel<XT, T, RELU, ITEMS>), grid, dim3(kThreads), pl.lds, a.stream,
                        static_cast<const XT *>(a.x), static_cast<XT *>(a.y), a.tile, a.alpha, P);
     return check_launch("tbn_conv2d_forward (matrix-core kernel)");
 }
 
+template <typename XT, int T, bool RELU>
+tbn_status launch_conv_items(const ConvArgs &a, const ConvMfmaParams &P, const ConvPlan &pl, dim3 grid) {
+    return pl.items == kItemsSmall ? launch_conv_typed<XT, T, RELU, kItemsSmall>(a, P, pl, grid)
+                                   : launch_conv_typed<XT, T, RELU, kItemsLarge>(a, P, pl, grid);
+}
+
 template <typename XT, int T>
 tbn_status launch_conv_relu(const ConvArgs &a, const ConvMfmaParams &P, const ConvPlan &pl, dim3 grid) {
-    return (a.flags & TBN_FLAG_RELU) ? launch_conv_typed<XT, T, true>(a, P, pl, grid)
-                                     : launch_conv_typed<XT, T, false>(a, P, pl, grid);
+    return (a.flags & TBN_FLAG_RELU) ? launch_conv_items<XT, T, true>(a, P, pl, grid)
+                                     : launch_conv_items<XT, T, false>(a, P, pl, grid);
 }
 
 template <typename XT>
