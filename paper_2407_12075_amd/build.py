@@ -21,6 +21,9 @@ FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-fno-gpu-rdc",
     # keep the compiler from forming packed-fp32 instructions
     "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
+    # the fully unrolled MFMA chains of the convolution kernel are longer than the default limit of
+    # `#pragma unroll`; partly unrolled, their register arrays would go to scratch memory
+    "-mllvm", "-pragma-unroll-threshold=100000",
     "-Wall", "-Wno-unused-function",
 ]
 

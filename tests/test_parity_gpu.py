@@ -310,6 +310,8 @@ CONV_SMALL = [
     (2, 32, 10, 10, 48, 3, 3, (1, 1), (1, 1), 9, 1),     # 5 1/3 filters per tile, one alpha
     (2, 32, 10, 10, 48, 3, 3, (1, 1), (1, 1), 9, 9),     # same with one alpha per tile (two-alpha channels)
     (1, 64, 6, 6, 40, 1, 1, (1, 1), (0, 0), 5, 5),       # 1x1, 8 filters per tile
+    (128, 32, 4, 4, 128, 3, 3, (1, 1), (1, 1), 1, 1),    # 128 distinct filters, 128 images: 64 filters per workgroup (bf16)
+    (128, 32, 4, 4, 128, 3, 3, (1, 1), (1, 1), 3, 3),    # same with tile ends inside filters
     (1, 32, 56, 56, 32, 3, 3, (1, 1), (1, 1), 4, 1),     # 56 wide: one output row per workgroup, the widest 3x3 patch the matrix-core kernel stages
     (1, 32, 20, 62, 32, 3, 3, (1, 1), (1, 1), 2, 2),     # 62 wide, 4 pixel tiles with a ragged last one
 ]
