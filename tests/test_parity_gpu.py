@@ -250,6 +250,31 @@ def test_extra_paper_shapes(tbn, c):
     _linear_full(tbn, c, full=True)
 
 
+def _random_linear_shapes(count, seed):
+    """Seeded random legal shapes: any M, in, out and any k that divides in*out (n_alpha 1 or k)."""
+    rng = np.random.default_rng(seed)
+    shapes = []
+    while len(shapes) < count:
+        M = int(rng.choice([1, 2, 7, 16, 33, 64, 65, 100, 129, 200, 257, 300]))
+        cin = int(rng.choice([8, 24, 40, 64, 72, 96, 128, 200, 256, 328, 512, 600, 1000, 1024, 1536, 2048]))
+        if rng.random() < 0.25:
+            cin = int(rng.integers(1, 400))            # also inner sizes that are not multiples of 8
+        cout = int(rng.integers(1, 700))
+        n = cin * cout
+        divisors = [d for d in range(1, 65) if n % d == 0]
+        k = int(rng.choice(divisors))
+        n_alpha = k if rng.random() < 0.6 else 1
+        shapes.append((M, cin, cout, k, n_alpha))
+    return shapes
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+@pytest.mark.parametrize("M,cin,cout,k,n_alpha", _random_linear_shapes(40, 20240712))
+def test_linear_random_shapes(tbn, M, cin, cout, k, n_alpha, dtype):
+    _linear_case(tbn, M, cin, cout, k, n_alpha, dtype, 0, 5000 + M + cin)
+    _linear_case(tbn, M, cin, cout, k, n_alpha, dtype, tbn.TBN_FLAG_RELU, 6000 + M + cin)
+
+
 @pytest.mark.parametrize("dtype", ["f32", "bf16"])
 def test_linear_output_pointer_not_16_byte_aligned(tbn, dtype):
     # the 16-byte store form needs an aligned y; one element further on the element-wise form has to take over
@@ -348,6 +373,33 @@ def test_conv_small_generic_kernel(tbn, N, C, H, W, O, kh, kw, stride, pad, k, n
 def test_conv_small_default_dispatch(tbn, N, C, H, W, O, kh, kw, stride, pad, k, n_alpha, dtype):
     _conv_case(tbn, N, C, H, W, O, kh, kw, stride, pad, k, n_alpha, dtype, 0, 60 + C + O)
     _conv_case(tbn, N, C, H, W, O, kh, kw, stride, pad, k, n_alpha, dtype, tbn.TBN_FLAG_RELU, 70 + C + O)
+
+
+def _random_conv_shapes(count, seed):
+    """Seeded random legal convolutions; about two thirds of them with channel counts the matrix-core
+    kernel takes (multiples of 32, 1x1 or 3x3)."""
+    rng = np.random.default_rng(seed)
+    shapes = []
+    while len(shapes) < count:
+        mfma_like = rng.random() < 0.67
+        C = int(rng.choice([32, 64, 96])) if mfma_like else int(rng.integers(1, 20))
+        kh, kw = (int(rng.choice([1, 3])),) * 2 if mfma_like else (int(rng.integers(1, 4)), int(rng.integers(1, 4)))
+        H, W = int(rng.integers(max(kh, 3), 30)), int(rng.integers(max(kw, 3), 66))
+        O = int(rng.integers(1, 100))
+        N = int(rng.integers(1, 4))
+        stride = (int(rng.integers(1, 3)), int(rng.integers(1, 3)))
+        pad = (int(rng.integers(0, kh)), int(rng.integers(0, kw)))
+        n = O * C * kh * kw
+        k = int(rng.choice([d for d in range(1, 33) if n % d == 0]))
+        n_alpha = k if rng.random() < 0.6 else 1
+        shapes.append((N, C, H, W, O, kh, kw, stride, pad, k, n_alpha))
+    return shapes
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+@pytest.mark.parametrize("N,C,H,W,O,kh,kw,stride,pad,k,n_alpha", _random_conv_shapes(24, 12075))
+def test_conv_random_shapes(tbn, N, C, H, W, O, kh, kw, stride, pad, k, n_alpha, dtype):
+    _conv_case(tbn, N, C, H, W, O, kh, kw, stride, pad, k, n_alpha, dtype, 0, 7000 + C + O)
 
 
 @pytest.mark.parametrize("c", [wl.CFG3, wl.CFG3_MISALIGNED], ids=lambda c: c.name)
