@@ -56,6 +56,8 @@ typedef enum {
 /* flags of the forward entry points */
 #define TBN_FLAG_RELU 0x1u          /* y = max(0, y): the fused ReLU of Algorithm 1 */
 #define TBN_FLAG_FORCE_GENERIC 0x100u /* testing aid: skip the specialised kernels */
+#define TBN_FLAG_LARGE_BATCH 0x200u   /* testing aid (linear only): batches above 64 skip the small-batch
+                                         kernel, which otherwise also takes small problems at larger batches */
 
 /* Number of 32-bit words of a tile of n / k entries (ceil(n / k / 32)); 0 if n <= 0, k <= 0 or
  * k does not divide n (the paper requires n divisible by the compression factor). */
@@ -103,7 +105,7 @@ tbn_status tbn_pack_tile(const float *w_real, const float *a_real, int64_t n, in
  *   y     : DEVICE, M x out, row-major, dense, element type dt; fully overwritten
  *   tile  : DEVICE, tbn_tile_words(in*out, k) words; read only
  *   alpha : DEVICE, n_alpha floats (n_alpha is 1 or k); read only
- *   flags : 0 or TBN_FLAG_RELU (| TBN_FLAG_FORCE_GENERIC)
+ *   flags : 0 or TBN_FLAG_RELU (| TBN_FLAG_FORCE_GENERIC | TBN_FLAG_LARGE_BATCH)
  * M == 0 is legal and does nothing (x and y may then be NULL).  x and y must not overlap.
  * Errors: TBN_ERR_NULL, TBN_ERR_SHAPE, TBN_ERR_UNSUPPORTED, TBN_ERR_DEVICE.
  */

@@ -101,7 +101,7 @@ tbn_status tbn_linear_forward(const void *x, void *y, tbn_dtype dt, int64_t M, i
         set_error("tbn_linear_forward: unknown dtype %d", (int)dt);
         return TBN_ERR_UNSUPPORTED;
     }
-    if (flags & ~(TBN_FLAG_RELU | TBN_FLAG_FORCE_GENERIC)) {
+    if (flags & ~(TBN_FLAG_RELU | TBN_FLAG_FORCE_GENERIC | TBN_FLAG_LARGE_BATCH)) {
         set_error("tbn_linear_forward: unknown flag bits 0x%x", flags);
         return TBN_ERR_UNSUPPORTED;
     }

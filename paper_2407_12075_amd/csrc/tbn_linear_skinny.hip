@@ -1,4 +1,5 @@
-// Small-batch (decode-shaped) kernel for the fully-connected tiled-bit layer: batch <= 64.
+// Small-batch (decode-shaped) kernel for the fully-connected tiled-bit layer: batch <= 64, and larger
+// batches as long as the problem is small (see linear_skinny_supported).
 //
 // Same mathematics as the large-batch kernel (Eq. 4-5, Algorithm 1): only the U = p / gcd(in, p)
 // distinct +-1 rows of the weight are multiplied, every output column o = u + t*U is alpha(o) * Z[:, u].
@@ -383,7 +384,20 @@ SkinnyParams make_params(const LinearArgs &a) {
 
 }  // namespace
 
-bool linear_skinny_supported(const LinearArgs &a) { return shape_ok(a) && a.M <= 64; }
+// Beyond batch 64 the kernel still takes small problems.  Its workgroups are 16 batch rows x 16 distinct
+// columns with K split over 8 waves, so a problem of a few hundred of them fills the chip, where the
+// 128 x 128 blocks of the large-batch kernels would leave most CUs idle behind a few long K loops.  Measured
+// on 4096 x 4096, k = 8 (this kernel / large-batch kernel, microseconds per call): bf16 9 / 27 at batch 128,
+// 16 / 27 at 256, 32 / 27 at 512; float32 13 / 105 at 128, 48 / 105 at 512, 94 / 107 at 1024, 186 / 110 at
+// 2048.  With fewer than 256 columns of K most of its waves have nothing to multiply and the large-batch
+// kernels win again.
+bool linear_skinny_supported(const LinearArgs &a) {
+    if (!shape_ok(a)) return false;
+    if (a.M <= 64) return true;
+    if ((a.flags & TBN_FLAG_LARGE_BATCH) || a.in < 256) return false;
+    const int64_t U = unique_rows(a.out, a.in, a.p);
+    return ((U + 15) / 16) * ((a.M + 15) / 16) <= (a.dt == TBN_F32 ? 2048 : 512);
+}
 
 // Recomputes the columns whose weight row holds a tile start (two alphas), at any batch size.
 tbn_status launch_linear_tile_ends(const LinearArgs &a) {

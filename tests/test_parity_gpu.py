@@ -129,10 +129,13 @@ LINEAR_SMALL = [
     (1, 3000, 96, 9, 9),
     (300, 264, 136, 3, 3),     # p = 11968 = 45 1/3 rows: no row repeats at all (U = out)
     (129, 64, 64, 64, 64),     # p = in: every row is the whole tile
-    (64, 1024, 512, 4, 4),     # largest batch of the small-batch kernel
+    (64, 1024, 512, 4, 4),     # largest batch the small-batch kernel takes whatever the problem size
     (17, 512, 256, 8, 8),      # two batch slabs, the second almost empty
     (48, 200, 90, 4, 4),       # small batch with tile ends inside rows
-    (65, 1024, 512, 4, 4),     # smallest batch of the large-batch kernel
+    (65, 1024, 512, 4, 4),     # smallest batch the large-batch kernels can take
+    (512, 1024, 1024, 4, 4),   # 16 x 32 = 512 workgroups of the small-batch kernel: its largest bf16 problem
+    (513, 1024, 1024, 4, 4),   # one more batch slab: bf16 goes to the large-batch kernel, float32 stays
+    (1040, 1024, 512, 4, 4),   # 8 x 65 workgroups: float32 on the small-batch kernel with many batch slabs
     (2, 4096, 40, 5, 5),       # 8 distinct rows only: a partly filled column tile
     # K-split matrix-core kernels: stage counts, tails, window wraps
     (130, 64, 256, 2, 2),      # one stage: the second K group only sees a stage past the end
@@ -183,10 +186,19 @@ def test_linear_small_default_dispatch(tbn, M, cin, cout, k, n_alpha, dtype):
 
 
 @pytest.mark.parametrize("dtype", ["f32", "bf16"])
+@pytest.mark.parametrize("M,cin,cout,k,n_alpha", [s for s in LINEAR_SMALL if s[0] > 64])
+def test_linear_small_large_batch_kernels(tbn, M, cin, cout, k, n_alpha, dtype):
+    # small problems at batches above 64 go to the small-batch kernel by default; this keeps them on the
+    # large-batch kernels, whose stage counts, tails and window wraps the shapes were chosen for
+    _linear_case(tbn, M, cin, cout, k, n_alpha, dtype, tbn.TBN_FLAG_LARGE_BATCH, 2500 + M + cin)
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
 @pytest.mark.parametrize("M,cin,cout,k,n_alpha", [(8, 256, 256, 4, 1), (130, 200, 120, 5, 5), (1, 784, 128, 4, 4)])
 def test_linear_fused_relu(tbn, M, cin, cout, k, n_alpha, dtype):
     _linear_case(tbn, M, cin, cout, k, n_alpha, dtype, tbn.TBN_FLAG_RELU, 3000 + M)
     _linear_case(tbn, M, cin, cout, k, n_alpha, dtype, tbn.TBN_FLAG_RELU | tbn.TBN_FLAG_FORCE_GENERIC, 3000 + M)
+    _linear_case(tbn, M, cin, cout, k, n_alpha, dtype, tbn.TBN_FLAG_RELU | tbn.TBN_FLAG_LARGE_BATCH, 3000 + M)
 
 
 def test_config1_pack_then_forward_on_device(tbn):
@@ -273,6 +285,8 @@ def _random_linear_shapes(count, seed):
 def test_linear_random_shapes(tbn, M, cin, cout, k, n_alpha, dtype):
     _linear_case(tbn, M, cin, cout, k, n_alpha, dtype, 0, 5000 + M + cin)
     _linear_case(tbn, M, cin, cout, k, n_alpha, dtype, tbn.TBN_FLAG_RELU, 6000 + M + cin)
+    if M > 64:
+        _linear_case(tbn, M, cin, cout, k, n_alpha, dtype, tbn.TBN_FLAG_RELU | tbn.TBN_FLAG_LARGE_BATCH, 6000 + M + cin)
 
 
 @pytest.mark.parametrize("dtype", ["f32", "bf16"])
@@ -292,10 +306,12 @@ def test_linear_output_pointer_not_16_byte_aligned(tbn, dtype):
     xd = x_to_device(x, bits)
     big = torch.zeros(M * cout + 8, dtype=xd.dtype, device="cuda")
     y = big[1:1 + M * cout].view(M, cout)
-    tbn.tbn_linear_forward(xd, dev(tile_ref.view(np.int32)), dev(alpha_ref), cout, k, y=y)
-    torch.cuda.synchronize()
-    assert_close(y_to_numpy(y), ref, dtype, f"linear with y offset by one element, {dtype}")
-    assert float(big[0]) == 0.0 and float(big[1 + M * cout:].abs().max()) == 0.0   # nothing written outside y
+    for flags in (tbn.TBN_FLAG_LARGE_BATCH, 0):
+        big.zero_()
+        tbn.tbn_linear_forward(xd, dev(tile_ref.view(np.int32)), dev(alpha_ref), cout, k, y=y, flags=flags)
+        torch.cuda.synchronize()
+        assert_close(y_to_numpy(y), ref, dtype, f"linear with y offset by one element, {dtype}, flags={flags:#x}")
+        assert float(big[0]) == 0.0 and float(big[1 + M * cout:].abs().max()) == 0.0   # nothing written outside y
 
 
 def test_aligned_output_blocks_are_scaled_copies_at_full_size(tbn):
