@@ -240,6 +240,17 @@ def time_other_configs(torch, tbn, wl, iters=30):
         us = timed(lambda: tbn.tbn_pack_tile(w, c.k, c.n_alpha, tile_out=tile, alpha_out=alpha, workspace=ws))
         out[c.name + ":pack"] = {"us": round(us, 2), "alg_gbs": round(c.n * 4 / us / 1e3, 1)}
         del w, x, y
+    # the same layers in the column-tiled layout (fold of the k column blocks + one +-1 product on in / k inputs)
+    for c in (wl.METRIC, *wl.CFG5):
+        w, x, _ = device_inputs(c, torch, wl)
+        tile, alpha = tbn.tbn_pack_coltile(w.view(c.cout, c.cin), c.k, c.k)
+        y = torch.empty((c.M, c.cout), dtype=x.dtype, device="cuda")
+        ws = torch.empty(tbn.tbn_linear_coltiled_workspace_bytes(x, c.k), dtype=torch.uint8, device="cuda")
+        us = timed(lambda: tbn.tbn_linear_coltiled_forward(x, tile, alpha, c.cout, c.k, y=y, workspace=ws))
+        byts = (c.M * c.cin + c.M * c.cout) * x.element_size() + c.p // 8
+        out[c.name + ":column_tiled"] = {"us": round(us, 2), "dense_equiv_tflops": round(2.0 * c.M * c.cin * c.cout / us / 1e6, 1),
+                                         "alg_gbs": round(byts / us / 1e3, 1)}
+        del w, x, y, ws
     for c in (wl.CFG3, wl.CFG3_MISALIGNED):
         w = torch.from_numpy(wl.draw_w_real(c.n, c.cfg, c.layer)).cuda()
         xv, _ = wl.draw_x((c.N, c.C, c.H, c.W), c.cfg, c.layer, c.dtype)

@@ -135,6 +135,58 @@ tbn_status tbn_conv2d_forward(const void *x, void *y, tbn_dtype dt, int64_t N, i
                               const uint32_t *tile, int32_t k, const float *alpha,
                               int32_t n_alpha, uint32_t flags, void *stream);
 
+/*
+ * Column-tiled variant of the fully-connected layer (Section "GPU Inference Kernel": the out x in weight
+ * is kept as one out x q block, q = in / k, which is used again for each of the k column blocks; with the
+ * per-copy scalars of Eq. 7-8, or the single scalar of Eq. 6):
+ *
+ *   W_hat[o, c*q + j] = alpha[c or 0] * t[o, j],  c < k, j < q;     Y = X * W_hat^T
+ *
+ * The tile holds t row-major: entry (o, j) is bit (o*q + j) % 32 of word (o*q + j) / 32, 1 means +1;
+ * it has tbn_tile_words(out*in, k) words.  k must divide in.
+ */
+
+/* Bytes of device workspace tbn_pack_coltile needs (0 on invalid sizes). */
+size_t tbn_pack_coltile_workspace_bytes(int64_t out, int64_t in, int32_t k, int32_t n_alpha);
+
+/*
+ * Tile and scalars of the column-tiled layout from a real out x in weight: Eq. 1-3 with the k column
+ * blocks as the k summands, Eq. 6 (n_alpha == 1) or Eq. 7-8 per column block (n_alpha == k).
+ *
+ *   s[o, j]   = sum_{c<k} w_real[o, c*q + j]           (double precision, c ascending)
+ *   t[o, j]   = +1 if s[o, j] > 0, else -1
+ *   alpha[c]  = sum_{o, j} |a[o, c*q + j]| / (out*q)   (alpha[0] = sum |a| / (out*in) if n_alpha == 1)
+ *
+ * Arguments, workspace rules and errors as for tbn_pack_tile, with w_real / a_real of out*in floats,
+ * row-major.  TBN_ERR_SHAPE also if k does not divide in.
+ */
+tbn_status tbn_pack_coltile(const float *w_real, const float *a_real, int64_t out, int64_t in, int32_t k,
+                            int32_t n_alpha, uint32_t *tile_out, float *alpha_out, void *workspace,
+                            size_t workspace_bytes, void *stream);
+
+/* Bytes of device workspace tbn_linear_coltiled_forward needs (0 on invalid sizes). */
+size_t tbn_linear_coltiled_workspace_bytes(tbn_dtype dt, int64_t M, int64_t in, int32_t k);
+
+/*
+ * Forward pass of the column-tiled layer, computed as
+ *
+ *   xf[m, j] = sum_{c<k} alpha[c or 0] * x[m, c*q + j]     (float32 sums, c ascending; rounded to dt)
+ *   y[m, o]  = sum_{j<q} xf[m, j] * t[o, j]                (binary32 accumulation)
+ *
+ * i.e. k times fewer multiply-adds than the dense layer and no repeated output columns.
+ *
+ *   x, y, tile, alpha, flags : as for tbn_linear_forward
+ *   workspace : DEVICE, at least tbn_linear_coltiled_workspace_bytes(dt, M, in, k) bytes, 16-byte
+ *               aligned; holds xf during the call; contents on entry are ignored, on exit undefined.
+ *               Calls that share a workspace must be ordered on one stream.
+ * M == 0 is legal and does nothing.
+ * Errors: TBN_ERR_NULL, TBN_ERR_SHAPE, TBN_ERR_WORKSPACE, TBN_ERR_UNSUPPORTED, TBN_ERR_DEVICE.
+ */
+tbn_status tbn_linear_coltiled_forward(const void *x, void *y, tbn_dtype dt, int64_t M, int64_t in,
+                                       int64_t out, const uint32_t *tile, int32_t k, const float *alpha,
+                                       int32_t n_alpha, uint32_t flags, void *workspace,
+                                       size_t workspace_bytes, void *stream);
+
 #ifdef __cplusplus
 }
 #endif

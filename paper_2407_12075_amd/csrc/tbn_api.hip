@@ -51,6 +51,48 @@ static tbn_status check_tiling(int64_t n, int32_t k, int32_t n_alpha) {
     return TBN_OK;
 }
 
+static tbn_status dispatch_linear(const LinearArgs &a) {
+    if (!(a.flags & TBN_FLAG_FORCE_GENERIC)) {
+        if (linear_skinny_supported(a)) return launch_linear_skinny(a);
+        if (linear_mfma_supported(a)) return launch_linear_mfma(a);
+        if (linear_rows_supported(a)) return launch_linear_rows(a);
+    }
+    return launch_linear_generic(a);
+}
+
+static tbn_status check_linear_args(const char *fn, const void *x, const void *y, tbn_dtype dt, int64_t M, int64_t in,
+                                    int64_t out, const uint32_t *tile, const float *alpha, uint32_t flags, int64_t *n) {
+    if (!tile || !alpha || (M > 0 && (!x || !y))) {  // an empty batch may come with NULL x and y
+        set_error("%s: x, y, tile and alpha must not be NULL", fn);
+        return TBN_ERR_NULL;
+    }
+    if (dt != TBN_F32 && dt != TBN_BF16) {
+        set_error("%s: unknown dtype %d", fn, (int)dt);
+        return TBN_ERR_UNSUPPORTED;
+    }
+    if (flags & ~(TBN_FLAG_RELU | TBN_FLAG_FORCE_GENERIC | TBN_FLAG_LARGE_BATCH)) {
+        set_error("%s: unknown flag bits 0x%x", fn, flags);
+        return TBN_ERR_UNSUPPORTED;
+    }
+    if (M < 0 || in <= 0 || out <= 0) {
+        set_error("%s: M (%lld) must be >= 0, in (%lld) and out (%lld) positive", fn,
+                  (long long)M, (long long)in, (long long)out);
+        return TBN_ERR_SHAPE;
+    }
+    int64_t xs, ys;
+    if (!mul_ok(in, out, n) || !mul_ok(M, in, &xs) || !mul_ok(M, out, &ys) || *n > (int64_t(1) << 40) ||
+        xs > (int64_t(1) << 40) || ys > (int64_t(1) << 40)) {
+        set_error("%s: sizes beyond the supported range", fn);
+        return TBN_ERR_UNSUPPORTED;
+    }
+    return TBN_OK;
+}
+
+static size_t coltile_xf_bytes(tbn_dtype dt, int64_t M, int64_t q) {
+    const size_t raw = static_cast<size_t>(M) * static_cast<size_t>(q) * (dt == TBN_F32 ? 4u : 2u);
+    return (raw + 255u) & ~static_cast<size_t>(255u);
+}
+
 }  // namespace tbn
 
 using namespace tbn;
@@ -93,41 +135,91 @@ tbn_status tbn_pack_tile(const float *w_real, const float *a_real, int64_t n, in
 tbn_status tbn_linear_forward(const void *x, void *y, tbn_dtype dt, int64_t M, int64_t in,
                               int64_t out, const uint32_t *tile, int32_t k, const float *alpha,
                               int32_t n_alpha, uint32_t flags, void *stream) {
-    if (!tile || !alpha || (M > 0 && (!x || !y))) {  // an empty batch may come with NULL x and y
-        set_error("tbn_linear_forward: x, y, tile and alpha must not be NULL");
-        return TBN_ERR_NULL;
-    }
-    if (dt != TBN_F32 && dt != TBN_BF16) {
-        set_error("tbn_linear_forward: unknown dtype %d", (int)dt);
-        return TBN_ERR_UNSUPPORTED;
-    }
-    if (flags & ~(TBN_FLAG_RELU | TBN_FLAG_FORCE_GENERIC | TBN_FLAG_LARGE_BATCH)) {
-        set_error("tbn_linear_forward: unknown flag bits 0x%x", flags);
-        return TBN_ERR_UNSUPPORTED;
-    }
-    if (M < 0 || in <= 0 || out <= 0) {
-        set_error("tbn_linear_forward: M >= 0, in > 0, out > 0 required (M=%lld in=%lld out=%lld)",
-                  (long long)M, (long long)in, (long long)out);
-        return TBN_ERR_SHAPE;
-    }
-    int64_t n, xs, ys;
-    if (!mul_ok(in, out, &n) || !mul_ok(M, in, &xs) || !mul_ok(M, out, &ys) || n > (int64_t(1) << 40) ||
-        xs > (int64_t(1) << 40) || ys > (int64_t(1) << 40)) {
-        set_error("tbn_linear_forward: sizes beyond the supported range");
-        return TBN_ERR_UNSUPPORTED;
-    }
-    tbn_status st = check_tiling(n, k, n_alpha);
+    int64_t n;
+    tbn_status st = check_linear_args("tbn_linear_forward", x, y, dt, M, in, out, tile, alpha, flags, &n);
+    if (st != TBN_OK) return st;
+    st = check_tiling(n, k, n_alpha);
     if (st != TBN_OK) return st;
     if (M == 0) return TBN_OK;
 
     LinearArgs a{x, y, (int)dt, M, in, out, tile, n / k, k, alpha, n_alpha, flags,
                  static_cast<hipStream_t>(stream)};
-    if (!(flags & TBN_FLAG_FORCE_GENERIC)) {
-        if (linear_skinny_supported(a)) return launch_linear_skinny(a);
-        if (linear_mfma_supported(a)) return launch_linear_mfma(a);
-        if (linear_rows_supported(a)) return launch_linear_rows(a);
+    return dispatch_linear(a);
+}
+
+size_t tbn_pack_coltile_workspace_bytes(int64_t out, int64_t in, int32_t k, int32_t n_alpha) {
+    int64_t n;
+    if (out <= 0 || in <= 0 || k <= 0 || in % k != 0 || (n_alpha != 1 && n_alpha != k) || !mul_ok(out, in, &n)) return 0;
+    return pack_workspace_bytes(n, k, n_alpha);
+}
+
+tbn_status tbn_pack_coltile(const float *w_real, const float *a_real, int64_t out, int64_t in, int32_t k,
+                            int32_t n_alpha, uint32_t *tile_out, float *alpha_out, void *workspace,
+                            size_t workspace_bytes, void *stream) {
+    if (!w_real || !tile_out || !alpha_out) {
+        set_error("tbn_pack_coltile: w_real, tile_out and alpha_out must not be NULL");
+        return TBN_ERR_NULL;
     }
-    return launch_linear_generic(a);
+    int64_t n;
+    if (out <= 0 || in <= 0 || !mul_ok(out, in, &n)) {
+        set_error("tbn_pack_coltile: out (%lld) and in (%lld) must be positive", (long long)out, (long long)in);
+        return TBN_ERR_SHAPE;
+    }
+    if (k <= 0 || in % k != 0) {
+        set_error("tbn_pack_coltile: in (%lld) is not divisible by the number of column blocks %d", (long long)in, k);
+        return TBN_ERR_SHAPE;
+    }
+    tbn_status st = check_tiling(n, k, n_alpha);
+    if (st != TBN_OK) return st;
+    const size_t need = pack_workspace_bytes(n, k, n_alpha);
+    if (!workspace || workspace_bytes < need || (reinterpret_cast<uintptr_t>(workspace) & 7u)) {
+        set_error("tbn_pack_coltile: workspace of %zu bytes, 8-byte aligned, required (got %zu at %p)",
+                  need, workspace_bytes, workspace);
+        return TBN_ERR_WORKSPACE;
+    }
+    return launch_pack(w_real, a_real, n, k, n_alpha, tile_out, alpha_out, workspace,
+                       static_cast<hipStream_t>(stream), in / k, in);
+}
+
+size_t tbn_linear_coltiled_workspace_bytes(tbn_dtype dt, int64_t M, int64_t in, int32_t k) {
+    int64_t xs;
+    if ((dt != TBN_F32 && dt != TBN_BF16) || M < 0 || in <= 0 || k <= 0 || in % k != 0 || !mul_ok(M, in, &xs) ||
+        xs > (int64_t(1) << 40))
+        return 0;
+    return coltile_xf_bytes(dt, M, in / k) + 256;
+}
+
+tbn_status tbn_linear_coltiled_forward(const void *x, void *y, tbn_dtype dt, int64_t M, int64_t in,
+                                       int64_t out, const uint32_t *tile, int32_t k, const float *alpha,
+                                       int32_t n_alpha, uint32_t flags, void *workspace,
+                                       size_t workspace_bytes, void *stream) {
+    int64_t n;
+    tbn_status st = check_linear_args("tbn_linear_coltiled_forward", x, y, dt, M, in, out, tile, alpha, flags, &n);
+    if (st != TBN_OK) return st;
+    if (k <= 0 || in % k != 0) {
+        set_error("tbn_linear_coltiled_forward: in (%lld) is not divisible by the number of column blocks %d",
+                  (long long)in, k);
+        return TBN_ERR_SHAPE;
+    }
+    if (n_alpha != 1 && n_alpha != k) {
+        set_error("n_alpha must be 1 or k (%d), got %d", k, n_alpha);
+        return TBN_ERR_SHAPE;
+    }
+    const int64_t q = in / k;
+    const size_t xf_bytes = coltile_xf_bytes(dt, M, q), need = xf_bytes + 256;
+    if (!workspace || workspace_bytes < need || (reinterpret_cast<uintptr_t>(workspace) & 15u)) {
+        set_error("tbn_linear_coltiled_forward: workspace of %zu bytes, 16-byte aligned, required (got %zu at %p)",
+                  need, workspace_bytes, workspace);
+        return TBN_ERR_WORKSPACE;
+    }
+    if (M == 0) return TBN_OK;
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    float *one = reinterpret_cast<float *>(static_cast<unsigned char *>(workspace) + xf_bytes);
+    st = launch_coltile_fold(x, workspace, (int)dt, M, in, k, alpha, n_alpha, one, s);
+    if (st != TBN_OK) return st;
+    // the +-1 product on the folded activations: the flat layer with one tile copy and alpha = 1
+    LinearArgs a{workspace, y, (int)dt, M, q, out, tile, out * q, 1, one, 1, flags, s};
+    return dispatch_linear(a);
 }
 
 tbn_status tbn_conv2d_forward(const void *x, void *y, tbn_dtype dt, int64_t N, int64_t C,

@@ -46,8 +46,10 @@ struct ConvArgs {
 };
 
 // kernel families; each returns TBN_OK after enqueueing, or an error with nothing enqueued
+// blk > 0: column-tiled layout, summand r of tile position i is element (i / blk) * ld + r * blk + i % blk
 tbn_status launch_pack(const float *w, const float *a, int64_t n, int32_t k, int32_t n_alpha,
-                       uint32_t *tile_out, float *alpha_out, void *workspace, hipStream_t stream);
+                       uint32_t *tile_out, float *alpha_out, void *workspace, hipStream_t stream,
+                       int64_t blk = 0, int64_t ld = 0);
 size_t pack_workspace_bytes(int64_t n, int32_t k, int32_t n_alpha);
 
 tbn_status launch_linear_generic(const LinearArgs &a);
@@ -59,6 +61,10 @@ tbn_status launch_linear_rows_fixup(const LinearArgs &a);  // recompute the colu
 tbn_status launch_linear_tile_ends(const LinearArgs &a);   // the same in one pass over X (falls back to the above)
 bool linear_mfma_supported(const LinearArgs &a);   // matrix-core kernel
 tbn_status launch_linear_mfma(const LinearArgs &a);
+
+// column-tiled layer: xf[m, j] = sum_c alpha[c] * x[m, c * q + j], and the float 1.0 written to *one_out
+tbn_status launch_coltile_fold(const void *x, void *xf, int dt, int64_t M, int64_t in, int32_t k,
+                               const float *alpha, int32_t n_alpha, float *one_out, hipStream_t stream);
 
 tbn_status launch_conv_generic(const ConvArgs &a);
 tbn_status launch_conv_generic_tile_ends(const ConvArgs &a);   // only the channels whose filter holds a tile end

@@ -499,33 +499,38 @@ namespace direct {
 constexpr int kNB = 4;                         // LDS stage buffers per K group
 constexpr int kBias = 3 * 1024;                // keeps the lane offsets non-negative, see below
 
-// The kernel exists with two K groups of two waves (one wave per SIMD) and with four K groups of two
-// waves (two waves per SIMD, which hides one wave's instruction issue and waits behind the other's
-// MFMAs).  A stage of a group is 128 / KG elements of K, so that both forms move through K at the same
-// pace and use the same 128 KiB of LDS.
-template <int KG>
+// The kernel exists in three forms.  Two K groups of two waves with stages of 64 elements of K (one wave per
+// SIMD, 128 KiB of LDS: one workgroup per CU) is the form for long K loops and one block per CU.  The same
+// with stages of 32 elements takes 64 KiB, so that two workgroups share a CU and the index work, pipeline
+// fill and epilogue of one hide behind the other's MFMAs: the form for short K loops and for grids of
+// several blocks per CU.  Four K groups of two waves (two waves of one workgroup per SIMD) is kept for
+// comparison.
+template <int KG, int BKP = 128 / KG>
 struct Cfg {
     static constexpr int kThreads = KG * 128;
-    static constexpr int BK = 128 / KG;                  // K elements per stage
+    static constexpr int BK = BKP;                       // K elements per stage
     static constexpr int KS = BK / 16;                   // MFMA steps per stage
     static constexpr int WW = (BK + 31) / 32;            // 32-bit window words per stage
     static constexpr int kRowBytes = BK * 2;             // unpadded
     static constexpr int kSwz = kRowBytes / 16 - 1;      // chunk swizzle mask
-    static constexpr int kSwzShift = KG == 2 ? 1 : 2;    // row bits that drive the swizzle start here
+    static constexpr int kSwzShift = kRowBytes == 128 ? 1 : 2;    // row bits that drive the swizzle start here
     // With 64-byte rows two row slots share the 32 banks.  The LDS serves the even and the odd lanes of
     // 16 in turn, so rows 2i and 2i + 2 must not sit in the same half: row slots trade their two lowest
     // row bits.
-    static __device__ __host__ constexpr int row_slot(int r) { return KG == 2 ? r : ((r & ~3) | ((r & 1) << 1) | ((r >> 1) & 1)); }
+    static __device__ __host__ constexpr int row_slot(int r) { return kRowBytes == 128 ? r : ((r & ~3) | ((r & 1) << 1) | ((r >> 1) & 1)); }
     static constexpr int kStageBytes = kBM * kRowBytes;
     static constexpr int kLoads = kStageBytes / 2 / 1024;   // 1 KiB wave-loads per wave and stage
     static constexpr int kRowsPerLoad = 1024 / kRowBytes;
     static constexpr int kLanesPerRow = kRowBytes / 16;
     static constexpr int kVmPerStage = kLoads + 1;       // vector-memory instructions per stage
-    static constexpr int kLdsBytes = KG * kNB * kStageBytes;   // 128 KiB
+    static constexpr int kStagesBytes = KG * kNB * kStageBytes;
+    static constexpr int kLdsBytes = kStagesBytes > KG * 32768 ? kStagesBytes : KG * 32768;   // the partial sums handed over at the end need 32 KiB per group
+    static constexpr int kWavesPerSimd = kLdsBytes <= 65536 ? 2 : 1;   // asked of the compiler: registers for two resident workgroups
     static constexpr int kRot = kTM / KG;                // row blocks a group keeps at the end
     static_assert(KG == 2 || KG == 4, "two or four K groups");
+    static_assert(BK == 32 || BK == 64, "stages of 32 or 64 elements");
     static_assert(kLoads == 2 * KS, "two wave-loads per MFMA step");
-    static_assert(kLdsBytes == 131072, "LDS budget");
+    static_assert(kLdsBytes == 131072 || kLdsBytes == 65536, "LDS budget");
 };
 
 // Operand reads are written as inline assembly so that the compiler does not see LDS reads next to the
@@ -563,12 +568,12 @@ __device__ __forceinline__ void stage_load_one(const unsigned char *src, uint32_
     __builtin_amdgcn_global_load_lds(src + off, dst + (J >> 2) * 4096, 16, (J & 3) * 1024, 0);
 }
 
-template <int KG, bool RELU>
-__global__ __launch_bounds__(Cfg<KG>::kThreads, 1) void linear_mfma_bf16_kernel(const uint16_t *__restrict__ x,
+template <int KG, int BKP, bool RELU>
+__global__ __launch_bounds__((Cfg<KG, BKP>::kThreads), (Cfg<KG, BKP>::kWavesPerSimd)) void linear_mfma_bf16_kernel(const uint16_t *__restrict__ x,
                                                                           uint16_t *__restrict__ y,
                                                                           const uint32_t *__restrict__ tile,
                                                                           const float *__restrict__ alpha, MfmaParams P) {
-    typedef Cfg<KG> C;
+    typedef Cfg<KG, BKP> C;
     constexpr int BK = C::BK, KS = C::KS, WW = C::WW, kRowBytes = C::kRowBytes, kStageBytes = C::kStageBytes;
     constexpr int kLoads = C::kLoads, kVmPerStage = C::kVmPerStage, kKG = KG;
     extern __shared__ __attribute__((aligned(1024))) unsigned char lds_raw[];
@@ -646,7 +651,7 @@ __global__ __launch_bounds__(Cfg<KG>::kThreads, 1) void linear_mfma_bf16_kernel(
             stage_load_one<6>(src, a_off[6], dst);
             stage_load_one<7>(src, a_off[7], dst);
         }
-        load_window_one<BK, 128>(P, tile, pos, wreg[slot], wpos[slot]);
+        load_window_one<BK, KG * BK>(P, tile, pos, wreg[slot], wpos[slot]);
     };
     auto load_stage_any = [&](int slot, int32_t v) {
         const int32_t k0 = (v * kKG + grp) * BK;
@@ -662,7 +667,7 @@ __global__ __launch_bounds__(Cfg<KG>::kThreads, 1) void linear_mfma_bf16_kernel(
             c = c < P.in - 8 ? c : P.in - 8;
             load_to_lds16(x_blk + (a_row[j] + static_cast<uint32_t>(c) * 2u), dst + j * 1024);
         }
-        load_window_one<BK, 128>(P, tile, pos, wreg[slot], wpos[slot]);
+        load_window_one<BK, KG * BK>(P, tile, pos, wreg[slot], wpos[slot]);
     };
     // Zeroes the part of stage v that lies past the end of K (its loads are waited for first).
     auto zero_tail = [&](int32_t v) {
@@ -804,7 +809,7 @@ __global__ __launch_bounds__(Cfg<KG>::kThreads, 1) void linear_mfma_bf16_kernel(
             // half's column here, the trade with the other half after the step's last MFMA; in the last
             // step the window load of stage st + 3
             if constexpr (ks == KS - 2) form_window_one<BK>(P, wreg[kBufNext], wpos[kBufNext], head, own);
-            if constexpr (ks == KS - 1) load_window_one<BK, 128>(P, tile, pos, wreg[kBufLoad], wpos[kBufLoad]);
+            if constexpr (ks == KS - 1) load_window_one<BK, KG * BK>(P, tile, pos, wreg[kBufLoad], wpos[kBufLoad]);
             __builtin_amdgcn_sched_barrier(0);
             mfma(3, 0);
             stage_load_one<2 * ks + 1>(src, a_off[2 * ks + 1], dst);
@@ -1090,20 +1095,37 @@ tbn_status set_lds_limit(K kernel, int lds, bool &done) {
     return TBN_OK;
 }
 
-// K groups of the bf16 kernel.  Four groups (two waves per SIMD) pass the same tests but measure about
-// 12 % slower in the main loop: the two waves of a SIMD do not alternate on the matrix pipe.
+// Forms of the bf16 kernel (see direct::Cfg).  Four K groups (two waves of one workgroup per SIMD) pass the
+// same tests but measure about 12 % slower in the main loop than two: the two waves of a SIMD do not
+// alternate on the matrix pipe.  The form with 32-element stages runs two workgroups per CU; it wins where a
+// workgroup's fixed work (index arithmetic, pipeline fill, hand-over of the partial sums, epilogue) weighs
+// against a short K loop and some CUs have more than one block to run: 8192 x 512 -> 4096 distinct columns 56 us
+// against 77, 8192 x 1024 -> 2048 42 against 55, 8192 x 1024 -> 768 (384 blocks) 21 against 26; at in = 4096 the
+// forms are within 4 % of each other, and with one block per CU the 64-element stages win (42.6 us against 45.2
+// on 8192 x 4096, 512 distinct columns).
 #ifndef TBN_BF16_GROUPS
 #define TBN_BF16_GROUPS 2
 #endif
 constexpr int kBf16Groups = TBN_BF16_GROUPS;
+#ifndef TBN_BF16_STAGE
+#define TBN_BF16_STAGE (128 / TBN_BF16_GROUPS)
+#endif
+constexpr int kBf16Stage = TBN_BF16_STAGE;
+#ifndef TBN_TWO_RESIDENT_MAX_K
+#define TBN_TWO_RESIDENT_MAX_K 3072
+#endif
+#ifndef TBN_TWO_RESIDENT_MIN_BLOCKS
+#define TBN_TWO_RESIDENT_MIN_BLOCKS 257   // more than one per CU
+#endif
 
-template <int KG, bool RELU>
+template <int KG, int BK, bool RELU>
 tbn_status launch_bf16(const LinearArgs &a, const MfmaParams &P, dim3 grid) {
+    typedef direct::Cfg<KG, BK> C;
     static bool attr_set = false;
-    tbn_status st = set_lds_limit(&direct::linear_mfma_bf16_kernel<KG, RELU>, direct::Cfg<KG>::kLdsBytes, attr_set);
+    tbn_status st = set_lds_limit(&direct::linear_mfma_bf16_kernel<KG, BK, RELU>, C::kLdsBytes, attr_set);
     if (st != TBN_OK) return st;
-    hipLaunchKernelGGL((direct::linear_mfma_bf16_kernel<KG, RELU>), grid, dim3(direct::Cfg<KG>::kThreads),
-                       direct::Cfg<KG>::kLdsBytes, a.stream, static_cast<const uint16_t *>(a.x),
+    hipLaunchKernelGGL((direct::linear_mfma_bf16_kernel<KG, BK, RELU>), grid, dim3(C::kThreads),
+                       C::kLdsBytes, a.stream, static_cast<const uint16_t *>(a.x),
                        static_cast<uint16_t *>(a.y), a.tile, a.alpha, P);
     return check_launch("tbn_linear_forward (matrix-core kernel)");
 }
@@ -1154,8 +1176,10 @@ tbn_status launch_linear_mfma(const LinearArgs &a) {
     tbn_status st;
     if (a.dt == TBN_F32)
         st = relu ? launch_f32<true>(a, P, grid) : launch_f32<false>(a, P, grid);
+    else if (kBf16Groups == 2 && blocks >= TBN_TWO_RESIDENT_MIN_BLOCKS && a.in <= TBN_TWO_RESIDENT_MAX_K)
+        st = relu ? launch_bf16<2, 32, true>(a, P, grid) : launch_bf16<2, 32, false>(a, P, grid);
     else
-        st = relu ? launch_bf16<kBf16Groups, true>(a, P, grid) : launch_bf16<kBf16Groups, false>(a, P, grid);
+        st = relu ? launch_bf16<kBf16Groups, kBf16Stage, true>(a, P, grid) : launch_bf16<kBf16Groups, kBf16Stage, false>(a, P, grid);
     if (st != TBN_OK) return st;
     // columns whose weight row straddles a tile end need two alphas
     if (a.n_alpha > 1 && !P.aligned) return launch_linear_tile_ends(a);

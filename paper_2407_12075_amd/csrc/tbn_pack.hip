@@ -9,6 +9,11 @@
 // precision: a wave reduces its share of row r and writes one partial per (wave, r) to the
 // workspace; a second small kernel adds the partials in a fixed order and divides (Eq. 6 / 8).
 // No floating-point atomics are used, so results are reproducible bit for bit.
+//
+// The same kernels build the tile of the column-tiled layout (GPU Inference Kernel section): there the k
+// summands of tile position i = o * blk + j are the entries (o, r * blk + j) of an out x in matrix with
+// blk = in / k, i.e. summand r of position i sits at (i / blk) * ld + r * blk + i % blk with ld = in.  The flat
+// layout of Eq. 1 is the case blk = p (one "row" holds the whole tile).
 #include "tbn_common.h"
 
 namespace tbn {
@@ -31,6 +36,7 @@ __device__ __forceinline__ double wave_sum_f64(double v) {
 template <int VEC, bool SEPARATE_A>
 __global__ __launch_bounds__(kPackThreads) void pack_kernel(const float *__restrict__ w,
                                                             const float *__restrict__ a, int64_t p, int32_t k,
+                                                            int64_t blk, int64_t ld,
                                                             uint32_t *__restrict__ tile_out, int64_t n_words,
                                                             double *__restrict__ partial) {
     constexpr int64_t kChunk = int64_t(kPackThreads) * VEC;   // positions covered by one load round
@@ -45,19 +51,20 @@ __global__ __launch_bounds__(kPackThreads) void pack_kernel(const float *__restr
 #pragma unroll
         for (int v = 0; v < VEC; ++v) s[q][v] = 0.0;
 
-    int64_t pos[kPackQ];
+    int64_t pos[kPackQ];   // offset of summand 0 of the thread's positions
     bool live[kPackQ];
 #pragma unroll
     for (int q = 0; q < kPackQ; ++q) {
-        pos[q] = block_base + q * kChunk + int64_t(tid) * VEC;
-        live[q] = pos[q] < p;  // VEC == 4 is only used when p % 4 == 0: a vector is all in or all out
+        const int64_t i = block_base + q * kChunk + int64_t(tid) * VEC;
+        live[q] = i < p;  // VEC == 4 is only used when p % 4 == 0: a vector is all in or all out
+        pos[q] = (blk == p || !live[q]) ? i : (i / blk) * ld + i % blk;   // blk % 4 == 0 with VEC == 4: no vector spans two rows
     }
 
     double *my_partial = partial + (int64_t(blockIdx.x) * kPackWaves + wave) * k;
 
     for (int32_t r = 0; r < k; ++r) {
-        const float *wr = w + int64_t(r) * p;
-        const float *ar = SEPARATE_A ? a + int64_t(r) * p : wr;
+        const float *wr = w + int64_t(r) * blk;
+        const float *ar = SEPARATE_A ? a + int64_t(r) * blk : wr;
         float wv[kPackQ][VEC];
         float av[kPackQ][VEC];
 #pragma unroll
@@ -159,10 +166,12 @@ size_t pack_workspace_bytes(int64_t n, int32_t k, int32_t /*n_alpha*/) {
 }
 
 tbn_status launch_pack(const float *w, const float *a, int64_t n, int32_t k, int32_t n_alpha,
-                       uint32_t *tile_out, float *alpha_out, void *workspace, hipStream_t stream) {
+                       uint32_t *tile_out, float *alpha_out, void *workspace, hipStream_t stream,
+                       int64_t blk, int64_t ld) {
     const int64_t p = n / k;
     const int64_t n_words = (p + 31) / 32;
-    const bool vec4 = (p % 4 == 0) && ((reinterpret_cast<uintptr_t>(w) & 15u) == 0) &&
+    if (blk <= 0) { blk = p; ld = 0; }   // flat layout
+    const bool vec4 = (p % 4 == 0) && (blk % 4 == 0) && (ld % 4 == 0) && ((reinterpret_cast<uintptr_t>(w) & 15u) == 0) &&
                       (!a || (reinterpret_cast<uintptr_t>(a) & 15u) == 0);
     const int64_t blocks = pack_blocks(p, vec4 ? 4 : 1);
     if (blocks > 0x7fffffffLL) {
@@ -172,11 +181,11 @@ tbn_status launch_pack(const float *w, const float *a, int64_t n, int32_t k, int
     double *partial = static_cast<double *>(workspace);
     const dim3 grid(static_cast<unsigned>(blocks)), block(kPackThreads);
     if (vec4) {
-        if (a) hipLaunchKernelGGL((pack_kernel<4, true>), grid, block, 0, stream, w, a, p, k, tile_out, n_words, partial);
-        else   hipLaunchKernelGGL((pack_kernel<4, false>), grid, block, 0, stream, w, a, p, k, tile_out, n_words, partial);
+        if (a) hipLaunchKernelGGL((pack_kernel<4, true>), grid, block, 0, stream, w, a, p, k, blk, ld, tile_out, n_words, partial);
+        else   hipLaunchKernelGGL((pack_kernel<4, false>), grid, block, 0, stream, w, a, p, k, blk, ld, tile_out, n_words, partial);
     } else {
-        if (a) hipLaunchKernelGGL((pack_kernel<1, true>), grid, block, 0, stream, w, a, p, k, tile_out, n_words, partial);
-        else   hipLaunchKernelGGL((pack_kernel<1, false>), grid, block, 0, stream, w, a, p, k, tile_out, n_words, partial);
+        if (a) hipLaunchKernelGGL((pack_kernel<1, true>), grid, block, 0, stream, w, a, p, k, blk, ld, tile_out, n_words, partial);
+        else   hipLaunchKernelGGL((pack_kernel<1, false>), grid, block, 0, stream, w, a, p, k, blk, ld, tile_out, n_words, partial);
     }
     tbn_status st = check_launch("tbn_pack_tile (tile kernel)");
     if (st != TBN_OK) return st;

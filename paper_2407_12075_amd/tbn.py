@@ -58,6 +58,15 @@ def lib() -> ctypes.CDLL:
         L.tbn_conv2d_forward.argtypes = [_c_vp, _c_vp, ctypes.c_int, _c_i64, _c_i64, _c_i64, _c_i64, _c_i64, _c_i32,
                                          _c_i32, _c_i32, _c_i32, _c_i32, _c_i32, _c_vp, _c_i32, _c_vp, _c_i32, _c_u32,
                                          _c_vp]
+        L.tbn_pack_coltile_workspace_bytes.restype = _c_sz
+        L.tbn_pack_coltile_workspace_bytes.argtypes = [_c_i64, _c_i64, _c_i32, _c_i32]
+        L.tbn_pack_coltile.restype = ctypes.c_int
+        L.tbn_pack_coltile.argtypes = [_c_vp, _c_vp, _c_i64, _c_i64, _c_i32, _c_i32, _c_vp, _c_vp, _c_vp, _c_sz, _c_vp]
+        L.tbn_linear_coltiled_workspace_bytes.restype = _c_sz
+        L.tbn_linear_coltiled_workspace_bytes.argtypes = [ctypes.c_int, _c_i64, _c_i64, _c_i32]
+        L.tbn_linear_coltiled_forward.restype = ctypes.c_int
+        L.tbn_linear_coltiled_forward.argtypes = [_c_vp, _c_vp, ctypes.c_int, _c_i64, _c_i64, _c_i64, _c_vp, _c_i32,
+                                                  _c_vp, _c_i32, _c_u32, _c_vp, _c_sz, _c_vp]
         _lib = L
     return _lib
 
@@ -146,6 +155,54 @@ def tbn_linear_forward(x: torch.Tensor, tile: torch.Tensor, alpha: torch.Tensor,
 
 def conv_out_hw(H: int, W: int, kh: int, kw: int, stride, pad) -> Tuple[int, int]:
     return (H + 2 * pad[0] - kh) // stride[0] + 1, (W + 2 * pad[1] - kw) // stride[1] + 1
+
+
+def tbn_pack_coltile(w_real: torch.Tensor, k: int, n_alpha: int = 1, a_real: Optional[torch.Tensor] = None,
+                     workspace: Optional[torch.Tensor] = None, stream=None) -> Tuple[torch.Tensor, torch.Tensor]:
+    """Tile and alpha of the column-tiled layout from a real (out, in) weight; k column blocks."""
+    if w_real.dim() != 2:
+        raise ValueError("w_real must be (out, in)")
+    out, cin = w_real.shape
+    dev = w_real.device
+    tile_out = torch.empty(max(tbn_tile_words(out * cin, k), 1), dtype=torch.int32, device=dev)
+    alpha_out = torch.empty(max(n_alpha, 1), dtype=torch.float32, device=dev)
+    need = int(lib().tbn_pack_coltile_workspace_bytes(out, cin, k, n_alpha))
+    if workspace is None:
+        workspace = torch.empty(max(need, 8), dtype=torch.uint8, device=dev)
+    st = lib().tbn_pack_coltile(_dev(w_real, "w_real", torch.float32),
+                                None if a_real is None else _dev(a_real, "a_real", torch.float32),
+                                out, cin, k, n_alpha, _dev(tile_out, "tile_out", torch.int32),
+                                _dev(alpha_out, "alpha_out", torch.float32), _dev(workspace, "workspace"),
+                                workspace.numel() * workspace.element_size(), _stream(stream))
+    if st != TBN_OK:
+        _raise(st)
+    return tile_out, alpha_out
+
+
+def tbn_linear_coltiled_workspace_bytes(x: torch.Tensor, k: int) -> int:
+    return int(lib().tbn_linear_coltiled_workspace_bytes(_dt(x), x.shape[0], x.shape[1], k))
+
+
+def tbn_linear_coltiled_forward(x: torch.Tensor, tile: torch.Tensor, alpha: torch.Tensor, out_features: int, k: int,
+                                y: Optional[torch.Tensor] = None, flags: int = 0,
+                                workspace: Optional[torch.Tensor] = None, stream=None) -> torch.Tensor:
+    """Column-tiled layer: W_hat[o, c*q + j] = alpha[c] * t[o, j]; y has shape (M, out_features) and x's dtype."""
+    if x.dim() != 2:
+        raise ValueError("x must be (M, in)")
+    M, cin = x.shape
+    if y is None:
+        y = torch.empty((M, out_features), dtype=x.dtype, device=x.device)
+    elif tuple(y.shape) != (M, out_features) or y.dtype != x.dtype:
+        raise ValueError("y must be (M, out) with x's dtype")
+    if workspace is None:
+        workspace = torch.empty(max(tbn_linear_coltiled_workspace_bytes(x, k), 16), dtype=torch.uint8, device=x.device)
+    st = lib().tbn_linear_coltiled_forward(_dev(x, "x"), _dev(y, "y"), _dt(x), M, cin, out_features,
+                                           _dev(tile, "tile", torch.int32), k, _dev(alpha, "alpha", torch.float32),
+                                           alpha.numel(), flags, _dev(workspace, "workspace"),
+                                           workspace.numel() * workspace.element_size(), _stream(stream))
+    if st != TBN_OK:
+        _raise(st)
+    return y
 
 
 def tbn_conv2d_forward(x: torch.Tensor, tile: torch.Tensor, alpha: torch.Tensor, out_channels: int, kh: int,

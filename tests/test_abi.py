@@ -90,6 +90,29 @@ def test_validation_status_codes(lib):
     assert lib.tbn_conv2d_forward(fake, fake, 0, 0, 1, 4, 4, 2, 3, 3, 1, 1, 0, 0, fake, 2, fake, 1, 0, None) == 0
 
 
+def test_column_tiled_entry_points_validate(lib):
+    p = ctypes.c_void_p
+    fake = p(256)
+    assert lib.tbn_pack_coltile_workspace_bytes(16, 10, 4, 4) == 0       # k must divide in, not just out * in
+    assert lib.tbn_pack_coltile_workspace_bytes(16, 12, 4, 4) > 0
+    assert lib.tbn_linear_coltiled_workspace_bytes(1, 8, 64, 4) == 8 * 16 * 2 + 256
+    assert lib.tbn_linear_coltiled_workspace_bytes(0, 3, 10, 5) == 256 + 256
+    assert lib.tbn_linear_coltiled_workspace_bytes(0, 3, 10, 4) == 0
+    assert lib.tbn_pack_coltile(None, None, 4, 8, 2, 1, fake, fake, fake, 1 << 20, None) == 1
+    assert lib.tbn_pack_coltile(fake, None, 16, 10, 4, 4, fake, fake, fake, 1 << 20, None) == 2
+    assert "column blocks" in _err(lib)
+    assert lib.tbn_pack_coltile(fake, None, 16, 12, 4, 2, fake, fake, fake, 1 << 20, None) == 2
+    assert lib.tbn_pack_coltile(fake, None, 1024, 1024, 2, 1, fake, fake, fake, 8, None) == 5
+    assert lib.tbn_linear_coltiled_forward(None, fake, 0, 1, 8, 4, fake, 2, fake, 1, 0, fake, 1 << 20, None) == 1
+    assert lib.tbn_linear_coltiled_forward(fake, fake, 0, 1, 10, 4, fake, 4, fake, 1, 0, fake, 1 << 20, None) == 2
+    assert lib.tbn_linear_coltiled_forward(fake, fake, 0, 1, 8, 4, fake, 2, fake, 3, 0, fake, 1 << 20, None) == 2
+    assert lib.tbn_linear_coltiled_forward(fake, fake, 5, 1, 8, 4, fake, 2, fake, 1, 0, fake, 1 << 20, None) == 3
+    assert lib.tbn_linear_coltiled_forward(fake, fake, 0, 1, 8, 4, fake, 2, fake, 1, 0, fake, 16, None) == 5
+    assert lib.tbn_linear_coltiled_forward(fake, fake, 0, 1, 8, 4, fake, 2, fake, 1, 0, p(264), 1 << 20, None) == 5
+    assert lib.tbn_linear_coltiled_forward(fake, fake, 0, 1, 8, 4, fake, 2, fake, 1, 0, None, 1 << 20, None) == 5
+    assert lib.tbn_linear_coltiled_forward(fake, fake, 0, 0, 8, 4, fake, 2, fake, 1, 0, fake, 1 << 20, None) == 0
+
+
 def test_binding_refuses_host_tensors():
     import torch
     from paper_2407_12075_amd import tbn

@@ -154,6 +154,20 @@ LINEAR_SMALL = [
 ]
 
 
+# More than 256 blocks of 128 x 128 and a short K loop: the bf16 kernel runs in its form with two workgroups
+# per CU (32-element stages).
+LINEAR_MANY_BLOCKS = [
+    (4224, 1000, 1024, 1, 1),   # 33 x 8 blocks; in % 64 = 40: the last stage of one K group is partly filled
+    (8320, 200, 1024, 2, 2),    # 65 x 4 blocks, the last row block all valid; 512 distinct rows, 2 replicas
+    (8300, 264, 544, 3, 3),     # tile ends inside rows: no row repeats, 5 column blocks, ragged row and column blocks
+    (4230, 32, 1040, 1, 1),     # one stage: the second K group only sees a stage past the end
+    (4230, 96, 1040, 2, 1),     # three stages
+    (4500, 520, 1024, 1, 1),    # in % 64 = 8: a last stage with one valid piece
+    (4224, 2048, 1024, 1, 1),   # 32 rounds of the steady-state loop
+    (4224, 448, 1024, 1, 1),    # the shortest K with a steady-state round
+]
+
+
 def _linear_case(tbn, M, cin, cout, k, n_alpha, dtype, flags, seed):
     rng = np.random.default_rng(seed)
     w = (0.02 * rng.standard_normal(cin * cout)).astype(np.float32)
@@ -191,6 +205,34 @@ def test_linear_small_large_batch_kernels(tbn, M, cin, cout, k, n_alpha, dtype):
     # small problems at batches above 64 go to the small-batch kernel by default; this keeps them on the
     # large-batch kernels, whose stage counts, tails and window wraps the shapes were chosen for
     _linear_case(tbn, M, cin, cout, k, n_alpha, dtype, tbn.TBN_FLAG_LARGE_BATCH, 2500 + M + cin)
+
+
+@pytest.mark.parametrize("dtype", ["bf16", "f32"])
+@pytest.mark.parametrize("M,cin,cout,k,n_alpha", LINEAR_MANY_BLOCKS)
+def test_linear_many_blocks_short_k(tbn, M, cin, cout, k, n_alpha, dtype):
+    _linear_case(tbn, M, cin, cout, k, n_alpha, dtype, tbn.TBN_FLAG_RELU if cin == 200 else 0, 2700 + M + cin)
+
+
+def _random_many_block_shapes(count, seed):
+    rng = np.random.default_rng(seed)
+    shapes = []
+    while len(shapes) < count:
+        M = int(rng.integers(4200, 8400))
+        cin = int(rng.choice([32, 40, 64, 72, 128, 200, 256, 328, 456, 512, 600]))
+        cout = int(rng.integers(520, 1200))
+        n = cin * cout
+        k = int(rng.choice([d for d in range(1, 9) if n % d == 0]))
+        p = n // k
+        U = min(cout, p // np.gcd(cin, p))
+        if p < cin or ((M + 127) // 128) * ((U + 127) // 128) <= 256:
+            continue
+        shapes.append((M, cin, cout, k, k if rng.random() < 0.6 else 1))
+    return shapes
+
+
+@pytest.mark.parametrize("M,cin,cout,k,n_alpha", _random_many_block_shapes(10, 1207))
+def test_linear_random_many_block_shapes(tbn, M, cin, cout, k, n_alpha):
+    _linear_case(tbn, M, cin, cout, k, n_alpha, "bf16", 0, 7000 + M + cin)
 
 
 @pytest.mark.parametrize("dtype", ["f32", "bf16"])
