@@ -98,6 +98,85 @@ __global__ __launch_bounds__(kThreads, 2) void conv_mfma_kernel(const XT *__rest
     const int PX = rows * static_cast<int>(P.Wo);                         // output pixels of the block
     const int64_t u0 = int64_t(blockIdx.z) * kFB;                         // first distinct filter of the block
 
+    // ---- staging items: (channel pair cp, valid patch pixel) -> registers -> LDS --------------------
+    // valid patch pixels = patch positions inside the image, enumerated row-major
+    const int iy_first = row0 * P.sh - P.ph;                               // image row of patch row 0 (may be < 0)
+    const int ix_first = -P.pw;
+    const int py_lo = iy_first < 0 ? -iy_first : 0;
+    const int py_hi = (iy_first + P.PR) > P.H ? static_cast<int>(P.H - iy_first) : P.PR;   // exclusive
+    const int px_lo = ix_first < 0 ? -ix_first : 0;
+    const int px_hi = (ix_first + P.PC) > P.W ? static_cast<int>(P.W - ix_first) : P.PC;   // exclusive
+    const int vrows = py_hi > py_lo ? py_hi - py_lo : 0, vcols = px_hi > px_lo ? px_hi - px_lo : 0;
+    const int npix = vrows * vcols;
+    const int n_items = npix * (kCK / 2);
+    int32_t it_goff[kMaxItems];   // element offset inside the chunk's first channel plane, or -1
+    int32_t it_loff[kMaxItems];   // byte offset inside a patch plane
+    {
+        // item q = tid + i * kThreads is (channel pair, valid row, valid column) = (q / npix, (q % npix) / vcols,
+        // q % vcols); the thread divides once and then steps by kThreads items with carries
+        const int np1 = npix > 0 ? npix : 1, vc1 = vcols > 0 ? vcols : 1;
+        int cp = tid / np1, pix = tid % np1;
+        int ry = pix / vc1, rx = pix % vc1;
+        const int d_cp = kThreads / np1, d_pix = kThreads % np1;   // uniform
+        const int d_ry = d_pix / vc1, d_rx = d_pix % vc1;
+        const int vr1 = vrows > 0 ? vrows : 1;
+#pragma unroll
+        for (int i = 0; i < kMaxItems; ++i) {
+            const int q = tid + i * kThreads;
+            if (q < n_items) {
+                const int py = py_lo + ry, px = px_lo + rx;
+                it_goff[i] = static_cast<int32_t>((2 * cp) * P.H * P.W + int64_t(iy_first + py) * P.W + (ix_first + px));
+                it_loff[i] = (py * P.PC + px) * kPixStride + cp * 4;
+            } else {
+                it_goff[i] = -1;
+                it_loff[i] = 0;
+            }
+            rx += d_rx; ry += d_ry; cp += d_cp;
+            if (rx >= vc1) { rx -= vc1; ++ry; }
+            if (ry >= vr1) { ry -= vr1; ++cp; }
+        }
+    }
+    const int64_t plane_hw = P.H * P.W;
+    const XT *x_img = x + img * P.C * plane_hw;
+
+    float st_a[1][kMaxItems], st_b[1][kMaxItems];   // the two channels of a pair
+    uint32_t st_pk[kMaxItems][NP];                  // ... split and packed, ready for LDS
+    auto load_chunk = [&](int chunk, int slot) {
+        const XT *base = x_img + int64_t(chunk) * kCK * plane_hw;
+#pragma unroll
+        for (int i = 0; i < kMaxItems; ++i) {
+            const int32_t g = it_goff[i] < 0 ? 0 : it_goff[i];
+            st_a[slot][i] = load_elem(base + g);
+            st_b[slot][i] = load_elem(base + g + plane_hw);
+        }
+    };
+    auto pack_item = [&](int i, int slot) {   // VALU only
+        if (NP == 3) {
+            uint32_t a0, a1, a2, b0, b1, b2;
+            split3(st_a[slot][i], a0, a1, a2);
+            split3(st_b[slot][i], b0, b1, b2);
+            st_pk[i][0] = pack_hi16(a0, b0);
+            st_pk[i][NP > 1 ? 1 : 0] = pack_hi16(a1, b1);
+            st_pk[i][NP > 2 ? 2 : 0] = pack_hi16(a2, b2);
+        } else {   // bf16 input: the float holds the exact value, its top half is the bf16 pattern
+            st_pk[i][0] = pack_hi16(__float_as_uint(st_a[slot][i]), __float_as_uint(st_b[slot][i]));
+        }
+    };
+    auto store_chunk = [&](int buf) {
+        unsigned char *dst = lds_patch + buf * buf_bytes;
+#pragma unroll
+        for (int i = 0; i < kMaxItems; ++i) {
+            if (it_goff[i] < 0) continue;
+#pragma unroll
+            for (int pl = 0; pl < NP; ++pl)
+                *reinterpret_cast<uint32_t *>(dst + pl * P.plane_bytes + it_loff[i]) = st_pk[i][pl];
+        }
+    };
+
+    // The first chunk's loads are issued before the zero fill and the filter-bit transposition, which hide their
+    // trip to memory.
+    load_chunk(0, 0);
+
     // ---- zero both patch buffers (halo positions and padding stay zero for the whole kernel) ----
     for (int i = tid * 16; i < 2 * buf_bytes; i += kThreads * 16)
         *reinterpret_cast<u32x4_t *>(lds_patch + i) = u32x4_t{0u, 0u, 0u, 0u};
@@ -151,69 +230,6 @@ __global__ __launch_bounds__(kThreads, 2) void conv_mfma_kernel(const XT *__rest
 #pragma unroll
         for (int tap = 0; tap < T; ++tap) lds_bits[(chunk * T + tap) * kFB + u] = o[tap];
     }
-
-    // ---- staging items: (channel pair cp, valid patch pixel) -> registers -> LDS --------------------
-    // valid patch pixels = patch positions inside the image, enumerated row-major
-    const int iy_first = row0 * P.sh - P.ph;                               // image row of patch row 0 (may be < 0)
-    const int ix_first = -P.pw;
-    const int py_lo = iy_first < 0 ? -iy_first : 0;
-    const int py_hi = (iy_first + P.PR) > P.H ? static_cast<int>(P.H - iy_first) : P.PR;   // exclusive
-    const int px_lo = ix_first < 0 ? -ix_first : 0;
-    const int px_hi = (ix_first + P.PC) > P.W ? static_cast<int>(P.W - ix_first) : P.PC;   // exclusive
-    const int vrows = py_hi > py_lo ? py_hi - py_lo : 0, vcols = px_hi > px_lo ? px_hi - px_lo : 0;
-    const int npix = vrows * vcols;
-    const int n_items = npix * (kCK / 2);
-    int32_t it_goff[kMaxItems];   // element offset inside the chunk's first channel plane, or -1
-    int32_t it_loff[kMaxItems];   // byte offset inside a patch plane
-#pragma unroll
-    for (int i = 0; i < kMaxItems; ++i) {
-        const int q = tid + i * kThreads;
-        if (q < n_items) {
-            const int cp = q / npix, pix = q % npix;
-            const int py = py_lo + pix / vcols, px = px_lo + pix % vcols;
-            it_goff[i] = static_cast<int32_t>((2 * cp) * P.H * P.W + int64_t(iy_first + py) * P.W + (ix_first + px));
-            it_loff[i] = (py * P.PC + px) * kPixStride + cp * 4;
-        } else {
-            it_goff[i] = -1;
-            it_loff[i] = 0;
-        }
-    }
-    const int64_t plane_hw = P.H * P.W;
-    const XT *x_img = x + img * P.C * plane_hw;
-
-    float st_a[1][kMaxItems], st_b[1][kMaxItems];   // the two channels of a pair
-    uint32_t st_pk[kMaxItems][NP];                  // ... split and packed, ready for LDS
-    auto load_chunk = [&](int chunk, int slot) {
-        const XT *base = x_img + int64_t(chunk) * kCK * plane_hw;
-#pragma unroll
-        for (int i = 0; i < kMaxItems; ++i) {
-            const int32_t g = it_goff[i] < 0 ? 0 : it_goff[i];
-            st_a[slot][i] = load_elem(base + g);
-            st_b[slot][i] = load_elem(base + g + plane_hw);
-        }
-    };
-    auto pack_item = [&](int i, int slot) {   // VALU only
-        if (NP == 3) {
-            uint32_t a0, a1, a2, b0, b1, b2;
-            split3(st_a[slot][i], a0, a1, a2);
-            split3(st_b[slot][i], b0, b1, b2);
-            st_pk[i][0] = pack_hi16(a0, b0);
-            st_pk[i][NP > 1 ? 1 : 0] = pack_hi16(a1, b1);
-            st_pk[i][NP > 2 ? 2 : 0] = pack_hi16(a2, b2);
-        } else {   // bf16 input: the float holds the exact value, its top half is the bf16 pattern
-            st_pk[i][0] = pack_hi16(__float_as_uint(st_a[slot][i]), __float_as_uint(st_b[slot][i]));
-        }
-    };
-    auto store_chunk = [&](int buf) {
-        unsigned char *dst = lds_patch + buf * buf_bytes;
-#pragma unroll
-        for (int i = 0; i < kMaxItems; ++i) {
-            if (it_goff[i] < 0) continue;
-#pragma unroll
-            for (int pl = 0; pl < NP; ++pl)
-                *reinterpret_cast<uint32_t *>(dst + pl * P.plane_bytes + it_loff[i]) = st_pk[i][pl];
-        }
-    };
 
     // ---- MFMA operands of this lane -----------------------------------------------------------------
     // pixel tiles of the wave: wave and wave + 4; lane column = pixel ln of the tile
@@ -328,7 +344,6 @@ __global__ __launch_bounds__(kThreads, 2) void conv_mfma_kernel(const XT *__rest
     // ---- main loop over channel chunks -----------------------------------------------------------------
     // Chunk c is multiplied from LDS buffer c % 2 while chunk c + 1 arrives in registers, is converted
     // in the shadow of the MFMAs and written to the other buffer at the end.
-    load_chunk(0, 0);
 #pragma unroll
     for (int i = 0; i < kMaxItems; ++i) pack_item(i, 0);
     __syncthreads();            // zero fill and filter bits are in place
