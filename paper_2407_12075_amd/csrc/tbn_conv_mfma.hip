@@ -74,8 +74,10 @@ __device__ __forceinline__ void split3(float x, uint32_t &t0, uint32_t &t1, uint
 // high halves of two words in one: (lo >> 16) | (hi & 0xffff0000), a single v_perm_b32
 __device__ __forceinline__ uint32_t pack_hi16(uint32_t lo, uint32_t hi) { return __builtin_amdgcn_perm(hi, lo, 0x07060302u); }
 
-__device__ __forceinline__ float load_elem(const float *p) { return *p; }
-__device__ __forceinline__ float load_elem(const uint16_t *p) { return bf16_bits_to_f32(*p); }
+// Staged inputs stay as loaded (float32 values / zero-extended bf16 patterns): nothing is computed from them
+// before the conversion step, so no wait for the loads is placed ahead of it.
+__device__ __forceinline__ uint32_t load_raw(const float *p) { return __float_as_uint(*p); }
+__device__ __forceinline__ uint32_t load_raw(const uint16_t *p) { return *p; }
 
 template <typename XT, int T, bool RELU, int kMaxItems, int NFT>
 __global__ __launch_bounds__(kThreads, 2) void conv_mfma_kernel(const XT *__restrict__ x, XT *__restrict__ y,
@@ -139,27 +141,27 @@ __global__ __launch_bounds__(kThreads, 2) void conv_mfma_kernel(const XT *__rest
     const int64_t plane_hw = P.H * P.W;
     const XT *x_img = x + img * P.C * plane_hw;
 
-    float st_a[1][kMaxItems], st_b[1][kMaxItems];   // the two channels of a pair
+    uint32_t st_a[1][kMaxItems], st_b[1][kMaxItems];   // the two channels of a pair, as loaded
     uint32_t st_pk[kMaxItems][NP];                  // ... split and packed, ready for LDS
     auto load_chunk = [&](int chunk, int slot) {
         const XT *base = x_img + int64_t(chunk) * kCK * plane_hw;
 #pragma unroll
         for (int i = 0; i < kMaxItems; ++i) {
             const int32_t g = it_goff[i] < 0 ? 0 : it_goff[i];
-            st_a[slot][i] = load_elem(base + g);
-            st_b[slot][i] = load_elem(base + g + plane_hw);
+            st_a[slot][i] = load_raw(base + g);
+            st_b[slot][i] = load_raw(base + g + plane_hw);
         }
     };
     auto pack_item = [&](int i, int slot) {   // VALU only
         if (NP == 3) {
             uint32_t a0, a1, a2, b0, b1, b2;
-            split3(st_a[slot][i], a0, a1, a2);
-            split3(st_b[slot][i], b0, b1, b2);
+            split3(__uint_as_float(st_a[slot][i]), a0, a1, a2);
+            split3(__uint_as_float(st_b[slot][i]), b0, b1, b2);
             st_pk[i][0] = pack_hi16(a0, b0);
             st_pk[i][NP > 1 ? 1 : 0] = pack_hi16(a1, b1);
             st_pk[i][NP > 2 ? 2 : 0] = pack_hi16(a2, b2);
-        } else {   // bf16 input: the float holds the exact value, its top half is the bf16 pattern
-            st_pk[i][0] = pack_hi16(__float_as_uint(st_a[slot][i]), __float_as_uint(st_b[slot][i]));
+        } else {   // bf16 input: the two patterns side by side, a single v_perm_b32
+            st_pk[i][0] = __builtin_amdgcn_perm(st_b[slot][i], st_a[slot][i], 0x05040100u);
         }
     };
     auto store_chunk = [&](int buf) {
