@@ -324,10 +324,10 @@ __global__ __launch_bounds__(kThreads, 2) void conv_mfma_kernel(const XT *__rest
             for (int ft = 0; ft < NFT; ++ft)
                 acc[ft][j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(wf[tap & 1][ft].v, x.v, acc[ft][j], 0, 0, 0);
             // one staged item of the next chunk per tap
-            // conversion of the next chunk's staged input: late in the chunk (its loads were issued at the
-            // start), two items per tap over the last taps
+            // conversion of the next chunk's staged input: as late as possible (its loads were issued at the
+            // start of the chunk), two items per tap over the last two taps and the rest after the last MFMA
             if (u % (J * NP) == J * NP - 1 && stage_next) {
-                constexpr int kFirst = T > (kMaxItems + 1) / 2 ? T - (kMaxItems + 1) / 2 : 0;
+                constexpr int kFirst = T > 2 ? T - 2 : 0;
                 if (tap >= kFirst) {
                     const int i0 = 2 * (tap - kFirst);
                     if (i0 < kMaxItems) pack_item(i0, next_slot);
@@ -336,7 +336,7 @@ __global__ __launch_bounds__(kThreads, 2) void conv_mfma_kernel(const XT *__rest
             }
         }
         if (stage_next) {
-            constexpr int kFirst = T > (kMaxItems + 1) / 2 ? T - (kMaxItems + 1) / 2 : 0;
+            constexpr int kFirst = T > 2 ? T - 2 : 0;
             constexpr int kDone = 2 * (T - kFirst) < kMaxItems ? 2 * (T - kFirst) : kMaxItems;
 #pragma unroll
             for (int i = kDone; i < kMaxItems; ++i) pack_item(i, next_slot);
