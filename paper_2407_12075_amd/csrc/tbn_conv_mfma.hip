@@ -10,8 +10,9 @@
 // contains a tile end (two alphas) are recomputed afterwards by the shape-agnostic kernel.
 //
 // gfx950 mapping (implicit GEMM on v_mfma_f32_16x16x32_bf16, filters as rows, pixels as columns):
-//   * workgroup = one image, a block of output rows (<= 128 pixels) and 32 distinct filters;
-//     4 waves, each owning up to 2 tiles of 16 pixels x the 2 tiles of 16 filters;
+//   * workgroup = one image, a block of output rows (<= 128 pixels = 8 tiles of 16) and 32 distinct filters:
+//     8 waves, each owning one pixel tile x the 2 tiles of 16 filters (64 filters for bf16 inputs where that
+//     many exist: then 4 waves of two pixel tiles x 4 filter tiles);
 //   * K runs over chunks of 32 input channels; inside a chunk over the kh*kw taps, so that one MFMA
 //     step (K = 32) is "32 channels of one tap".  The input patch of a chunk (with its zero halo)
 //     is staged in LDS channel-last as bf16, which makes the 8 channels a lane needs one 16-byte
@@ -36,13 +37,18 @@ typedef uint32_t u32x4_t __attribute__((ext_vector_type(4)));
 
 namespace {
 
-constexpr int kThreads = 256;
+// Waves per workgroup.  With 32 distinct filters per workgroup 8 waves share the 8 pixel tiles, one each: two
+// waves per SIMD cover each other's waits (a 14 x 14 layer's waves spent 41 % of their life waiting with one
+// wave per SIMD) and the prologue and the staging are spread over twice the threads: 4 - 18 % faster.  With 64
+// filters (bf16) 4 waves of two pixel tiles each measured faster: the expanded filter operands serve twice the
+// MFMAs.
+constexpr int waves_of(int nft) { return nft == 4 ? 4 : 8; }
 constexpr int kFtSmall = 2;        // MFMA row tiles of 16 distinct filters per workgroup: 32 filters,
 constexpr int kFtLarge = 4;        // or 64 where there are that many (the staged input then feeds twice the MFMAs)
 constexpr int kCK = 32;            // input channels per chunk (one MFMA step per tap)
 constexpr int kMaxPix = 128;       // output pixels per workgroup (8 MFMA column tiles)
-constexpr int kItemsSmall = 10;     // staged (channel pair, pixel) items per thread and chunk: patches up to 160 pixels
-constexpr int kItemsLarge = 12;     // ... up to 192 pixels (one output row of a 56- to 62-wide image with its 3x3 halo)
+constexpr int kItemsSmall = 2560;   // staged (channel pair, pixel) items per workgroup and chunk: patches up to 160 pixels
+constexpr int kItemsLarge = 3072;   // ... up to 192 pixels (one output row of a 56- to 62-wide image with its 3x3 halo)
 constexpr int kPixStride = kCK * 2 + 16;   // bytes per patch pixel in LDS: 32 bf16 channels + 16 B padding
 
 struct ConvMfmaParams {
@@ -79,12 +85,15 @@ __device__ __forceinline__ uint32_t pack_hi16(uint32_t lo, uint32_t hi) { return
 __device__ __forceinline__ uint32_t load_raw(const float *p) { return __float_as_uint(*p); }
 __device__ __forceinline__ uint32_t load_raw(const uint16_t *p) { return *p; }
 
-template <typename XT, int T, bool RELU, int kMaxItems, int NFT>
-__global__ __launch_bounds__(kThreads, 2) void conv_mfma_kernel(const XT *__restrict__ x, XT *__restrict__ y,
+template <typename XT, int T, bool RELU, int kBudget, int NFT>
+__global__ __launch_bounds__((64 * waves_of(NFT)), (waves_of(NFT) == 8 ? 4 : 2)) void conv_mfma_kernel(const XT *__restrict__ x, XT *__restrict__ y,
                                                                   const uint32_t *__restrict__ tile,
                                                                   const float *__restrict__ alpha, ConvMfmaParams P) {
     constexpr int NP = CTraits<XT>::planes;
     constexpr int kFB = 16 * NFT;   // distinct filters per workgroup
+    constexpr int kWaves = waves_of(NFT), kThreads = 64 * kWaves;
+    constexpr int kTilesPerWave = 8 / kWaves;      // pixel tiles of 16 per wave
+    constexpr int kMaxItems = kBudget / kThreads;  // staged items per thread and chunk
     extern __shared__ __attribute__((aligned(16))) unsigned char lds_raw[];
     // layout: patch buffers [2][NP][PR*PC][kPixStride bytes], then filter bits [chunk][tap][kFB filters]
     unsigned char *lds_patch = lds_raw;
@@ -235,22 +244,22 @@ __global__ __launch_bounds__(kThreads, 2) void conv_mfma_kernel(const XT *__rest
 
     // ---- MFMA operands of this lane -----------------------------------------------------------------
     // pixel tiles of the wave: wave and wave + 4; lane column = pixel ln of the tile
-    int pix_off[2];
-    bool tile_live[2];
+    int pix_off[kTilesPerWave];
+    bool tile_live[kTilesPerWave];
 #pragma unroll
-    for (int j = 0; j < 2; ++j) {
-        const int pt = wave + 4 * j;
+    for (int j = 0; j < kTilesPerWave; ++j) {
+        const int pt = wave + kWaves * j;
         tile_live[j] = pt * 16 < PX;
         int q = pt * 16 + ln;
         q = q < PX ? q : (PX > 0 ? PX - 1 : 0);   // lanes past the block read a valid pixel; results are dropped
         const int yo = q / static_cast<int>(P.Wo), xo = q % static_cast<int>(P.Wo);
         pix_off[j] = ((yo * P.sh) * P.PC + xo * P.sw) * kPixStride + lg * 16;
     }
-    f32x4_t acc[NFT][2];   // [filter tile][pixel tile]
+    f32x4_t acc[NFT][kTilesPerWave];   // [filter tile][pixel tile]
 #pragma unroll
     for (int a = 0; a < NFT; ++a)
 #pragma unroll
-        for (int b = 0; b < 2; ++b) acc[a][b] = f32x4_t{0.f, 0.f, 0.f, 0.f};
+        for (int b = 0; b < kTilesPerWave; ++b) acc[a][b] = f32x4_t{0.f, 0.f, 0.f, 0.f};
 
     union Frag { bf16x8_t v; uint32_t u[4]; u32x4_t q; };
     int tap_off[T];   // byte offset of a tap inside the patch (uniform)
@@ -366,9 +375,14 @@ __global__ __launch_bounds__(kThreads, 2) void conv_mfma_kernel(const XT *__rest
             __syncthreads();
         }
     };
-    if (tile_live[1]) main_loop(std::integral_constant<int, 2>{});
-    else if (tile_live[0]) main_loop(std::integral_constant<int, 1>{});
-    else main_loop(std::integral_constant<int, 0>{});
+    if constexpr (kTilesPerWave == 2) {
+        if (tile_live[1]) main_loop(std::integral_constant<int, 2>{});
+        else if (tile_live[0]) main_loop(std::integral_constant<int, 1>{});
+        else main_loop(std::integral_constant<int, 0>{});
+    } else {
+        if (tile_live[0]) main_loop(std::integral_constant<int, 1>{});
+        else main_loop(std::integral_constant<int, 0>{});
+    }
 
     // ---- epilogue: y[img, u + t*R, row0.., :] = alpha[t] * Z[u] ---------------------------------------------
     // lane holds pixel ln of its tiles and filters 4*lg + i of each filter tile
@@ -389,8 +403,8 @@ __global__ __launch_bounds__(kThreads, 2) void conv_mfma_kernel(const XT *__rest
                     const float al = kPerReplica ? al_t : alpha[(o * P.F) / P.p];
                     XT *dst = y + ((img * P.O + o) * plane_out) + int64_t(row0) * P.Wo;
 #pragma unroll
-                    for (int j = 0; j < 2; ++j) {
-                        const int q = (wave + 4 * j) * 16 + ln;
+                    for (int j = 0; j < kTilesPerWave; ++j) {
+                        const int q = (wave + kWaves * j) * 16 + ln;
                         if (q >= PX) continue;
                         float v = al * acc[ft][j][i];
                         if (RELU) v = fmaxf(v, 0.f);
@@ -443,7 +457,7 @@ ConvPlan plan_conv(const ConvArgs &a) {
             const int64_t PR = (r - 1) * a.sh + a.kh, PC = (a.Wo - 1) * a.sw + a.kw;
             const int64_t vrows = PR < a.H ? PR : a.H, vcols = PC < a.W ? PC : a.W;
             const size_t lds = 2 * size_t(planes) * PR * PC * kPixStride + bits_bytes;
-            if (vrows * vcols * (kCK / 2) <= int64_t(items) * kThreads && lds <= 150 * 1024) {
+            if (vrows * vcols * (kCK / 2) <= int64_t(items) && lds <= 150 * 1024) {
                 pl.ok = true;
                 pl.rows_per_blk = static_cast<int>(r);
                 pl.PR = static_cast<int>(PR);
@@ -470,7 +484,7 @@ tbn_status launch_conv_typed(const ConvArgs &a, const ConvMfmaParams &P, const C
         }
         attr_bytes = pl.lds;
     }
-    hipLaunchKernelGGL((conv_mfma_kernel<XT, T, RELU, ITEMS, NFT>), grid, dim3(kThreads), pl.lds, a.stream,
+    hipLaunchKernelGGL((conv_mfma_kernel<XT, T, RELU, ITEMS, NFT>), grid, dim3(64 * waves_of(NFT)), pl.lds, a.stream,
                        static_cast<const XT *>(a.x), static_cast<XT *>(a.y), a.tile, a.alpha, P);
     return check_launch("tbn_conv2d_forward (matrix-core kernel)");
 }
