@@ -525,6 +525,8 @@ struct Cfg {
     static constexpr int kVmPerStage = kLoads + 1;       // vector-memory instructions per stage
     static constexpr int kStagesBytes = KG * kNB * kStageBytes;
     static constexpr int kLdsBytes = kStagesBytes > KG * 32768 ? kStagesBytes : KG * 32768;   // the partial sums handed over at the end need 32 KiB per group
+    static constexpr int kTableBytes = 256 * 16;   // the +-1 operand of every byte of tile bits, behind the stage buffers
+    static constexpr int kLdsTotal = kLdsBytes + kTableBytes;
     static constexpr int kWavesPerSimd = kLdsBytes <= 65536 ? 2 : 1;   // asked of the compiler: registers for two resident workgroups
     static constexpr int kRot = kTM / KG;                // row blocks a group keeps at the end
     static_assert(KG == 2 || KG == 4, "two or four K groups");
@@ -533,7 +535,7 @@ struct Cfg {
     static_assert(kLdsBytes == 131072 || kLdsBytes == 65536, "LDS budget");
 };
 
-// Operand reads are written as inline assembly so that the compiler does not see LDS reads next to the
+// Operand reads (activation fragments and, from the table, the +-1 operands) are written as inline assembly so that the compiler does not see LDS reads next to the
 // asynchronous global -> LDS loads (it would make every read wait for all of those loads).  The
 // waits are explicit; tying the destination registers to the wait keeps the MFMAs behind it.
 template <int OFF>
@@ -551,6 +553,24 @@ template <int N>
 __device__ __forceinline__ void lds_wait(Frag (&a)[kTM]) {   // at most N younger LDS operations pending
     static_assert(kTM == 4, "four operand fragments");
     asm volatile("s_waitcnt lgkmcnt(%4)" : "+v"(a[0].q), "+v"(a[1].q), "+v"(a[2].q), "+v"(a[3].q) : "n"(N));
+}
+
+// The same for a whole step: four activation fragments and the two +-1 operands read from the table.
+template <int N>
+__device__ __forceinline__ void lds_wait_step(Frag (&a)[kTM], Frag (&b)[kTN]) {
+    static_assert(kTM == 4 && kTN == 2, "six operand registers sets");
+    asm volatile("s_waitcnt lgkmcnt(%6)"
+                 : "+v"(a[0].q), "+v"(a[1].q), "+v"(a[2].q), "+v"(a[3].q), "+v"(b[0].q), "+v"(b[1].q)
+                 : "n"(N));
+}
+// The +-1 operand of one MFMA step from the table in LDS: entry e (16 bytes) holds the eight bf16 values
+// -1 / +1 for the bits 0 .. 7 of e set / clear (the windows are kept inverted).  Lane group lg takes byte
+// 2*ks + lg of the window, i.e. the 8 bits at `shift` of the word that holds it: one bit-field extract, one
+// shift-add and the read, where expanding the byte in registers takes nine vector instructions.
+__device__ __forceinline__ void table_read(u32x4_t &dst, uint32_t word, uint32_t shift, uint32_t table_addr) {
+    const uint32_t byte = __builtin_amdgcn_ubfe(word, shift, 8);
+    const uint32_t addr = (byte << 4) + table_addr;
+    asm volatile("ds_read_b128 %0, %1" : "=v"(dst) : "v"(addr));
 }
 
 template <int N>
@@ -700,15 +720,27 @@ __global__ __launch_bounds__((Cfg<KG, BKP>::kThreads), (Cfg<KG, BKP>::kWavesPerS
 #pragma unroll
     for (int ks = 0; ks < KS; ++ks) a_rd[ks] = static_cast<uint32_t>(C::row_slot(ln) * kRowBytes + (((2 * ks + lg) ^ ((ln >> C::kSwzShift) & C::kSwz)) << 4));
 
-    // Operand constants kept in registers (two literals do not fit one instruction).
-    uint32_t sign_mask = 0x80008000u, one_bits = 0x3f803f80u;
-    asm volatile("" : "+v"(sign_mask), "+v"(one_bits));
-    uint32_t byte_sel[KS];   // v_perm selector replicating byte 2*ks + lg of the window
+    // The +-1 operands come from a table of 256 entries behind the stage buffers (see table_read): entry e,
+    // element i is -1 if bit i of e is set (the windows are inverted), +1 otherwise.  Step ks needs byte
+    // 2*ks + lg of the window: word ks / 2 (one word with 32-element stages), bits 16*(ks % 2) + 8*lg on.
+    typedef __attribute__((address_space(3))) unsigned char lds_byte_t;
+    {
+        unsigned char *table = lds_raw + C::kLdsBytes;
+        for (int e = tid; e < 256; e += C::kThreads) {
+            u32x4_t t;
 #pragma unroll
-    for (int ks = 0; ks < KS; ++ks) byte_sel[ks] = 0x01010101u * static_cast<uint32_t>(2 * ks + lg);
+            for (int v = 0; v < 4; ++v)
+                t[v] = (((e >> (2 * v)) & 1) ? 0xbf80u : 0x3f80u) | ((((e >> (2 * v + 1)) & 1) ? 0xbf80u : 0x3f80u) << 16);
+            *reinterpret_cast<u32x4_t *>(table + e * 16) = t;
+        }
+    }
+    const uint32_t table_addr = static_cast<uint32_t>(reinterpret_cast<uintptr_t>((lds_byte_t *)(lds_raw + C::kLdsBytes)));
+    uint32_t bsh[2] = {8u * static_cast<uint32_t>(lg), 16u + 8u * static_cast<uint32_t>(lg)};
+    auto read_signs = [&](u32x4_t &dst, const uint32_t (&w)[WW], int ks) {   // ks is a compile-time constant where it is called
+        table_read(dst, w[(2 * ks) >> 2], bsh[ks & 1], table_addr);
+    };
 
     // The fragments of step ks + 1 are requested before the MFMAs of step ks are issued.
-    typedef __attribute__((address_space(3))) unsigned char lds_byte_t;
     const uint32_t lds_grp_addr = static_cast<uint32_t>(reinterpret_cast<uintptr_t>((lds_byte_t *)lds_grp));
     auto read_frags = [&](Frag (&a)[kTM], uint32_t base, int ks) {
         const uint32_t addr = base + a_rd[ks];
@@ -725,12 +757,13 @@ __global__ __launch_bounds__((Cfg<KG, BKP>::kThreads), (Cfg<KG, BKP>::kWavesPerS
         read_frags(a[0], base, 0);
 #pragma unroll
         for (int ks = 0; ks < KS; ++ks) {
-            if (ks + 1 < KS) read_frags(a[(ks + 1) & 1], base, ks + 1);
             Frag b[kTN];
 #pragma unroll
-            for (int tn = 0; tn < kTN; ++tn)
-                expand_operand(win[tn][0], win[tn][WW - 1], byte_sel[ks], sign_mask, one_bits, b[tn]);
-            if (ks + 1 < KS) lds_wait<kTM>(a[ks & 1]); else lds_wait<0>(a[ks & 1]);
+            for (int tn = 0; tn < kTN; ++tn) read_signs(b[tn].q, win[tn], ks);
+            if (ks + 1 < KS) read_frags(a[(ks + 1) & 1], base, ks + 1);
+            // LDS reads complete in order: with the next step's four fragments still pending, this step's
+            // fragments and signs have arrived
+            if (ks + 1 < KS) lds_wait_step<kTM>(a[ks & 1], b); else lds_wait_step<0>(a[ks & 1], b);
 #pragma unroll
             for (int tm = 0; tm < kTM; ++tm)
 #pragma unroll
@@ -778,28 +811,23 @@ __global__ __launch_bounds__((Cfg<KG, BKP>::kThreads), (Cfg<KG, BKP>::kWavesPerS
             constexpr int cur = ks & 1, nx = cur ^ 1, ksn = (ks + 1) % KS;
             constexpr int kRd = (ks + 1 < KS ? D_ : kBufNext) * kStageBytes;   // buffer of the operands requested here
             const uint32_t raddr = a_rdg[ksn];
-            uint32_t rep;
             auto mfma = [&](int tm, int tn) {
                 acc[tm][tn] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(pb[cur][tn].v, pa[cur][tm].v, acc[tm][tn], 0, 0, 0);
             };
-            lds_wait<0>(pa[cur]);   // the four reads of the step before (the last was issued five MFMAs ago)
+            lds_wait_step<0>(pa[cur], pb[cur]);   // the six reads of the step before (the last was issued five MFMAs ago)
             mfma(0, 0);
-            lds_read16_then<kRd + 0 * 32 * kRowBytes>(pa[nx][0].q, raddr, byte_sel[ksn]);
-            rep = window_byte(win[0][0], win[0][WW - 1], byte_sel[ksn]);
-            expand_operand_half(rep, sign_mask, one_bits, 0, pb[nx][0]);
+            lds_read16<kRd + 0 * 32 * kRowBytes>(pa[nx][0].q, raddr);
+            read_signs(pb[nx][0].q, win[0], ksn);
             __builtin_amdgcn_sched_barrier(0);
             mfma(0, 1);
             lds_read16<kRd + 1 * 32 * kRowBytes>(pa[nx][1].q, raddr);
-            expand_operand_half(rep, sign_mask, one_bits, 1, pb[nx][0]);
             __builtin_amdgcn_sched_barrier(0);
             mfma(1, 0);
-            lds_read16_then<kRd + 2 * 32 * kRowBytes>(pa[nx][2].q, raddr, byte_sel[ksn]);
-            rep = window_byte(win[1][0], win[1][WW - 1], byte_sel[ksn]);
-            expand_operand_half(rep, sign_mask, one_bits, 0, pb[nx][1]);
+            lds_read16<kRd + 2 * 32 * kRowBytes>(pa[nx][2].q, raddr);
+            read_signs(pb[nx][1].q, win[1], ksn);
             __builtin_amdgcn_sched_barrier(0);
             mfma(1, 1);
             lds_read16<kRd + 3 * 32 * kRowBytes>(pa[nx][3].q, raddr);
-            expand_operand_half(rep, sign_mask, one_bits, 1, pb[nx][1]);
             __builtin_amdgcn_sched_barrier(0);
             mfma(2, 0);
             stage_load_one<2 * ks>(src, a_off[2 * ks], dst);
@@ -840,8 +868,7 @@ __global__ __launch_bounds__((Cfg<KG, BKP>::kThreads), (Cfg<KG, BKP>::kWavesPerS
     if (kNB + D <= n_full) {   // the steady loop runs: request the first operands
         read_frags(pa[0], lds_grp_addr, 0);
 #pragma unroll
-        for (int tn = 0; tn < kTN; ++tn)
-            expand_operand(win[tn][0], win[tn][WW - 1], byte_sel[0], sign_mask, one_bits, pb[0][tn]);
+        for (int tn = 0; tn < kTN; ++tn) read_signs(pb[0][tn].q, win[tn], 0);
     }
     for (; st0 + kNB + D <= n_full; st0 += kNB) {
         steady_round(std::integral_constant<int, 0>{}, st0);
@@ -851,7 +878,7 @@ __global__ __launch_bounds__((Cfg<KG, BKP>::kThreads), (Cfg<KG, BKP>::kWavesPerS
     }
     // The last steady round has requested operands nobody will use: let them land before their
     // registers can be given to anything else.
-    if (st0 > 0) lds_wait<0>(pa[0]);
+    if (st0 > 0) lds_wait_step<0>(pa[0], pb[0]);
     // Drain: st0 is a multiple of kNB, so slot numbers stay static.  Every round opens with the meeting
     // that makes stage st + 1 readable; `win` holds the windows of stage st on entry.
     for (; st0 < n_stages; st0 += kNB) {
@@ -1122,10 +1149,10 @@ template <int KG, int BK, bool RELU>
 tbn_status launch_bf16(const LinearArgs &a, const MfmaParams &P, dim3 grid) {
     typedef direct::Cfg<KG, BK> C;
     static bool attr_set = false;
-    tbn_status st = set_lds_limit(&direct::linear_mfma_bf16_kernel<KG, BK, RELU>, C::kLdsBytes, attr_set);
+    tbn_status st = set_lds_limit(&direct::linear_mfma_bf16_kernel<KG, BK, RELU>, C::kLdsTotal, attr_set);
     if (st != TBN_OK) return st;
     hipLaunchKernelGGL((direct::linear_mfma_bf16_kernel<KG, BK, RELU>), grid, dim3(C::kThreads),
-                       C::kLdsBytes, a.stream, static_cast<const uint16_t *>(a.x),
+                       C::kLdsTotal, a.stream, static_cast<const uint16_t *>(a.x),
                        static_cast<uint16_t *>(a.y), a.tile, a.alpha, P);
     return check_launch("tbn_linear_forward (matrix-core kernel)");
 }
