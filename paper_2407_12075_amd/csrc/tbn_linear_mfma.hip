@@ -281,27 +281,6 @@ __device__ __forceinline__ void expand_operand(uint32_t win_lo, uint32_t win_hi,
     }
 }
 
-// The byte of the (inverted) window that a lane expands in one MFMA step, four times.
-__device__ __forceinline__ uint32_t window_byte(uint32_t win_lo, uint32_t win_hi, uint32_t byte_sel) {
-    return __builtin_amdgcn_perm(win_hi, win_lo, byte_sel);
-}
-// Registers 2h and 2h + 1 of the operand (so that the work can be spread between MFMAs).  Both shifts
-// come before both merges: the result of a packed shift cannot be read by the very next instruction.
-__device__ __forceinline__ void expand_operand_half(uint32_t rep, uint32_t sign_mask, uint32_t one_bits, int h, Frag &b) {
-    const u16x2_t r2 = __builtin_bit_cast(u16x2_t, rep);
-    uint32_t s[2];
-#pragma unroll
-    for (int i = 0; i < 2; ++i) {
-        const int v = 2 * h + i;
-        const u16x2_t sh = {static_cast<uint16_t>(15 - 2 * v), static_cast<uint16_t>(14 - 2 * v)};
-        s[i] = __builtin_bit_cast(uint32_t, static_cast<u16x2_t>(r2 << sh));
-    }
-    uint32_t r0 = (s[0] & sign_mask) | one_bits, r1 = (s[1] & sign_mask) | one_bits;
-    asm volatile("" : "+v"(r0), "+v"(r1));   // computed here, between these MFMAs, not wherever the first use is
-    b.q[2 * h] = r0;
-    b.q[2 * h + 1] = r1;
-}
-
 // Adds up the K groups' partial sums through LDS.  Accumulator index tm of group g stands for row block
 // (tm + (4/KG)*g) % 4, so every group ends up with the finished sums of its row blocks in its first
 // accumulators.  Two groups: each hands acc[2..3] to the other.  Four groups: first g and g ^ 2 trade
@@ -542,20 +521,8 @@ template <int OFF>
 __device__ __forceinline__ void lds_read16(u32x4_t &dst, uint32_t addr) {
     asm volatile("ds_read_b128 %0, %1 offset:%2" : "=v"(dst) : "v"(addr), "n"(OFF));
 }
-// The same, and `after` is handed through: what is computed from it comes after the read.  (The compiler
-// pads its own hazard waits around every assembly statement, so the statement goes first and the
-// arithmetic follows in one run.)
-template <int OFF>
-__device__ __forceinline__ void lds_read16_then(u32x4_t &dst, uint32_t addr, uint32_t &after) {
-    asm volatile("ds_read_b128 %0, %2 offset:%3" : "=v"(dst), "+v"(after) : "v"(addr), "n"(OFF));
-}
-template <int N>
-__device__ __forceinline__ void lds_wait(Frag (&a)[kTM]) {   // at most N younger LDS operations pending
-    static_assert(kTM == 4, "four operand fragments");
-    asm volatile("s_waitcnt lgkmcnt(%4)" : "+v"(a[0].q), "+v"(a[1].q), "+v"(a[2].q), "+v"(a[3].q) : "n"(N));
-}
-
-// The same for a whole step: four activation fragments and the two +-1 operands read from the table.
+// At most N younger LDS operations pending; a whole step's operands are tied to the wait: four activation
+// fragments and the two +-1 operands read from the table.
 template <int N>
 __device__ __forceinline__ void lds_wait_step(Frag (&a)[kTM], Frag (&b)[kTN]) {
     static_assert(kTM == 4 && kTN == 2, "six operand registers sets");
@@ -571,11 +538,6 @@ __device__ __forceinline__ void table_read(u32x4_t &dst, uint32_t word, uint32_t
     const uint32_t byte = __builtin_amdgcn_ubfe(word, shift, 8);
     const uint32_t addr = (byte << 4) + table_addr;
     asm volatile("ds_read_b128 %0, %1" : "=v"(dst) : "v"(addr));
-}
-
-template <int N>
-__device__ __forceinline__ void lds_wait2(Frag &a0, Frag &a1) {   // at most N younger LDS operations pending
-    asm volatile("s_waitcnt lgkmcnt(%2)" : "+v"(a0.q), "+v"(a1.q) : "n"(N));
 }
 
 // One 16-byte-per-lane load from global memory straight into LDS (lane i's bytes land at lds + 16*i).
