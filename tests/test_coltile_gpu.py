@@ -134,6 +134,25 @@ def test_coltiled_pack_then_forward_on_device_and_workspace_reuse(tbn):
         tbn.tbn_linear_coltiled_forward(xd, tile, alpha, out, k, workspace=ws[: ws.numel() // 2])
 
 
+def test_coltiled_empty_batch_and_k_equal_in(tbn):
+    out, cin = 40, 96
+    rng = np.random.default_rng(4)
+    w = (0.02 * rng.standard_normal((out, cin))).astype(np.float32)
+    tile, alpha = tbn.tbn_pack_coltile(dev(w), cin, cin)          # blocks of one column: the tile is one bit per row
+    tile_ref, alpha_ref = col.pack_coltile(w, out, cin, cin, cin)
+    torch.cuda.synchronize()
+    np.testing.assert_array_equal(tile.cpu().numpy().view(np.uint32), tile_ref)
+    assert ulp_diff(alpha.cpu().numpy(), alpha_ref) <= 1
+    y = tbn.tbn_linear_coltiled_forward(torch.empty((0, cin), device="cuda"), tile, alpha, out, cin)
+    torch.cuda.synchronize()
+    assert tuple(y.shape) == (0, out)
+    x = rng.standard_normal((70, cin)).astype(np.float32)
+    y = tbn.tbn_linear_coltiled_forward(dev(x), tile, alpha, out, cin)
+    torch.cuda.synchronize()
+    assert_close(y.cpu().numpy().astype(np.float64), col.linear_coltiled_forward(x, tile_ref, alpha_ref, out, cin), "f32",
+                 "column-tiled layer with k = in")
+
+
 def test_coltiled_full_size_sampled(tbn):
     # the metric layer's sizes in the column-tiled layout: sampled outputs, each from the definition
     M, cin, out, k = 8192, 4096, 4096, 8
