@@ -214,6 +214,10 @@ tbn_status tbn_linear_coltiled_forward(const void *x, void *y, tbn_dtype dt, int
     }
     if (M == 0) return TBN_OK;
     hipStream_t s = static_cast<hipStream_t>(stream);
+    if (k == 1) {   // one block: the flat layer with one tile copy, nothing to fold
+        LinearArgs a{x, y, (int)dt, M, in, out, tile, n, 1, alpha, 1, flags, s};
+        return dispatch_linear(a);
+    }
     float *one = reinterpret_cast<float *>(static_cast<unsigned char *>(workspace) + xf_bytes);
     st = launch_coltile_fold(x, workspace, (int)dt, M, in, k, alpha, n_alpha, one, s);
     if (st != TBN_OK) return st;
