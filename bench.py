@@ -251,6 +251,17 @@ def time_other_configs(torch, tbn, wl, iters=30):
         out[c.name + ":column_tiled"] = {"us": round(us, 2), "dense_equiv_tflops": round(2.0 * c.M * c.cin * c.cout / us / 1e6, 1),
                                          "alg_gbs": round(byts / us / 1e3, 1)}
         del w, x, y, ws
+    # batch sweep on the metric layer (bf16): which kernel family serves which batch size, and at what cost
+    c = wl.METRIC
+    w, x, _ = device_inputs(c, torch, wl)
+    tile, alpha = tbn.tbn_pack_tile(w, c.k, c.n_alpha)
+    sweep = {}
+    for M in (1, 16, 64, 128, 256, 512, 1024, 2048, 4096, 8192):
+        xm = x[:M].contiguous()
+        ym = torch.empty((M, c.cout), dtype=x.dtype, device="cuda")
+        sweep[str(M)] = round(timed(lambda: tbn.tbn_linear_forward(xm, tile, alpha, c.cout, c.k, y=ym)), 2)
+    out["metric_layer_batch_sweep_us"] = sweep
+    del w, x
     for c in (wl.CFG3, wl.CFG3_MISALIGNED):
         w = torch.from_numpy(wl.draw_w_real(c.n, c.cfg, c.layer)).cuda()
         xv, _ = wl.draw_x((c.N, c.C, c.H, c.W), c.cfg, c.layer, c.dtype)
