@@ -63,6 +63,8 @@ PACK_CASES = [
     (12, 12, 12, False),             # p = 1
     (64, 1, 1, False),               # k = 1
     (3 * 5000 * 16, 16, 16, False),  # several blocks, ragged tail block
+    (100 * 6400, 100, 100, False),   # more than 64 rows: every wave writes its own partial sums
+    (65 * 4100, 65, 1, True),
     (2 * 1048580, 2, 2, True),
 ]
 
