@@ -6,8 +6,7 @@
 // with its neighbours' and each weight is read exactly once.  Column sums s_i (Eq. 2) are kept
 // in double precision in row order, which makes the sign (Eq. 3) independent of the launch
 // shape and identical to a sequential double-precision sum.  |a| is summed per row in double
-// precision: a wave reduces its share of row r; the four waves of a block add theirs in LDS (k <= 64) and
-// the block writes one partial per row (else every wave writes its own) to the
+// precision: a wave reduces its share of row r and writes one partial per (wave, r) to the
 // workspace; a second small kernel adds the partials in a fixed order and divides (Eq. 6 / 8).
 // No floating-point atomics are used, so results are reproducible bit for bit.
 //
@@ -22,7 +21,6 @@ namespace tbn {
 constexpr int kPackThreads = 256;
 constexpr int kPackWaves = kPackThreads / kWave;
 constexpr int kPackQ = 4;  // loads per row per thread
-constexpr int kPackLdsK = 64;  // up to this many rows the four waves of a block add their partials in LDS
 
 template <int VEC> struct PackVec;
 template <> struct PackVec<4> { using type = float4; };
@@ -62,9 +60,6 @@ __global__ __launch_bounds__(kPackThreads) void pack_kernel(const float *__restr
         pos[q] = (blk == p || !live[q]) ? i : (i / blk) * ld + i % blk;   // blk % 4 == 0 with VEC == 4: no vector spans two rows
     }
 
-    // one partial per (block, row) where the rows fit the LDS array, else one per (wave, row)
-    __shared__ double wsum[kPackWaves][kPackLdsK];
-    const bool block_sums = k <= kPackLdsK;
     double *my_partial = partial + (int64_t(blockIdx.x) * kPackWaves + wave) * k;
 
     for (int32_t r = 0; r < k; ++r) {
@@ -100,15 +95,7 @@ __global__ __launch_bounds__(kPackThreads) void pack_kernel(const float *__restr
                 l1 += static_cast<double>(fabsf(SEPARATE_A ? av[q][v] : wv[q][v]));
             }
         l1 = wave_sum_f64(l1);
-        if (lane == 0) {
-            if (block_sums) wsum[wave][r] = l1; else my_partial[r] = l1;
-        }
-    }
-
-    if (block_sums) {   // uniform
-        __syncthreads();
-        static_assert(kPackWaves == 4, "fixed order of the four wave sums");
-        if (tid < k) partial[int64_t(blockIdx.x) * k + tid] = (wsum[0][tid] + wsum[1][tid]) + (wsum[2][tid] + wsum[3][tid]);
+        if (lane == 0) my_partial[r] = l1;
     }
 
     // Eq. 3 and bit packing, LSB first
@@ -203,7 +190,7 @@ tbn_status launch_pack(const float *w, const float *a, int64_t n, int32_t k, int
     tbn_status st = check_launch("tbn_pack_tile (tile kernel)");
     if (st != TBN_OK) return st;
     hipLaunchKernelGGL(pack_alpha_kernel, dim3(static_cast<unsigned>(n_alpha)), dim3(256), 0, stream, partial,
-                       k <= kPackLdsK ? blocks : blocks * kPackWaves, k, n_alpha, p, alpha_out);
+                       blocks * kPackWaves, k, n_alpha, p, alpha_out);
     return check_launch("tbn_pack_tile (alpha kernel)");
 }
 
