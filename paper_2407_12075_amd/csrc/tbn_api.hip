@@ -54,6 +54,7 @@ static tbn_status check_tiling(int64_t n, int32_t k, int32_t n_alpha) {
 static tbn_status dispatch_linear(const LinearArgs &a) {
     if (!(a.flags & TBN_FLAG_FORCE_GENERIC)) {
         if (linear_skinny_supported(a)) return launch_linear_skinny(a);
+        if (!(a.flags & TBN_FLAG_BLOCK_KERNEL) && linear_stream_supported(a)) return launch_linear_stream(a);
         if (linear_mfma_supported(a)) return launch_linear_mfma(a);
         if (linear_rows_supported(a)) return launch_linear_rows(a);
     }
@@ -70,7 +71,7 @@ static tbn_status check_linear_args(const char *fn, const void *x, const void *y
         set_error("%s: unknown dtype %d", fn, (int)dt);
         return TBN_ERR_UNSUPPORTED;
     }
-    if (flags & ~(TBN_FLAG_RELU | TBN_FLAG_FORCE_GENERIC | TBN_FLAG_LARGE_BATCH)) {
+    if (flags & ~(TBN_FLAG_RELU | TBN_FLAG_FORCE_GENERIC | TBN_FLAG_LARGE_BATCH | TBN_FLAG_BLOCK_KERNEL)) {
         set_error("%s: unknown flag bits 0x%x", fn, flags);
         return TBN_ERR_UNSUPPORTED;
     }

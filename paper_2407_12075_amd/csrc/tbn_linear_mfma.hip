@@ -839,8 +839,9 @@ __global__ __launch_bounds__((Cfg<KG, BKP>::kThreads), (Cfg<KG, BKP>::kWavesPerS
         steady_round(std::integral_constant<int, 3>{}, st0 + 3);
     }
     // The last steady round has requested operands nobody will use: let them land before their
-    // registers can be given to anything else.
-    if (st0 > 0) lds_wait_step<0>(pa[0], pb[0]);
+    // registers can be given to anything else (unconditionally: a wait with nothing pending costs nothing,
+    // and no path exists on which a read is in flight past this point).
+    lds_wait_step<0>(pa[0], pb[0]);
     // Drain: st0 is a multiple of kNB, so slot numbers stay static.  Every round opens with the meeting
     // that makes stage st + 1 readable; `win` holds the windows of stage st on entry.
     for (; st0 < n_stages; st0 += kNB) {

@@ -1,0 +1,121 @@
+"""GPU parity in exact arithmetic: activations drawn from {-1, 0, +1} and alpha = 1 make every output of
+the fully-connected layer an integer that float32 accumulation and (after the same rounding on both
+sides) bfloat16 hold exactly, so the matrix-core kernels must agree with the CPU oracle bit for bit.
+One wrong tile bit, window position, K slice or output column changes an output by at least 1: the
+tolerance tests at long K cannot see that (2e-2 of max|y| is about 0.1 there), these can.
+
+Shapes reach every large-batch bfloat16 kernel form: the streaming kernel (tile of whole rows, K a
+multiple of 256: half tiles, ragged batches and column blocks, several half tiles per workgroup, short K
+with more replicas than rounds, one replica), the one-block-per-tile kernel (other K, tiles that end
+inside rows) and, with float32 activations, the float32 kernel.
+"""
+import numpy as np
+import pytest
+import torch
+
+from oracle import tbn_oracle as orc
+from paper_2407_12075_amd import workloads as wl
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def tbn():
+    assert torch.cuda.is_available(), "GPU tests need a GPU"
+    from paper_2407_12075_amd import tbn as binding
+    binding.lib()
+    return binding
+
+
+def _ternary(rng, shape, p_nonzero):
+    u = rng.random(shape, dtype=np.float32)
+    x = np.zeros(shape, dtype=np.float32)
+    x[u < p_nonzero / 2] = -1.0
+    x[u > 1.0 - p_nonzero / 2] = 1.0
+    return x
+
+
+def _exact_case(tbn, M, cin, cout, k, dtype, flags, seed, alpha_vals=None):
+    rng = np.random.default_rng(seed)
+    n = cin * cout
+    p = n // k
+    tile_ref = rng.integers(0, 2 ** 32, size=(p + 31) // 32, dtype=np.uint64).astype(np.uint32)
+    if p % 32:
+        tile_ref[-1] &= np.uint32((1 << (p % 32)) - 1)   # unused high bits of the last word are zero
+    # few enough non-zeros that every sum stays below 256 in magnitude (6 sigma)
+    x = _ternary(rng, (M, cin), min(1.0, 1500.0 / cin))
+    alpha_ref = np.ones(k, dtype=np.float32) if alpha_vals is None else np.asarray(alpha_vals, dtype=np.float32)
+    ref = orc.linear_forward(x, tile_ref, alpha_ref, cout, k)
+    if flags & 1:
+        ref = np.maximum(ref, 0.0)
+    assert np.abs(ref).max() < 2 ** 24
+    tile = torch.from_numpy(tile_ref.view(np.int32)).cuda()
+    alpha = torch.from_numpy(alpha_ref).cuda()
+    if dtype == "bf16":
+        bits = wl.f32_to_bf16_bits(x).reshape(M, cin)   # exact: -1, 0, 1 are bfloat16 numbers
+        xd = torch.from_numpy(bits.view(np.int16)).cuda().view(torch.bfloat16)
+        want = wl.bf16_bits_to_f32(wl.f32_to_bf16_bits(ref.astype(np.float32))).reshape(M, cout)
+    else:
+        xd = torch.from_numpy(x).cuda()
+        want = ref.astype(np.float32)
+    y = tbn.tbn_linear_forward(xd, tile, alpha, cout, k, flags=flags)
+    torch.cuda.synchronize()
+    got = y.float().cpu().numpy()
+    bad = np.argwhere(got != want)
+    assert bad.size == 0, (f"M={M} in={cin} out={cout} k={k} {dtype} flags={flags:#x}: {len(bad)} of {got.size} outputs "
+                           f"differ, first at {tuple(bad[0])}: got {got[tuple(bad[0])]}, want {want[tuple(bad[0])]}")
+
+
+# M, in, out, k
+EXACT_STREAM = [
+    (128, 256, 1024, 8),      # one pair of rounds per half tile: more replicas than rounds
+    (100, 512, 256, 2),       # two half tiles in one row block, the second ragged
+    (8192, 4096, 4096, 8),    # the shape the headline metric is quoted on
+    (8192 + 37, 1024, 1024, 4),   # ragged last row half
+    (4100, 512, 1088, 8),     # U = 136: a ragged second column block; ragged rows
+    (4096, 1024, 4096, 2),    # U = 2048: 16 column blocks, four half tiles per workgroup with changing columns
+    (3 * 64 * 8 + 64, 768, 512 * 16, 16),   # 16 replicas in 6 rounds; XCDs with different numbers of row halves
+    (1000, 2048, 128 * 3, 1),   # one replica: k = 1
+    (4224, 2048, 1024, 1),
+    (640, 256, 64 * 64, 64),  # 64 replicas, U = 64: half a column block
+    (11300, 256, 768, 2),     # three column blocks: a workgroup's half tiles change rows and columns
+]
+
+
+@pytest.mark.parametrize("M,cin,cout,k", EXACT_STREAM)
+def test_exact_bf16_whole_row_tiles(tbn, M, cin, cout, k):
+    _exact_case(tbn, M, cin, cout, k, "bf16", tbn.TBN_FLAG_LARGE_BATCH, 11 * M + cin)
+
+
+@pytest.mark.parametrize("M,cin,cout,k", [(8192, 4096, 4096, 8), (640, 256, 64 * 64, 64), (300, 1024, 1024, 4)])
+def test_exact_bf16_default_dispatch(tbn, M, cin, cout, k):
+    _exact_case(tbn, M, cin, cout, k, "bf16", 0, 13 * M + cin)
+
+
+def test_exact_bf16_relu_and_scalars(tbn):
+    # powers of two as scalars keep the arithmetic exact and show that replica t is scaled by alpha[t]
+    _exact_case(tbn, 640, 1024, 1024, 8, "bf16", tbn.TBN_FLAG_LARGE_BATCH | tbn.TBN_FLAG_RELU, 5,
+                alpha_vals=[1, 2, 0.5, 4, 0.25, 8, 1, 2])
+    _exact_case(tbn, 200, 512, 768, 4, "bf16", tbn.TBN_FLAG_LARGE_BATCH | tbn.TBN_FLAG_RELU, 6,
+                alpha_vals=[2, 1, 0.5, 4])
+
+
+# shapes that stay on the one-block-per-tile kernels: K no multiple of 256, tiles that end inside rows
+EXACT_BLOCK = [
+    (70, 8192, 80, 4),        # U = 20 distinct rows, long K
+    (4224, 1000, 1024, 1),
+    (2048, 3000, 3072, 9),    # tile and alpha boundaries inside rows
+    (1024, 3000, 3072, 6),    # rows start at bit offsets that are no multiples of 32
+    (4230, 96, 1040, 2),
+]
+
+
+@pytest.mark.parametrize("dtype", ["bf16", "f32"])
+@pytest.mark.parametrize("M,cin,cout,k", EXACT_BLOCK)
+def test_exact_block_kernels(tbn, M, cin, cout, k, dtype):
+    _exact_case(tbn, M, cin, cout, k, dtype, tbn.TBN_FLAG_LARGE_BATCH, 17 * M + cin)
+
+
+@pytest.mark.parametrize("M,cin,cout,k", [(1000, 2048, 384, 1), (4100, 512, 1088, 8)])
+def test_exact_f32_whole_row_tiles(tbn, M, cin, cout, k):
+    _exact_case(tbn, M, cin, cout, k, "f32", tbn.TBN_FLAG_LARGE_BATCH, 19 * M + cin)
