@@ -58,8 +58,10 @@ typedef enum {
 #define TBN_FLAG_FORCE_GENERIC 0x100u /* testing aid: skip the specialised kernels */
 #define TBN_FLAG_LARGE_BATCH 0x200u   /* testing aid (linear only): batches above 64 skip the small-batch
                                          kernel, which otherwise also takes small problems at larger batches */
-#define TBN_FLAG_BLOCK_KERNEL 0x400u  /* testing aid (linear only): skip the streaming large-batch kernel, so
-                                         that its shapes also reach the one-block-per-tile kernel */
+#define TBN_FLAG_BLOCK_KERNEL 0x400u  /* testing aid (linear only): skip the two bfloat16 kernels for tiles of whole
+                                         rows, so that their shapes also reach the general matrix-core kernel */
+#define TBN_FLAG_STREAM_KERNEL 0x800u /* testing aid (linear only): take the streaming kernel (half tiles, used by
+                                         default for grids that leave CUs idle) wherever it supports the shape */
 
 /* Number of 32-bit words of a tile of n / k entries (ceil(n / k / 32)); 0 if n <= 0, k <= 0 or
  * k does not divide n (the paper requires n divisible by the compression factor). */
@@ -107,7 +109,8 @@ tbn_status tbn_pack_tile(const float *w_real, const float *a_real, int64_t n, in
  *   y     : DEVICE, M x out, row-major, dense, element type dt; fully overwritten
  *   tile  : DEVICE, tbn_tile_words(in*out, k) words; read only
  *   alpha : DEVICE, n_alpha floats (n_alpha is 1 or k); read only
- *   flags : 0 or TBN_FLAG_RELU (| TBN_FLAG_FORCE_GENERIC | TBN_FLAG_LARGE_BATCH | TBN_FLAG_BLOCK_KERNEL)
+ *   flags : 0 or TBN_FLAG_RELU (| TBN_FLAG_FORCE_GENERIC | TBN_FLAG_LARGE_BATCH | TBN_FLAG_BLOCK_KERNEL |
+ *           TBN_FLAG_STREAM_KERNEL)
  * M == 0 is legal and does nothing (x and y may then be NULL).  x and y must not overlap.
  * Errors: TBN_ERR_NULL, TBN_ERR_SHAPE, TBN_ERR_UNSUPPORTED, TBN_ERR_DEVICE.
  */

@@ -171,7 +171,7 @@ def compile_to_asm(src: str) -> str:
         return open(out).read()
 
 
-CHECKED_SOURCES = ("tbn_linear_stream.hip", "tbn_linear_mfma.hip", "tbn_conv_mfma.hip")
+CHECKED_SOURCES = ("tbn_linear_block.hip", "tbn_linear_stream.hip", "tbn_linear_mfma.hip", "tbn_conv_mfma.hip")
 
 
 def main() -> int:

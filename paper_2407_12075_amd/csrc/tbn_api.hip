@@ -54,7 +54,16 @@ static tbn_status check_tiling(int64_t n, int32_t k, int32_t n_alpha) {
 static tbn_status dispatch_linear(const LinearArgs &a) {
     if (!(a.flags & TBN_FLAG_FORCE_GENERIC)) {
         if (linear_skinny_supported(a)) return launch_linear_skinny(a);
-        if (!(a.flags & TBN_FLAG_BLOCK_KERNEL) && linear_stream_supported(a)) return launch_linear_stream(a);
+        if (!(a.flags & TBN_FLAG_BLOCK_KERNEL)) {
+            // bfloat16, tile of whole rows: 128 x 128 blocks with load waves; the streaming kernel (64-row half
+            // tiles, twice the workgroups) where the blocks would leave more than half of the CUs idle
+            // (4096 x 4096, k = 8, batch 512 / 1024 / 2048: 16 / 17 / 20 us against 23 / 22 / 23)
+            const int64_t U = a.p % a.in == 0 ? a.p / a.in : 0;
+            const int64_t blocks = ((a.M + 127) / 128) * ((U + 127) / 128);
+            const bool stream = (a.flags & TBN_FLAG_STREAM_KERNEL) || blocks < 128;
+            if (stream && linear_stream_supported(a)) return launch_linear_stream(a);
+            if (linear_block_supported(a)) return launch_linear_block(a);
+        }
         if (linear_mfma_supported(a)) return launch_linear_mfma(a);
         if (linear_rows_supported(a)) return launch_linear_rows(a);
     }
@@ -71,7 +80,8 @@ static tbn_status check_linear_args(const char *fn, const void *x, const void *y
         set_error("%s: unknown dtype %d", fn, (int)dt);
         return TBN_ERR_UNSUPPORTED;
     }
-    if (flags & ~(TBN_FLAG_RELU | TBN_FLAG_FORCE_GENERIC | TBN_FLAG_LARGE_BATCH | TBN_FLAG_BLOCK_KERNEL)) {
+    if (flags & ~(TBN_FLAG_RELU | TBN_FLAG_FORCE_GENERIC | TBN_FLAG_LARGE_BATCH | TBN_FLAG_BLOCK_KERNEL |
+                  TBN_FLAG_STREAM_KERNEL)) {
         set_error("%s: unknown flag bits 0x%x", fn, flags);
         return TBN_ERR_UNSUPPORTED;
     }

@@ -62,6 +62,8 @@ tbn_status launch_linear_tile_ends(const LinearArgs &a);   // the same in one pa
 bool linear_mfma_supported(const LinearArgs &a);   // matrix-core kernel
 bool linear_stream_supported(const LinearArgs &a); // streaming matrix-core kernel (bfloat16, tile of whole rows)
 tbn_status launch_linear_stream(const LinearArgs &a);
+bool linear_block_supported(const LinearArgs &a);  // one block per workgroup with load waves (bfloat16, tile of whole rows)
+tbn_status launch_linear_block(const LinearArgs &a);
 tbn_status launch_linear_mfma(const LinearArgs &a);
 
 // column-tiled layer: xf[m, j] = sum_c alpha[c] * x[m, c * q + j], and the float 1.0 written to *one_out

@@ -7,26 +7,32 @@
 // ("only one of the tile computations needs to be executed", Section "CNN Architectures", applied to
 // matrix columns).
 //
-// How the work is laid out on gfx950 (the reasons are measurements of the earlier one-block-per-tile kernel:
-// with one 128 x 128 block per CU the index set-up, the pipeline fill, the hand-over of the K halves and
-// above all the replicated-column stores -- 8 of 9 bytes the kernel moves are output -- ran one after the
-// other, the matrix pipe idle meanwhile):
-//   * a workgroup of four waves stays on its CU and works through a sequence of half tiles, 64 rows of X
-//     by 128 tile rows each.  Wave (g, h) multiplies the 64 rows with tile rows 64h .. 64h + 63 over the
-//     K slices congruent to g (mod 2): 2 x 2 MFMA tiles of 32 x 32 x 16, the +-1 rows as the row operand;
-//   * everything a round of 128 K elements needs streams through LDS rings five rounds ahead of its use,
-//     across half-tile borders: the activations (global -> LDS directly, 16 bytes per lane, XOR-swizzled
-//     so that operand reads are free of bank conflicts) and the chunk of the packed tile that the
-//     workgroup's 128 tile rows need for two rounds (coalesced 16-byte pieces; every wave then reads
-//     the 64 window bits of its columns with one LDS instruction per round).  Tile bits are never
-//     fetched lane by lane from global memory;
-//   * a byte of tile bits becomes the +-1 bf16 MFMA operand through a 256-entry table in LDS;
-//   * at the end of a half tile the two K groups add their partial sums through LDS, the wave turns its
-//     32 x 64 block round (so that eight lanes hold one row's 64 columns: 16-byte stores that cover whole
-//     128-byte lines) and keeps it in registers; the alpha-scaled, replicated stores of that block are
-//     issued between the MFMAs of the NEXT half tile, one half replica per round.  Only the last half
-//     tile's stores are exposed;
-//   * workgroup j of XCD x takes half tiles j, j + W, j + 2W .. of that XCD's share of the rows (row-half
+// How the work is laid out on gfx950.  Measurements of the one-block-per-tile kernel and of a first
+// streaming form shaped this: with one 128 x 128 block per CU the index set-up, the pipeline fill, the
+// hand-over of the K halves and above all the replicated-column stores (8 of 9 bytes the kernel moves are
+// output) ran one after the other with the matrix pipe idle; and a round's cost is set by the instructions
+// a wave has to issue beside its MFMAs (LDS reads, wave-loads, the workgroup barrier), not by bank
+// conflicts or memory latency.
+//   * A workgroup of four waves stays on its CU and works through a sequence of half tiles, 64 rows of X
+//     by 128 tile rows each.  The four waves split K in quarters: wave w multiplies all 64 rows with all
+//     128 tile rows over K elements w*in/4 .. (w+1)*in/4 - 1 (2 x 4 MFMA tiles of 32 x 32 x 16, the +-1 rows
+//     as the row operand: 0.75 LDS operand reads per MFMA).  Nothing a wave reads in the main loop was
+//     loaded by another wave, so the loop has no barrier: a wave waits for its own loads only, and the
+//     waves drift apart instead of sending their loads to the CU's load path at the same moment.
+//   * Everything a round of 32 K elements needs streams through per-wave LDS rings five rounds ahead of
+//     its use, across half-tile borders: the activations (global -> LDS directly, 16 bytes per lane,
+//     swizzled so that operand reads are free of bank conflicts) and, every fourth round, the 128 bits
+//     of each of the 128 tile rows for the next four rounds (coalesced 16-byte pieces; the wave then
+//     takes the window words of its columns with four LDS reads per four rounds).  Tile bits are never
+//     fetched lane by lane from global memory.
+//   * A byte of tile bits becomes the +-1 bf16 MFMA operand through a 256-entry table in LDS.
+//   * At the end of a half tile the four waves add their partial sums through LDS (wave w ends with the
+//     32 x 64 block of row half w / 2, column half w % 2), turn that block round (eight lanes then hold
+//     one row's 64 columns: 16-byte stores that cover whole 128-byte lines) and keep it in registers; its
+//     alpha-scaled, replicated stores are issued between the MFMAs of the NEXT half tile, two per round.
+//     Only the last half tile's stores are exposed.  The waits for the wave's loads count those stores
+//     (the counter is shared and retires in order), so a round never waits for a store to complete.
+//   * Workgroup j of XCD x takes half tiles j, j + W, j + 2W .. of that XCD's share of the rows (row-half
 //     major, column block fastest), so at any moment the workgroups of an XCD work on the same few row
 //     blocks of X and find them in that XCD's L2.
 #include "tbn_common.h"
@@ -51,20 +57,19 @@ union Frag {
 constexpr int kThreads = 256;
 constexpr int kHT = 64;                  // rows of X per half tile
 constexpr int kBN = 128;                 // tile rows (distinct output columns) per workgroup
-constexpr int kRoundK = 128;             // K elements per round: 64 for each of the two K groups
-constexpr int kNB = 6;                   // ring slots of activations
+constexpr int kRoundK = 32;              // K elements per wave and round
+constexpr int kNB = 6;                   // ring slots of activations per wave
 constexpr int kLA = kNB - 1;             // rounds the loads run ahead
-constexpr int kSlotBytes = 2 * kHT * 128;   // [K group][64 rows][128 bytes]
-constexpr int kTileSlots = 4;            // ring of tile chunks, one chunk = two rounds
-constexpr int kTileSlotBytes = 4096;     // [16-byte piece (= round parity)][128 columns][16 bytes]
+constexpr int kSlotBytes = kHT * kRoundK * 2;   // 64 rows of 64 bytes
+constexpr int kTileSlotBytes = 2048;     // 128 tile rows x 16 bytes: the bits of four rounds
 constexpr int kBias = 3 * 1024;          // keeps the lane offsets of the wave-loads non-negative
 
 // LDS map.  The sign table sits at address 0 so that a table read needs no base.
 constexpr int kTableOff = 0;                               // 256 entries of 16 bytes
-constexpr int kRingOff = 4096;
-constexpr int kXchgOff = kRingOff + kNB * kSlotBytes;      // 4 x 8 KiB, one slot per wave
-constexpr int kTileOff = kXchgOff + 4 * 8192;
-constexpr int kLdsBytes = kTileOff + kTileSlots * kTileSlotBytes;
+constexpr int kRingOff = 4096;                             // per wave kNB slots
+constexpr int kXchgOff = kRingOff + 4 * kNB * kSlotBytes;  // 4 x 8 KiB, one slot per wave
+constexpr int kTileOff = kXchgOff + 4 * 8192;              // per wave two chunks
+constexpr int kLdsBytes = kTileOff + 4 * 2 * kTileSlotBytes;
 static_assert(kLdsBytes <= 160 * 1024, "LDS budget of a gfx950 workgroup");
 
 struct StreamParams {
@@ -76,24 +81,25 @@ struct StreamParams {
     int32_t rows_xcd;     // row halves per XCD
     int32_t tiles_n;      // ceil(U / 128)
     int32_t wg_per_xcd;
-    int32_t nr;           // rounds per half tile = in / 128 (even)
+    int32_t n_sr;         // groups of four rounds per wave and half tile = in / 512
 };
 
 // s_waitcnt immediate that waits for the vector-memory counter only (gfx9 encoding: vmcnt in bits
 // 3:0 and 15:14, expcnt 6:4 and lgkmcnt 11:8 left at their maxima).
 constexpr int vmcnt_imm(int n) { return (n & 15) | ((n >> 4) << 14) | (7 << 4) | (15 << 8); }
 
+// With 64-byte rows two row slots share the 32 banks.  The LDS serves the even and the odd lanes of 16 in
+// turn, so rows 2i and 2i + 2 must not sit in the same half: row slots trade their two lowest row bits.
+__device__ __host__ constexpr int row_slot(int r) { return (r & ~3) | ((r & 1) << 1) | ((r >> 1) & 1); }
+
 // All LDS traffic of this kernel is written as inline assembly: the compiler would otherwise make every
 // LDS access wait for all global -> LDS loads in flight, and loads are in flight from the first to the
 // last round.  The waits are explicit; a register that a read fills is handed to the compiler only
-// through tie() after the wait that covers it.
+// through tie() after the wait that covers it (paper_2407_12075_amd/asm_check.py verifies on the generated
+// assembly that nothing touches such a register earlier).
 template <int OFF>
 __device__ __forceinline__ void lds_read16(u32x4_t &dst, uint32_t addr) {
     asm volatile("ds_read_b128 %0, %1 offset:%2" : "=v"(dst) : "v"(addr), "n"(OFF));
-}
-// two 8-byte reads 512 bytes apart: registers 0-1 from addr, 2-3 from addr + 512
-__device__ __forceinline__ void lds_read2x8(u32x4_t &dst, uint32_t addr) {
-    asm volatile("ds_read2_b64 %0, %1 offset0:0 offset1:64" : "=v"(dst) : "v"(addr));
 }
 template <int OFF>
 __device__ __forceinline__ void lds_write16(uint32_t addr, const u32x4_t &v) {
@@ -117,6 +123,8 @@ __device__ __forceinline__ uint32_t pack2(float a, float b) {
     return __builtin_bit_cast(uint32_t, __builtin_convertvector(f, bf16x2_t));   // round to nearest even in hardware
 }
 
+template <int V> using Int = std::integral_constant<int, V>;
+
 // RELU: fused max(0, .) of Algorithm 1.  MASKED: the batch is no multiple of 64 or U no multiple of 128, so
 // stores are predicated per lane; otherwise the rounds contain no control flow at all.
 template <bool RELU, bool MASKED>
@@ -128,9 +136,7 @@ __global__ __launch_bounds__(kThreads, 1) void linear_stream_bf16_kernel(const u
     extern __shared__ __attribute__((aligned(1024))) unsigned char lds_raw[];
     const int tid = threadIdx.x;
     const int lane = tid & 63;
-    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-    const int grp = wave >> 1;   // K group
-    const int wn = wave & 1;     // column half
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);   // K quarter
     const int ln = lane & 31;    // operand lane inside a 32 x 32 tile
     const int lg = lane >> 5;    // K half of the operand registers
 
@@ -143,94 +149,117 @@ __global__ __launch_bounds__(kThreads, 1) void linear_stream_bf16_kernel(const u
     const int32_t W = P.wg_per_xcd;
     const int32_t n_ht = (n_mine - wg + W - 1) / W;
     const int32_t step_r = W / P.tiles_n, step_c = W - step_r * P.tiles_n;
-    const int32_t NR = P.nr;
+    const int32_t n_sr = P.n_sr;
+    const int32_t NR = 4 * n_sr;   // rounds per half tile
     const int32_t first_row = r_lo + wg / P.tiles_n, first_col = wg % P.tiles_n;
     const int32_t rows_last = static_cast<int32_t>(P.M - int64_t(P.rows_half - 1) * kHT);   // 1 .. 64 rows in the last row half
+    const bool ragged = MASKED && rows_last < kHT;
+
+    // Which sums a wave keeps at the end: the 32 x 64 block of row half wave / 2, column half wave % 2.  Its
+    // accumulator indices are rotated accordingly (index tm stands for row block tm ^ (wave / 2), index tn for
+    // column block tn ^ 2 * (wave % 2)), so that every wave keeps acc[0][0..1] and hands the others over with
+    // static register indices.
+    const int rot_m = wave >> 1, rot_n = wave & 1;
 
     // ---- per-lane constants of the activation loads -------------------------------------------------
-    // Wave-load j of a wave fills 1 KiB of its K group's 8 KiB: piece q = 4*wn + j, row slot sr = 8*q + lane/8,
-    // chunk slot lane%8.  Row-slot block sr/32 holds row block (sr/32 + grp) % 2 of the half tile (so that
-    // each K group ends with the sums it keeps in its first accumulators), chunk slot s of row slot sr holds
-    // 16-byte chunk s ^ ((sr >> 1) & 7) of the round's 128 bytes of that row.  Rows past M repeat row M - 1.
+    // Wave-load j fills 1 KiB of the round's 4 KiB slot: row slots 16*j + lane/4, chunk slot lane%4.  Row
+    // slot sr holds row 32*((sr / 32) ^ rot_m) + row_slot(sr % 32) of the half tile, chunk slot s of it
+    // 16-byte chunk s ^ ((sr >> 2) & 3) of the round's 64 bytes of that row.  Rows past M repeat row M - 1.
     uint32_t a_off[4], a_off_last[4];
 #pragma unroll
     for (int j = 0; j < 4; ++j) {
-        const int sr = 8 * (4 * wn + j) + (lane >> 3);
-        const int xr = ((((sr >> 5) + grp) & 1) << 5) + (sr & 31);
-        const int chunk = (lane & 7) ^ ((sr >> 1) & 7);
+        const int sr = 16 * j + (lane >> 2);
+        const int xr = (((sr >> 5) ^ rot_m) << 5) + row_slot(sr & 31);
+        const int chunk = (lane & 3) ^ ((sr >> 2) & 3);
         const int xr_last = xr < rows_last ? xr : rows_last - 1;
         const uint32_t fix = static_cast<uint32_t>(chunk * 16 + kBias - j * 1024);
         a_off[j] = static_cast<uint32_t>(xr) * static_cast<uint32_t>(P.in) * 2u + fix;
         a_off_last[j] = static_cast<uint32_t>(xr_last) * static_cast<uint32_t>(P.in) * 2u + fix;
     }
-    const bool ragged = MASKED && rows_last < kHT;
+    const uint32_t quarter_bytes = static_cast<uint32_t>(P.in) >> 1;   // in / 4 elements of 2 bytes
 
     // ---- per-lane constants of the tile-chunk loads -----------------------------------------------
-    // A chunk holds, for the workgroup's 128 tile rows, the 256 bits of two rounds: two 16-byte pieces per
-    // row.  Lane i of wave w fills slot S = 64*w + i of the chunk's 256: piece S / 128, LDS row S % 128.
-    // LDS row 64*h + 32*tn + l holds the tile row that operand lane l of wave half h supplies for MFMA tile
-    // tn, i.e. column 64*h + 16*(l/8) + 8*((l/4)%2) + 4*tn + l%4 of the block (with this numbering a lane
-    // ends up with eight adjacent columns of one row of Y).
-    const int t_piece = wave >> 1;
-    int t_col;
-    {
-        const int rho = (64 * wave + lane) & 127;
-        const int l = rho & 31;
-        t_col = (rho & 64) + 16 * (l >> 3) + 8 * ((l >> 2) & 1) + 4 * ((rho >> 5) & 1) + (l & 3);
+    // A chunk holds the wave's next 128 bits of each of the workgroup's 128 tile rows, 16 bytes per row: two
+    // wave-loads.  LDS row 32*tn + l of the chunk holds the tile row that operand lane l supplies for MFMA
+    // tile tn, i.e. column 64*((tn / 2) ^ rot_n) + 16*(l/8) + 8*((l/4)%2) + 4*(tn % 2) + l%4 of the block (with
+    // this numbering a lane ends up with eight adjacent columns of one row of Y).
+    int t_col[2];
+#pragma unroll
+    for (int j = 0; j < 2; ++j) {
+        const int rho = 64 * j + lane, tn = rho >> 5, l = rho & 31;
+        t_col[j] = 64 * ((tn >> 1) ^ rot_n) + 16 * (l >> 3) + 8 * ((l >> 2) & 1) + 4 * (tn & 1) + (l & 3);
     }
     const uint32_t row_bytes = static_cast<uint32_t>(P.in) >> 3;   // bytes of one tile row
-    auto tile_lane_off = [&](int32_t col_block) -> uint32_t {
-        int32_t u = col_block * kBN + t_col;
+    auto tile_lane_off = [&](int32_t col_block, int j) -> uint32_t {
+        int32_t u = col_block * kBN + t_col[j];
         u = u < P.U ? u : P.U - 1;   // columns past U repeat the last one; they are never written
-        return static_cast<uint32_t>(u) * row_bytes + static_cast<uint32_t>(t_piece * 16);
+        return static_cast<uint32_t>(u) * row_bytes + static_cast<uint32_t>(wave) * (row_bytes >> 2);
     };
 
-    // ---- load cursor: runs kLA rounds ahead of the multiplication --------------------------------------
-    // Past the workgroup's last half tile it goes over that half tile again: the rounds stay free of
-    // conditions (the wait counts are immediates), the extra loads hit the L2 and land in ring slots that
-    // nobody reads.
-    int32_t ld_row = first_row, ld_col = first_col, ld_h = 0, ld_r = 0, ld_slot = 0, ld_tslot = 0;
+    // ---- load cursors ---------------------------------------------------------------------------
+    // The activation cursor runs kLA rounds ahead of the multiplication, the tile cursor two groups of four
+    // rounds.  Past the workgroup's last half tile they go over that half tile again: the rounds stay free
+    // of conditions (the wait counts are immediates), the extra loads hit the L2 and land where nobody reads.
     const unsigned char *x_bytes = reinterpret_cast<const unsigned char *>(x);
     const unsigned char *tile_bytes = reinterpret_cast<const unsigned char *>(tile);
-    const unsigned char *ld_x = x_bytes + int64_t(ld_row) * kHT * P.in * 2 + (grp * 128 - kBias);
-    uint32_t ld_toff = tile_lane_off(ld_col);
+    unsigned char *const ring_wave = lds_raw + kRingOff + wave * (kNB * kSlotBytes);
+    unsigned char *const tring_wave = lds_raw + kTileOff + wave * (2 * kTileSlotBytes);
+    auto x_base_of = [&](int32_t row) -> const unsigned char * {
+        return x_bytes + int64_t(row) * kHT * P.in * 2 + (static_cast<int64_t>(wave) * quarter_bytes - kBias);
+    };
+    int32_t ld_row = first_row, ld_col = first_col, ld_h = 0, ld_r = 0, ld_off = 0;   // ld_off: ring slot in bytes
+    const unsigned char *ld_x = x_base_of(ld_row);
     bool ld_last = ragged && ld_row == P.rows_half - 1;
-    unsigned char *const ring_wave = lds_raw + kRingOff + grp * 8192 + wn * 4096;
-    unsigned char *const tring_wave = lds_raw + kTileOff + wave * 1024;
+    int32_t tl_col = first_col, tl_h = 0, tl_s = 0, tl_slot = 0;
+    uint32_t tl_off[2] = {tile_lane_off(tl_col, 0), tile_lane_off(tl_col, 1)};
 
-    auto issue_x = [&](auto j_c) {
+    // src: the round's scalar base (made opaque once per round, see round()); the lane offset is widened to
+    // 64 bits here, not once outside the loops, so that the wave-load takes it as a 32-bit offset to that base
+    auto issue_x = [&](auto j_c, const unsigned char *src) {
         constexpr int J = decltype(j_c)::value;
-        const unsigned char *src = ld_x;
-        asm volatile("" : "+s"(src));   // one scalar base, the lane offset stays a 32-bit register
-        // widened to 64 bits here, not once outside the loops: the wave-load then takes it as a 32-bit
-        // offset to the scalar base
         uint32_t off = ld_last ? a_off_last[J] : a_off[J];
         asm volatile("" : "+v"(off));
-        wave_load<J>(src, off, ring_wave + ld_slot * kSlotBytes);
+        wave_load<J>(src, off, ring_wave + ld_off);
     };
-    auto issue_tile = [&]() {   // the chunk of the round under the cursor (an even one) and the next
-        const unsigned char *src = tile_bytes + ld_r * 16;   // 128 bits per round
-        asm volatile("" : "+s"(src));
-        uint32_t off = ld_toff;
-        asm volatile("" : "+v"(off));
-        __builtin_amdgcn_global_load_lds(src + off, tring_wave + ld_tslot * kTileSlotBytes, 16, 0, 0);
-        ld_tslot = (ld_tslot + 1) & (kTileSlots - 1);
-    };
-    auto advance_load = [&]() {
-        ld_slot = ld_slot + 1 == kNB ? 0 : ld_slot + 1;
+    // after the four loads of a round; CHECK: the cursor may have reached the end of its half tile
+    auto advance_x = [&](auto check_c) {
+        ld_off = ld_off + kSlotBytes == kNB * kSlotBytes ? 0 : ld_off + kSlotBytes;
         ++ld_r;
         ld_x += 2 * kRoundK;
-        if (ld_r == NR) {   // uniform
-            ld_r = 0;
-            if (ld_h + 1 < n_ht) {   // next half tile
-                ++ld_h;
-                ld_col += step_c;
-                ld_row += step_r;
-                if (ld_col >= P.tiles_n) { ld_col -= P.tiles_n; ++ld_row; }
-                ld_toff = tile_lane_off(ld_col);
-                ld_last = ragged && ld_row == P.rows_half - 1;
+        if constexpr (decltype(check_c)::value != 0) {
+            if (ld_r == NR) {   // uniform
+                ld_r = 0;
+                if (ld_h + 1 < n_ht) {   // next half tile
+                    ++ld_h;
+                    ld_col += step_c;
+                    ld_row += step_r;
+                    if (ld_col >= P.tiles_n) { ld_col -= P.tiles_n; ++ld_row; }
+                    ld_last = ragged && ld_row == P.rows_half - 1;
+                }
+                ld_x = x_base_of(ld_row);
             }
-            ld_x = x_bytes + int64_t(ld_row) * kHT * P.in * 2 + (grp * 128 - kBias);
+        }
+    };
+    auto issue_tile = [&](auto j_c) {
+        constexpr int J = decltype(j_c)::value;
+        const unsigned char *src = tile_bytes + tl_s * 16;   // 128 bits per group of four rounds
+        asm volatile("" : "+s"(src));
+        uint32_t off = tl_off[J];
+        asm volatile("" : "+v"(off));
+        __builtin_amdgcn_global_load_lds(src + off, tring_wave + tl_slot * kTileSlotBytes + J * 1024, 16, 0, 0);
+    };
+    auto advance_tile = [&]() {
+        tl_slot ^= 1;
+        ++tl_s;
+        if (tl_s == n_sr) {   // uniform
+            tl_s = 0;
+            if (tl_h + 1 < n_ht) {
+                ++tl_h;
+                tl_col += step_c;
+                if (tl_col >= P.tiles_n) tl_col -= P.tiles_n;
+                tl_off[0] = tile_lane_off(tl_col, 0);
+                tl_off[1] = tile_lane_off(tl_col, 1);
+            }
         }
     };
 
@@ -243,17 +272,15 @@ __global__ __launch_bounds__(kThreads, 1) void linear_stream_bf16_kernel(const u
         asm volatile("global_load_dword %0, %1, %2" : "=v"(alpha_lanes) : "v"(off), "s"(alpha));
     }
 
-    // ---- prologue: loads of the first kLA rounds ---------------------------------------------------
-    // issue order per round, which the wait counts below rely on: four activation wave-loads, then (even
-    // rounds) the tile chunk of this round and the next
+    // ---- prologue: tile chunks 0 and 1, activations of rounds 0 .. 4 -----------------------------------
+    // in the order the steady state would have issued them (the wait counts rely on it): chunk 0, rounds 0,
+    // 1, 2, chunk 1, rounds 3, 4
+    issue_tile(Int<0>{}); issue_tile(Int<1>{}); advance_tile();
 #pragma unroll
     for (int d = 0; d < kLA; ++d) {
-        issue_x(std::integral_constant<int, 0>{});
-        issue_x(std::integral_constant<int, 1>{});
-        issue_x(std::integral_constant<int, 2>{});
-        issue_x(std::integral_constant<int, 3>{});
-        if ((d & 1) == 0) issue_tile();
-        advance_load();
+        if (d == 3) { issue_tile(Int<0>{}); issue_tile(Int<1>{}); advance_tile(); }
+        issue_x(Int<0>{}, ld_x); issue_x(Int<1>{}, ld_x); issue_x(Int<2>{}, ld_x); issue_x(Int<3>{}, ld_x);
+        advance_x(Int<1>{});
     }
 
     // sign table: entry e, element i is +1 if bit i of e is set, else -1
@@ -266,34 +293,34 @@ __global__ __launch_bounds__(kThreads, 1) void linear_stream_bf16_kernel(const u
         lds_write16<kTableOff>(static_cast<uint32_t>(e) * 16u, t);
     }
 
-    // operand read addresses inside a ring slot: row slot 32*tm + ln, K step ks: chunk 2*ks + lg at chunk
-    // slot (2*ks + lg) ^ ((ln >> 1) & 7)
-    uint32_t a_rd[4];
+    // operand read addresses inside a ring slot: row slot 32*tm + row_slot(ln), K step ks: chunk 2*ks + lg at
+    // chunk slot (2*ks + lg) ^ ((ln >> 2) & 3)
+    uint32_t a_rd[2];
 #pragma unroll
-    for (int ks = 0; ks < 4; ++ks)
-        a_rd[ks] = static_cast<uint32_t>(kRingOff + grp * 8192 + ln * 128 + (((2 * ks + lg) ^ ((ln >> 1) & 7)) << 4));
-    // window read: LDS row 64*wn + ln (tn = 0) and + 32 (tn = 1) of the chunk, the K group's 8 bytes of the piece
-    const uint32_t w_rd = static_cast<uint32_t>(kTileOff + (64 * wn + ln) * 16 + 8 * grp);
-    // byte 2*ks + lg of a window: word ks / 2, bits 16*(ks % 2) + 8*lg on
+    for (int ks = 0; ks < 2; ++ks)
+        a_rd[ks] = static_cast<uint32_t>(kRingOff + wave * (kNB * kSlotBytes) + row_slot(ln) * 64 + (((2 * ks + lg) ^ ((ln >> 2) & 3)) << 4));
+    // window read: LDS row 32*tn + ln of a chunk
+    const uint32_t w_rd = static_cast<uint32_t>(kTileOff + wave * (2 * kTileSlotBytes) + ln * 16);
+    // byte 2*ks + lg of a window word: bits 16*ks + 8*lg on
     uint32_t bsh[2] = {8u * static_cast<uint32_t>(lg), 16u + 8u * static_cast<uint32_t>(lg)};
     asm volatile("" : "+v"(bsh[0]), "+v"(bsh[1]));
 
     // exchange / turn-round addresses
     const uint32_t xchg_mine = static_cast<uint32_t>(kXchgOff + wave * 8192);
-    const uint32_t xchg_partner = static_cast<uint32_t>(kXchgOff + (wave ^ 2) * 8192);
     const int g8 = lane & 7, rr = lane >> 3;   // store layout: lane holds columns 8*g8 .. + 7 of rows rr + 8*i
 
-    f32x16_t acc[2][2];
+    f32x16_t acc[2][4];
 #pragma unroll
     for (int i = 0; i < 2; ++i)
 #pragma unroll
-        for (int j = 0; j < 2; ++j)
+        for (int j = 0; j < 4; ++j)
 #pragma unroll
             for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.f;
 
-    Frag A[2][2][2];    // [operand set][K step of the pair][tm]
-    Frag B[2][2][2];    // [operand set][K step of the pair][tn]
-    u32x4_t win[2];     // [round parity]: words 0-1 the 64 window bits of column tn = 0, words 2-3 of tn = 1
+    Frag A[2][2];       // [operand set][tm]
+    Frag B[2][4];       // [operand set][tn]
+    u32x4_t wcur[4];    // [tn]: the 128 window bits of the column for the current four rounds (word = round % 4)
+    u32x4_t wnxt[4];    // the same for the next four rounds
     float zr[4][8];     // finished block of the previous half tile in store layout
 #pragma unroll
     for (int i = 0; i < 4; ++i)
@@ -303,27 +330,16 @@ __global__ __launch_bounds__(kThreads, 1) void linear_stream_bf16_kernel(const u
     unsigned char *z_base = reinterpret_cast<unsigned char *>(y);   // Y address of the block's row 0, column 0 (replica 0)
     uint32_t z_lane = 0;               // byte offset of the lane's first element
     int32_t z_t = P.reps;              // next replica to store; reps = nothing pending
+    unsigned char *z_rep = z_base;     // Y address of that replica's row 0, column 0
     const uint32_t out_bytes8 = static_cast<uint32_t>(P.out) * 16u;   // eight rows of Y in bytes
     const uint32_t rep_bytes = static_cast<uint32_t>(P.U) * 2u;
 
     // multiplication cursor
-    int32_t cp_row = first_row, cp_col = first_col, cp_slot = 0, cp_tslot = 0;
+    int32_t cp_row = first_row, cp_col = first_col, cp_off = 0, cp_tslot = 0;   // cp_off: ring slot in bytes
 
-#ifndef TBN_X_TABLE
-#define TBN_X_TABLE 0
-#endif
-    uint32_t x_zero = 0;
-    asm volatile("" : "+v"(x_zero));
     auto table_read = [&](u32x4_t &dst, uint32_t word, uint32_t shift) {
-#if TBN_X_TABLE == 1
-        const uint32_t addr = (__builtin_amdgcn_ubfe(word, shift, 8) << 4) & x_zero;   // timing only: one entry
-#else
         const uint32_t addr = __builtin_amdgcn_ubfe(word, shift, 8) << 4;
-#endif
         lds_read16<kTableOff>(dst, addr);
-    };
-    auto mfma = [&](int set, int ks, int tm, int tn) {
-        acc[tm][tn] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(B[set][ks][tn].v, A[set][ks][tm].v, acc[tm][tn], 0, 0, 0);
     };
     auto alpha_of = [&](int32_t t) -> float {
         return __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, alpha_lanes), t));
@@ -342,221 +358,244 @@ __global__ __launch_bounds__(kThreads, 1) void linear_stream_bf16_kernel(const u
     };
     auto job_store = [&](auto i_c, const u32x4_t &pk) {
         constexpr int I = decltype(i_c)::value;
-        unsigned char *dst = z_base + static_cast<uint32_t>(z_t) * rep_bytes;
+        typedef __attribute__((address_space(1))) u32x4_t global_u32x4_t;
+        unsigned char *dst = z_rep;
         asm volatile("" : "+s"(dst));
-#ifdef TBN_X_NOSTORE
-        if (z_lane == 0xffffffffu)
-#endif
-        if (!MASKED || (z_mask & (1u << I)))
-            *reinterpret_cast<u32x4_t *>(dst + (z_lane + static_cast<uint32_t>(I) * out_bytes8)) = pk;
+        uint32_t off = z_lane + static_cast<uint32_t>(I) * out_bytes8;
+        asm volatile("" : "+v"(off));   // scalar base + 32-bit lane offset
+        // non-temporal: the output must not push the activations, which the other column blocks of the same
+        // rows still need, out of the XCD's L2 (8192 x 4096 -> 16384, k = 8: 174 us against 209 with plain stores)
+        if (!MASKED || (z_mask & (1u << I))) __builtin_nontemporal_store(pk, (global_u32x4_t *)(dst + off));
     };
     auto store_replica = [&]() {   // all four row groups of replica z_t, outside the rounds
         const float al = alpha_of(z_t);
         float v[8];
         u32x4_t pk;
-        job_scale(std::integral_constant<int, 0>{}, al, v); job_pack(v, pk); job_store(std::integral_constant<int, 0>{}, pk);
-        job_scale(std::integral_constant<int, 1>{}, al, v); job_pack(v, pk); job_store(std::integral_constant<int, 1>{}, pk);
-        job_scale(std::integral_constant<int, 2>{}, al, v); job_pack(v, pk); job_store(std::integral_constant<int, 2>{}, pk);
-        job_scale(std::integral_constant<int, 3>{}, al, v); job_pack(v, pk); job_store(std::integral_constant<int, 3>{}, pk);
+        job_scale(Int<0>{}, al, v); job_pack(v, pk); job_store(Int<0>{}, pk);
+        job_scale(Int<1>{}, al, v); job_pack(v, pk); job_store(Int<1>{}, pk);
+        job_scale(Int<2>{}, al, v); job_pack(v, pk); job_store(Int<2>{}, pk);
+        job_scale(Int<3>{}, al, v); job_pack(v, pk); job_store(Int<3>{}, pk);
     };
 
     // ---- first operands -------------------------------------------------------------------------
-    // round 0 is readable once its loads (the oldest) have landed and the workgroup has met
-    __builtin_amdgcn_s_waitcnt(vmcnt_imm(4 + 5 + 4 + 5));   // the loads of rounds 1 .. 4 may be in flight
+    // chunk 0 and round 0 are readable once their loads (the oldest) have landed
+    __builtin_amdgcn_s_waitcnt(vmcnt_imm(4 + 4 + 2 + 4 + 4));   // rounds 1, 2, chunk 1, rounds 3, 4 may be in flight
     asm volatile("" : "+v"(alpha_lanes));
-    lds_wait<0>();   // the table
-    __builtin_amdgcn_s_barrier();
-    lds_read2x8(win[0], w_rd);   // windows of round 0: chunk slot 0, piece 0
     lds_wait<0>();
-    tie(win[0]);
-    {
-        const uint32_t ar0 = a_rd[0], ar1 = a_rd[1];   // ring slot 0
-        table_read(B[0][0][0].q, win[0][0], bsh[0]);
-        lds_read16<0>(A[0][0][0].q, ar0);
-        lds_read16<4096>(A[0][0][1].q, ar0);
-        table_read(B[0][0][1].q, win[0][2], bsh[0]);
-        table_read(B[0][1][0].q, win[0][0], bsh[1]);
-        lds_read16<0>(A[0][1][0].q, ar1);
-        lds_read16<4096>(A[0][1][1].q, ar1);
-        table_read(B[0][1][1].q, win[0][2], bsh[1]);
-    }
+    __builtin_amdgcn_s_barrier();   // the table, written by all waves
+    lds_read16<0 * 512>(wcur[0], w_rd);
+    lds_read16<1 * 512>(wcur[1], w_rd);
+    lds_read16<2 * 512>(wcur[2], w_rd);
+    lds_read16<3 * 512>(wcur[3], w_rd);
+    lds_wait<0>();
+    tie(wcur[0]); tie(wcur[1]); tie(wcur[2]); tie(wcur[3]);
+    table_read(B[0][0].q, wcur[0][0], bsh[0]);
+    lds_read16<0>(A[0][0].q, a_rd[0]);
+    lds_read16<2048>(A[0][1].q, a_rd[0]);
+    table_read(B[0][1].q, wcur[1][0], bsh[0]);
+    table_read(B[0][2].q, wcur[2][0], bsh[0]);
+    table_read(B[0][3].q, wcur[3][0], bsh[0]);
     // all of operand set 0 has landed (what a loop is entered with, see below)
     auto settle = [&]() {
         lds_wait<0>();
-#pragma unroll
-        for (int ks = 0; ks < 2; ++ks)
-#pragma unroll
-            for (int t = 0; t < 2; ++t) { tie(A[0][ks][t].q); tie(B[0][ks][t].q); }
+        tie(A[0][0].q); tie(A[0][1].q);
+        tie(B[0][0].q); tie(B[0][1].q); tie(B[0][2].q); tie(B[0][3].q);
     };
     settle();
 
-    // ---- one round: 16 MFMAs per wave ---------------------------------------------------------------
-    // PAR: parity of the round (inside its half tile and overall: a half tile has an even number of rounds).
-    // JOB: the round also stores two of the eight-row groups of a replica of the previous half tile's block.
-    // On entry the operands of the round's first two K steps have been requested (operand set 0).  LDS
-    // operations complete in order, so "at most N pending" names exactly which operands have arrived: the
-    // eight reads of a pair of K steps are issued one after an MFMA each, in the order in which the next
-    // pair's MFMAs need them, and an MFMA waits with six (seven while the window read is among the younger
-    // ones) operations pending: every operand has the time of six MFMAs to arrive.
-#ifdef TBN_X_NOLOAD
-#define X_LOAD(x)
-#else
-#define X_LOAD(x) x
-#endif
-#ifdef TBN_X_NOREAD
-#define X_READ(x)
-#else
-#define X_READ(x) x
-#endif
-    auto round = [&](auto par_c, auto job_c) {
-        constexpr int PAR = decltype(par_c)::value;
-        constexpr bool JOB = decltype(job_c)::value != 0;
-        // Loads that may still be in flight when round + 1 must be readable: those of rounds + 2 .. + 4, four
-        // wave-loads each and the tile chunk with the even ones.  (Stores of a job are younger operations
-        // too; not counting them errs on the safe side.)
-        __builtin_amdgcn_s_waitcnt(vmcnt_imm(PAR == 0 ? 14 : 13));
-#ifndef TBN_X_NOBAR
-        __builtin_amdgcn_s_barrier();   // round + 1 is readable, the slot of round - 1 is free
-#endif
-
-        const uint32_t cur_off = static_cast<uint32_t>(cp_slot * kSlotBytes);
-        cp_slot = cp_slot + 1 == kNB ? 0 : cp_slot + 1;
-        const uint32_t nxt_off = static_cast<uint32_t>(cp_slot * kSlotBytes);
-        // windows of the next round: an even round reads the second piece of its own chunk, an odd round
-        // the first piece of the next chunk
-        if constexpr (PAR == 1) cp_tslot = (cp_tslot + 1) & (kTileSlots - 1);
-        const uint32_t w_addr = w_rd + static_cast<uint32_t>(cp_tslot * kTileSlotBytes + (PAR == 0 ? 2048 : 0));
-        const uint32_t ar2 = a_rd[2] + cur_off, ar3 = a_rd[3] + cur_off;
-        const uint32_t ar0 = a_rd[0] + nxt_off, ar1 = a_rd[1] + nxt_off;
-        u32x4_t &wc = win[PAR];        // this round's windows
-        u32x4_t &wx = win[PAR ^ 1];    // the next round's
-        typedef std::integral_constant<int, 2 * PAR> RowA;
-        typedef std::integral_constant<int, 2 * PAR + 1> RowB;
-        float al = 0.f, v[8];
-        u32x4_t pk;
-        if constexpr (JOB) al = alpha_of(z_t);
-
-        // ---- K steps 0 and 1 (operand set 0); requests K steps 2 and 3 into set 1
-        lds_wait<6>(); tie(B[0][0][0].q); tie(A[0][0][0].q);
-        mfma(0, 0, 0, 0);
-        X_READ(table_read(B[1][0][0].q, wc[1], bsh[0]);)
-        X_READ(lds_read2x8(wx, w_addr);)
+    // ---- one K step: 8 MFMAs ---------------------------------------------------------------------
+    // Multiplies with operand set S and requests the operands of the following K step into the other set: six
+    // LDS reads, one in each of the first six MFMA slots, in the order in which the MFMAs of that step need
+    // them (+-1 operand of tn = 0, the two activation fragments, +-1 operands of tn = 1, 2, 3).  LDS operations
+    // complete in order, so "at most N pending" names exactly which operands have arrived; three waits cover
+    // the step, and every operand has the time of at least six MFMAs to arrive.  A slot is: wait, request,
+    // MFMA, side work (an instruction between the wait that hands registers over and the MFMA that reads
+    // them also saves the compiler a hazard no-op).  W4 = 4: four window reads were issued behind the
+    // previous step's requests.  nw: the window words (one per tn) and NKS the K step inside its round of the
+    // step requested here.
+    auto kstep = [&](auto s_c, auto w4_c, uint32_t n_addr, uint32_t (&nw)[4], auto nks_c, auto &&side) __attribute__((always_inline)) {
+        constexpr int S = decltype(s_c)::value, N = S ^ 1, W4 = decltype(w4_c)::value, NKS = decltype(nks_c)::value;
+        auto mfma = [&](int tm, int tn) {
+            acc[tm][tn] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(B[S][tn].v, A[S][tm].v, acc[tm][tn], 0, 0, 0);
+        };
+        lds_wait<3 + W4>(); tie(B[S][0].q); tie(A[S][0].q); tie(A[S][1].q);
+        side(Int<-1>{});   // what else this wait covers
+        table_read(B[N][0].q, nw[0], bsh[NKS]);
+        mfma(0, 0);
+        side(Int<0>{});
         __builtin_amdgcn_sched_barrier(0);
-        lds_wait<7>(); tie(A[0][0][1].q);
-        mfma(0, 0, 1, 0);
-        X_READ(lds_read16<0>(A[1][0][0].q, ar2);)
-        if constexpr (JOB) job_scale(RowA{}, al, v);
+        lds_read16<0>(A[N][0].q, n_addr);
+        mfma(1, 0);
+        side(Int<1>{});
         __builtin_amdgcn_sched_barrier(0);
-        lds_wait<7>(); tie(B[0][0][1].q);
-        mfma(0, 0, 0, 1);
-        X_READ(lds_read16<4096>(A[1][0][1].q, ar2);)
-        if constexpr (JOB) job_pack(v, pk);
+        lds_wait<4 + W4>(); tie(B[S][1].q);
+        lds_read16<2048>(A[N][1].q, n_addr);
+        mfma(0, 1);
+        side(Int<2>{});
         __builtin_amdgcn_sched_barrier(0);
-        mfma(0, 0, 1, 1);
-        X_READ(table_read(B[1][0][1].q, wc[3], bsh[0]);)
-        X_LOAD(issue_x(std::integral_constant<int, 0>{}));
+        table_read(B[N][1].q, nw[1], bsh[NKS]);
+        mfma(1, 1);
+        side(Int<3>{});
         __builtin_amdgcn_sched_barrier(0);
-        lds_wait<7>(); tie(B[0][1][0].q); tie(A[0][1][0].q);
-        mfma(0, 1, 0, 0);
-        X_READ(table_read(B[1][1][0].q, wc[1], bsh[1]);)
+        lds_wait<4 + W4>(); tie(B[S][2].q); tie(B[S][3].q);
+        table_read(B[N][2].q, nw[2], bsh[NKS]);
+        mfma(0, 2);
+        side(Int<4>{});
         __builtin_amdgcn_sched_barrier(0);
-        lds_wait<7>(); tie(A[0][1][1].q);
-        mfma(0, 1, 1, 0);
-        X_READ(lds_read16<0>(A[1][1][0].q, ar3);)
-        if constexpr (JOB) job_store(RowA{}, pk);
+        table_read(B[N][3].q, nw[3], bsh[NKS]);
+        mfma(1, 2);
+        side(Int<5>{});
         __builtin_amdgcn_sched_barrier(0);
-        lds_wait<7>(); tie(B[0][1][1].q);
-        mfma(0, 1, 0, 1);
-        X_READ(lds_read16<4096>(A[1][1][1].q, ar3);)
+        mfma(0, 3);
+        side(Int<6>{});
         __builtin_amdgcn_sched_barrier(0);
-        mfma(0, 1, 1, 1);
-        X_READ(table_read(B[1][1][1].q, wc[3], bsh[1]);)
-        X_LOAD(issue_x(std::integral_constant<int, 1>{}));
-        __builtin_amdgcn_sched_barrier(0);
-
-        // ---- K steps 2 and 3 (operand set 1); requests the next round's K steps 0 and 1 into set 0
-        lds_wait<6>(); tie(B[1][0][0].q); tie(A[1][0][0].q); tie(wx);
-        mfma(1, 0, 0, 0);
-        X_READ(table_read(B[0][0][0].q, wx[0], bsh[0]);)
-        __builtin_amdgcn_sched_barrier(0);
-        lds_wait<6>(); tie(A[1][0][1].q);
-        mfma(1, 0, 1, 0);
-        X_READ(lds_read16<0>(A[0][0][0].q, ar0);)
-        if constexpr (JOB) job_scale(RowB{}, al, v);
-        __builtin_amdgcn_sched_barrier(0);
-        lds_wait<6>(); tie(B[1][0][1].q);
-        mfma(1, 0, 0, 1);
-        X_READ(lds_read16<4096>(A[0][0][1].q, ar0);)
-        if constexpr (JOB) job_pack(v, pk);
-        __builtin_amdgcn_sched_barrier(0);
-        mfma(1, 0, 1, 1);
-        X_READ(table_read(B[0][0][1].q, wx[2], bsh[0]);)
-        X_LOAD(issue_x(std::integral_constant<int, 2>{}));
-        __builtin_amdgcn_sched_barrier(0);
-        lds_wait<6>(); tie(B[1][1][0].q); tie(A[1][1][0].q);
-        mfma(1, 1, 0, 0);
-        X_READ(table_read(B[0][1][0].q, wx[0], bsh[1]);)
-        __builtin_amdgcn_sched_barrier(0);
-        lds_wait<6>(); tie(A[1][1][1].q);
-        mfma(1, 1, 1, 0);
-        X_READ(lds_read16<0>(A[0][1][0].q, ar1);)
-        if constexpr (JOB) job_store(RowB{}, pk);
-        __builtin_amdgcn_sched_barrier(0);
-        lds_wait<6>(); tie(B[1][1][1].q);
-        mfma(1, 1, 0, 1);
-        X_READ(lds_read16<4096>(A[0][1][1].q, ar1);)
-        __builtin_amdgcn_sched_barrier(0);
-        mfma(1, 1, 1, 1);
-        X_READ(table_read(B[0][1][1].q, wx[2], bsh[1]);)
-        X_LOAD(issue_x(std::integral_constant<int, 3>{}));
-        if constexpr (PAR == 1) X_LOAD(issue_tile());
-        advance_load();
-        if constexpr (JOB && PAR == 1) ++z_t;
+        mfma(1, 3);
+        side(Int<7>{});
         __builtin_amdgcn_sched_barrier(0);
     };
 
-    // ---- the half tiles -------------------------------------------------------------------------
-    // Two plain loops per half tile: rounds that carry stores of the previous block, then rounds that do
-    // not.  Operands requested by a loop's last round are allowed to land before the loop is left
-    // (settle), so that a register with a read in flight only ever crosses a loop's own back edge.
-    for (int32_t h = 0; h < n_ht; ++h) {
-        int32_t pr = 0;
-        const int32_t n_pr = NR >> 1;
-        if (z_t < P.reps) {
-            do {
-                round(std::integral_constant<int, 0>{}, std::true_type{});
-                round(std::integral_constant<int, 1>{}, std::true_type{});
-                ++pr;
-            } while (pr < n_pr && z_t < P.reps);
-            settle();
+    // ---- one round: two K steps, 16 MFMAs --------------------------------------------------------------
+    // Q: the round's place in its group of four (window word Q).  JOB: the round stores two eight-row groups
+    // of a replica of the previous half tile's block (K step 0).  STORES: how many stores this and the three
+    // rounds before have issued.  K step 1 issues the loads of round + 5 (and, for Q = 2, the tile chunk of
+    // the group after the next and the reads of the next group's windows).
+    auto round = [&](auto q_c, auto job_c, auto stores_c) __attribute__((always_inline)) {
+        constexpr int Q = decltype(q_c)::value;
+        constexpr bool JOB = decltype(job_c)::value != 0;
+        constexpr int STORES = decltype(stores_c)::value;
+        const uint32_t ar1 = a_rd[1] + static_cast<uint32_t>(cp_off);
+        cp_off = cp_off + kSlotBytes == kNB * kSlotBytes ? 0 : cp_off + kSlotBytes;
+        const uint32_t ar0 = a_rd[0] + static_cast<uint32_t>(cp_off);
+        const unsigned char *src = ld_x;
+        asm volatile("" : "+s"(src));   // one scalar base for the round's four wave-loads
+        float al = 0.f, v[8];
+        u32x4_t pk;
+        if constexpr (JOB) al = alpha_of(z_t);
+        typedef Int<2 * (Q & 1)> RowA;
+        typedef Int<2 * (Q & 1) + 1> RowB;
+
+        // K step 0 (set 0): requests K step 1 of this round
+        uint32_t w1[4] = {wcur[0][Q], wcur[1][Q], wcur[2][Q], wcur[3][Q]};
+        kstep(Int<0>{}, Int<(Q == 3 ? 4 : 0)>{}, ar1, w1, Int<1>{}, [&](auto slot_c) __attribute__((always_inline)) {
+            constexpr int SLOT = decltype(slot_c)::value;
+            if constexpr (JOB) {
+                if constexpr (SLOT == 1) job_scale(RowA{}, al, v);
+                if constexpr (SLOT == 2) job_pack(v, pk);
+                if constexpr (SLOT == 3) job_store(RowA{}, pk);
+                if constexpr (SLOT == 4) job_scale(RowB{}, al, v);
+                if constexpr (SLOT == 5) job_pack(v, pk);
+                if constexpr (SLOT == 6) job_store(RowB{}, pk);
+            }
+        });
+
+        // Round + 1 must be readable from here on.  Vector-memory operations issued after its loads, which
+        // may still be in flight: the loads of rounds + 2 .. + 4 (four each, and the two of a tile chunk if a
+        // round with Q = 2 is among the three before this one) and the stores counted in STORES.
+        __builtin_amdgcn_s_waitcnt(vmcnt_imm(12 + (Q == 2 ? 0 : 2) + STORES));
+
+        // K step 1 (set 1): requests K step 0 of the next round
+        // (Q = 3: the next group's windows, requested during round Q = 2, are older than this step's operands
+        // and handed over behind its first wait; the words are picked there)
+        uint32_t w0[4];
+        if constexpr (Q < 3) {
+#pragma unroll
+            for (int tn = 0; tn < 4; ++tn) w0[tn] = wcur[tn][(Q + 1) & 3];
         }
-        if (pr < n_pr) {
-            do {
-                round(std::integral_constant<int, 0>{}, std::false_type{});
-                round(std::integral_constant<int, 1>{}, std::false_type{});
-                ++pr;
-            } while (pr < n_pr);
+        const uint32_t w_addr = w_rd + static_cast<uint32_t>((cp_tslot ^ 1) * kTileSlotBytes);
+        kstep(Int<1>{}, Int<0>{}, ar0, w0, Int<0>{}, [&](auto slot_c) __attribute__((always_inline)) {
+            constexpr int SLOT = decltype(slot_c)::value;
+            if constexpr (SLOT == -1 && Q == 3) {
+#pragma unroll
+                for (int tn = 0; tn < 4; ++tn) { tie(wnxt[tn]); w0[tn] = wnxt[tn][0]; }
+            }
+            if constexpr (SLOT == 1) issue_x(Int<0>{}, src);
+            if constexpr (SLOT == 3) issue_x(Int<1>{}, src);
+            if constexpr (SLOT == 5) issue_x(Int<2>{}, src);
+            if constexpr (Q == 2) {
+                if constexpr (SLOT == 2) issue_tile(Int<0>{});
+                if constexpr (SLOT == 4) { issue_tile(Int<1>{}); advance_tile(); }
+                if constexpr (SLOT == 6) { lds_read16<0 * 512>(wnxt[0], w_addr); lds_read16<1 * 512>(wnxt[1], w_addr); }
+                if constexpr (SLOT == 7) { lds_read16<2 * 512>(wnxt[2], w_addr); lds_read16<3 * 512>(wnxt[3], w_addr); }
+            }
+            if constexpr (SLOT == 7) {
+                issue_x(Int<3>{}, src);
+                advance_x(Int<(Q == 2)>{});   // the cursor moves on to round + 6: a half tile can only end there if Q = 2
+            }
+        });
+        if constexpr (JOB && (Q & 1) == 1) { ++z_t; z_rep += rep_bytes; }
+        if constexpr (Q == 3) {
+#pragma unroll
+            for (int tn = 0; tn < 4; ++tn) wcur[tn] = wnxt[tn];
+            cp_tslot ^= 1;
+        }
+    };
+    // four rounds; JP / J: the previous / this group's rounds carry stores (two each)
+    auto group = [&](auto jp_c, auto j_c) __attribute__((always_inline)) {
+        constexpr int JP = decltype(jp_c)::value, J = decltype(j_c)::value;
+        round(Int<0>{}, j_c, Int<2 * (3 * JP + J)>{});
+        round(Int<1>{}, j_c, Int<2 * (2 * JP + 2 * J)>{});
+        round(Int<2>{}, j_c, Int<2 * (JP + 3 * J)>{});
+        round(Int<3>{}, j_c, Int<2 * (4 * J)>{});
+    };
+
+    // ---- the half tiles -------------------------------------------------------------------------
+    // Per half tile: groups of rounds that carry stores of the previous block, then groups that do not.
+    // Operands requested by a loop's last round are allowed to land before the loop is left (settle), so that
+    // a register with a read in flight only ever crosses a loop's own back edge.
+    bool jp = false;   // the group before carried stores
+    for (int32_t h = 0; h < n_ht; ++h) {
+        int32_t sr = 0;
+        if (z_t + 2 <= P.reps) {   // a group of four rounds stores two replicas
+            if (jp) group(Int<1>{}, Int<1>{}); else group(Int<0>{}, Int<1>{});
+            ++sr;
             settle();
+            if (sr < n_sr && z_t + 2 <= P.reps) {
+                do {
+                    group(Int<1>{}, Int<1>{});
+                    ++sr;
+                } while (sr < n_sr && z_t + 2 <= P.reps);
+                settle();
+            }
+            jp = true;
+        }
+        if (sr < n_sr) {
+            if (jp) group(Int<1>{}, Int<0>{}); else group(Int<0>{}, Int<0>{});
+            ++sr;
+            settle();
+            if (sr < n_sr) {
+                do {
+                    group(Int<0>{}, Int<0>{});
+                    ++sr;
+                } while (sr < n_sr);
+                settle();
+            }
+            jp = false;
         }
 
         // ---- end of the half tile ---------------------------------------------------------------
-        // replicas of the previous block that found no round (short K, many replicas)
-        for (; z_t < P.reps; ++z_t) store_replica();
+        // replicas of the previous block that found no round (short K, many replicas, an odd last one)
+        if (z_t < P.reps) {
+            for (; z_t < P.reps; ++z_t, z_rep += rep_bytes) store_replica();
+            jp = false;   // conservative for the wait counts: fewer stores assumed than were issued
+        }
 
-        // The K groups add their partial sums: accumulator index tm of group g stands for row block
-        // (tm + g) % 2, so each group keeps acc[0] and hands acc[1] to the other one.  The matrix pipe
-        // must have written the accumulators back before the assembly below reads them.
+        // The waves add their partial sums.  Three steps: in step s = 1, 2, 3 wave w hands the block that wave
+        // w ^ s keeps (accumulators [0][2..3], [1][0..1], [1][2..3] by the rotation of the indices) to that
+        // wave through its 8 KiB slot.  The matrix pipe must have written the accumulators back before the
+        // assembly below reads them.
         asm volatile("s_nop 15");
         asm volatile("s_nop 15");
-        {
+#pragma unroll
+        for (int step = 1; step <= 3; ++step) {
+            const int tm = step >> 1, tn0 = 2 * (step & 1);
             u32x4_t s[8];
 #pragma unroll
-            for (int tn = 0; tn < 2; ++tn)
+            for (int t = 0; t < 2; ++t)
 #pragma unroll
                 for (int q = 0; q < 4; ++q)
 #pragma unroll
-                    for (int e = 0; e < 4; ++e) s[tn * 4 + q][e] = __float_as_uint(acc[1][tn][4 * q + e]);
-            const uint32_t dst = xchg_partner + static_cast<uint32_t>(lane) * 16u;
+                    for (int e = 0; e < 4; ++e) s[t * 4 + q][e] = __float_as_uint(acc[tm][tn0 + t][4 * q + e]);
+            const uint32_t dst = static_cast<uint32_t>(kXchgOff + (wave ^ step) * 8192) + static_cast<uint32_t>(lane) * 16u;
             lds_write16<0 * 1024>(dst, s[0]);
             lds_write16<1 * 1024>(dst, s[1]);
             lds_write16<2 * 1024>(dst, s[2]);
@@ -565,10 +604,8 @@ __global__ __launch_bounds__(kThreads, 1) void linear_stream_bf16_kernel(const u
             lds_write16<5 * 1024>(dst, s[5]);
             lds_write16<6 * 1024>(dst, s[6]);
             lds_write16<7 * 1024>(dst, s[7]);
-        }
-        lds_wait<0>();
-        __builtin_amdgcn_s_barrier();
-        {
+            lds_wait<0>();
+            __builtin_amdgcn_s_barrier();
             u32x4_t got[8];
             const uint32_t src = xchg_mine + static_cast<uint32_t>(lane) * 16u;
             lds_read16<0 * 1024>(got[0], src);
@@ -583,19 +620,19 @@ __global__ __launch_bounds__(kThreads, 1) void linear_stream_bf16_kernel(const u
 #pragma unroll
             for (int i = 0; i < 8; ++i) tie(got[i]);
 #pragma unroll
-            for (int tn = 0; tn < 2; ++tn)
+            for (int t = 0; t < 2; ++t)
 #pragma unroll
                 for (int q = 0; q < 4; ++q)
 #pragma unroll
-                    for (int e = 0; e < 4; ++e) acc[0][tn][4 * q + e] += __uint_as_float(got[tn * 4 + q][e]);
+                    for (int e = 0; e < 4; ++e) acc[0][t][4 * q + e] += __uint_as_float(got[t * 4 + q][e]);
+            __builtin_amdgcn_s_barrier();   // every slot has been read: the next step (or the turn-round) may write
         }
-        // Turn the finished 32 x 64 block round inside the wave's own slot (the partner wrote it before the
-        // barrier and will not write to it again before the next half tile's hand-over).  On entry the lane
-        // holds row ln and, in registers 4q .. 4q + 3 of tiles 0 and 1, columns 16*q + 8*lg .. + 7.  LDS
-        // row r is 256 bytes; the 16-byte chunk ch of it (columns 4*ch .. 4*ch + 3) sits at chunk position
-        // ch ^ s(r), s(r) = ((r >> 1) & 7) ^ (2 * (r & 1)): the writes (lanes = rows) and the reads (eight
-        // lanes per row; a lane reads chunks 2*g8 and 2*g8 + 1, the upper four lanes in the other order)
-        // are then free of bank conflicts.
+        // Turn the finished 32 x 64 block round inside the wave's own slot.  On entry the lane holds row ln
+        // and, in registers 4q .. 4q + 3 of tiles 0 and 1, columns 16*q + 8*lg .. + 7.  LDS row r is 256
+        // bytes; the 16-byte chunk ch of it (columns 4*ch .. 4*ch + 3) sits at chunk position ch ^ s(r),
+        // s(r) = ((r >> 1) & 7) ^ (2 * (r & 1)): the writes (lanes = rows) and the reads (eight lanes per row;
+        // a lane reads chunks 2*g8 and 2*g8 + 1, the upper four lanes in the other order) are then free of
+        // bank conflicts.
         {
             const int s_w = ((ln >> 1) & 7) ^ (2 * (ln & 1));
 #pragma unroll
@@ -630,10 +667,11 @@ __global__ __launch_bounds__(kThreads, 1) void linear_stream_bf16_kernel(const u
                     zr[i][4 + e] = __uint_as_float(g8 < 4 ? zb[i][e] : za[i][e]);
                 }
         }
-        // where the block goes: rows cp_row*64 + 32*grp + rr + 8*i, columns cp_col*128 + 64*wn + 8*g8 .. + 7
+        __builtin_amdgcn_s_barrier();   // the slots are free for the next half tile's hand-over
+        // where the block goes: rows cp_row*64 + 32*rot_m + rr + 8*i, columns cp_col*128 + 64*rot_n + 8*g8 .. + 7
         {
-            const int64_t row0 = int64_t(cp_row) * kHT + 32 * grp;
-            const int32_t col0 = cp_col * kBN + 64 * wn;
+            const int64_t row0 = int64_t(cp_row) * kHT + 32 * rot_m;
+            const int32_t col0 = cp_col * kBN + 64 * rot_n;
             z_base = reinterpret_cast<unsigned char *>(y) + (row0 * P.out + col0) * 2;
             z_lane = (static_cast<uint32_t>(rr) * static_cast<uint32_t>(P.out) + static_cast<uint32_t>(8 * g8)) * 2u;
             if (MASKED) {
@@ -645,11 +683,12 @@ __global__ __launch_bounds__(kThreads, 1) void linear_stream_bf16_kernel(const u
                     if (col_ok && rr + 8 * i < rows_left) z_mask |= 1u << i;
             }
             z_t = 0;
+            z_rep = z_base;
         }
 #pragma unroll
         for (int i = 0; i < 2; ++i)
 #pragma unroll
-            for (int j = 0; j < 2; ++j)
+            for (int j = 0; j < 4; ++j)
 #pragma unroll
                 for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.f;
         cp_col += step_c;
@@ -658,7 +697,7 @@ __global__ __launch_bounds__(kThreads, 1) void linear_stream_bf16_kernel(const u
     }
 
     // ---- the last block's replicas; the loads issued past the end have landed by then -------------------
-    for (; z_t < P.reps; ++z_t) store_replica();
+    for (; z_t < P.reps; ++z_t, z_rep += rep_bytes) store_replica();
     __builtin_amdgcn_s_waitcnt(vmcnt_imm(0));
 }
 
@@ -673,11 +712,11 @@ tbn_status set_lds_limit_once(const void *kernel, int lds) {
 
 }  // namespace
 
-// Shapes the streaming kernel takes: bfloat16, tile of whole rows, K in whole pairs of rounds, 16-byte
-// stores possible, every offset inside a half tile in 32 bits.
+// Shapes the streaming kernel takes: bfloat16, tile of whole rows, K in whole groups of four rounds per wave
+// (in % 512 == 0), 16-byte stores possible, every offset inside a half tile in 32 bits.
 bool linear_stream_supported(const LinearArgs &a) {
     if (a.dt != TBN_BF16) return false;
-    if (a.in % 256 != 0 || a.p % a.in != 0) return false;
+    if (a.in % 512 != 0 || a.p % a.in != 0) return false;
     const int64_t U = a.p / a.in;
     if (U > a.out || a.out % U != 0) return false;   // (holds whenever p % in == 0; U = out / k)
     if (U % 8 != 0 || a.out / U > 64) return false;
@@ -704,7 +743,7 @@ tbn_status launch_linear_stream(const LinearArgs &a) {
     P.rows_half = static_cast<int32_t>(rows_half);
     P.rows_xcd = (P.rows_half + 7) / 8;
     P.tiles_n = (P.U + kBN - 1) / kBN;
-    P.nr = P.in / kRoundK;
+    P.n_sr = P.in / 512;
     // one workgroup per CU (the LDS footprint allows no second one): 32 per XCD on the 256 CUs of an
     // MI355X, fewer when an XCD's share of the half tiles is smaller
     int device = 0, cus = 256;

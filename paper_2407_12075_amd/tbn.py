@@ -19,6 +19,7 @@ TBN_FLAG_RELU = 0x1
 TBN_FLAG_FORCE_GENERIC = 0x100
 TBN_FLAG_LARGE_BATCH = 0x200
 TBN_FLAG_BLOCK_KERNEL = 0x400
+TBN_FLAG_STREAM_KERNEL = 0x800
 
 _STATUS = {1: "TBN_ERR_NULL", 2: "TBN_ERR_SHAPE", 3: "TBN_ERR_UNSUPPORTED", 4: "TBN_ERR_DEVICE",
            5: "TBN_ERR_WORKSPACE"}

@@ -4,10 +4,11 @@ sides) bfloat16 hold exactly, so the matrix-core kernels must agree with the CPU
 One wrong tile bit, window position, K slice or output column changes an output by at least 1: the
 tolerance tests at long K cannot see that (2e-2 of max|y| is about 0.1 there), these can.
 
-Shapes reach every large-batch bfloat16 kernel form: the streaming kernel (tile of whole rows, K a
-multiple of 256: half tiles, ragged batches and column blocks, several half tiles per workgroup, short K
-with more replicas than rounds, one replica), the one-block-per-tile kernel (other K, tiles that end
-inside rows) and, with float32 activations, the float32 kernel.
+Shapes reach every large-batch bfloat16 kernel form: the two kernels for tiles of whole rows (128 x 128
+blocks with load waves, K a multiple of 256; streaming half tiles, K a multiple of 512: ragged batches and
+column blocks, several half tiles per workgroup, short K with more replicas than rounds, one replica), the
+general one-block-per-tile kernel (other K, tiles that end inside rows) and, with float32 activations, the
+float32 kernel.
 """
 import numpy as np
 import pytest
@@ -68,45 +69,52 @@ def _exact_case(tbn, M, cin, cout, k, dtype, flags, seed, alpha_vals=None):
 
 # M, in, out, k
 EXACT_STREAM = [
-    (128, 256, 1024, 8),      # one pair of rounds per half tile: more replicas than rounds
+    (128, 512, 1024, 8),      # one group of four rounds per half tile: more replicas than rounds
     (100, 512, 256, 2),       # two half tiles in one row block, the second ragged
     (8192, 4096, 4096, 8),    # the shape the headline metric is quoted on
     (8192 + 37, 1024, 1024, 4),   # ragged last row half
     (4100, 512, 1088, 8),     # U = 136: a ragged second column block; ragged rows
     (4096, 1024, 4096, 2),    # U = 2048: 16 column blocks, four half tiles per workgroup with changing columns
-    (3 * 64 * 8 + 64, 768, 512 * 16, 16),   # 16 replicas in 6 rounds; XCDs with different numbers of row halves
+    (3 * 64 * 8 + 64, 1536, 512 * 16, 16),   # 16 replicas in 12 rounds; XCDs with different numbers of row halves
     (1000, 2048, 128 * 3, 1),   # one replica: k = 1
     (4224, 2048, 1024, 1),
-    (640, 256, 64 * 64, 64),  # 64 replicas, U = 64: half a column block
-    (11300, 256, 768, 2),     # three column blocks: a workgroup's half tiles change rows and columns
+    (640, 512, 64 * 64, 64),  # 64 replicas, U = 64: half a column block
+    (11300, 512, 768, 2),     # three column blocks: a workgroup's half tiles change rows and columns
 ]
 
 
+@pytest.mark.parametrize("kernel", ["default", "stream", "general"])
 @pytest.mark.parametrize("M,cin,cout,k", EXACT_STREAM)
-def test_exact_bf16_whole_row_tiles(tbn, M, cin, cout, k):
-    _exact_case(tbn, M, cin, cout, k, "bf16", tbn.TBN_FLAG_LARGE_BATCH, 11 * M + cin)
+def test_exact_bf16_whole_row_tiles(tbn, M, cin, cout, k, kernel):
+    # default: the block kernel with load waves, or the streaming kernel for small grids
+    flags = {"default": 0, "stream": tbn.TBN_FLAG_STREAM_KERNEL, "general": tbn.TBN_FLAG_BLOCK_KERNEL}[kernel]
+    _exact_case(tbn, M, cin, cout, k, "bf16", tbn.TBN_FLAG_LARGE_BATCH | flags, 11 * M + cin)
 
 
-@pytest.mark.parametrize("M,cin,cout,k", [(8192, 4096, 4096, 8), (640, 256, 64 * 64, 64), (300, 1024, 1024, 4)])
+@pytest.mark.parametrize("M,cin,cout,k", [(8192, 4096, 4096, 8), (640, 512, 64 * 64, 64), (300, 1024, 1024, 4)])
 def test_exact_bf16_default_dispatch(tbn, M, cin, cout, k):
     _exact_case(tbn, M, cin, cout, k, "bf16", 0, 13 * M + cin)
 
 
 def test_exact_bf16_relu_and_scalars(tbn):
     # powers of two as scalars keep the arithmetic exact and show that replica t is scaled by alpha[t]
-    _exact_case(tbn, 640, 1024, 1024, 8, "bf16", tbn.TBN_FLAG_LARGE_BATCH | tbn.TBN_FLAG_RELU, 5,
-                alpha_vals=[1, 2, 0.5, 4, 0.25, 8, 1, 2])
-    _exact_case(tbn, 200, 512, 768, 4, "bf16", tbn.TBN_FLAG_LARGE_BATCH | tbn.TBN_FLAG_RELU, 6,
-                alpha_vals=[2, 1, 0.5, 4])
+    for extra in (0, tbn.TBN_FLAG_STREAM_KERNEL):
+        _exact_case(tbn, 640, 1024, 1024, 8, "bf16", tbn.TBN_FLAG_LARGE_BATCH | tbn.TBN_FLAG_RELU | extra, 5,
+                    alpha_vals=[1, 2, 0.5, 4, 0.25, 8, 1, 2])
+        _exact_case(tbn, 200, 512, 768, 4, "bf16", tbn.TBN_FLAG_LARGE_BATCH | tbn.TBN_FLAG_RELU | extra, 6,
+                    alpha_vals=[2, 1, 0.5, 4])
+    # 40 x 8 = 320 blocks of 128 x 128: more than the chip has CUs, so the block kernel streams its stores
+    _exact_case(tbn, 5120, 512, 2048, 2, "bf16", tbn.TBN_FLAG_LARGE_BATCH | tbn.TBN_FLAG_RELU, 7, alpha_vals=[0.5, 2])
 
 
-# shapes that stay on the one-block-per-tile kernels: K no multiple of 256, tiles that end inside rows
+# shapes that stay on the one-block-per-tile kernels: K no multiple of 512, tiles that end inside rows
 EXACT_BLOCK = [
     (70, 8192, 80, 4),        # U = 20 distinct rows, long K
     (4224, 1000, 1024, 1),
     (2048, 3000, 3072, 9),    # tile and alpha boundaries inside rows
     (1024, 3000, 3072, 6),    # rows start at bit offsets that are no multiples of 32
     (4230, 96, 1040, 2),
+    (1600, 768, 4096, 8),     # whole rows per tile, but K = 1.5 * 512
 ]
 
 
