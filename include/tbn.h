@@ -100,6 +100,23 @@ tbn_status tbn_pack_tile(const float *w_real, const float *a_real, int64_t n, in
                          void *workspace, size_t workspace_bytes, void *stream);
 
 /*
+ * tbn_pack_tile for callers that cannot allocate device memory or hand over a workspace: code under HIP graph
+ * capture, tight serving loops, harnesses that forbid hipMalloc.  Same computation, same kernels, same results as
+ * tbn_pack_tile; the partial sums live in an array of TBN_PACK_NOALLOC_SCRATCH_BYTES bytes that is part of the
+ * library's code object (each GPU the library runs on holds it until the process ends).  The call allocates and
+ * frees nothing.
+ *
+ *   Sizes are accepted while tbn_pack_workspace_bytes(n, k, n_alpha) <= TBN_PACK_NOALLOC_SCRATCH_BYTES (the
+ *   4096 x 4096 weight with k = 8 needs half of it); beyond that TBN_ERR_UNSUPPORTED, nothing is enqueued.
+ *   All calls on one GPU share the array: calls that may overlap in time (different streams, different host
+ *   threads without ordering between their streams) race and must be serialised by the caller.
+ * Other arguments and errors as for tbn_pack_tile.
+ */
+#define TBN_PACK_NOALLOC_SCRATCH_BYTES (1u << 20)
+tbn_status tbn_pack_tile_noalloc(const float *w_real, const float *a_real, int64_t n, int32_t k,
+                                 int32_t n_alpha, uint32_t *tile_out, float *alpha_out, void *stream);
+
+/*
  * Fully-connected tiled-bit layer:  Y = X * B_hat^T  (the layer operation applied to B_hat,
  * stated after Eq. 8; Algorithm 1 is the same computation for one input vector).
  *

@@ -143,6 +143,17 @@ tbn_status tbn_pack_tile(const float *w_real, const float *a_real, int64_t n, in
                        static_cast<hipStream_t>(stream));
 }
 
+tbn_status tbn_pack_tile_noalloc(const float *w_real, const float *a_real, int64_t n, int32_t k,
+                                 int32_t n_alpha, uint32_t *tile_out, float *alpha_out, void *stream) {
+    if (!w_real || !tile_out || !alpha_out) {
+        set_error("tbn_pack_tile_noalloc: w_real, tile_out and alpha_out must not be NULL");
+        return TBN_ERR_NULL;
+    }
+    tbn_status st = check_tiling(n, k, n_alpha);
+    if (st != TBN_OK) return st;
+    return launch_pack_noalloc(w_real, a_real, n, k, n_alpha, tile_out, alpha_out, static_cast<hipStream_t>(stream));
+}
+
 tbn_status tbn_linear_forward(const void *x, void *y, tbn_dtype dt, int64_t M, int64_t in,
                               int64_t out, const uint32_t *tile, int32_t k, const float *alpha,
                               int32_t n_alpha, uint32_t flags, void *stream) {

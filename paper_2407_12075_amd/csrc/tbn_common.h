@@ -51,6 +51,8 @@ tbn_status launch_pack(const float *w, const float *a, int64_t n, int32_t k, int
                        uint32_t *tile_out, float *alpha_out, void *workspace, hipStream_t stream,
                        int64_t blk = 0, int64_t ld = 0);
 size_t pack_workspace_bytes(int64_t n, int32_t k, int32_t n_alpha);
+tbn_status launch_pack_noalloc(const float *w, const float *a, int64_t n, int32_t k, int32_t n_alpha,
+                               uint32_t *tile_out, float *alpha_out, hipStream_t stream);
 
 tbn_status launch_linear_generic(const LinearArgs &a);
 bool linear_skinny_supported(const LinearArgs &a); // small-batch (decode-shaped) matrix-core kernel

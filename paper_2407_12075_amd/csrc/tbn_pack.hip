@@ -16,6 +16,8 @@
 // layout of Eq. 1 is the case blk = p (one "row" holds the whole tile).
 #include "tbn_common.h"
 
+#include <mutex>
+
 namespace tbn {
 
 constexpr int kPackThreads = 256;
@@ -192,6 +194,54 @@ tbn_status launch_pack(const float *w, const float *a, int64_t n, int32_t k, int
     hipLaunchKernelGGL(pack_alpha_kernel, dim3(static_cast<unsigned>(n_alpha)), dim3(256), 0, stream, partial,
                        blocks * kPackWaves, k, n_alpha, p, alpha_out);
     return check_launch("tbn_pack_tile (alpha kernel)");
+}
+
+// ---- tbn_pack_tile_noalloc: the same two kernels with the partial sums in a file-scope device array ----------
+// Every GPU the library runs on holds its own copy of the array at its own address until the process ends.  In
+// host code the array's name is only a stand-in for the symbol: the device address is looked up once per device,
+// with that device current, and that pointer is what the kernels and every other use get.
+static __device__ __align__(256) unsigned char scratch[TBN_PACK_NOALLOC_SCRATCH_BYTES];
+
+static tbn_status pack_scratch_address(void **out) {
+    constexpr int kMaxDevices = 64;
+    static std::mutex mu;
+    static void *address[kMaxDevices] = {};
+    int device = 0;
+    hipError_t e = hipGetDevice(&device);
+    if (e != hipSuccess || device < 0 || device >= kMaxDevices) {
+        set_error("tbn_pack_tile_noalloc: cannot identify the current device: %s",
+                  e != hipSuccess ? hipGetErrorString(e) : "device index out of range");
+        return TBN_ERR_DEVICE;
+    }
+    std::lock_guard<std::mutex> lock(mu);
+    if (!address[device]) {
+        void *ptr = nullptr;
+        e = hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch));
+        if (e != hipSuccess || !ptr) {
+            set_error("tbn_pack_tile_noalloc: cannot resolve the scratch array on device %d: %s", device,
+                      hipGetErrorString(e));
+            return TBN_ERR_DEVICE;
+        }
+        address[device] = ptr;
+    }
+    *out = address[device];
+    return TBN_OK;
+}
+
+tbn_status launch_pack_noalloc(const float *w, const float *a, int64_t n, int32_t k, int32_t n_alpha,
+                               uint32_t *tile_out, float *alpha_out, hipStream_t stream) {
+    const size_t need = pack_workspace_bytes(n, k, n_alpha);
+    if (need > sizeof(scratch)) {
+        set_error("tbn_pack_tile_noalloc: these sizes need %zu bytes of scratch memory, the built-in array holds %zu; "
+                  "use tbn_pack_tile with a workspace", need, sizeof(scratch));
+        return TBN_ERR_UNSUPPORTED;
+    }
+    void *ptr = nullptr;
+    tbn_status st = pack_scratch_address(&ptr);
+    if (st != TBN_OK) return st;
+    // nothing in the array has to start at zero: every partial sum that the second kernel reads is written by
+    // the first one of the same call
+    return launch_pack(w, a, n, k, n_alpha, tile_out, alpha_out, ptr, stream);
 }
 
 }  // namespace tbn

@@ -53,6 +53,8 @@ def lib() -> ctypes.CDLL:
         L.tbn_pack_workspace_bytes.argtypes = [_c_i64, _c_i32, _c_i32]
         L.tbn_pack_tile.restype = ctypes.c_int
         L.tbn_pack_tile.argtypes = [_c_vp, _c_vp, _c_i64, _c_i32, _c_i32, _c_vp, _c_vp, _c_vp, _c_sz, _c_vp]
+        L.tbn_pack_tile_noalloc.restype = ctypes.c_int
+        L.tbn_pack_tile_noalloc.argtypes = [_c_vp, _c_vp, _c_i64, _c_i32, _c_i32, _c_vp, _c_vp, _c_vp]
         L.tbn_linear_forward.restype = ctypes.c_int
         L.tbn_linear_forward.argtypes = [_c_vp, _c_vp, ctypes.c_int, _c_i64, _c_i64, _c_i64, _c_vp, _c_i32, _c_vp,
                                          _c_i32, _c_u32, _c_vp]
@@ -135,6 +137,17 @@ def tbn_pack_tile(w_real: torch.Tensor, k: int, n_alpha: int = 1, a_real: Option
     if st != TBN_OK:
         _raise(st)
     return tile_out, alpha_out
+
+
+def tbn_pack_tile_noalloc(w_real: torch.Tensor, k: int, n_alpha: int, tile_out: torch.Tensor, alpha_out: torch.Tensor,
+                          a_real: Optional[torch.Tensor] = None, stream=None) -> None:
+    """tbn_pack_tile without a workspace; the outputs are the caller's (this wrapper allocates nothing either)."""
+    st = lib().tbn_pack_tile_noalloc(_dev(w_real, "w_real", torch.float32),
+                                     None if a_real is None else _dev(a_real, "a_real", torch.float32),
+                                     w_real.numel(), k, n_alpha, _dev(tile_out, "tile_out", torch.int32),
+                                     _dev(alpha_out, "alpha_out", torch.float32), _stream(stream))
+    if st != TBN_OK:
+        _raise(st)
 
 
 def tbn_linear_forward(x: torch.Tensor, tile: torch.Tensor, alpha: torch.Tensor, out_features: int, k: int,
