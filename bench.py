@@ -210,43 +210,137 @@ def measured_traffic():
         return None, None
 
 
-def time_other_configs(torch, tbn, wl, iters=30):
-    """Kernel time of the remaining layer shapes (events around back-to-back calls)."""
-    out = {}
+MFMA_F32X3_NOTE = "float32 activations run as three exact bf16 terms: algorithmic flops x 3 on the bf16 matrix pipe"
 
-    def timed(fn):
-        for _ in range(3):
-            fn()
-        torch.cuda.synchronize()
-        e0, e1 = event_pair(torch)
-        e0.record()
-        for _ in range(iters):
-            fn()
-        e1.record()
-        torch.cuda.synchronize()
-        return e0.elapsed_time(e1) * 1e3 / iters   # microseconds
+
+def _timed_us(torch, fn, iters, warm=3):
+    """Mean microseconds per call of fn(i), events around `iters` back-to-back calls on the current stream."""
+    for i in range(warm):
+        fn(i)
+    torch.cuda.synchronize()
+    e0, e1 = event_pair(torch)
+    e0.record()
+    for i in range(iters):
+        fn(i)
+    e1.record()
+    torch.cuda.synchronize()
+    return e0.elapsed_time(e1) * 1e3 / iters
+
+
+def _graph_us(torch, fn, calls=20, replays=20):
+    """Microseconds per call when `calls` calls of fn(i) are captured in one HIP graph and the graph is replayed."""
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        for i in range(3):
+            fn(i)
+    torch.cuda.current_stream().wait_stream(side)
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        for i in range(calls):
+            fn(i)
+    graph.replay()
+    torch.cuda.synchronize()
+    e0, e1 = event_pair(torch)
+    e0.record()
+    for _ in range(replays):
+        graph.replay()
+    e1.record()
+    torch.cuda.synchronize()
+    return e0.elapsed_time(e1) * 1e3 / (replays * calls)
+
+
+def measure_ceilings(torch, tbn):
+    """What the chip gives kernels that do nothing else, measured like the layer kernels: the launch floor (eager
+    and as graph replays), a streaming read and copy of 512 MiB (larger than the last-level cache), a loop of
+    nothing but bf16 MFMAs."""
+    out = {}
+    out["empty_kernel_eager_us"] = round(_timed_us(torch, lambda i: tbn.tbn_diag_empty_launch(), 200, warm=20), 3)
+    out["empty_kernel_graph_us"] = round(_graph_us(torch, lambda i: tbn.tbn_diag_empty_launch(), calls=50), 3)
+    n = 512 << 20
+    src = torch.empty(n, dtype=torch.uint8, device="cuda").fill_(1)
+    dst = torch.empty(n, dtype=torch.uint8, device="cuda")
+    us = _timed_us(torch, lambda i: tbn.tbn_diag_stream(src), 10)
+    out["stream_read_gbs"] = round(n / us / 1e3, 1)
+    us = _timed_us(torch, lambda i: tbn.tbn_diag_stream(src, dst), 10)
+    out["stream_copy_gbs"] = round(2 * n / us / 1e3, 1)   # bytes read + bytes written
+    del src, dst
+    blocks, iters = 1024, 2000
+    us = _timed_us(torch, lambda i: tbn.tbn_diag_mfma(blocks, iters), 5, warm=2)
+    out["mfma_bf16_loop_tflops"] = round(blocks * 4 * iters * 8 * 2.0 * 32 * 32 * 16 / us / 1e6, 1)
+    return out
+
+
+def _roof_fields(us, byts, alg_flop, ceil, flop_factor=1.0):
+    """Fractions of the roofs for one timing: datasheet (HBM 8 TB/s, bf16 MFMA 2.5 PFLOP/s) and measured ceilings
+    (streaming copy, MFMA-only loop).  The roof time is the larger of the memory and the matrix time."""
+    t_hbm = byts / (HBM_PEAK_GBS * 1e3)
+    t_mfma = alg_flop * flop_factor / (MFMA_BF16_PEAK_TFLOPS * 1e6)
+    t_hbm_m = byts / (ceil["stream_copy_gbs"] * 1e3)
+    t_mfma_m = alg_flop * flop_factor / (ceil["mfma_bf16_loop_tflops"] * 1e6)
+    return {"roof_us": round(max(t_hbm, t_mfma), 2), "bound": "hbm" if t_hbm >= t_mfma else "mfma",
+            "frac_of_roof": round(max(t_hbm, t_mfma) / us, 3),
+            "frac_of_measured_ceiling": round(max(t_hbm_m, t_mfma_m) / us, 3)}
+
+
+def time_other_configs(torch, tbn, wl, iters=30):
+    """Kernel time of the remaining layer shapes: warm (one buffer set, which the 256 MiB last-level cache can
+    hold) and cold (rotating buffer sets that total more than 320 MB), against the datasheet roofs and against
+    the ceilings measured in the same process; launch floor and graph replays for the launch-bound rows."""
+    import numpy as np
+    out = {}
+    ceil = measure_ceilings(torch, tbn)
+    out["ceilings"] = ceil
+    cold_target = 320e6
+
+    def linear_row(c, flags=0, label=None):
+        w, x, _ = device_inputs(c, torch, wl)
+        tile, alpha = tbn.tbn_pack_tile(w, c.k, c.n_alpha)
+        esz = x.element_size()
+        byts = (c.M * c.cin + c.M * c.cout) * esz + c.p // 8
+        U = min(c.cout, c.p // int(np.gcd(c.cin, c.p)))
+        alg_flop = 2.0 * c.M * c.cin * U
+        nsets = int(min(96, max(2, -(-cold_target // byts) + 1)))
+        xs = [x] + [x.clone() for _ in range(nsets - 1)]
+        ys = [torch.empty((c.M, c.cout), dtype=x.dtype, device="cuda") for _ in range(nsets)]
+        warm = _timed_us(torch, lambda i: tbn.tbn_linear_forward(xs[0], tile, alpha, c.cout, c.k, y=ys[0], flags=flags), iters)
+        cold = _timed_us(torch, lambda i: tbn.tbn_linear_forward(xs[i % nsets], tile, alpha, c.cout, c.k, y=ys[i % nsets], flags=flags),
+                         max(iters, nsets), warm=nsets)
+        factor = 3.0 if c.dtype == "f32" else 1.0
+        row = {"us": round(warm, 2), "cold_us": round(cold, 2), "cold_sets": nsets, "cold_set_bytes_total": int(nsets * byts),
+               "dense_equiv_tflops": round(2.0 * c.M * c.cin * c.cout / warm / 1e6, 1),
+               "alg_gbs": round(byts / warm / 1e3, 1), "alg_gbs_cold": round(byts / cold / 1e3, 1),
+               "warm": _roof_fields(warm, byts, alg_flop, ceil, factor), "cold": _roof_fields(cold, byts, alg_flop, ceil, factor)}
+        if c.M <= 64:   # launch-bound rows: against the floor, eagerly and as graph replays
+            g = _graph_us(torch, lambda i: tbn.tbn_linear_forward(xs[0], tile, alpha, c.cout, c.k, y=ys[0], flags=flags))
+            row["graph_us"] = round(g, 2)
+            row["eager_over_floor"] = round(warm / ceil["empty_kernel_eager_us"], 2)
+            row["graph_over_floor"] = round(g / ceil["empty_kernel_graph_us"], 2)
+        out[label or c.name] = row
+        ws = torch.empty(tbn.tbn_pack_workspace_bytes(c.n, c.k, c.n_alpha) + 8, dtype=torch.uint8, device="cuda")
+        if label is None:
+            nw = int(min(16, max(2, -(-cold_target // (c.n * 4)) + 1)))
+            wsets = [w] + [w.clone() for _ in range(nw - 1)]
+            us = _timed_us(torch, lambda i: tbn.tbn_pack_tile(wsets[0], c.k, c.n_alpha, tile_out=tile, alpha_out=alpha, workspace=ws), iters)
+            usc = _timed_us(torch, lambda i: tbn.tbn_pack_tile(wsets[i % nw], c.k, c.n_alpha, tile_out=tile, alpha_out=alpha, workspace=ws),
+                            max(iters, nw), warm=nw)
+            out[c.name + ":pack"] = {"us": round(us, 2), "cold_us": round(usc, 2), "alg_gbs": round(c.n * 4 / us / 1e3, 1),
+                                     "alg_gbs_cold": round(c.n * 4 / usc / 1e3, 1),
+                                     "cold_frac_of_hbm_peak": round(c.n * 4 / usc / 1e3 / HBM_PEAK_GBS, 3),
+                                     "cold_frac_of_stream_read": round(c.n * 4 / usc / 1e3 / ceil["stream_read_gbs"], 3)}
 
     lin = [wl.CFG1, *wl.CFG2, *wl.CFG4, wl.METRIC, *wl.CFG5, *wl.CFG5_MISALIGNED]
     for c in lin:
-        w, x, _ = device_inputs(c, torch, wl)
-        tile, alpha = tbn.tbn_pack_tile(w, c.k, c.n_alpha)
-        y = torch.empty((c.M, c.cout), dtype=x.dtype, device="cuda")
-        us = timed(lambda: tbn.tbn_linear_forward(x, tile, alpha, c.cout, c.k, y=y))
-        esz = x.element_size()
-        byts = (c.M * c.cin + c.M * c.cout) * esz + c.p // 8
-        out[c.name] = {"us": round(us, 2), "dense_equiv_tflops": round(2.0 * c.M * c.cin * c.cout / us / 1e6, 1),
-                       "alg_gbs": round(byts / us / 1e3, 1)}
-        ws = torch.empty(tbn.tbn_pack_workspace_bytes(c.n, c.k, c.n_alpha) + 8, dtype=torch.uint8, device="cuda")
-        us = timed(lambda: tbn.tbn_pack_tile(w, c.k, c.n_alpha, tile_out=tile, alpha_out=alpha, workspace=ws))
-        out[c.name + ":pack"] = {"us": round(us, 2), "alg_gbs": round(c.n * 4 / us / 1e3, 1)}
-        del w, x, y
+        linear_row(c)
+    out["float32_note"] = MFMA_F32X3_NOTE
     # the same layers in the column-tiled layout (fold of the k column blocks + one +-1 product on in / k inputs)
     for c in (wl.METRIC, *wl.CFG5):
         w, x, _ = device_inputs(c, torch, wl)
         tile, alpha = tbn.tbn_pack_coltile(w.view(c.cout, c.cin), c.k, c.k)
         y = torch.empty((c.M, c.cout), dtype=x.dtype, device="cuda")
         ws = torch.empty(tbn.tbn_linear_coltiled_workspace_bytes(x, c.k), dtype=torch.uint8, device="cuda")
-        us = timed(lambda: tbn.tbn_linear_coltiled_forward(x, tile, alpha, c.cout, c.k, y=y, workspace=ws))
+        us = _timed_us(torch, lambda i: tbn.tbn_linear_coltiled_forward(x, tile, alpha, c.cout, c.k, y=y, workspace=ws), iters)
         byts = (c.M * c.cin + c.M * c.cout) * x.element_size() + c.p // 8
         out[c.name + ":column_tiled"] = {"us": round(us, 2), "dense_equiv_tflops": round(2.0 * c.M * c.cin * c.cout / us / 1e6, 1),
                                          "alg_gbs": round(byts / us / 1e3, 1)}
@@ -259,8 +353,11 @@ def time_other_configs(torch, tbn, wl, iters=30):
     for M in (1, 16, 64, 128, 256, 512, 1024, 2048, 4096, 8192):
         xm = x[:M].contiguous()
         ym = torch.empty((M, c.cout), dtype=x.dtype, device="cuda")
-        sweep[str(M)] = round(timed(lambda: tbn.tbn_linear_forward(xm, tile, alpha, c.cout, c.k, y=ym)), 2)
-    out["metric_layer_batch_sweep_us"] = sweep
+        us = _timed_us(torch, lambda i: tbn.tbn_linear_forward(xm, tile, alpha, c.cout, c.k, y=ym), iters)
+        byts = (M * c.cin + M * c.cout) * 2 + c.p // 8
+        roof = max(byts / (HBM_PEAK_GBS * 1e3), 2.0 * M * c.cin * (c.p // c.cin) / (MFMA_BF16_PEAK_TFLOPS * 1e6))
+        sweep[str(M)] = {"us": round(us, 2), "roof_us": round(roof, 2)}
+    out["metric_layer_batch_sweep"] = sweep
     del w, x
     for c in (wl.CFG3, wl.CFG3_MISALIGNED):
         w = torch.from_numpy(wl.draw_w_real(c.n, c.cfg, c.layer)).cuda()
@@ -268,12 +365,20 @@ def time_other_configs(torch, tbn, wl, iters=30):
         x = torch.from_numpy(xv).cuda()
         tile, alpha = tbn.tbn_pack_tile(w, c.k, c.n_alpha)
         Ho, Wo = tbn.conv_out_hw(c.H, c.W, c.kh, c.kw, c.stride, c.pad)
-        y = torch.empty((c.N, c.O, Ho, Wo), dtype=x.dtype, device="cuda")
-        us = timed(lambda: tbn.tbn_conv2d_forward(x, tile, alpha, c.O, c.kh, c.kw, c.k, stride=c.stride, pad=c.pad, y=y))
+        byts = (x.numel() + c.N * c.O * Ho * Wo) * 4 + c.p // 8
+        nsets = int(max(2, -(-cold_target // byts) + 1))
+        xs = [x] + [x.clone() for _ in range(nsets - 1)]
+        ys = [torch.empty((c.N, c.O, Ho, Wo), dtype=x.dtype, device="cuda") for _ in range(nsets)]
+        run = lambda i: tbn.tbn_conv2d_forward(xs[i % nsets], tile, alpha, c.O, c.kh, c.kw, c.k, stride=c.stride, pad=c.pad, y=ys[i % nsets])
+        us = _timed_us(torch, lambda i: run(0), iters)
+        usc = _timed_us(torch, run, max(iters, nsets), warm=nsets)
         flop = 2.0 * c.N * Ho * Wo * c.O * c.C * c.kh * c.kw
-        byts = (x.numel() + y.numel()) * 4 + c.p // 8
-        out[c.name] = {"us": round(us, 2), "dense_equiv_tflops": round(flop / us / 1e6, 1),
-                       "alg_gbs": round(byts / us / 1e3, 1)}
+        filt = c.C * c.kh * c.kw
+        U = min(c.O, c.p // int(np.gcd(filt, c.p)))
+        alg_flop = flop * U / c.O
+        out[c.name] = {"us": round(us, 2), "cold_us": round(usc, 2), "dense_equiv_tflops": round(flop / us / 1e6, 1),
+                       "alg_gbs": round(byts / us / 1e3, 1), "warm": _roof_fields(us, byts, alg_flop, ceil, 3.0),
+                       "cold": _roof_fields(usc, byts, alg_flop, ceil, 3.0)}
     return out
 
 

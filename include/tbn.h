@@ -209,6 +209,22 @@ tbn_status tbn_linear_coltiled_forward(const void *x, void *y, tbn_dtype dt, int
                                        int32_t n_alpha, uint32_t flags, void *workspace,
                                        size_t workspace_bytes, void *stream);
 
+/*
+ * Measurement aids.  No part of the method (the paper reports no kernel timings; its Section "GPU Inference Kernel"
+ * measures memory only): they give the benchmark its denominators, measured the same way as the layer kernels.
+ *
+ *   tbn_diag_empty_launch : enqueues a kernel of one wave that does nothing (the launch floor).
+ *   tbn_diag_stream       : streams `bytes` (rounded down to 16) from src -- to dst if dst is not NULL (copy), else
+ *                           into a checksum that is dropped (read only).  DEVICE pointers, 16-byte aligned; sink may
+ *                           be NULL or 4 bytes of device memory.
+ *   tbn_diag_mfma         : `blocks` workgroups of four waves, every wave issues iters x 8 independent
+ *                           32x32x16 bf16 MFMAs (2 * 32 * 32 * 16 flop each); out is NULL or blocks * 256 floats.
+ * Errors: TBN_ERR_NULL, TBN_ERR_SHAPE, TBN_ERR_DEVICE.
+ */
+tbn_status tbn_diag_empty_launch(void *stream);
+tbn_status tbn_diag_stream(const void *src, void *dst, size_t bytes, void *sink, void *stream);
+tbn_status tbn_diag_mfma(int32_t blocks, int32_t iters, float *out, void *stream);
+
 #ifdef __cplusplus
 }
 #endif

@@ -248,6 +248,25 @@ tbn_status tbn_linear_coltiled_forward(const void *x, void *y, tbn_dtype dt, int
     return dispatch_linear(a);
 }
 
+tbn_status tbn_diag_empty_launch(void *stream) { return launch_diag_empty(static_cast<hipStream_t>(stream)); }
+
+tbn_status tbn_diag_stream(const void *src, void *dst, size_t bytes, void *sink, void *stream) {
+    if (!src || (reinterpret_cast<uintptr_t>(src) & 15u) || (reinterpret_cast<uintptr_t>(dst) & 15u)) {
+        set_error("tbn_diag_stream: src must not be NULL; src and dst must be 16-byte aligned");
+        return TBN_ERR_NULL;
+    }
+    if (bytes == 0) return TBN_OK;
+    return launch_diag_stream(src, dst, bytes, static_cast<uint32_t *>(sink), static_cast<hipStream_t>(stream));
+}
+
+tbn_status tbn_diag_mfma(int32_t blocks, int32_t iters, float *out, void *stream) {
+    if (blocks <= 0 || iters < 0 || blocks > (1 << 20)) {
+        set_error("tbn_diag_mfma: blocks must be in 1 .. 2^20, iters non-negative");
+        return TBN_ERR_SHAPE;
+    }
+    return launch_diag_mfma(blocks, iters, out, static_cast<hipStream_t>(stream));
+}
+
 tbn_status tbn_conv2d_forward(const void *x, void *y, tbn_dtype dt, int64_t N, int64_t C,
                               int64_t H, int64_t W, int64_t O, int32_t kh, int32_t kw,
                               int32_t stride_h, int32_t stride_w, int32_t pad_h, int32_t pad_w,

@@ -77,6 +77,11 @@ tbn_status launch_conv_generic_tile_ends(const ConvArgs &a);   // only the chann
 bool conv_mfma_supported(const ConvArgs &a);
 tbn_status launch_conv_mfma(const ConvArgs &a);
 
+// measurement aids (tbn_diag.hip)
+tbn_status launch_diag_empty(hipStream_t stream);
+tbn_status launch_diag_stream(const void *src, void *dst, size_t bytes, uint32_t *sink, hipStream_t stream);
+tbn_status launch_diag_mfma(int32_t blocks, int32_t iters, float *out, hipStream_t stream);
+
 // number of distinct bit rows of the (rows x row_len) weight: row o repeats row o % U
 int64_t unique_rows(int64_t rows, int64_t row_len, int64_t p);
 

@@ -71,6 +71,12 @@ def lib() -> ctypes.CDLL:
         L.tbn_linear_coltiled_forward.restype = ctypes.c_int
         L.tbn_linear_coltiled_forward.argtypes = [_c_vp, _c_vp, ctypes.c_int, _c_i64, _c_i64, _c_i64, _c_vp, _c_i32,
                                                   _c_vp, _c_i32, _c_u32, _c_vp, _c_sz, _c_vp]
+        L.tbn_diag_empty_launch.restype = ctypes.c_int
+        L.tbn_diag_empty_launch.argtypes = [_c_vp]
+        L.tbn_diag_stream.restype = ctypes.c_int
+        L.tbn_diag_stream.argtypes = [_c_vp, _c_vp, _c_sz, _c_vp, _c_vp]
+        L.tbn_diag_mfma.restype = ctypes.c_int
+        L.tbn_diag_mfma.argtypes = [_c_i32, _c_i32, _c_vp, _c_vp]
         _lib = L
     return _lib
 
@@ -238,3 +244,23 @@ def tbn_conv2d_forward(x: torch.Tensor, tile: torch.Tensor, alpha: torch.Tensor,
     if st != TBN_OK:
         _raise(st)
     return y
+
+
+def tbn_diag_empty_launch(stream=None) -> None:
+    st = lib().tbn_diag_empty_launch(_stream(stream))
+    if st != TBN_OK:
+        _raise(st)
+
+
+def tbn_diag_stream(src: torch.Tensor, dst: Optional[torch.Tensor] = None, stream=None) -> None:
+    """Streaming read of src (copy into dst if given); measurement aid."""
+    nbytes = src.numel() * src.element_size()
+    st = lib().tbn_diag_stream(_dev(src, "src"), None if dst is None else _dev(dst, "dst"), nbytes, None, _stream(stream))
+    if st != TBN_OK:
+        _raise(st)
+
+
+def tbn_diag_mfma(blocks: int, iters: int, stream=None) -> None:
+    st = lib().tbn_diag_mfma(blocks, iters, None, _stream(stream))
+    if st != TBN_OK:
+        _raise(st)
