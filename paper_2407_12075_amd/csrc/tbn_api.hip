@@ -53,6 +53,7 @@ static tbn_status check_tiling(int64_t n, int32_t k, int32_t n_alpha) {
 
 static tbn_status dispatch_linear(const LinearArgs &a) {
     if (!(a.flags & TBN_FLAG_FORCE_GENERIC)) {
+        if (!(a.flags & TBN_FLAG_LARGE_BATCH) && linear_decode_supported(a)) return launch_linear_decode(a);
         if (linear_skinny_supported(a)) return launch_linear_skinny(a);
         if (!(a.flags & TBN_FLAG_BLOCK_KERNEL)) {
             // bfloat16, tile of whole rows: 128 x 128 blocks with load waves; the streaming kernel (64-row half

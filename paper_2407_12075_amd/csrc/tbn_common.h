@@ -57,6 +57,8 @@ tbn_status launch_pack_noalloc(const float *w, const float *a, int64_t n, int32_
 tbn_status launch_linear_generic(const LinearArgs &a);
 bool linear_skinny_supported(const LinearArgs &a); // small-batch (decode-shaped) matrix-core kernel
 tbn_status launch_linear_skinny(const LinearArgs &a);
+bool linear_decode_supported(const LinearArgs &a); // at most 16 batch rows, tile of whole rows: latency-built GEMV kernel
+tbn_status launch_linear_decode(const LinearArgs &a);
 bool linear_rows_supported(const LinearArgs &a);   // wave-per-row kernel (also repairs tile-end columns)
 tbn_status launch_linear_rows(const LinearArgs &a);
 tbn_status launch_linear_rows_fixup(const LinearArgs &a);  // recompute the columns whose row holds a tile end

@@ -127,3 +127,26 @@ def test_exact_block_kernels(tbn, M, cin, cout, k, dtype):
 @pytest.mark.parametrize("M,cin,cout,k", [(1000, 2048, 384, 1), (4100, 512, 1088, 8)])
 def test_exact_f32_whole_row_tiles(tbn, M, cin, cout, k):
     _exact_case(tbn, M, cin, cout, k, "f32", tbn.TBN_FLAG_LARGE_BATCH, 19 * M + cin)
+
+
+# at most 16 batch rows and whole rows per tile: the decode kernel (default) and, with the large-batch flag, the
+# matrix-core small-batch kernel on the same data
+EXACT_DECODE = [
+    (1, 4096, 4096, 8),
+    (16, 4096, 4096, 8),
+    (3, 4096, 4096, 8),
+    (5, 264, 96, 4),          # 24 distinct rows of 264 bits: rows start at byte, not word, boundaries
+    (8, 256, 256, 4),
+    (16, 8192, 80, 4),        # 20 distinct rows: a ragged last workgroup with four rows each
+    (2, 1000, 70, 1),         # k = 1, one replica, K no multiple of 512
+    (11, 512, 3 * 1024, 3),   # 1024 distinct rows
+]
+
+
+@pytest.mark.parametrize("dtype", ["bf16", "f32"])
+@pytest.mark.parametrize("M,cin,cout,k", EXACT_DECODE)
+def test_exact_decode_shapes(tbn, M, cin, cout, k, dtype):
+    _exact_case(tbn, M, cin, cout, k, dtype, 0, 23 * M + cin)
+    _exact_case(tbn, M, cin, cout, k, dtype, tbn.TBN_FLAG_RELU, 23 * M + cin + 1,
+                alpha_vals=[2.0 ** ((i % 5) - 2) for i in range(k)])
+    _exact_case(tbn, M, cin, cout, k, dtype, tbn.TBN_FLAG_LARGE_BATCH, 23 * M + cin + 2)
