@@ -137,7 +137,7 @@ def main():
     roofline = {
         "bound": "hbm", "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
         "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": traffic, "traffic_source": traffic_src,
-        "kernel": "linear_mfma_bf16_kernel (batch 8192)", "avg_kernel_ms": round(kern_avg_ms, 5),
+        "kernel": "linear_block_bf16_kernel (batch 8192)", "avg_kernel_ms": round(kern_avg_ms, 5),
         "median_kernel_ms": round(kern_ms[len(kern_ms) // 2], 5),
         "algorithmic_bytes": alg_bytes,
         "algorithmic_tflops": round(alg_flop / (kern_avg_ms * 1e-3) / 1e12, 1),
@@ -197,7 +197,7 @@ def measured_traffic():
     documented rocprofv3 --pmc runs of this very command produced (FETCH_SIZE and WRITE_SIZE, each
     scaled by the same counter on a plain copy of known size).  None when no summary is there.
     """
-    path = os.path.join(ROOT, "profiles", "linear_mfma_bf16_metric_4096x4096_k8_hbm_traffic.txt")
+    path = os.path.join(ROOT, "profiles", "linear_block_bf16_metric_4096x4096_k8_hbm_traffic.txt")
     try:
         vals = {}
         for ln in open(path):
