@@ -18,8 +18,12 @@
  *
  * Conventions for every entry point
  *   - Pointers named below as DEVICE pointers must be device memory of the current HIP device;
- *     the caller owns every buffer.  The library keeps no state between calls and allocates
- *     no device memory.
+ *     the caller owns every buffer.  The library allocates no device memory and keeps no data
+ *     from one call for the next.  What it does keep per process: the permission of each kernel
+ *     to use more LDS than the default limit (set on the kernel's first launch, thread safe), the
+ *     last error text of each thread, and the fixed scratch array of tbn_pack_tile_noalloc.
+ *     Calls from several threads are safe; the kernels of two calls that write the same buffer
+ *     race like any two kernels.
  *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).  Work is enqueued
  *     on it and the call returns without synchronising.
  *   - On TBN_ERR_NULL / _SHAPE / _UNSUPPORTED / _WORKSPACE nothing has been enqueued and no

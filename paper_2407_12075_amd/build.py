@@ -17,6 +17,13 @@ OBJ = os.path.join(CSRC, "_build")
 LIB = os.path.join(HERE, "libtbn.so")
 
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
+# The compiler the hand-scheduled kernels were validated with.  Several kernels read LDS through inline assembly
+# and hand the destination registers to the compiler before the data has arrived; that is sound only if the
+# compiler puts nothing that touches them between a read and its wait.  asm_check.py verifies this on the
+# generated assembly; with another compiler version the check (and the GPU tests) have to be repeated before
+# these strings are changed.
+VALIDATED_HIP_VERSION = "7.2.26015"
+VALIDATED_CLANG = "roc-7.2.0 26014"
 FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-fno-gpu-rdc",
     # keep the compiler from forming packed-fp32 instructions
@@ -51,6 +58,10 @@ def build(verbose: bool = True) -> str:
     if verbose:
         print(f"built {LIB} from {len(srcs)} sources")
     return LIB
+
+
+def hipcc_version() -> str:
+    return subprocess.run([HIPCC, "--version"], capture_output=True, text=True, check=True).stdout
 
 
 if __name__ == "__main__":

@@ -417,6 +417,8 @@ __global__ __launch_bounds__((64 * waves_of(NFT)), (waves_of(NFT) == 8 ? 4 : 2))
     if (per_replica) write_all(std::true_type{}); else write_all(std::false_type{});
 }
 
+constexpr int kPlanLdsMax = 150 * 1024;   // most LDS a plan may ask for
+
 struct ConvPlan {
     bool ok;
     int rows_per_blk, PR, PC, nblk;
@@ -457,7 +459,7 @@ ConvPlan plan_conv(const ConvArgs &a) {
             const int64_t PR = (r - 1) * a.sh + a.kh, PC = (a.Wo - 1) * a.sw + a.kw;
             const int64_t vrows = PR < a.H ? PR : a.H, vcols = PC < a.W ? PC : a.W;
             const size_t lds = 2 * size_t(planes) * PR * PC * kPixStride + bits_bytes;
-            if (vrows * vcols * (kCK / 2) <= int64_t(items) && lds <= 150 * 1024) {
+            if (vrows * vcols * (kCK / 2) <= int64_t(items) && lds <= size_t(kPlanLdsMax)) {
                 pl.ok = true;
                 pl.rows_per_blk = static_cast<int>(r);
                 pl.PR = static_cast<int>(PR);
@@ -474,15 +476,13 @@ ConvPlan plan_conv(const ConvArgs &a) {
 
 template <typename XT, int T, bool RELU, int ITEMS, int NFT>
 tbn_status launch_conv_typed(const ConvArgs &a, const ConvMfmaParams &P, const ConvPlan &pl, dim3 grid) {
-    static size_t attr_bytes = 0;   // largest dynamic LDS size allowed so far for this instantiation
-    if (pl.lds > attr_bytes) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(&conv_mfma_kernel<XT, T, RELU, ITEMS, NFT>),
-                                           hipFuncAttributeMaxDynamicSharedMemorySize, static_cast<int>(pl.lds));
-        if (e != hipSuccess) {
-            set_error("tbn_conv2d_forward: cannot reserve %zu bytes of LDS: %s", pl.lds, hipGetErrorString(e));
-            return TBN_ERR_DEVICE;
-        }
-        attr_bytes = pl.lds;
+    // Dynamic LDS above the default limit has to be allowed once per kernel: the plan's upper bound, set by the
+    // thread-safe initialisation of a static.
+    static const hipError_t attr = hipFuncSetAttribute(reinterpret_cast<const void *>(&conv_mfma_kernel<XT, T, RELU, ITEMS, NFT>),
+                                                       hipFuncAttributeMaxDynamicSharedMemorySize, kPlanLdsMax);
+    if (attr != hipSuccess || pl.lds > size_t(kPlanLdsMax)) {
+        set_error("tbn_conv2d_forward: cannot reserve %zu bytes of LDS", pl.lds);
+        return TBN_ERR_DEVICE;
     }
     hipLaunchKernelGGL((conv_mfma_kernel<XT, T, RELU, ITEMS, NFT>), grid, dim3(64 * waves_of(NFT)), pl.lds, a.stream,
                        static_cast<const XT *>(a.x), static_cast<XT *>(a.y), a.tile, a.alpha, P);

@@ -16,7 +16,6 @@
 //   * a workgroup (4 waves) owns a 128 x 128 block of Z; wave (g, h) multiplies all 128 rows with
 //     column half h over the stages of K congruent to g mod 2 (128 accumulator registers); the two
 //     partial blocks are added through LDS at the end and every wave writes 64 rows x 64 columns
-//     (the bf16 kernel is written for two or four K groups; two is what the launcher builds);
 //   * bf16 activations go from global memory straight into LDS (global_load_lds_dwordx4, four stage
 //     buffers per K group, no staging registers, no LDS stores); rows are unpadded and their
 //     16-byte chunks are XOR-swizzled by choosing which chunk each lane fetches, so that the
@@ -25,9 +24,10 @@
 //     when they are written to LDS (8 + 8 + 8 significand bits; the weights are +-1, so every product
 //     is exact and the sums are float32 accumulations in the matrix pipe);
 //   * the +-1 operand never exists in memory, nor the tile bits in LDS: lanes fetch the words of
-//     their columns' cyclic tile windows (they stay in L1 / L2), and per MFMA step replicate a
-//     byte (v_perm), shift both 16-bit halves so that two neighbouring bits land on the two sign
-//     positions (v_pk_lshlrev_b16), and merge with the pattern of 1.0;
+//     their columns' cyclic tile windows (they stay in L1 / L2); the bf16 kernel turns a byte of window
+//     bits into the eight +-1 values of an MFMA operand with one read of a 256-entry table in LDS (one
+//     bit-field extract and one shift-add per operand), the float32 kernel expands the byte in registers
+//     (v_perm, a shift of both 16-bit halves, a merge with the pattern of 1.0);
 //   * the +-1 operand is the MFMA's row operand and the activations its column operand, with the
 //     operand lanes numbered so that a lane ends up with eight adjacent columns of one row of Y; the
 //     epilogue scales by alpha, turns the block round through LDS so that eight lanes hold a whole
@@ -282,9 +282,8 @@ __device__ __forceinline__ void expand_operand(uint32_t win_lo, uint32_t win_hi,
 }
 
 // Adds up the K groups' partial sums through LDS.  Accumulator index tm of group g stands for row block
-// (tm + (4/KG)*g) % 4, so every group ends up with the finished sums of its row blocks in its first
-// accumulators.  Two groups: each hands acc[2..3] to the other.  Four groups: first g and g ^ 2 trade
-// acc[2..3] (added to the partner's acc[0..1]), then g hands acc[1] to g + 1 (added to its acc[0]).
+// (tm + 2*g) % 4, so every group ends up with the finished sums of its row blocks in its first
+// accumulators: each of the two groups hands acc[2..3] to the other.
 template <int NT>
 __device__ __forceinline__ void hand_over(f32x16_t (&acc)[kTM][kTN], float *red, int from_tm, int to_wave, int wave, int lane) {
     constexpr int kSlotFloats = NT * kTN * 16 * 64;   // per wave
@@ -314,24 +313,15 @@ __device__ __forceinline__ void hand_over(f32x16_t (&acc)[kTM][kTN], float *red,
                 acc[tm][tn][4 * q + 3] += v[3];
             }
 }
-template <int KG>
 __device__ __forceinline__ void exchange_partials(f32x16_t (&acc)[kTM][kTN], unsigned char *lds_raw, int wave, int lane) {
     float *red = reinterpret_cast<float *>(lds_raw);
     __syncthreads();   // all waves are done with the staging buffers
-    if constexpr (KG == 2) {
-        hand_over<2>(acc, red, 2, wave ^ 2, wave, lane);
-    } else {
-        hand_over<2>(acc, red, 2, wave ^ 4, wave, lane);
-        __syncthreads();   // everybody has read its slot
-        hand_over<1>(acc, red, 1, (wave + 2) & 7, wave, lane);
-    }
+    hand_over<2>(acc, red, 2, wave ^ 2, wave, lane);
 }
 
-// The slot of the last hand-over that only this wave has read: free for the wave's own use afterwards
-// (16 KiB with two K groups, 8 KiB with four).
-template <int KG>
+// The slot of the hand-over that only this wave has read: 16 KiB free for the wave's own use afterwards.
 __device__ __forceinline__ float *stage_slot(unsigned char *lds_raw, int wave) {
-    constexpr int kSlotFloats = (KG == 2 ? 2 : 1) * kTN * 16 * 64;
+    constexpr int kSlotFloats = 2 * kTN * 16 * 64;
     return reinterpret_cast<float *>(lds_raw) + wave * kSlotFloats;
 }
 
@@ -478,14 +468,15 @@ namespace direct {
 constexpr int kNB = 4;                         // LDS stage buffers per K group
 constexpr int kBias = 3 * 1024;                // keeps the lane offsets non-negative, see below
 
-// The kernel exists in three forms.  Two K groups of two waves with stages of 64 elements of K (one wave per
-// SIMD, 128 KiB of LDS: one workgroup per CU) is the form for long K loops and one block per CU.  The same
-// with stages of 32 elements takes 64 KiB, so that two workgroups share a CU and the index work, pipeline
-// fill and epilogue of one hide behind the other's MFMAs: the form for short K loops and for grids of
-// several blocks per CU.  Four K groups of two waves (two waves of one workgroup per SIMD) is kept for
-// comparison.
-template <int KG, int BKP = 128 / KG>
+// The kernel exists in two forms, both with two K groups of two waves.  Stages of 64 elements of K (one wave
+// per SIMD, 128 KiB of LDS: one workgroup per CU) is the form for long K loops and one block per CU.  Stages
+// of 32 elements take 64 KiB, so that two workgroups share a CU and the index work, pipeline fill and
+// epilogue of one hide behind the other's MFMAs: the form for short K loops and for grids of several
+// blocks per CU.  (Four K groups, two waves of one workgroup per SIMD, measured about 12 % slower in the
+// main loop: the two waves of a SIMD do not alternate on the matrix pipe.)
+template <int BKP>
 struct Cfg {
+    static constexpr int KG = kKG;
     static constexpr int kThreads = KG * 128;
     static constexpr int BK = BKP;                       // K elements per stage
     static constexpr int KS = BK / 16;                   // MFMA steps per stage
@@ -508,7 +499,7 @@ struct Cfg {
     static constexpr int kLdsTotal = kLdsBytes + kTableBytes;
     static constexpr int kWavesPerSimd = kLdsBytes <= 65536 ? 2 : 1;   // asked of the compiler: registers for two resident workgroups
     static constexpr int kRot = kTM / KG;                // row blocks a group keeps at the end
-    static_assert(KG == 2 || KG == 4, "two or four K groups");
+    static_assert(KG == 2, "two K groups");
     static_assert(BK == 32 || BK == 64, "stages of 32 or 64 elements");
     static_assert(kLoads == 2 * KS, "two wave-loads per MFMA step");
     static_assert(kLdsBytes == 131072 || kLdsBytes == 65536, "LDS budget");
@@ -550,14 +541,14 @@ __device__ __forceinline__ void stage_load_one(const unsigned char *src, uint32_
     __builtin_amdgcn_global_load_lds(src + off, dst + (J >> 2) * 4096, 16, (J & 3) * 1024, 0);
 }
 
-template <int KG, int BKP, bool RELU>
-__global__ __launch_bounds__((Cfg<KG, BKP>::kThreads), (Cfg<KG, BKP>::kWavesPerSimd)) void linear_mfma_bf16_kernel(const uint16_t *__restrict__ x,
+template <int BKP, bool RELU>
+__global__ __launch_bounds__((Cfg<BKP>::kThreads), (Cfg<BKP>::kWavesPerSimd)) void linear_mfma_bf16_kernel(const uint16_t *__restrict__ x,
                                                                           uint16_t *__restrict__ y,
                                                                           const uint32_t *__restrict__ tile,
                                                                           const float *__restrict__ alpha, MfmaParams P) {
-    typedef Cfg<KG, BKP> C;
+    typedef Cfg<BKP> C;
     constexpr int BK = C::BK, KS = C::KS, WW = C::WW, kRowBytes = C::kRowBytes, kStageBytes = C::kStageBytes;
-    constexpr int kLoads = C::kLoads, kVmPerStage = C::kVmPerStage, kKG = KG;
+    constexpr int kLoads = C::kLoads, kVmPerStage = C::kVmPerStage, KG = C::KG;
     extern __shared__ __attribute__((aligned(1024))) unsigned char lds_raw[];
     const int tid = threadIdx.x;
     const int lane = tid & 63;
@@ -863,8 +854,8 @@ __global__ __launch_bounds__((Cfg<KG, BKP>::kThreads), (Cfg<KG, BKP>::kWavesPerS
     }
     static_assert(D == 3 && kNB == 4, "the wait counts are written for three stages in flight");
 
-    exchange_partials<KG>(acc, lds_raw, wave, lane);
-    write_output<uint16_t, RELU, C::kRot>(acc, P, y, alpha, m0, n0 + wn * kWN, grp, lane, stage_slot<KG>(lds_raw, wave));
+    exchange_partials(acc, lds_raw, wave, lane);
+    write_output<uint16_t, RELU, C::kRot>(acc, P, y, alpha, m0, n0 + wn * kWN, grp, lane, stage_slot(lds_raw, wave));
 }
 
 }  // namespace direct
@@ -1067,54 +1058,37 @@ __global__ __launch_bounds__(kThreads, 1) void linear_mfma_f32_kernel(const floa
         }
     }
 
-    exchange_partials<2>(acc, lds_raw, wave, lane);
-    write_output<float, RELU, kTmOut>(acc, P, y, alpha, m0, n0 + wn * kWN, grp, lane, stage_slot<2>(lds_raw, wave));
+    exchange_partials(acc, lds_raw, wave, lane);
+    write_output<float, RELU, kTmOut>(acc, P, y, alpha, m0, n0 + wn * kWN, grp, lane, stage_slot(lds_raw, wave));
 }
 
 }  // namespace ring
 
-template <typename K>
-tbn_status set_lds_limit(K kernel, int lds, bool &done) {
-    if (done) return TBN_OK;   // dynamic LDS above the default limit has to be allowed once
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kernel), hipFuncAttributeMaxDynamicSharedMemorySize, lds);
-    if (e != hipSuccess) {
-        set_error("tbn_linear_forward: cannot reserve %d bytes of LDS: %s", lds, hipGetErrorString(e));
-        return TBN_ERR_DEVICE;
-    }
-    done = true;
-    return TBN_OK;
+// Dynamic LDS above the default limit has to be allowed once per kernel.
+tbn_status set_lds_limit_once(const void *kernel, int lds) {
+    hipError_t e = hipFuncSetAttribute(kernel, hipFuncAttributeMaxDynamicSharedMemorySize, lds);
+    return e == hipSuccess ? TBN_OK : TBN_ERR_DEVICE;
 }
 
-// Forms of the bf16 kernel (see direct::Cfg).  Four K groups (two waves of one workgroup per SIMD) pass the
-// same tests but measure about 12 % slower in the main loop than two: the two waves of a SIMD do not
-// alternate on the matrix pipe.  The form with 32-element stages runs two workgroups per CU; it wins where a
-// workgroup's fixed work (index arithmetic, pipeline fill, hand-over of the partial sums, epilogue) weighs
-// against a short K loop and some CUs have more than one block to run: 8192 x 512 -> 4096 distinct columns 56 us
-// against 77, 8192 x 1024 -> 2048 42 against 55, 8192 x 1024 -> 768 (384 blocks) 21 against 26; at in = 4096 the
-// forms are within 4 % of each other, and with one block per CU the 64-element stages win (42.6 us against 45.2
-// on 8192 x 4096, 512 distinct columns).
-#ifndef TBN_BF16_GROUPS
-#define TBN_BF16_GROUPS 2
-#endif
-constexpr int kBf16Groups = TBN_BF16_GROUPS;
-#ifndef TBN_BF16_STAGE
-#define TBN_BF16_STAGE (128 / TBN_BF16_GROUPS)
-#endif
-constexpr int kBf16Stage = TBN_BF16_STAGE;
-#ifndef TBN_TWO_RESIDENT_MAX_K
-#define TBN_TWO_RESIDENT_MAX_K 3072
-#endif
-#ifndef TBN_TWO_RESIDENT_MIN_BLOCKS
-#define TBN_TWO_RESIDENT_MIN_BLOCKS 257   // more than one per CU
-#endif
+// Which form of the bf16 kernel runs (see direct::Cfg).  The form with 32-element stages runs two workgroups
+// per CU; it wins where a workgroup's fixed work (index arithmetic, pipeline fill, hand-over of the partial
+// sums, epilogue) weighs against a short K loop and some CUs have more than one block to run: 8192 x 512 ->
+// 4096 distinct columns 56 us against 77, 8192 x 1024 -> 2048 42 against 55, 8192 x 1024 -> 768 (384 blocks)
+// 21 against 26; at in = 4096 the forms are within 4 % of each other, and with one block per CU the
+// 64-element stages win (42.6 us against 45.2 on 8192 x 4096, 512 distinct columns).
+constexpr int kTwoResidentMaxK = 3072;
+constexpr int64_t kTwoResidentMinBlocks = 257;   // more than one per CU
 
-template <int KG, int BK, bool RELU>
+template <int BK, bool RELU>
 tbn_status launch_bf16(const LinearArgs &a, const MfmaParams &P, dim3 grid) {
-    typedef direct::Cfg<KG, BK> C;
-    static bool attr_set = false;
-    tbn_status st = set_lds_limit(&direct::linear_mfma_bf16_kernel<KG, BK, RELU>, C::kLdsTotal, attr_set);
-    if (st != TBN_OK) return st;
-    hipLaunchKernelGGL((direct::linear_mfma_bf16_kernel<KG, BK, RELU>), grid, dim3(C::kThreads),
+    typedef direct::Cfg<BK> C;
+    static const tbn_status attr =   // thread-safe static initialisation: set once per process
+        set_lds_limit_once(reinterpret_cast<const void *>(&direct::linear_mfma_bf16_kernel<BK, RELU>), C::kLdsTotal);
+    if (attr != TBN_OK) {
+        set_error("tbn_linear_forward: cannot reserve %d bytes of LDS", C::kLdsTotal);
+        return TBN_ERR_DEVICE;
+    }
+    hipLaunchKernelGGL((direct::linear_mfma_bf16_kernel<BK, RELU>), grid, dim3(C::kThreads),
                        C::kLdsTotal, a.stream, static_cast<const uint16_t *>(a.x),
                        static_cast<uint16_t *>(a.y), a.tile, a.alpha, P);
     return check_launch("tbn_linear_forward (matrix-core kernel)");
@@ -1122,9 +1096,12 @@ tbn_status launch_bf16(const LinearArgs &a, const MfmaParams &P, dim3 grid) {
 
 template <bool RELU>
 tbn_status launch_f32(const LinearArgs &a, const MfmaParams &P, dim3 grid) {
-    static bool attr_set = false;
-    tbn_status st = set_lds_limit(&ring::linear_mfma_f32_kernel<RELU>, ring::kLdsBytes, attr_set);
-    if (st != TBN_OK) return st;
+    static const tbn_status attr =
+        set_lds_limit_once(reinterpret_cast<const void *>(&ring::linear_mfma_f32_kernel<RELU>), ring::kLdsBytes);
+    if (attr != TBN_OK) {
+        set_error("tbn_linear_forward: cannot reserve %d bytes of LDS", ring::kLdsBytes);
+        return TBN_ERR_DEVICE;
+    }
     hipLaunchKernelGGL((ring::linear_mfma_f32_kernel<RELU>), grid, dim3(kThreads), ring::kLdsBytes, a.stream,
                        static_cast<const float *>(a.x), static_cast<float *>(a.y), a.tile, a.alpha, P);
     return check_launch("tbn_linear_forward (matrix-core kernel)");
@@ -1166,10 +1143,10 @@ tbn_status launch_linear_mfma(const LinearArgs &a) {
     tbn_status st;
     if (a.dt == TBN_F32)
         st = relu ? launch_f32<true>(a, P, grid) : launch_f32<false>(a, P, grid);
-    else if (kBf16Groups == 2 && blocks >= TBN_TWO_RESIDENT_MIN_BLOCKS && a.in <= TBN_TWO_RESIDENT_MAX_K)
-        st = relu ? launch_bf16<2, 32, true>(a, P, grid) : launch_bf16<2, 32, false>(a, P, grid);
+    else if (blocks >= kTwoResidentMinBlocks && a.in <= kTwoResidentMaxK)
+        st = relu ? launch_bf16<32, true>(a, P, grid) : launch_bf16<32, false>(a, P, grid);
     else
-        st = relu ? launch_bf16<kBf16Groups, kBf16Stage, true>(a, P, grid) : launch_bf16<kBf16Groups, kBf16Stage, false>(a, P, grid);
+        st = relu ? launch_bf16<64, true>(a, P, grid) : launch_bf16<64, false>(a, P, grid);
     if (st != TBN_OK) return st;
     // columns whose weight row straddles a tile end need two alphas
     if (a.n_alpha > 1 && !P.aligned) return launch_linear_tile_ends(a);
