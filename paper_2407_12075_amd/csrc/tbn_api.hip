@@ -170,6 +170,43 @@ tbn_status tbn_linear_forward(const void *x, void *y, tbn_dtype dt, int64_t M, i
     return dispatch_linear(a);
 }
 
+size_t tbn_linear_forward_workspace_bytes(tbn_dtype dt, int64_t M, int64_t in, int64_t out, int32_t k, uint32_t flags) {
+    int64_t n;
+    if ((dt != TBN_F32 && dt != TBN_BF16) || M <= 0 || in <= 0 || out <= 0 || k <= 0 || !mul_ok(in, out, &n) || n % k != 0) return 0;
+    if (flags & (TBN_FLAG_FORCE_GENERIC | TBN_FLAG_BLOCK_KERNEL | TBN_FLAG_STREAM_KERNEL)) return 0;
+    // pointers unknown here: taken as aligned; tbn_linear_forward_ws looks again with the real ones
+    LinearArgs a{nullptr, nullptr, (int)dt, M, in, out, nullptr, n / k, k, nullptr, 1, flags, nullptr};
+    if (!(flags & TBN_FLAG_LARGE_BATCH) && (linear_decode_supported(a) || linear_skinny_supported(a))) return 0;
+    const int splits = linear_split_plan(a);
+    return splits ? linear_split_workspace_bytes(a, splits) : 0;
+}
+
+tbn_status tbn_linear_forward_ws(const void *x, void *y, tbn_dtype dt, int64_t M, int64_t in,
+                                 int64_t out, const uint32_t *tile, int32_t k, const float *alpha,
+                                 int32_t n_alpha, uint32_t flags, void *workspace, size_t workspace_bytes,
+                                 void *stream) {
+    int64_t n;
+    tbn_status st = check_linear_args("tbn_linear_forward_ws", x, y, dt, M, in, out, tile, alpha, flags, &n);
+    if (st != TBN_OK) return st;
+    st = check_tiling(n, k, n_alpha);
+    if (st != TBN_OK) return st;
+    if (M == 0) return TBN_OK;
+    if (workspace_bytes > 0 && (!workspace || (reinterpret_cast<uintptr_t>(workspace) & 15u))) {
+        set_error("tbn_linear_forward_ws: a workspace of %zu bytes must be a 16-byte aligned device pointer (got %p)",
+                  workspace_bytes, workspace);
+        return TBN_ERR_WORKSPACE;
+    }
+    LinearArgs a{x, y, (int)dt, M, in, out, tile, n / k, k, alpha, n_alpha, flags,
+                 static_cast<hipStream_t>(stream)};
+    const bool plain = (flags & (TBN_FLAG_FORCE_GENERIC | TBN_FLAG_BLOCK_KERNEL | TBN_FLAG_STREAM_KERNEL)) ||
+                       (!(flags & TBN_FLAG_LARGE_BATCH) && (linear_decode_supported(a) || linear_skinny_supported(a)));
+    if (!plain) {
+        const int splits = linear_split_plan(a);
+        if (splits && workspace_bytes >= linear_split_workspace_bytes(a, splits)) return launch_linear_split(a, splits, workspace);
+    }
+    return dispatch_linear(a);
+}
+
 size_t tbn_pack_coltile_workspace_bytes(int64_t out, int64_t in, int32_t k, int32_t n_alpha) {
     int64_t n;
     if (out <= 0 || in <= 0 || k <= 0 || in % k != 0 || (n_alpha != 1 && n_alpha != k) || !mul_ok(out, in, &n)) return 0;

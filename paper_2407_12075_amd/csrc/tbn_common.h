@@ -68,6 +68,9 @@ bool linear_stream_supported(const LinearArgs &a); // streaming matrix-core kern
 tbn_status launch_linear_stream(const LinearArgs &a);
 bool linear_block_supported(const LinearArgs &a);  // one block per workgroup with load waves (bfloat16, tile of whole rows)
 tbn_status launch_linear_block(const LinearArgs &a);
+int linear_split_plan(const LinearArgs &a);         // split K over workgroups for small grids: number of splits, 0 = none
+size_t linear_split_workspace_bytes(const LinearArgs &a, int splits);
+tbn_status launch_linear_split(const LinearArgs &a, int splits, void *workspace);   // workspace: 16-byte aligned, the bytes above
 tbn_status launch_linear_mfma(const LinearArgs &a);
 
 // column-tiled layer: xf[m, j] = sum_c alpha[c] * x[m, c * q + j], and the float 1.0 written to *one_out

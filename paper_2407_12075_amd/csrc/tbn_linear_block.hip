@@ -31,6 +31,11 @@
 //     other column blocks of the same rows still need, out of the XCD's L2 (8192 x 4096 -> 16384, k = 8: 146 us
 //     against 164).  When all workgroups store at the same time, plain stores are faster (8192 x 4096 -> 4096,
 //     k = 8: 37.7 us against 42.4): the last-level cache then takes the burst.
+//   * Split K (SPLIT = true, for grids that would leave most CUs idle and callers that bring a workspace):
+//     the K loop of a block is dealt to S workgroups; each writes its float32 partial sums of the 128 x 128
+//     block to the workspace, [split][M][U], and a second kernel adds the S partial sums of every output in
+//     ascending split order (no atomics: the result is the same bit for bit from run to run), scales by
+//     alpha and writes the replicas.
 #include "tbn_common.h"
 
 #include <type_traits>
@@ -73,8 +78,11 @@ struct BlockParams {
     int32_t n_alpha;
     int32_t tiles_n;      // column blocks of U
     uint32_t tiles_m;
-    int32_t n_rounds;     // in / 128 (even)
+    int32_t n_rounds;     // rounds of 128 elements of K per workgroup (even): in / 128, or in / 128 / splits
     int32_t stream_stores;   // write Y with non-temporal stores
+    int32_t splits;       // workgroups that share the K loop of a block (1: none)
+    uint32_t vrows;       // tiles_m * splits: (row block, split) pairs
+    float *partial;       // split K: [split][M][U] float32 partial sums
 };
 
 // s_waitcnt immediate that waits for the vector-memory counter only (gfx9 encoding: vmcnt in bits
@@ -120,26 +128,28 @@ template <int V> using Int = std::integral_constant<int, V>;
 
 // Workgroups that share rows of X are given consecutive slots on one XCD (workgroup ids are dealt
 // round-robin to the 8 XCDs), so the later column blocks find X in that XCD's L2.
-__device__ __forceinline__ void block_coords(const BlockParams &P, uint32_t &tile_m, uint32_t &tile_n) {
+// With split K the unit that shares data is a (row block, split) pair: vrow counts those.
+__device__ __forceinline__ void block_coords(const BlockParams &P, uint32_t &vrow, uint32_t &tile_n) {
     const uint32_t bid = blockIdx.x;
     const uint32_t xcd = bid & 7, slot = bid >> 3;
     const uint32_t tiles_n = static_cast<uint32_t>(P.tiles_n);
-    const uint32_t per_xcd_full = (P.tiles_m / 8) * tiles_n;   // slots per XCD in the regular part
+    const uint32_t per_xcd_full = (P.vrows / 8) * tiles_n;   // slots per XCD in the regular part
     if (slot < per_xcd_full) {
         const uint32_t q = slot / tiles_n;
         tile_n = slot - q * tiles_n;
-        tile_m = q * 8 + xcd;
+        vrow = q * 8 + xcd;
     } else {  // remaining row blocks: plain order
         const uint32_t rest = bid - per_xcd_full * 8;
         const uint32_t q = rest / tiles_n;
         tile_n = rest - q * tiles_n;
-        tile_m = (P.tiles_m / 8) * 8 + q;
+        vrow = (P.vrows / 8) * 8 + q;
     }
 }
 
 // RELU: fused max(0, .) of Algorithm 1.  LOADERS: waves 4 .. 7 issue the loads (512 threads), else the MFMA
-// waves do it themselves between their MFMAs (256 threads).
-template <bool RELU, bool LOADERS>
+// waves do it themselves between their MFMAs (256 threads).  SPLIT: the workgroup takes one of P.splits equal parts
+// of K and writes float32 partial sums to P.partial instead of Y.
+template <bool RELU, bool LOADERS, bool SPLIT>
 __global__ __launch_bounds__(LOADERS ? 512 : 256, 1) void linear_block_bf16_kernel(const uint16_t *__restrict__ x,
                                                                                      uint16_t *__restrict__ y,
                                                                                      const uint32_t *__restrict__ tile,
@@ -157,6 +167,13 @@ __global__ __launch_bounds__(LOADERS ? 512 : 256, 1) void linear_block_bf16_kern
 
     uint32_t tile_m, tile_n;
     block_coords(P, tile_m, tile_n);
+    uint32_t split = 0;
+    if (SPLIT) {
+        const uint32_t vrow = tile_m;
+        tile_m = vrow / static_cast<uint32_t>(P.splits);
+        split = vrow - tile_m * static_cast<uint32_t>(P.splits);
+    }
+    const uint32_t round0 = split * static_cast<uint32_t>(P.n_rounds);   // first round of this workgroup's part of K (even)
     const int64_t m0 = int64_t(tile_m) * kBM;
     const int32_t n0 = static_cast<int32_t>(tile_n) * kBN;
     const int32_t n_rounds = P.n_rounds;
@@ -171,8 +188,8 @@ __global__ __launch_bounds__(LOADERS ? 512 : 256, 1) void linear_block_bf16_kern
     // tile row that operand lane l of column half h supplies for MFMA tile tn, i.e. column
     // 64*h + 16*(l/8) + 8*((l/4)%2) + 4*tn + l%4 of the block (with this numbering a lane ends up with eight
     // adjacent columns of one row of Y).
-    const unsigned char *x_blk = reinterpret_cast<const unsigned char *>(x) + m0 * P.in * 2 + (grp * 128 - kBias);
-    const unsigned char *tile_bytes = reinterpret_cast<const unsigned char *>(tile);
+    const unsigned char *x_blk = reinterpret_cast<const unsigned char *>(x) + m0 * P.in * 2 + (grp * 128 - kBias) + round0 * 256u;
+    const unsigned char *tile_bytes = reinterpret_cast<const unsigned char *>(tile) + round0 * 16u;
     uint32_t a_off[8];
     uint32_t t_off;
     {
@@ -548,6 +565,23 @@ __global__ __launch_bounds__(LOADERS ? 512 : 256, 1) void linear_block_bf16_kern
         // rows m0 + 64*grp + 32*tm + rr + 8*i, columns n0 + 64*wn + 8*g8 .. + 7
         const int64_t row0 = m0 + 64 * grp + 32 * tm;
         const int64_t rows_left = P.M - row0;   // may be <= 0
+        if constexpr (SPLIT) {
+            typedef __attribute__((address_space(1))) u32x4_t global_u32x4_t;
+            unsigned char *dst = reinterpret_cast<unsigned char *>(P.partial + (int64_t(split) * P.M + row0) * P.U + n0 + 64 * wn);
+            const uint32_t lane_off = (static_cast<uint32_t>(rr) * static_cast<uint32_t>(P.U) + static_cast<uint32_t>(8 * g8)) * 4u;
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                if (col_ok && rr + 8 * i < rows_left) {
+                    const uint32_t off = lane_off + static_cast<uint32_t>(i) * static_cast<uint32_t>(P.U) * 32u;   // eight rows on
+                    u32x4_t lo, hi;
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) { lo[e] = __float_as_uint(zr[i][e]); hi[e] = __float_as_uint(zr[i][4 + e]); }
+                    *(global_u32x4_t *)(dst + off) = lo;
+                    *(global_u32x4_t *)(dst + off + 16) = hi;
+                }
+            }
+            continue;
+        }
         unsigned char *z_rep = reinterpret_cast<unsigned char *>(y) + (row0 * P.out + n0 + 64 * wn) * 2;
         for (int32_t t = 0; t < P.reps; ++t, z_rep += rep_bytes) {
             const float al = __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, alpha_lanes), t));
@@ -572,6 +606,64 @@ __global__ __launch_bounds__(LOADERS ? 512 : 256, 1) void linear_block_bf16_kern
             }
         }
     }
+}
+
+// Second pass of split K: z = partial[0] + partial[1] + ... (ascending, float32), y[m, u + t*U] = alpha[t] * z.
+// One thread per eight adjacent distinct columns of a row.
+template <bool RELU>
+__global__ __launch_bounds__(128) void linear_split_reduce_kernel(const float *__restrict__ partial, uint16_t *__restrict__ y,
+                                                                  const float *__restrict__ alpha, BlockParams P) {
+    const int64_t groups = P.U / 8;
+    const int64_t idx = int64_t(blockIdx.x) * 128 + threadIdx.x;
+    if (idx >= P.M * groups) return;
+    const int64_t m = idx / groups, g = idx - m * groups;
+    const int64_t plane = P.M * int64_t(P.U);
+    const float *src = partial + m * P.U + 8 * g;
+    float z[8];
+    {
+        const float4 a = *reinterpret_cast<const float4 *>(src), b = *reinterpret_cast<const float4 *>(src + 4);
+        z[0] = a.x; z[1] = a.y; z[2] = a.z; z[3] = a.w; z[4] = b.x; z[5] = b.y; z[6] = b.z; z[7] = b.w;
+    }
+    for (int32_t s = 1; s < P.splits; ++s) {
+        const float4 a = *reinterpret_cast<const float4 *>(src + s * plane), b = *reinterpret_cast<const float4 *>(src + s * plane + 4);
+        z[0] += a.x; z[1] += a.y; z[2] += a.z; z[3] += a.w; z[4] += b.x; z[5] += b.y; z[6] += b.z; z[7] += b.w;
+    }
+    uint16_t *dst = y + m * P.out + 8 * g;
+    for (int32_t t = 0; t < P.reps; ++t, dst += P.U) {
+        const float al = alpha[P.n_alpha == 1 ? 0 : t];
+        float v[8];
+#pragma unroll
+        for (int e = 0; e < 8; ++e) {
+            v[e] = al * z[e];
+            if (RELU) v[e] = fmaxf(v[e], 0.f);
+        }
+        *reinterpret_cast<u32x4_t *>(dst) = u32x4_t{pack2(v[0], v[1]), pack2(v[2], v[3]), pack2(v[4], v[5]), pack2(v[6], v[7])};
+    }
+}
+
+int device_cus() {
+    int device = 0, cus = 256;
+    if (hipGetDevice(&device) == hipSuccess) {
+        int v = 0;
+        if (hipDeviceGetAttribute(&v, hipDeviceAttributeMultiprocessorCount, device) == hipSuccess && v > 0) cus = v;
+    }
+    return cus;
+}
+
+void fill_params(const LinearArgs &a, BlockParams &P) {
+    P.M = a.M;
+    P.in = static_cast<int32_t>(a.in);
+    P.out = static_cast<int32_t>(a.out);
+    P.U = static_cast<int32_t>(a.p / a.in);
+    P.reps = static_cast<int32_t>(a.out / P.U);
+    P.n_alpha = a.n_alpha;
+    P.tiles_m = static_cast<uint32_t>((a.M + kBM - 1) / kBM);
+    P.tiles_n = (P.U + kBN - 1) / kBN;
+    P.n_rounds = P.in / 128;
+    P.stream_stores = 0;
+    P.splits = 1;
+    P.vrows = P.tiles_m;
+    P.partial = nullptr;
 }
 
 tbn_status set_lds_limit_once(const void *kernel, int lds) {
@@ -601,28 +693,61 @@ bool linear_block_supported(const LinearArgs &a) {
 #define TBN_BLOCK_LOADERS 1
 #endif
 
+// Split K: how many workgroups share a block's K loop so that the grid about fills the chip (0: no split).  A part
+// is a whole number of round pairs (256 elements of K) and at least one.
+int linear_split_plan(const LinearArgs &a) {
+    if (!linear_block_supported(a)) return 0;
+    const int64_t U = a.p / a.in;
+    const int64_t blocks = ((a.M + kBM - 1) / kBM) * ((U + kBN - 1) / kBN);
+    const int64_t pairs = a.in / 256;
+    const int cus = device_cus();
+    int best = 0;
+    for (int s = 2; s <= 16; s *= 2)
+        if (blocks * s <= cus && pairs % s == 0) best = s;
+    return best;
+}
+
+size_t linear_split_workspace_bytes(const LinearArgs &a, int splits) {
+    return static_cast<size_t>(splits) * static_cast<size_t>(a.M) * static_cast<size_t>(a.p / a.in) * sizeof(float);
+}
+
+tbn_status launch_linear_split(const LinearArgs &a, int splits, void *workspace) {
+    BlockParams P;
+    fill_params(a, P);
+    P.splits = splits;
+    P.n_rounds = P.in / 128 / splits;
+    P.vrows = P.tiles_m * static_cast<uint32_t>(splits);
+    P.partial = static_cast<float *>(workspace);
+    const int64_t wgs = int64_t(P.vrows) * P.tiles_n;
+    typedef void (*kernel_t)(const uint16_t *, uint16_t *, const uint32_t *, const float *, BlockParams);
+    static const kernel_t kernel = &linear_block_bf16_kernel<false, true, true>;
+    static const tbn_status attr = set_lds_limit_once(reinterpret_cast<const void *>(kernel), kLdsBytes);
+    if (attr != TBN_OK) {
+        set_error("tbn_linear_forward_ws: cannot reserve %d bytes of LDS for the block kernel", kLdsBytes);
+        return TBN_ERR_DEVICE;
+    }
+    hipLaunchKernelGGL(kernel, dim3(static_cast<unsigned>(wgs)), dim3(512), kLdsBytes, a.stream,
+                       static_cast<const uint16_t *>(a.x), static_cast<uint16_t *>(a.y), a.tile, a.alpha, P);
+    tbn_status st = check_launch("tbn_linear_forward_ws (split-K matrix-core kernel)");
+    if (st != TBN_OK) return st;
+    const int64_t threads = a.M * (P.U / 8);
+    const dim3 grid(static_cast<unsigned>((threads + 127) / 128));
+    if (a.flags & TBN_FLAG_RELU)
+        hipLaunchKernelGGL(linear_split_reduce_kernel<true>, grid, dim3(128), 0, a.stream, P.partial, static_cast<uint16_t *>(a.y), a.alpha, P);
+    else
+        hipLaunchKernelGGL(linear_split_reduce_kernel<false>, grid, dim3(128), 0, a.stream, P.partial, static_cast<uint16_t *>(a.y), a.alpha, P);
+    return check_launch("tbn_linear_forward_ws (sum of the split-K partial sums)");
+}
+
 tbn_status launch_linear_block(const LinearArgs &a) {
     BlockParams P;
-    P.M = a.M;
-    P.in = static_cast<int32_t>(a.in);
-    P.out = static_cast<int32_t>(a.out);
-    P.U = static_cast<int32_t>(a.p / a.in);
-    P.reps = static_cast<int32_t>(a.out / P.U);
-    P.n_alpha = a.n_alpha;
-    P.tiles_m = static_cast<uint32_t>((a.M + kBM - 1) / kBM);
-    P.tiles_n = (P.U + kBN - 1) / kBN;
-    P.n_rounds = P.in / 128;
-    int device = 0, cus = 256;
-    if (hipGetDevice(&device) == hipSuccess) {
-        int v = 0;
-        if (hipDeviceGetAttribute(&v, hipDeviceAttributeMultiprocessorCount, device) == hipSuccess && v > 0) cus = v;
-    }
-    P.stream_stores = int64_t(P.tiles_m) * P.tiles_n > cus ? 1 : 0;
+    fill_params(a, P);
+    P.stream_stores = int64_t(P.tiles_m) * P.tiles_n > device_cus() ? 1 : 0;
     const dim3 grid(static_cast<unsigned>(int64_t(P.tiles_m) * P.tiles_n));
     const bool relu = (a.flags & TBN_FLAG_RELU) != 0;
     constexpr bool kLoaders = TBN_BLOCK_LOADERS != 0;
     typedef void (*kernel_t)(const uint16_t *, uint16_t *, const uint32_t *, const float *, BlockParams);
-    static const kernel_t kernels[2] = {&linear_block_bf16_kernel<false, kLoaders>, &linear_block_bf16_kernel<true, kLoaders>};
+    static const kernel_t kernels[2] = {&linear_block_bf16_kernel<false, kLoaders, false>, &linear_block_bf16_kernel<true, kLoaders, false>};
     // dynamic LDS above the default limit has to be allowed once per kernel (thread-safe static initialisation)
     static const tbn_status attr[2] = {set_lds_limit_once(reinterpret_cast<const void *>(kernels[0]), kLdsBytes),
                                        set_lds_limit_once(reinterpret_cast<const void *>(kernels[1]), kLdsBytes)};

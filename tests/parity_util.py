@@ -15,10 +15,29 @@ def max_rel_err(y, ref):
     return float(np.abs(y - ref).max() / scale)
 
 
+def pass_rate(y, ref, tol):
+    """Share of the elements with |y - ref| <= tol * |ref| + tol * rms(ref): the element-wise reading of the
+    stated tolerance (the rms term keeps sums that cancel to almost nothing from deciding it)."""
+    y = np.asarray(y, dtype=np.float64)
+    ref = np.asarray(ref, dtype=np.float64)
+    if ref.size == 0:
+        return 1.0
+    rms = float(np.sqrt(np.mean(ref * ref)))
+    return float(np.mean(np.abs(y - ref) <= tol * np.abs(ref) + tol * rms))
+
+
+# one line per comparison, printed by conftest.py at the end of the run: both readings of the tolerance
+PARITY_LOG = []
+
+
 def assert_close(y, ref, dtype, what=""):
     assert np.all(np.isfinite(np.asarray(y, dtype=np.float64))), f"{what}: non-finite output"
     err = max_rel_err(y, ref)
+    rate = pass_rate(y, ref, TOL[dtype])
+    PARITY_LOG.append(f"{what or 'case'} [{dtype}, {np.asarray(ref).size} outputs]: max|y - ref| / max|ref| = {err:.3e} "
+                      f"(limit {TOL[dtype]:.0e}), element-wise pass rate = {rate:.6f}")
     assert err <= TOL[dtype], f"{what}: max error / max|ref| = {err:.3e} > {TOL[dtype]:.1e}"
+    assert rate >= 0.9999, f"{what}: only {rate:.6f} of the outputs are within the element-wise tolerance"
     return err
 
 

@@ -277,9 +277,7 @@ def _linear_full(tbn, c, samples=4096, full=False):
     rows, cols = sample_linear(c.M, c.cout, c.cin, c.p, samples, seed=c.cfg * 31 + c.k)
     ref = orc.linear_forward_at(x, tile_ref, alpha_ref, c.cout, c.k, rows, cols)
     # scale the error by a magnitude typical of the whole output, estimated from the samples
-    err = float(np.abs(yh[rows, cols] - ref).max() / np.abs(ref).max())
-    assert err <= TOL[c.dtype], f"{c.name}: sampled max error / max|ref| = {err:.3e}"
-    return err
+    return assert_close(yh[rows, cols], ref, c.dtype, f"{c.name} ({len(rows)} sampled outputs)")
 
 
 @pytest.mark.parametrize("c", wl.CFG2, ids=lambda c: c.name)
@@ -293,7 +291,8 @@ def test_config4_decode(tbn, c):
 
 
 def test_metric_shape_b8192(tbn):
-    _linear_full(tbn, wl.METRIC)
+    # every one of the 8192 x 4096 outputs against the oracle (a few seconds of CPU time)
+    _linear_full(tbn, wl.METRIC, full=True)
 
 
 @pytest.mark.parametrize("c", wl.CFG5 + wl.CFG5_MISALIGNED, ids=lambda c: c.name)
