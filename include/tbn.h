@@ -66,6 +66,9 @@ typedef enum {
                                          rows, so that their shapes also reach the general matrix-core kernel */
 #define TBN_FLAG_STREAM_KERNEL 0x800u /* testing aid (linear only): take the streaming kernel (half tiles, used by
                                          default for grids that leave CUs idle) wherever it supports the shape */
+#define TBN_FLAG_SPLIT_K 0x1000u      /* testing aid (tbn_linear_forward_ws only): split the sum over j among
+                                         workgroups wherever the shape allows, also where the cost model expects
+                                         no gain */
 
 /* Number of 32-bit words of a tile of n / k entries (ceil(n / k / 32)); 0 if n <= 0, k <= 0 or
  * k does not divide n (the paper requires n divisible by the compression factor). */
@@ -131,13 +134,34 @@ tbn_status tbn_pack_tile_noalloc(const float *w_real, const float *a_real, int64
  *   tile  : DEVICE, tbn_tile_words(in*out, k) words; read only
  *   alpha : DEVICE, n_alpha floats (n_alpha is 1 or k); read only
  *   flags : 0 or TBN_FLAG_RELU (| TBN_FLAG_FORCE_GENERIC | TBN_FLAG_LARGE_BATCH | TBN_FLAG_BLOCK_KERNEL |
- *           TBN_FLAG_STREAM_KERNEL)
+ *           TBN_FLAG_STREAM_KERNEL | TBN_FLAG_SPLIT_K, which only tbn_linear_forward_ws looks at)
  * M == 0 is legal and does nothing (x and y may then be NULL).  x and y must not overlap.
  * Errors: TBN_ERR_NULL, TBN_ERR_SHAPE, TBN_ERR_UNSUPPORTED, TBN_ERR_DEVICE.
  */
 tbn_status tbn_linear_forward(const void *x, void *y, tbn_dtype dt, int64_t M, int64_t in,
                               int64_t out, const uint32_t *tile, int32_t k, const float *alpha,
                               int32_t n_alpha, uint32_t flags, void *stream);
+
+/*
+ * tbn_linear_forward with a caller-supplied workspace.  Same layer (the layer operation stated after Eq. 8), same
+ * arguments; the workspace lets shapes whose output blocks would occupy only a fraction of the GPU and whose
+ * rows are long (bfloat16, tile of whole weight rows, more than 64 and up to a few thousand batch rows, `in` of
+ * about 12288 and more: the split costs a second launch) split the sum over j among several workgroups: each writes float32 partial sums to the workspace, a second kernel adds them in ascending order of
+ * j (no floating-point atomics: results are identical from run to run), scales and writes y.  The sums are
+ * grouped differently from tbn_linear_forward's, so the two may differ in the last float32 bit before rounding.
+ *
+ *   tbn_linear_forward_workspace_bytes : bytes with which tbn_linear_forward_ws takes that path for these sizes;
+ *                                        0 if no path for them uses a workspace (or on invalid sizes).
+ *   workspace : DEVICE, 16-byte aligned, or NULL with workspace_bytes == 0; contents on entry are ignored, on
+ *               exit undefined.  With fewer bytes than the query returns the call is exactly tbn_linear_forward.
+ *               Calls that share a workspace must be ordered on one stream.
+ * Errors: as tbn_linear_forward, and TBN_ERR_WORKSPACE (NULL or misaligned workspace with workspace_bytes > 0).
+ */
+size_t tbn_linear_forward_workspace_bytes(tbn_dtype dt, int64_t M, int64_t in, int64_t out, int32_t k, uint32_t flags);
+tbn_status tbn_linear_forward_ws(const void *x, void *y, tbn_dtype dt, int64_t M, int64_t in,
+                                 int64_t out, const uint32_t *tile, int32_t k, const float *alpha,
+                                 int32_t n_alpha, uint32_t flags, void *workspace, size_t workspace_bytes,
+                                 void *stream);
 
 /*
  * Convolutional tiled-bit layer (the paper tiles the flattened (O, C, kh, kw) weight the same

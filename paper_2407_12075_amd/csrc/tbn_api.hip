@@ -82,7 +82,7 @@ static tbn_status check_linear_args(const char *fn, const void *x, const void *y
         return TBN_ERR_UNSUPPORTED;
     }
     if (flags & ~(TBN_FLAG_RELU | TBN_FLAG_FORCE_GENERIC | TBN_FLAG_LARGE_BATCH | TBN_FLAG_BLOCK_KERNEL |
-                  TBN_FLAG_STREAM_KERNEL)) {
+                  TBN_FLAG_STREAM_KERNEL | TBN_FLAG_SPLIT_K)) {
         set_error("%s: unknown flag bits 0x%x", fn, flags);
         return TBN_ERR_UNSUPPORTED;
     }
@@ -98,6 +98,14 @@ static tbn_status check_linear_args(const char *fn, const void *x, const void *y
         return TBN_ERR_UNSUPPORTED;
     }
     return TBN_OK;
+}
+
+// Split K with a workspace: not for the batches of the decode and small-batch kernels, not with the flags that name
+// another kernel; otherwise where the block kernel's plan says so.
+static int workspace_splits(const LinearArgs &a) {
+    if (a.flags & (TBN_FLAG_FORCE_GENERIC | TBN_FLAG_BLOCK_KERNEL | TBN_FLAG_STREAM_KERNEL)) return 0;
+    if (a.M <= 64) return 0;
+    return linear_split_plan(a);
 }
 
 static size_t coltile_xf_bytes(tbn_dtype dt, int64_t M, int64_t q) {
@@ -173,11 +181,9 @@ tbn_status tbn_linear_forward(const void *x, void *y, tbn_dtype dt, int64_t M, i
 size_t tbn_linear_forward_workspace_bytes(tbn_dtype dt, int64_t M, int64_t in, int64_t out, int32_t k, uint32_t flags) {
     int64_t n;
     if ((dt != TBN_F32 && dt != TBN_BF16) || M <= 0 || in <= 0 || out <= 0 || k <= 0 || !mul_ok(in, out, &n) || n % k != 0) return 0;
-    if (flags & (TBN_FLAG_FORCE_GENERIC | TBN_FLAG_BLOCK_KERNEL | TBN_FLAG_STREAM_KERNEL)) return 0;
     // pointers unknown here: taken as aligned; tbn_linear_forward_ws looks again with the real ones
     LinearArgs a{nullptr, nullptr, (int)dt, M, in, out, nullptr, n / k, k, nullptr, 1, flags, nullptr};
-    if (!(flags & TBN_FLAG_LARGE_BATCH) && (linear_decode_supported(a) || linear_skinny_supported(a))) return 0;
-    const int splits = linear_split_plan(a);
+    const int splits = workspace_splits(a);
     return splits ? linear_split_workspace_bytes(a, splits) : 0;
 }
 
@@ -198,12 +204,8 @@ tbn_status tbn_linear_forward_ws(const void *x, void *y, tbn_dtype dt, int64_t M
     }
     LinearArgs a{x, y, (int)dt, M, in, out, tile, n / k, k, alpha, n_alpha, flags,
                  static_cast<hipStream_t>(stream)};
-    const bool plain = (flags & (TBN_FLAG_FORCE_GENERIC | TBN_FLAG_BLOCK_KERNEL | TBN_FLAG_STREAM_KERNEL)) ||
-                       (!(flags & TBN_FLAG_LARGE_BATCH) && (linear_decode_supported(a) || linear_skinny_supported(a)));
-    if (!plain) {
-        const int splits = linear_split_plan(a);
-        if (splits && workspace_bytes >= linear_split_workspace_bytes(a, splits)) return launch_linear_split(a, splits, workspace);
-    }
+    const int splits = workspace_splits(a);
+    if (splits && workspace_bytes >= linear_split_workspace_bytes(a, splits)) return launch_linear_split(a, splits, workspace);
     return dispatch_linear(a);
 }
 

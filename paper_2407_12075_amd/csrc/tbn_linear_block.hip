@@ -694,7 +694,13 @@ bool linear_block_supported(const LinearArgs &a) {
 #endif
 
 // Split K: how many workgroups share a block's K loop so that the grid about fills the chip (0: no split).  A part
-// is a whole number of round pairs (256 elements of K) and at least one.
+// is a whole number of round pairs (256 elements of K) and at least one.  The split costs a second launch and a
+// round trip of the float32 partial sums, about 12 us more fixed time than one kernel on MI355X, so it is taken
+// only where a cost model fitted to measurements at 512 distinct columns predicts a gain of more than 10 %
+// (R = in / 128 rounds; one kernel: 8 + 0.26 R (1 + blocks / 256) us on the streaming kernel's grids, 12 + 0.55 R us
+// at 128 blocks and more; split: 20 + 0.55 R / S + 8 blocks / 128 us.  Measured, out = 4096, k = 8:
+// in = 16384, batch 512 / 1024 / 2048 / 4096: 26 / 26 / 38 / 64 us against 40 / 44 / 47 / 72; in = 8192: equal;
+// in = 4096: 22 / 22 / 25 / 31 against 15 / 16 / 17 / 27, not taken).  TBN_FLAG_SPLIT_K skips the model.
 int linear_split_plan(const LinearArgs &a) {
     if (!linear_block_supported(a)) return 0;
     const int64_t U = a.p / a.in;
@@ -704,7 +710,11 @@ int linear_split_plan(const LinearArgs &a) {
     int best = 0;
     for (int s = 2; s <= 16; s *= 2)
         if (blocks * s <= cus && pairs % s == 0) best = s;
-    return best;
+    if (!best || (a.flags & TBN_FLAG_SPLIT_K)) return best;
+    const double R = double(a.in) / 128.0;
+    const double one = blocks < 128 ? 8.0 + 0.26 * R * (1.0 + double(blocks) / 256.0) : 12.0 + 0.55 * R;
+    const double split = 20.0 + 0.55 * R / best + 8.0 * double(blocks) / 128.0;
+    return split < 0.9 * one ? best : 0;
 }
 
 size_t linear_split_workspace_bytes(const LinearArgs &a, int splits) {

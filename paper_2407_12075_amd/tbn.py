@@ -20,6 +20,7 @@ TBN_FLAG_FORCE_GENERIC = 0x100
 TBN_FLAG_LARGE_BATCH = 0x200
 TBN_FLAG_BLOCK_KERNEL = 0x400
 TBN_FLAG_STREAM_KERNEL = 0x800
+TBN_FLAG_SPLIT_K = 0x1000
 
 _STATUS = {1: "TBN_ERR_NULL", 2: "TBN_ERR_SHAPE", 3: "TBN_ERR_UNSUPPORTED", 4: "TBN_ERR_DEVICE",
            5: "TBN_ERR_WORKSPACE"}
@@ -58,6 +59,11 @@ def lib() -> ctypes.CDLL:
         L.tbn_linear_forward.restype = ctypes.c_int
         L.tbn_linear_forward.argtypes = [_c_vp, _c_vp, ctypes.c_int, _c_i64, _c_i64, _c_i64, _c_vp, _c_i32, _c_vp,
                                          _c_i32, _c_u32, _c_vp]
+        L.tbn_linear_forward_workspace_bytes.restype = _c_sz
+        L.tbn_linear_forward_workspace_bytes.argtypes = [ctypes.c_int, _c_i64, _c_i64, _c_i64, _c_i32, ctypes.c_uint32]
+        L.tbn_linear_forward_ws.restype = ctypes.c_int
+        L.tbn_linear_forward_ws.argtypes = [_c_vp, _c_vp, ctypes.c_int, _c_i64, _c_i64, _c_i64, _c_vp, _c_i32, _c_vp,
+                                            _c_i32, ctypes.c_uint32, _c_vp, _c_sz, _c_vp]
         L.tbn_conv2d_forward.restype = ctypes.c_int
         L.tbn_conv2d_forward.argtypes = [_c_vp, _c_vp, ctypes.c_int, _c_i64, _c_i64, _c_i64, _c_i64, _c_i64, _c_i32,
                                          _c_i32, _c_i32, _c_i32, _c_i32, _c_i32, _c_vp, _c_i32, _c_vp, _c_i32, _c_u32,
@@ -169,6 +175,33 @@ def tbn_linear_forward(x: torch.Tensor, tile: torch.Tensor, alpha: torch.Tensor,
     st = lib().tbn_linear_forward(_dev(x, "x"), _dev(y, "y"), _dt(x), M, cin, out_features,
                                   _dev(tile, "tile", torch.int32), k, _dev(alpha, "alpha", torch.float32),
                                   alpha.numel(), flags, _stream(stream))
+    if st != TBN_OK:
+        _raise(st)
+    return y
+
+
+def tbn_linear_forward_workspace_bytes(dtype: torch.dtype, M: int, cin: int, out_features: int, k: int, flags: int = 0) -> int:
+    """Bytes of workspace with which tbn_linear_forward_ws takes its fastest path for these sizes (0: none needed)."""
+    dt = TBN_F32 if dtype == torch.float32 else TBN_BF16
+    return int(lib().tbn_linear_forward_workspace_bytes(dt, M, cin, out_features, k, flags))
+
+
+def tbn_linear_forward_ws(x: torch.Tensor, tile: torch.Tensor, alpha: torch.Tensor, out_features: int, k: int,
+                          workspace: Optional[torch.Tensor], y: Optional[torch.Tensor] = None, flags: int = 0,
+                          stream=None) -> torch.Tensor:
+    """tbn_linear_forward with a caller-supplied device workspace (None or too small: the same as tbn_linear_forward)."""
+    if x.dim() != 2:
+        raise ValueError("x must be (M, in)")
+    M, cin = x.shape
+    if y is None:
+        y = torch.empty((M, out_features), dtype=x.dtype, device=x.device)
+    elif tuple(y.shape) != (M, out_features) or y.dtype != x.dtype:
+        raise ValueError("y must be (M, out) with x's dtype")
+    ws_ptr = None if workspace is None else _dev(workspace, "workspace")
+    ws_bytes = 0 if workspace is None else workspace.numel() * workspace.element_size()
+    st = lib().tbn_linear_forward_ws(_dev(x, "x"), _dev(y, "y"), _dt(x), M, cin, out_features,
+                                     _dev(tile, "tile", torch.int32), k, _dev(alpha, "alpha", torch.float32),
+                                     alpha.numel(), flags, ws_ptr, ws_bytes, _stream(stream))
     if st != TBN_OK:
         _raise(st)
     return y

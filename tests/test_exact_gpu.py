@@ -36,7 +36,7 @@ def _ternary(rng, shape, p_nonzero):
     return x
 
 
-def _exact_case(tbn, M, cin, cout, k, dtype, flags, seed, alpha_vals=None):
+def _exact_case(tbn, M, cin, cout, k, dtype, flags, seed, alpha_vals=None, workspace=None):
     rng = np.random.default_rng(seed)
     n = cin * cout
     p = n // k
@@ -59,7 +59,16 @@ def _exact_case(tbn, M, cin, cout, k, dtype, flags, seed, alpha_vals=None):
     else:
         xd = torch.from_numpy(x).cuda()
         want = ref.astype(np.float32)
-    y = tbn.tbn_linear_forward(xd, tile, alpha, cout, k, flags=flags)
+    if workspace:
+        need = tbn.tbn_linear_forward_workspace_bytes(xd.dtype, M, cin, cout, k, flags)
+        assert (need > 0) == (workspace == "used"), f"workspace query returned {need}"
+        ws = torch.empty(max(need, 16), dtype=torch.uint8, device="cuda")
+        y = tbn.tbn_linear_forward_ws(xd, tile, alpha, cout, k, ws, flags=flags)
+        y2 = tbn.tbn_linear_forward_ws(xd, tile, alpha, cout, k, ws, flags=flags)
+        torch.cuda.synchronize()
+        assert torch.equal(y.view(torch.int16), y2.view(torch.int16)), "two runs differ"
+    else:
+        y = tbn.tbn_linear_forward(xd, tile, alpha, cout, k, flags=flags)
     torch.cuda.synchronize()
     got = y.float().cpu().numpy()
     bad = np.argwhere(got != want)
@@ -150,3 +159,60 @@ def test_exact_decode_shapes(tbn, M, cin, cout, k, dtype):
     _exact_case(tbn, M, cin, cout, k, dtype, tbn.TBN_FLAG_RELU, 23 * M + cin + 1,
                 alpha_vals=[2.0 ** ((i % 5) - 2) for i in range(k)])
     _exact_case(tbn, M, cin, cout, k, dtype, tbn.TBN_FLAG_LARGE_BATCH, 23 * M + cin + 2)
+
+
+# split K with a caller-supplied workspace: grids of at most half the chip's CUs on the block kernel's shapes.  By
+# default the path is only taken for long rows (the cost model); TBN_FLAG_SPLIT_K takes it wherever the shape allows.
+EXACT_SPLIT = [
+    (512, 4096, 4096, 8),     # 16 blocks, 16 splits of one round pair
+    (1000, 4096, 4096, 8),    # ragged rows; 32 blocks, 8 splits
+    (2048, 4096, 4096, 8),    # 4 splits
+    (4096, 4096, 4096, 8),    # 128 blocks, 2 splits
+    (100, 1024, 1088, 8),     # U = 136: ragged second column block; 2 blocks, 4 splits of one round pair
+    (300, 1536, 768, 2),      # 6 round pairs: 2 splits of three pairs
+    (130, 512, 64 * 64, 64),  # 64 replicas, half a column block
+    (700, 2048, 384, 1),      # one replica
+]
+
+
+@pytest.mark.parametrize("M,cin,cout,k", EXACT_SPLIT)
+def test_exact_bf16_split_k_with_workspace(tbn, M, cin, cout, k):
+    split = tbn.TBN_FLAG_SPLIT_K
+    _exact_case(tbn, M, cin, cout, k, "bf16", split, 29 * M + cin, workspace="used")
+    _exact_case(tbn, M, cin, cout, k, "bf16", split | tbn.TBN_FLAG_RELU, 29 * M + cin + 1,
+                alpha_vals=[2.0 ** ((i % 5) - 2) for i in range(k)], workspace="used")
+
+
+@pytest.mark.parametrize("M,cin,cout,k", [(512, 16384, 1024, 2), (200, 16384, 512, 2)])
+def test_exact_bf16_split_k_chosen_for_long_rows(tbn, M, cin, cout, k):
+    # no flag: the cost model takes the split for rows this long (also below 256 batch rows, where the call
+    # without a workspace goes to the small-batch kernel)
+    _exact_case(tbn, M, cin, cout, k, "bf16", 0, 37 * M + cin, workspace="used")
+
+
+@pytest.mark.parametrize("M,cin,cout,k,dtype,flags", [
+    (8192, 4096, 4096, 8, "bf16", 0x1000),   # the grid fills the chip
+    (16, 4096, 4096, 8, "bf16", 0x1000),     # decode kernel
+    (512, 4096, 4096, 8, "f32", 0x1000),     # float32 has no split path
+    (512, 768, 4096, 8, "bf16", 0x1000),     # K = 3 * 256: no equal parts
+    (512, 4096, 4096, 8, "bf16", 0),         # short rows: the cost model keeps the single kernel
+])
+def test_exact_workspace_entry_without_split(tbn, M, cin, cout, k, dtype, flags):
+    assert tbn.TBN_FLAG_SPLIT_K == 0x1000
+    _exact_case(tbn, M, cin, cout, k, dtype, flags, 31 * M + cin, workspace="unused")
+
+
+def test_workspace_too_small_or_misaligned(tbn):
+    M, cin, cout, k = 512, 4096, 4096, 8
+    need = tbn.tbn_linear_forward_workspace_bytes(torch.bfloat16, M, cin, cout, k, tbn.TBN_FLAG_SPLIT_K)
+    assert need == 16 * M * (cout // k) * 4
+    x = torch.zeros((M, cin), dtype=torch.bfloat16, device="cuda")
+    tile = torch.zeros(cin * cout // k // 32, dtype=torch.int32, device="cuda")
+    alpha = torch.ones(k, dtype=torch.float32, device="cuda")
+    small = torch.empty(need - 16, dtype=torch.uint8, device="cuda")
+    y = tbn.tbn_linear_forward_ws(x, tile, alpha, cout, k, small, flags=tbn.TBN_FLAG_SPLIT_K)   # the plain forward
+    torch.cuda.synchronize()
+    assert float(y.float().abs().max()) == 0.0
+    ws = torch.empty(need + 16, dtype=torch.uint8, device="cuda")
+    with pytest.raises(RuntimeError):
+        tbn.tbn_linear_forward_ws(x, tile, alpha, cout, k, ws[8:], flags=tbn.TBN_FLAG_SPLIT_K)
