@@ -64,6 +64,8 @@ static tbn_status dispatch_linear(const LinearArgs &a) {
             const bool stream = (a.flags & TBN_FLAG_STREAM_KERNEL) || blocks < 128;
             if (stream && linear_stream_supported(a)) return launch_linear_stream(a);
             if (linear_block_supported(a)) return launch_linear_block(a);
+            // float32, tile of whole rows, few distinct rows: memory-bound layers, one wave per 32 batch rows
+            if (linear_f32tile_supported(a)) return launch_linear_f32tile(a);
         }
         if (linear_mfma_supported(a)) return launch_linear_mfma(a);
         if (linear_rows_supported(a)) return launch_linear_rows(a);

@@ -133,9 +133,28 @@ def test_exact_block_kernels(tbn, M, cin, cout, k, dtype):
     _exact_case(tbn, M, cin, cout, k, dtype, tbn.TBN_FLAG_LARGE_BATCH, 17 * M + cin)
 
 
-@pytest.mark.parametrize("M,cin,cout,k", [(1000, 2048, 384, 1), (4100, 512, 1088, 8)])
-def test_exact_f32_whole_row_tiles(tbn, M, cin, cout, k):
-    _exact_case(tbn, M, cin, cout, k, "f32", tbn.TBN_FLAG_LARGE_BATCH, 19 * M + cin)
+# float32, tile of whole rows: at most 512 distinct rows go to the kernel that feeds the matrix cores straight from
+# global memory (one wave per 32 batch rows, one or four K slices per workgroup), the rest and everything under
+# TBN_FLAG_BLOCK_KERNEL to the general float32 kernel
+EXACT_F32_ROWS = [
+    (1000, 2048, 384, 1),     # three groups of four column tiles, four K slices
+    (4100, 512, 1088, 8),     # U = 136: two groups of three tiles, the last tile of the second outside; one K slice
+    (12608, 384, 1536, 4),    # transformer MLP, first layer: 394 row tiles, K = 6 chunks
+    (12608, 1536, 384, 4),    # second layer: U = 96, three tiles, four K slices of 384
+    (65, 1024, 8, 2),         # U = 4: one tile, four waves add into it; ragged rows
+    (300, 64, 64 * 5, 5),     # one chunk of K, two tiles
+    (200, 1280, 2 * 520, 2),  # U = 520 > 512: general kernel
+    (97, 4096, 160, 1),       # five tiles in two groups; K = 16 chunks per slice
+]
+
+
+@pytest.mark.parametrize("kernel", ["default", "general"])
+@pytest.mark.parametrize("M,cin,cout,k", EXACT_F32_ROWS)
+def test_exact_f32_whole_row_tiles(tbn, M, cin, cout, k, kernel):
+    extra = tbn.TBN_FLAG_BLOCK_KERNEL if kernel == "general" else 0
+    _exact_case(tbn, M, cin, cout, k, "f32", tbn.TBN_FLAG_LARGE_BATCH | extra, 19 * M + cin)
+    _exact_case(tbn, M, cin, cout, k, "f32", tbn.TBN_FLAG_LARGE_BATCH | tbn.TBN_FLAG_RELU | extra, 19 * M + cin + 1,
+                alpha_vals=[2.0 ** ((i % 5) - 2) for i in range(k)])
 
 
 # at most 16 batch rows and whole rows per tile: the decode kernel (default) and, with the large-batch flag, the
