@@ -85,7 +85,14 @@ __device__ __forceinline__ uint32_t pack_hi16(uint32_t lo, uint32_t hi) { return
 __device__ __forceinline__ uint32_t load_raw(const float *p) { return __float_as_uint(*p); }
 __device__ __forceinline__ uint32_t load_raw(const uint16_t *p) { return *p; }
 
-template <typename XT, int T, bool RELU, int kBudget, int NFT>
+// FIX: the repair pass behind the main pass when tiles end inside filters (one alpha per tile).  The main pass
+// scales a whole output channel by the alpha of its first weight; a channel whose filter contains the start of tile
+// number c (flat index c * p, at most one per filter since p >= F) needs alpha[c - 1] for the weights before it and
+// alpha[c] from it on.  Here the "distinct filters" of a workgroup are pairs of masked copies of such filters:
+// pseudo-filter 2i keeps the weights before the start of tile u0 / 2 + i + 1 and has zeros after it, pseudo-filter
+// 2i + 1 the rest (a zero weight is the +-1 pattern ANDed away: +0.0 in bfloat16).  A lane's accumulators hold both
+// halves of a pair, so the epilogue writes alpha[c - 1] * before + alpha[c] * after over what the main pass wrote.
+template <typename XT, int T, bool RELU, int kBudget, int NFT, bool FIX>
 __global__ __launch_bounds__((64 * waves_of(NFT)), (waves_of(NFT) == 8 ? 4 : 2)) void conv_mfma_kernel(const XT *__restrict__ x, XT *__restrict__ y,
                                                                   const uint32_t *__restrict__ tile,
                                                                   const float *__restrict__ alpha, ConvMfmaParams P) {
@@ -99,6 +106,7 @@ __global__ __launch_bounds__((64 * waves_of(NFT)), (waves_of(NFT) == 8 ? 4 : 2))
     unsigned char *lds_patch = lds_raw;
     const int buf_bytes = NP * P.plane_bytes;
     uint32_t *lds_bits = reinterpret_cast<uint32_t *>(lds_raw + 2 * buf_bytes);
+    uint32_t *lds_mask = lds_bits + T * (P.C / kCK) * kFB;   // FIX only: which weights a pseudo-filter keeps, same layout
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int ln = lane & 15, lg = lane >> 4;
@@ -198,16 +206,26 @@ __global__ __launch_bounds__((64 * waves_of(NFT)), (waves_of(NFT) == 8 ? 4 : 2))
     for (int id = tid; id < kFB * n_chunks; id += kThreads) {
         const int u = id % kFB, chunk = id / kFB;
         uint32_t w[T], o[T];
-        const bool live = (u0 + u) < P.R;
-        if (P.aligned) {
+        int64_t filt = u0 + u;          // filter whose bits are read
+        bool live = filt < P.R;
+        int64_t keep_before = 0;        // FIX: weights of the filter before the tile start
+        if constexpr (FIX) {
+            const int64_t c = (u0 + u) / 2 + 1;              // tile number whose start is looked at
+            const int64_t f = c * P.p;                       // flat index where it starts
+            filt = f / P.F;
+            keep_before = f - filt * P.F;
+            live = c < P.n_alpha && keep_before != 0 && filt < P.O;   // n_alpha == k; a start on a filter boundary needs no repair
+            if (!live) filt = 0;
+        }
+        if (!FIX && P.aligned) {
             // whole filters per tile and F % 32 == 0: the block is T consecutive words of the tile
-            const int64_t word0 = ((u0 + u) * P.F) / 32 + int64_t(chunk) * T;
+            const int64_t word0 = (filt * P.F) / 32 + int64_t(chunk) * T;
 #pragma unroll
             for (int i = 0; i < T; ++i) w[i] = live ? tile[word0 + i] : 0u;
         } else {
             // the 32*T bits of this (filter, chunk) start at cyclic tile position pos; all loads are
             // issued first (unconditionally, with clamped indices) so that they overlap
-            int64_t pos = live ? ((u0 + u) * P.F + int64_t(chunk) * 32 * T) % P.p : 0;
+            int64_t pos = live ? (filt * P.F + int64_t(chunk) * 32 * T) % P.p : 0;
             uint32_t lo[T], hi[T];
             int64_t wpos[T];
     #pragma unroll
@@ -240,6 +258,20 @@ __global__ __launch_bounds__((64 * waves_of(NFT)), (waves_of(NFT) == 8 ? 4 : 2))
         }
 #pragma unroll
         for (int tap = 0; tap < T; ++tap) lds_bits[(chunk * T + tap) * kFB + u] = o[tap];
+        if constexpr (FIX) {
+            // weight (channel j of the chunk, tap) has index chunk * 32 * T + j * T + tap inside the filter: the channels
+            // with an index below keep_before are j < ceil((keep_before - chunk * 32 * T - tap) / T)
+            const int64_t rem = keep_before - int64_t(chunk) * 32 * T;
+#pragma unroll
+            for (int tap = 0; tap < T; ++tap) {
+                int64_t cnt = (rem - tap + T - 1) / T;
+                if (rem - tap <= 0) cnt = 0;
+                if (cnt > 32) cnt = 32;
+                const uint32_t before = cnt >= 32 ? 0xffffffffu : ((1u << cnt) - 1u);
+                const uint32_t m = ((u0 + u) & 1) ? ~before : before;
+                lds_mask[(chunk * T + tap) * kFB + u] = live ? m : 0u;
+            }
+        }
     }
 
     // ---- MFMA operands of this lane -----------------------------------------------------------------
@@ -287,10 +319,14 @@ __global__ __launch_bounds__((64 * waves_of(NFT)), (waves_of(NFT) == 8 ? 4 : 2))
         const uint32_t src = patch_addr + static_cast<uint32_t>(buf * buf_bytes);
         const uint32_t *bits = lds_bits + chunk * T * kFB + ln;
         uint32_t nw[T][NFT];   // inverted filter bits of the chunk (bit 1 of the tile is +1: sign bit clear)
+        uint32_t mw[FIX ? T : 1][NFT];   // FIX: the weights kept
 #pragma unroll
         for (int tap = 0; tap < T; ++tap)
 #pragma unroll
-            for (int ft = 0; ft < NFT; ++ft) nw[tap][ft] = ~bits[tap * kFB + ft * 16];
+            for (int ft = 0; ft < NFT; ++ft) {
+                nw[tap][ft] = ~bits[tap * kFB + ft * 16];
+                if constexpr (FIX) mw[tap][ft] = (lds_mask + chunk * T * kFB + ln)[tap * kFB + ft * 16];
+            }
         auto unit_addr = [&](int u) {
             const int tap = u / (J * NP), j = (u / NP) % J, pl = u % NP;
             return src + static_cast<uint32_t>(pix_off[j] + tap_off[tap] + pl * P.plane_bytes);
@@ -306,6 +342,17 @@ __global__ __launch_bounds__((64 * waves_of(NFT)), (waves_of(NFT) == 8 ? 4 : 2))
                 for (int v = 0; v < 4; ++v) {
                     const u16x2_t sh = {static_cast<uint16_t>(15 - 2 * v), static_cast<uint16_t>(14 - 2 * v)};
                     wf[ft].u[v] = (__builtin_bit_cast(uint32_t, static_cast<u16x2_t>(r2 << sh)) & sign_mask) | one_bits;
+                }
+                if constexpr (FIX) {   // zero where the pseudo-filter has no weight: the kept bit spread over its half word
+                    typedef int16_t i16x2_t __attribute__((ext_vector_type(2)));
+                    const u16x2_t m2 = __builtin_bit_cast(u16x2_t, __builtin_amdgcn_perm(mw[tap][ft], mw[tap][ft], byte_sel));
+#pragma unroll
+                    for (int v = 0; v < 4; ++v) {
+                        const u16x2_t sh = {static_cast<uint16_t>(15 - 2 * v), static_cast<uint16_t>(14 - 2 * v)};
+                        const i16x2_t top = __builtin_bit_cast(i16x2_t, static_cast<u16x2_t>(m2 << sh));
+                        const i16x2_t fifteen = {15, 15};
+                        wf[ft].u[v] &= __builtin_bit_cast(uint32_t, static_cast<i16x2_t>(top >> fifteen));
+                    }
                 }
             }
         };
@@ -387,6 +434,29 @@ __global__ __launch_bounds__((64 * waves_of(NFT)), (waves_of(NFT) == 8 ? 4 : 2))
     // ---- epilogue: y[img, u + t*R, row0.., :] = alpha[t] * Z[u] ---------------------------------------------
     // lane holds pixel ln of its tiles and filters 4*lg + i of each filter tile
     const int64_t plane_out = P.Ho * P.Wo;
+    if constexpr (FIX) {
+        // registers i = 0, 1 and i = 2, 3 of a filter tile are the two halves of a pair
+#pragma unroll
+        for (int ft = 0; ft < NFT; ++ft)
+#pragma unroll
+            for (int i = 0; i < 4; i += 2) {
+                const int64_t c = (u0 + ft * 16 + 4 * lg + i) / 2 + 1;
+                if (c >= P.n_alpha) continue;
+                const int64_t f = c * P.p, o = f / P.F;
+                if (f == o * P.F || o >= P.O) continue;
+                const float a_before = alpha[c - 1], a_after = alpha[c];
+                XT *dst = y + ((img * P.O + o) * plane_out) + int64_t(row0) * P.Wo;
+#pragma unroll
+                for (int j = 0; j < kTilesPerWave; ++j) {
+                    const int q = (wave + kWaves * j) * 16 + ln;
+                    if (q >= PX) continue;
+                    float v = a_before * acc[ft][j][i] + a_after * acc[ft][j][i + 1];
+                    if (RELU) v = fmaxf(v, 0.f);
+                    ElemIO<XT>::store(dst + q, v);
+                }
+            }
+        return;
+    }
     const int64_t reps = (P.O + P.R - 1) / P.R;
     const bool per_replica = (P.n_alpha == 1) || P.aligned;   // alpha depends on the replica only (uniform)
     auto write_all = [&](auto per_replica_c) __attribute__((always_inline)) {
@@ -425,10 +495,11 @@ struct ConvPlan {
     size_t lds;
     int items;   // kItemsSmall or kItemsLarge
     int nft;     // kFtSmall or kFtLarge
+    bool fix;    // launch the repair pass (pairs of masked filters) instead of the main pass
 };
 
 ConvPlan plan_conv(const ConvArgs &a) {
-    ConvPlan pl{false, 0, 0, 0, 0, 0, kItemsSmall, kFtSmall};
+    ConvPlan pl{false, 0, 0, 0, 0, 0, kItemsSmall, kFtSmall, false};
     const int64_t F = a.C * a.kh * a.kw;
     const int T = a.kh * a.kw;
     if (T != 1 && T != 9) return pl;                     // instantiated tap counts: 1x1 and 3x3
@@ -474,19 +545,27 @@ ConvPlan plan_conv(const ConvArgs &a) {
     return pl;
 }
 
-template <typename XT, int T, bool RELU, int ITEMS, int NFT>
-tbn_status launch_conv_typed(const ConvArgs &a, const ConvMfmaParams &P, const ConvPlan &pl, dim3 grid) {
+template <typename XT, int T, bool RELU, int ITEMS, int NFT, bool FIX>
+tbn_status launch_conv_fix(const ConvArgs &a, const ConvMfmaParams &P, size_t lds, dim3 grid) {
     // Dynamic LDS above the default limit has to be allowed once per kernel: the plan's upper bound, set by the
     // thread-safe initialisation of a static.
-    static const hipError_t attr = hipFuncSetAttribute(reinterpret_cast<const void *>(&conv_mfma_kernel<XT, T, RELU, ITEMS, NFT>),
+    static const hipError_t attr = hipFuncSetAttribute(reinterpret_cast<const void *>(&conv_mfma_kernel<XT, T, RELU, ITEMS, NFT, FIX>),
                                                        hipFuncAttributeMaxDynamicSharedMemorySize, kPlanLdsMax);
-    if (attr != hipSuccess || pl.lds > size_t(kPlanLdsMax)) {
-        set_error("tbn_conv2d_forward: cannot reserve %zu bytes of LDS", pl.lds);
+    if (attr != hipSuccess || lds > size_t(kPlanLdsMax)) {
+        set_error("tbn_conv2d_forward: cannot reserve %zu bytes of LDS", lds);
         return TBN_ERR_DEVICE;
     }
-    hipLaunchKernelGGL((conv_mfma_kernel<XT, T, RELU, ITEMS, NFT>), grid, dim3(64 * waves_of(NFT)), pl.lds, a.stream,
+    hipLaunchKernelGGL((conv_mfma_kernel<XT, T, RELU, ITEMS, NFT, FIX>), grid, dim3(64 * waves_of(NFT)), lds, a.stream,
                        static_cast<const XT *>(a.x), static_cast<XT *>(a.y), a.tile, a.alpha, P);
-    return check_launch("tbn_conv2d_forward (matrix-core kernel)");
+    return check_launch(FIX ? "tbn_conv2d_forward (matrix-core repair pass)" : "tbn_conv2d_forward (matrix-core kernel)");
+}
+
+template <typename XT, int T, bool RELU, int ITEMS, int NFT>
+tbn_status launch_conv_typed(const ConvArgs &a, const ConvMfmaParams &P, const ConvPlan &pl, dim3 grid) {
+    if constexpr (NFT == kFtSmall) {
+        if (pl.fix) return launch_conv_fix<XT, T, RELU, ITEMS, NFT, true>(a, P, pl.lds, grid);
+    }
+    return launch_conv_fix<XT, T, RELU, ITEMS, NFT, false>(a, P, pl.lds, grid);
 }
 
 template <typename XT, int T, bool RELU>
@@ -541,9 +620,21 @@ tbn_status launch_conv_mfma(const ConvArgs &a) {
     const dim3 grid(static_cast<unsigned>(pl.nblk), static_cast<unsigned>(a.N), static_cast<unsigned>(fblocks));
     tbn_status st = (a.dt == TBN_F32) ? launch_conv_taps<float>(a, P, pl, grid) : launch_conv_taps<uint16_t>(a, P, pl, grid);
     if (st != TBN_OK) return st;
-    // channels whose filter contains a tile end are scaled by two alphas
-    if (a.n_alpha > 1 && !P.aligned) return launch_conv_generic_tile_ends(a);
-    return TBN_OK;
+    if (a.n_alpha == 1 || P.aligned) return TBN_OK;
+    // Channels whose filter contains a tile start are scaled by two alphas: a second pass of the same kernel over
+    // pairs of masked filters, 16 such channels per workgroup, where the doubled filter-bit area still fits the LDS
+    // (else the plain kernel for those channels).
+    ConvPlan fp = pl;
+    fp.fix = true;
+    fp.nft = kFtSmall;
+    const size_t bits_small = size_t(a.kh * a.kw) * a.C * 4 * (16 * kFtSmall / 32);
+    const size_t bits_main = size_t(a.kh * a.kw) * a.C * 4 * (16 * pl.nft / 32);
+    fp.lds = pl.lds - bits_main + 2 * bits_small;
+    const int64_t pairs_per_blk = 16 * kFtSmall / 2;
+    const int64_t fix_blocks = (int64_t(a.k) - 1 + pairs_per_blk - 1) / pairs_per_blk;
+    if (fp.lds > size_t(kPlanLdsMax) || fix_blocks > 65535) return launch_conv_generic_tile_ends(a);
+    const dim3 fgrid(static_cast<unsigned>(pl.nblk), static_cast<unsigned>(a.N), static_cast<unsigned>(fix_blocks));
+    return (a.dt == TBN_F32) ? launch_conv_taps<float>(a, P, fp, fgrid) : launch_conv_taps<uint16_t>(a, P, fp, fgrid);
 }
 
 }  // namespace tbn

@@ -196,7 +196,6 @@ __global__ __launch_bounds__(64 * KW) void linear_f32_tile_kernel(const float *_
     int t_end = NT;
     if constexpr (KW > 1) {
         static_assert(KW >= NT, "every column tile needs a wave");
-        constexpr int SL = L::SL;
         __syncthreads();   // every wave is done with its chunk: the regions change their use
 #pragma unroll
         for (int t = 0; t < NT; ++t) {
