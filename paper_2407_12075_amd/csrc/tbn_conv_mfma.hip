@@ -51,6 +51,8 @@ constexpr int kItemsSmall = 2560;   // staged (channel pair, pixel) items per wo
 constexpr int kItemsLarge = 3072;   // ... up to 192 pixels (one output row of a 56- to 62-wide image with its 3x3 halo)
 constexpr int kPixStride = kCK * 2 + 16;   // bytes per patch pixel in LDS: 32 bf16 channels + 16 B padding
 
+constexpr __host__ __device__ int n_chunks_of(int64_t C) { return static_cast<int>((C + kCK - 1) / kCK); }
+
 struct ConvMfmaParams {
     int64_t N, C, H, W, O, Ho, Wo;
     int32_t kh, kw, sh, sw, ph, pw;
@@ -92,7 +94,9 @@ __device__ __forceinline__ uint32_t load_raw(const uint16_t *p) { return *p; }
 // pseudo-filter 2i keeps the weights before the start of tile u0 / 2 + i + 1 and has zeros after it, pseudo-filter
 // 2i + 1 the rest (a zero weight is the +-1 pattern ANDed away: +0.0 in bfloat16).  A lane's accumulators hold both
 // halves of a pair, so the epilogue writes alpha[c - 1] * before + alpha[c] * after over what the main pass wrote.
-template <typename XT, int T, bool RELU, int kBudget, int NFT, bool FIX>
+// SHORT: C is no multiple of 32; the channels that the last chunk lacks are staged as zeros (a form of its own: the
+// extra selects in the loads cost the other form registers it does not have).
+template <typename XT, int T, bool RELU, int kBudget, int NFT, bool FIX, bool SHORT>
 __global__ __launch_bounds__((64 * waves_of(NFT)), (waves_of(NFT) == 8 ? 4 : 2)) void conv_mfma_kernel(const XT *__restrict__ x, XT *__restrict__ y,
                                                                   const uint32_t *__restrict__ tile,
                                                                   const float *__restrict__ alpha, ConvMfmaParams P) {
@@ -106,11 +110,11 @@ __global__ __launch_bounds__((64 * waves_of(NFT)), (waves_of(NFT) == 8 ? 4 : 2))
     unsigned char *lds_patch = lds_raw;
     const int buf_bytes = NP * P.plane_bytes;
     uint32_t *lds_bits = reinterpret_cast<uint32_t *>(lds_raw + 2 * buf_bytes);
-    uint32_t *lds_mask = lds_bits + T * (P.C / kCK) * kFB;   // FIX only: which weights a pseudo-filter keeps, same layout
+    uint32_t *lds_mask = lds_bits + T * n_chunks_of(P.C) * kFB;   // FIX only: which weights a pseudo-filter keeps, same layout
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int ln = lane & 15, lg = lane >> 4;
-    const int n_chunks = static_cast<int>(P.C / kCK);
+    const int n_chunks = static_cast<int>((P.C + kCK - 1) / kCK);   // the last chunk may be short: its missing channels are staged as zeros
     const int64_t img = blockIdx.y;
     const int row0 = blockIdx.x * P.rows_per_blk;                         // first output row of the block
     const int rows = (P.Ho - row0) < P.rows_per_blk ? static_cast<int>(P.Ho - row0) : P.rows_per_blk;
@@ -129,7 +133,7 @@ __global__ __launch_bounds__((64 * waves_of(NFT)), (waves_of(NFT) == 8 ? 4 : 2))
     const int npix = vrows * vcols;
     const int n_items = npix * (kCK / 2);
     int32_t it_goff[kMaxItems];   // element offset inside the chunk's first channel plane, or -1
-    int32_t it_loff[kMaxItems];   // byte offset inside a patch plane
+    int32_t it_loff[kMaxItems];   // byte offset inside a patch plane: pixel * kPixStride + 4 * channel pair
     {
         // item q = tid + i * kThreads is (channel pair, valid row, valid column) = (q / npix, (q % npix) / vcols,
         // q % vcols); the thread divides once and then steps by kThreads items with carries
@@ -162,11 +166,24 @@ __global__ __launch_bounds__((64 * waves_of(NFT)), (waves_of(NFT) == 8 ? 4 : 2))
     uint32_t st_pk[kMaxItems][NP];                  // ... split and packed, ready for LDS
     auto load_chunk = [&](int chunk, int slot) {
         const XT *base = x_img + int64_t(chunk) * kCK * plane_hw;
+        const int c_left = static_cast<int>(P.C) - chunk * kCK;   // channels of this chunk that exist (uniform)
+        if (!SHORT || c_left >= kCK) {
 #pragma unroll
-        for (int i = 0; i < kMaxItems; ++i) {
-            const int32_t g = it_goff[i] < 0 ? 0 : it_goff[i];
-            st_a[slot][i] = load_raw(base + g);
-            st_b[slot][i] = load_raw(base + g + plane_hw);
+            for (int i = 0; i < kMaxItems; ++i) {
+                const int32_t g = it_goff[i] < 0 ? 0 : it_goff[i];
+                st_a[slot][i] = load_raw(base + g);
+                st_b[slot][i] = load_raw(base + g + plane_hw);
+            }
+        } else {   // short last chunk: channels past C read as zero (and nothing past the end of x is touched)
+#pragma unroll
+            for (int i = 0; i < kMaxItems; ++i) {
+                const int ch = (it_loff[i] % kPixStride) / 2;   // first channel of the pair inside the chunk
+                const bool ok_a = it_goff[i] >= 0 && ch < c_left, ok_b = it_goff[i] >= 0 && ch + 1 < c_left;
+                const uint32_t va = load_raw(base + (ok_a ? it_goff[i] : 0));
+                const uint32_t vb = load_raw(base + (ok_b ? it_goff[i] + plane_hw : 0));
+                st_a[slot][i] = ok_a ? va : 0u;
+                st_b[slot][i] = ok_b ? vb : 0u;
+            }
         }
     };
     auto pack_item = [&](int i, int slot) {   // VALU only
@@ -217,8 +234,8 @@ __global__ __launch_bounds__((64 * waves_of(NFT)), (waves_of(NFT) == 8 ? 4 : 2))
             live = c < P.n_alpha && keep_before != 0 && filt < P.O;   // n_alpha == k; a start on a filter boundary needs no repair
             if (!live) filt = 0;
         }
-        if (!FIX && P.aligned) {
-            // whole filters per tile and F % 32 == 0: the block is T consecutive words of the tile
+        if (!FIX && !SHORT && P.aligned) {
+            // whole filters per tile and whole chunks (so F % 32 == 0): the block is T consecutive words of the tile
             const int64_t word0 = (filt * P.F) / 32 + int64_t(chunk) * T;
 #pragma unroll
             for (int i = 0; i < T; ++i) w[i] = live ? tile[word0 + i] : 0u;
@@ -504,7 +521,6 @@ ConvPlan plan_conv(const ConvArgs &a) {
     const int T = a.kh * a.kw;
     if (T != 1 && T != 9) return pl;                     // instantiated tap counts: 1x1 and 3x3
     if (a.p < F || a.p < 64) return pl;                  // at most one tile end per filter
-    if (a.C % kCK != 0) return pl;
     if (a.Wo > kMaxPix || a.Wo <= 0 || a.Ho <= 0) return pl;
     if (a.C * a.H * a.W >= (int64_t(1) << 31)) return pl;   // 32-bit element offsets inside an image
     if (a.N > 65535) return pl;
@@ -512,10 +528,10 @@ ConvPlan plan_conv(const ConvArgs &a) {
     const int64_t R = unique_rows(a.O, F, a.p);
     // 64 filters per workgroup for bf16 inputs where that many exist and enough workgroups remain to fill
     // the chip (measured 12 % faster; with float32 inputs, three planes per operand, it measured 8 % slower)
-    pl.nft = (a.dt != TBN_F32 && R >= 16 * kFtLarge && ((R + 16 * kFtLarge - 1) / (16 * kFtLarge)) * a.N >= 256) ? kFtLarge
-                                                                                                                 : kFtSmall;
+    pl.nft = (a.dt != TBN_F32 && a.C % kCK == 0 && R >= 16 * kFtLarge && ((R + 16 * kFtLarge - 1) / (16 * kFtLarge)) * a.N >= 256)
+                 ? kFtLarge : kFtSmall;
     const int kFB = 16 * pl.nft;
-    const size_t bits_bytes = size_t(T) * a.C * 4 * (kFB / 32);   // kFB filters * T * C/32 words
+    const size_t bits_bytes = size_t(T) * n_chunks_of(a.C) * kCK * 4 * (kFB / 32);   // kFB filters * T * ceil(C/32) words
     // balanced row blocks of at most kMaxPix pixels whose valid input patch fits the staging budget
     int64_t rows = kMaxPix / a.Wo;
     if (rows > a.Ho) rows = a.Ho;
@@ -545,17 +561,17 @@ ConvPlan plan_conv(const ConvArgs &a) {
     return pl;
 }
 
-template <typename XT, int T, bool RELU, int ITEMS, int NFT, bool FIX>
+template <typename XT, int T, bool RELU, int ITEMS, int NFT, bool FIX, bool SHORT>
 tbn_status launch_conv_fix(const ConvArgs &a, const ConvMfmaParams &P, size_t lds, dim3 grid) {
     // Dynamic LDS above the default limit has to be allowed once per kernel: the plan's upper bound, set by the
     // thread-safe initialisation of a static.
-    static const hipError_t attr = hipFuncSetAttribute(reinterpret_cast<const void *>(&conv_mfma_kernel<XT, T, RELU, ITEMS, NFT, FIX>),
+    static const hipError_t attr = hipFuncSetAttribute(reinterpret_cast<const void *>(&conv_mfma_kernel<XT, T, RELU, ITEMS, NFT, FIX, SHORT>),
                                                        hipFuncAttributeMaxDynamicSharedMemorySize, kPlanLdsMax);
     if (attr != hipSuccess || lds > size_t(kPlanLdsMax)) {
         set_error("tbn_conv2d_forward: cannot reserve %zu bytes of LDS", lds);
         return TBN_ERR_DEVICE;
     }
-    hipLaunchKernelGGL((conv_mfma_kernel<XT, T, RELU, ITEMS, NFT, FIX>), grid, dim3(64 * waves_of(NFT)), lds, a.stream,
+    hipLaunchKernelGGL((conv_mfma_kernel<XT, T, RELU, ITEMS, NFT, FIX, SHORT>), grid, dim3(64 * waves_of(NFT)), lds, a.stream,
                        static_cast<const XT *>(a.x), static_cast<XT *>(a.y), a.tile, a.alpha, P);
     return check_launch(FIX ? "tbn_conv2d_forward (matrix-core repair pass)" : "tbn_conv2d_forward (matrix-core kernel)");
 }
@@ -563,9 +579,10 @@ tbn_status launch_conv_fix(const ConvArgs &a, const ConvMfmaParams &P, size_t ld
 template <typename XT, int T, bool RELU, int ITEMS, int NFT>
 tbn_status launch_conv_typed(const ConvArgs &a, const ConvMfmaParams &P, const ConvPlan &pl, dim3 grid) {
     if constexpr (NFT == kFtSmall) {
-        if (pl.fix) return launch_conv_fix<XT, T, RELU, ITEMS, NFT, true>(a, P, pl.lds, grid);
+        if (pl.fix) return launch_conv_fix<XT, T, RELU, ITEMS, NFT, true, false>(a, P, pl.lds, grid);   // whole chunks only
+        if (a.C % kCK != 0) return launch_conv_fix<XT, T, RELU, ITEMS, NFT, false, true>(a, P, pl.lds, grid);
     }
-    return launch_conv_fix<XT, T, RELU, ITEMS, NFT, false>(a, P, pl.lds, grid);
+    return launch_conv_fix<XT, T, RELU, ITEMS, NFT, false, false>(a, P, pl.lds, grid);
 }
 
 template <typename XT, int T, bool RELU>
@@ -627,12 +644,12 @@ tbn_status launch_conv_mfma(const ConvArgs &a) {
     ConvPlan fp = pl;
     fp.fix = true;
     fp.nft = kFtSmall;
-    const size_t bits_small = size_t(a.kh * a.kw) * a.C * 4 * (16 * kFtSmall / 32);
-    const size_t bits_main = size_t(a.kh * a.kw) * a.C * 4 * (16 * pl.nft / 32);
+    const size_t bits_small = size_t(a.kh * a.kw) * n_chunks_of(a.C) * kCK * 4 * (16 * kFtSmall / 32);
+    const size_t bits_main = size_t(a.kh * a.kw) * n_chunks_of(a.C) * kCK * 4 * (16 * pl.nft / 32);
     fp.lds = pl.lds - bits_main + 2 * bits_small;
     const int64_t pairs_per_blk = 16 * kFtSmall / 2;
     const int64_t fix_blocks = (int64_t(a.k) - 1 + pairs_per_blk - 1) / pairs_per_blk;
-    if (fp.lds > size_t(kPlanLdsMax) || fix_blocks > 65535) return launch_conv_generic_tile_ends(a);
+    if (fp.lds > size_t(kPlanLdsMax) || fix_blocks > 65535 || a.C % kCK != 0) return launch_conv_generic_tile_ends(a);
     const dim3 fgrid(static_cast<unsigned>(pl.nblk), static_cast<unsigned>(a.N), static_cast<unsigned>(fix_blocks));
     return (a.dt == TBN_F32) ? launch_conv_taps<float>(a, P, fp, fgrid) : launch_conv_taps<uint16_t>(a, P, fp, fgrid);
 }

@@ -398,6 +398,13 @@ CONV_SMALL = [
     (128, 32, 4, 4, 128, 3, 3, (1, 1), (1, 1), 3, 3),    # same with tile ends inside filters
     (1, 32, 56, 56, 32, 3, 3, (1, 1), (1, 1), 4, 1),     # 56 wide: one output row per workgroup, the widest 3x3 patch the matrix-core kernel stages
     (1, 32, 20, 62, 32, 3, 3, (1, 1), (1, 1), 2, 2),     # 62 wide, 4 pixel tiles with a ragged last one
+    # channel counts that are no multiple of 32 on the matrix-core kernel: the last chunk of channels is short
+    (2, 3, 32, 32, 64, 3, 3, (1, 1), (1, 1), 4, 4),      # a colour image: one chunk with 3 of 32 channels
+    (2, 48, 14, 14, 64, 3, 3, (1, 1), (1, 1), 8, 1),     # one whole chunk and a half one; whole filters per tile
+    (1, 72, 9, 11, 40, 3, 3, (2, 2), (1, 1), 5, 5),      # 2 1/4 chunks, stride 2, tile starts inside filters (two alphas)
+    (3, 80, 7, 7, 96, 1, 1, (1, 1), (0, 0), 3, 3),       # 1x1 with 2 1/2 chunks, 32 whole filters per tile
+    (2, 33, 10, 10, 33, 3, 3, (1, 1), (1, 1), 11, 11),   # one channel beyond a chunk; 3 filters per tile
+    (1, 17, 12, 12, 24, 3, 3, (1, 1), (1, 1), 9, 9),     # tile starts inside filters of a short chunk
 ]
 
 
