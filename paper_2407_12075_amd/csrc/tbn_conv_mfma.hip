@@ -10,10 +10,11 @@
 // contains a tile end (two alphas) are recomputed afterwards by the shape-agnostic kernel.
 //
 // gfx950 mapping (implicit GEMM on v_mfma_f32_16x16x32_bf16, filters as rows, pixels as columns):
-//   * workgroup = one image, a block of output rows (<= 128 pixels = 8 tiles of 16) and 32 distinct filters:
+//   * workgroup = one image, a block of output rows (<= 128 pixels = 8 tiles of 16; a row whose input patch is too
+//     wide to stage is cut into equal column blocks) and 32 distinct filters:
 //     8 waves, each owning one pixel tile x the 2 tiles of 16 filters (64 filters for bf16 inputs where that
 //     many exist: then 4 waves of two pixel tiles x 4 filter tiles);
-//   * K runs over chunks of 32 input channels; inside a chunk over the kh*kw taps, so that one MFMA
+//   * K runs over chunks of 32 input channels (a short last chunk is filled with zeros); inside a chunk over the kh*kw taps, so that one MFMA
 //     step (K = 32) is "32 channels of one tap".  The input patch of a chunk (with its zero halo)
 //     is staged in LDS channel-last as bf16, which makes the 8 channels a lane needs one 16-byte
 //     LDS read at (pixel + tap offset); float32 inputs are split exactly into three bf16 planes
@@ -62,6 +63,8 @@ struct ConvMfmaParams {
     int32_t aligned;      // p % F == 0
     int32_t n_alpha;
     int32_t rows_per_blk; // output rows per workgroup
+    int32_t cols_per_blk; // output columns per workgroup (Wo unless a row's patch is too wide to stage)
+    int32_t n_colblk;     // column blocks per row block
     int32_t PR, PC;       // input patch rows / columns (with halo)
     int32_t plane_bytes;  // PR*PC*kPixStride
 };
@@ -116,15 +119,18 @@ __global__ __launch_bounds__((64 * waves_of(NFT)), (waves_of(NFT) == 8 ? 4 : 2))
     const int ln = lane & 15, lg = lane >> 4;
     const int n_chunks = static_cast<int>((P.C + kCK - 1) / kCK);   // the last chunk may be short: its missing channels are staged as zeros
     const int64_t img = blockIdx.y;
-    const int row0 = blockIdx.x * P.rows_per_blk;                         // first output row of the block
+    const int rb = blockIdx.x / P.n_colblk, cb = blockIdx.x - rb * P.n_colblk;
+    const int row0 = rb * P.rows_per_blk;                                 // first output row of the block
+    const int col0 = cb * P.cols_per_blk;                                 // first output column
     const int rows = (P.Ho - row0) < P.rows_per_blk ? static_cast<int>(P.Ho - row0) : P.rows_per_blk;
-    const int PX = rows * static_cast<int>(P.Wo);                         // output pixels of the block
+    const int cols = (P.Wo - col0) < P.cols_per_blk ? static_cast<int>(P.Wo - col0) : P.cols_per_blk;
+    const int PX = rows * cols;                                           // output pixels of the block, row-major
     const int64_t u0 = int64_t(blockIdx.z) * kFB;                         // first distinct filter of the block
 
     // ---- staging items: (channel pair cp, valid patch pixel) -> registers -> LDS --------------------
     // valid patch pixels = patch positions inside the image, enumerated row-major
     const int iy_first = row0 * P.sh - P.ph;                               // image row of patch row 0 (may be < 0)
-    const int ix_first = -P.pw;
+    const int ix_first = col0 * P.sw - P.pw;                               // image column of patch column 0 (may be < 0)
     const int py_lo = iy_first < 0 ? -iy_first : 0;
     const int py_hi = (iy_first + P.PR) > P.H ? static_cast<int>(P.H - iy_first) : P.PR;   // exclusive
     const int px_lo = ix_first < 0 ? -ix_first : 0;
@@ -301,7 +307,7 @@ __global__ __launch_bounds__((64 * waves_of(NFT)), (waves_of(NFT) == 8 ? 4 : 2))
         tile_live[j] = pt * 16 < PX;
         int q = pt * 16 + ln;
         q = q < PX ? q : (PX > 0 ? PX - 1 : 0);   // lanes past the block read a valid pixel; results are dropped
-        const int yo = q / static_cast<int>(P.Wo), xo = q % static_cast<int>(P.Wo);
+        const int yo = q / cols, xo = q % cols;
         pix_off[j] = ((yo * P.sh) * P.PC + xo * P.sw) * kPixStride + lg * 16;
     }
     f32x4_t acc[NFT][kTilesPerWave];   // [filter tile][pixel tile]
@@ -451,6 +457,16 @@ __global__ __launch_bounds__((64 * waves_of(NFT)), (waves_of(NFT) == 8 ? 4 : 2))
     // ---- epilogue: y[img, u + t*R, row0.., :] = alpha[t] * Z[u] ---------------------------------------------
     // lane holds pixel ln of its tiles and filters 4*lg + i of each filter tile
     const int64_t plane_out = P.Ho * P.Wo;
+    // pixel q of the block (row-major over rows x cols) sits at (q / cols) * Wo + q % cols from the block's first pixel
+    int out_pix[kTilesPerWave];
+    bool out_live[kTilesPerWave];
+#pragma unroll
+    for (int j = 0; j < kTilesPerWave; ++j) {
+        const int q = (wave + kWaves * j) * 16 + ln;
+        out_live[j] = q < PX;
+        const int yo = q / cols, xo = q - yo * cols;
+        out_pix[j] = yo * static_cast<int>(P.Wo) + xo;
+    }
     if constexpr (FIX) {
         // registers i = 0, 1 and i = 2, 3 of a filter tile are the two halves of a pair
 #pragma unroll
@@ -462,14 +478,13 @@ __global__ __launch_bounds__((64 * waves_of(NFT)), (waves_of(NFT) == 8 ? 4 : 2))
                 const int64_t f = c * P.p, o = f / P.F;
                 if (f == o * P.F || o >= P.O) continue;
                 const float a_before = alpha[c - 1], a_after = alpha[c];
-                XT *dst = y + ((img * P.O + o) * plane_out) + int64_t(row0) * P.Wo;
+                XT *dst = y + ((img * P.O + o) * plane_out) + int64_t(row0) * P.Wo + col0;
 #pragma unroll
                 for (int j = 0; j < kTilesPerWave; ++j) {
-                    const int q = (wave + kWaves * j) * 16 + ln;
-                    if (q >= PX) continue;
+                    if (!out_live[j]) continue;
                     float v = a_before * acc[ft][j][i] + a_after * acc[ft][j][i + 1];
                     if (RELU) v = fmaxf(v, 0.f);
-                    ElemIO<XT>::store(dst + q, v);
+                    ElemIO<XT>::store(dst + out_pix[j], v);
                 }
             }
         return;
@@ -488,14 +503,13 @@ __global__ __launch_bounds__((64 * waves_of(NFT)), (waves_of(NFT) == 8 ? 4 : 2))
                     const int64_t o = u + t * P.R;
                     if (u >= P.R || o >= P.O) continue;
                     const float al = kPerReplica ? al_t : alpha[(o * P.F) / P.p];
-                    XT *dst = y + ((img * P.O + o) * plane_out) + int64_t(row0) * P.Wo;
+                    XT *dst = y + ((img * P.O + o) * plane_out) + int64_t(row0) * P.Wo + col0;
 #pragma unroll
                     for (int j = 0; j < kTilesPerWave; ++j) {
-                        const int q = (wave + kWaves * j) * 16 + ln;
-                        if (q >= PX) continue;
+                        if (!out_live[j]) continue;
                         float v = al * acc[ft][j][i];
                         if (RELU) v = fmaxf(v, 0.f);
-                        ElemIO<XT>::store(dst + q, v);
+                        ElemIO<XT>::store(dst + out_pix[j], v);
                     }
                 }
             }
@@ -508,7 +522,7 @@ constexpr int kPlanLdsMax = 150 * 1024;   // most LDS a plan may ask for
 
 struct ConvPlan {
     bool ok;
-    int rows_per_blk, PR, PC, nblk;
+    int rows_per_blk, cols_per_blk, n_colblk, PR, PC, nblk;   // nblk: row blocks
     size_t lds;
     int items;   // kItemsSmall or kItemsLarge
     int nft;     // kFtSmall or kFtLarge
@@ -516,12 +530,12 @@ struct ConvPlan {
 };
 
 ConvPlan plan_conv(const ConvArgs &a) {
-    ConvPlan pl{false, 0, 0, 0, 0, 0, kItemsSmall, kFtSmall, false};
+    ConvPlan pl{false, 0, 0, 0, 0, 0, 0, 0, kItemsSmall, kFtSmall, false};
     const int64_t F = a.C * a.kh * a.kw;
     const int T = a.kh * a.kw;
     if (T != 1 && T != 9) return pl;                     // instantiated tap counts: 1x1 and 3x3
     if (a.p < F || a.p < 64) return pl;                  // at most one tile end per filter
-    if (a.Wo > kMaxPix || a.Wo <= 0 || a.Ho <= 0) return pl;
+    if (a.Wo <= 0 || a.Ho <= 0 || a.Wo > (1 << 20) || a.Ho > (1 << 20)) return pl;
     if (a.C * a.H * a.W >= (int64_t(1) << 31)) return pl;   // 32-bit element offsets inside an image
     if (a.N > 65535) return pl;
     const int planes = (a.dt == TBN_F32) ? 3 : 1;
@@ -532,26 +546,42 @@ ConvPlan plan_conv(const ConvArgs &a) {
                  ? kFtLarge : kFtSmall;
     const int kFB = 16 * pl.nft;
     const size_t bits_bytes = size_t(T) * n_chunks_of(a.C) * kCK * 4 * (kFB / 32);   // kFB filters * T * ceil(C/32) words
+    // Column blocks: one, unless even a single output row's patch is too wide for the larger staging budget (or the
+    // row has more than kMaxPix pixels); then the fewest equal blocks that fit.
+    int64_t cols = a.Wo, n_colblk = 1;
+    auto row_fits = [&](int64_t c) {
+        const int64_t PC = (c - 1) * a.sw + a.kw, vcols = PC < a.W ? PC : a.W, vrows = a.kh < a.H ? a.kh : a.H;
+        return c <= kMaxPix && vrows * vcols * (kCK / 2) <= int64_t(kItemsLarge);
+    };
+    while (!row_fits(cols)) {
+        if (cols == 1) return pl;
+        ++n_colblk;
+        cols = (a.Wo + n_colblk - 1) / n_colblk;
+    }
     // balanced row blocks of at most kMaxPix pixels whose valid input patch fits the staging budget
-    int64_t rows = kMaxPix / a.Wo;
+    int64_t rows = kMaxPix / cols;
     if (rows > a.Ho) rows = a.Ho;
     int64_t nblk0 = (a.Ho + rows - 1) / rows;
     // With fewer workgroups than CUs (256), halve the row blocks as long as a block keeps at least 3 rows.
     const int64_t fblocks = (R + kFB - 1) / kFB;
-    while (nblk0 * a.N * fblocks < 256 && (a.Ho + 2 * nblk0 - 1) / (2 * nblk0) >= 3) nblk0 *= 2;
+    while (nblk0 * n_colblk * a.N * fblocks < 256 && (a.Ho + 2 * nblk0 - 1) / (2 * nblk0) >= 3) nblk0 *= 2;
     rows = (a.Ho + nblk0 - 1) / nblk0;
     // the smaller staging budget first (less work per thread for the patches it covers)
     for (int items : {kItemsSmall, kItemsLarge}) {
         for (int64_t r = rows; r >= 1; --r) {
-            const int64_t PR = (r - 1) * a.sh + a.kh, PC = (a.Wo - 1) * a.sw + a.kw;
+            const int64_t PR = (r - 1) * a.sh + a.kh, PC = (cols - 1) * a.sw + a.kw;
             const int64_t vrows = PR < a.H ? PR : a.H, vcols = PC < a.W ? PC : a.W;
             const size_t lds = 2 * size_t(planes) * PR * PC * kPixStride + bits_bytes;
             if (vrows * vcols * (kCK / 2) <= int64_t(items) && lds <= size_t(kPlanLdsMax)) {
+                const int64_t nblk = (a.Ho + r - 1) / r;
+                if (nblk * n_colblk > 0x7fffffffLL) return pl;
                 pl.ok = true;
                 pl.rows_per_blk = static_cast<int>(r);
+                pl.cols_per_blk = static_cast<int>(cols);
+                pl.n_colblk = static_cast<int>(n_colblk);
                 pl.PR = static_cast<int>(PR);
                 pl.PC = static_cast<int>(PC);
-                pl.nblk = static_cast<int>((a.Ho + r - 1) / r);
+                pl.nblk = static_cast<int>(nblk);
                 pl.lds = lds;
                 pl.items = items;
                 return pl;
@@ -627,6 +657,8 @@ tbn_status launch_conv_mfma(const ConvArgs &a) {
     P.aligned = (a.p % P.F == 0) ? 1 : 0;
     P.n_alpha = a.n_alpha;
     P.rows_per_blk = pl.rows_per_blk;
+    P.cols_per_blk = pl.cols_per_blk;
+    P.n_colblk = pl.n_colblk;
     P.PR = pl.PR; P.PC = pl.PC;
     P.plane_bytes = pl.PR * pl.PC * kPixStride;
     const int64_t fblocks = (P.R + 16 * pl.nft - 1) / (16 * pl.nft);
@@ -634,7 +666,7 @@ tbn_status launch_conv_mfma(const ConvArgs &a) {
         set_error("tbn_conv2d_forward: too many distinct filters for one launch");
         return TBN_ERR_UNSUPPORTED;
     }
-    const dim3 grid(static_cast<unsigned>(pl.nblk), static_cast<unsigned>(a.N), static_cast<unsigned>(fblocks));
+    const dim3 grid(static_cast<unsigned>(pl.nblk * pl.n_colblk), static_cast<unsigned>(a.N), static_cast<unsigned>(fblocks));
     tbn_status st = (a.dt == TBN_F32) ? launch_conv_taps<float>(a, P, pl, grid) : launch_conv_taps<uint16_t>(a, P, pl, grid);
     if (st != TBN_OK) return st;
     if (a.n_alpha == 1 || P.aligned) return TBN_OK;
@@ -650,7 +682,7 @@ tbn_status launch_conv_mfma(const ConvArgs &a) {
     const int64_t pairs_per_blk = 16 * kFtSmall / 2;
     const int64_t fix_blocks = (int64_t(a.k) - 1 + pairs_per_blk - 1) / pairs_per_blk;
     if (fp.lds > size_t(kPlanLdsMax) || fix_blocks > 65535 || a.C % kCK != 0) return launch_conv_generic_tile_ends(a);
-    const dim3 fgrid(static_cast<unsigned>(pl.nblk), static_cast<unsigned>(a.N), static_cast<unsigned>(fix_blocks));
+    const dim3 fgrid(static_cast<unsigned>(pl.nblk * pl.n_colblk), static_cast<unsigned>(a.N), static_cast<unsigned>(fix_blocks));
     return (a.dt == TBN_F32) ? launch_conv_taps<float>(a, P, fp, fgrid) : launch_conv_taps<uint16_t>(a, P, fp, fgrid);
 }
 

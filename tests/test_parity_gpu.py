@@ -405,6 +405,11 @@ CONV_SMALL = [
     (3, 80, 7, 7, 96, 1, 1, (1, 1), (0, 0), 3, 3),       # 1x1 with 2 1/2 chunks, 32 whole filters per tile
     (2, 33, 10, 10, 33, 3, 3, (1, 1), (1, 1), 11, 11),   # one channel beyond a chunk; 3 filters per tile
     (1, 17, 12, 12, 24, 3, 3, (1, 1), (1, 1), 9, 9),     # tile starts inside filters of a short chunk
+    # rows too wide to stage at once: column blocks
+    (1, 32, 6, 112, 32, 3, 3, (1, 1), (1, 1), 4, 4),     # 112 wide: two column blocks of 56
+    (2, 64, 5, 130, 16, 1, 1, (1, 1), (0, 0), 2, 1),     # 1x1, 130 pixels per row: two blocks of 65
+    (1, 32, 9, 150, 24, 3, 3, (2, 2), (1, 1), 3, 3),     # stride 2, 75 outputs per row in three blocks of 25; two alphas
+    (1, 64, 4, 224, 8, 3, 3, (1, 1), (1, 1), 2, 2),      # 224 wide: four blocks of 56
 ]
 
 
