@@ -69,6 +69,8 @@ typedef enum {
 #define TBN_FLAG_SPLIT_K 0x1000u      /* testing aid (tbn_linear_forward_ws only): split the sum over j among
                                          workgroups wherever the shape allows, also where the cost model expects
                                          no gain */
+#define TBN_FLAG_TILE_KERNEL 0x2000u  /* testing aid (linear only): take the kernel with one wave per 32 batch rows
+                                         wherever it supports the shape */
 
 /* Number of 32-bit words of a tile of n / k entries (ceil(n / k / 32)); 0 if n <= 0, k <= 0 or
  * k does not divide n (the paper requires n divisible by the compression factor). */
@@ -134,7 +136,8 @@ tbn_status tbn_pack_tile_noalloc(const float *w_real, const float *a_real, int64
  *   tile  : DEVICE, tbn_tile_words(in*out, k) words; read only
  *   alpha : DEVICE, n_alpha floats (n_alpha is 1 or k); read only
  *   flags : 0 or TBN_FLAG_RELU (| TBN_FLAG_FORCE_GENERIC | TBN_FLAG_LARGE_BATCH | TBN_FLAG_BLOCK_KERNEL |
- *           TBN_FLAG_STREAM_KERNEL | TBN_FLAG_SPLIT_K, which only tbn_linear_forward_ws looks at)
+ *           TBN_FLAG_STREAM_KERNEL | TBN_FLAG_TILE_KERNEL | TBN_FLAG_SPLIT_K, which only tbn_linear_forward_ws
+ *           looks at)
  * M == 0 is legal and does nothing (x and y may then be NULL).  x and y must not overlap.
  * Errors: TBN_ERR_NULL, TBN_ERR_SHAPE, TBN_ERR_UNSUPPORTED, TBN_ERR_DEVICE.
  */

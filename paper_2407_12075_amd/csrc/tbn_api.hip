@@ -54,6 +54,7 @@ static tbn_status check_tiling(int64_t n, int32_t k, int32_t n_alpha) {
 static tbn_status dispatch_linear(const LinearArgs &a) {
     if (!(a.flags & TBN_FLAG_FORCE_GENERIC)) {
         if (!(a.flags & TBN_FLAG_LARGE_BATCH) && linear_decode_supported(a)) return launch_linear_decode(a);
+        if (!(a.flags & (TBN_FLAG_BLOCK_KERNEL | TBN_FLAG_STREAM_KERNEL)) && linear_tile_preferred(a)) return launch_linear_tile(a);
         if (linear_skinny_supported(a)) return launch_linear_skinny(a);
         if (!(a.flags & TBN_FLAG_BLOCK_KERNEL)) {
             // bfloat16, tile of whole rows: 128 x 128 blocks with load waves; the streaming kernel (64-row half
@@ -61,11 +62,12 @@ static tbn_status dispatch_linear(const LinearArgs &a) {
             // (4096 x 4096, k = 8, batch 512 / 1024 / 2048: 16 / 17 / 20 us against 23 / 22 / 23)
             const int64_t U = a.p % a.in == 0 ? a.p / a.in : 0;
             const int64_t blocks = ((a.M + 127) / 128) * ((U + 127) / 128);
+            if ((a.flags & TBN_FLAG_TILE_KERNEL) && linear_tile_supported(a)) return launch_linear_tile(a);
             const bool stream = (a.flags & TBN_FLAG_STREAM_KERNEL) || blocks < 128;
             if (stream && linear_stream_supported(a)) return launch_linear_stream(a);
             if (linear_block_supported(a)) return launch_linear_block(a);
             // float32, tile of whole rows, few distinct rows: memory-bound layers, one wave per 32 batch rows
-            if (linear_f32tile_supported(a)) return launch_linear_f32tile(a);
+            if (a.dt == TBN_F32 && linear_tile_supported(a)) return launch_linear_tile(a);
         }
         if (linear_mfma_supported(a)) return launch_linear_mfma(a);
         if (linear_rows_supported(a)) return launch_linear_rows(a);
@@ -84,7 +86,7 @@ static tbn_status check_linear_args(const char *fn, const void *x, const void *y
         return TBN_ERR_UNSUPPORTED;
     }
     if (flags & ~(TBN_FLAG_RELU | TBN_FLAG_FORCE_GENERIC | TBN_FLAG_LARGE_BATCH | TBN_FLAG_BLOCK_KERNEL |
-                  TBN_FLAG_STREAM_KERNEL | TBN_FLAG_SPLIT_K)) {
+                  TBN_FLAG_STREAM_KERNEL | TBN_FLAG_SPLIT_K | TBN_FLAG_TILE_KERNEL)) {
         set_error("%s: unknown flag bits 0x%x", fn, flags);
         return TBN_ERR_UNSUPPORTED;
     }
@@ -105,7 +107,7 @@ static tbn_status check_linear_args(const char *fn, const void *x, const void *y
 // Split K with a workspace: not for the batches of the decode and small-batch kernels, not with the flags that name
 // another kernel; otherwise where the block kernel's plan says so.
 static int workspace_splits(const LinearArgs &a) {
-    if (a.flags & (TBN_FLAG_FORCE_GENERIC | TBN_FLAG_BLOCK_KERNEL | TBN_FLAG_STREAM_KERNEL)) return 0;
+    if (a.flags & (TBN_FLAG_FORCE_GENERIC | TBN_FLAG_BLOCK_KERNEL | TBN_FLAG_STREAM_KERNEL | TBN_FLAG_TILE_KERNEL)) return 0;
     if (a.M <= 64) return 0;
     return linear_split_plan(a);
 }

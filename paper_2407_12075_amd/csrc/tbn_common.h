@@ -71,8 +71,9 @@ tbn_status launch_linear_block(const LinearArgs &a);
 int linear_split_plan(const LinearArgs &a);         // split K over workgroups for small grids: number of splits, 0 = none
 size_t linear_split_workspace_bytes(const LinearArgs &a, int splits);
 tbn_status launch_linear_split(const LinearArgs &a, int splits, void *workspace);   // workspace: 16-byte aligned, the bytes above
-bool linear_f32tile_supported(const LinearArgs &a); // float32, tile of whole rows, at most 512 distinct rows: operands straight from global memory
-tbn_status launch_linear_f32tile(const LinearArgs &a);
+bool linear_tile_supported(const LinearArgs &a);   // tile of whole rows, at most 512 distinct rows: one wave per 32 batch rows
+bool linear_tile_preferred(const LinearArgs &a);   // bfloat16 at a few hundred batch rows: faster than the other kernels
+tbn_status launch_linear_tile(const LinearArgs &a);
 tbn_status launch_linear_mfma(const LinearArgs &a);
 
 // column-tiled layer: xf[m, j] = sum_c alpha[c] * x[m, c * q + j], and the float 1.0 written to *one_out

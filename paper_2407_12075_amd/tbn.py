@@ -21,6 +21,7 @@ TBN_FLAG_LARGE_BATCH = 0x200
 TBN_FLAG_BLOCK_KERNEL = 0x400
 TBN_FLAG_STREAM_KERNEL = 0x800
 TBN_FLAG_SPLIT_K = 0x1000
+TBN_FLAG_TILE_KERNEL = 0x2000
 
 _STATUS = {1: "TBN_ERR_NULL", 2: "TBN_ERR_SHAPE", 3: "TBN_ERR_UNSUPPORTED", 4: "TBN_ERR_DEVICE",
            5: "TBN_ERR_WORKSPACE"}

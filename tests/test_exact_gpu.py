@@ -235,3 +235,24 @@ def test_workspace_too_small_or_misaligned(tbn):
     ws = torch.empty(need + 16, dtype=torch.uint8, device="cuda")
     with pytest.raises(RuntimeError):
         tbn.tbn_linear_forward_ws(x, tile, alpha, cout, k, ws[8:], flags=tbn.TBN_FLAG_SPLIT_K)
+
+
+# bfloat16 on the kernel with one wave per 32 batch rows (default for small grids; the flag takes it everywhere)
+EXACT_BF16_TILE = [
+    (512, 4096, 4096, 8),     # 4 groups of 4 column tiles, 8 K slices of 512
+    (1000, 4096, 4096, 8),    # ragged rows
+    (100, 1024, 1088, 8),     # U = 136: two groups of three tiles, the last outside; 4 K slices of two chunks
+    (1000, 2048, 384, 1),     # one replica, three groups
+    (130, 512, 64 * 64, 64),  # 64 replicas, two tiles, 4 K slices of one chunk
+    (300, 128, 256, 2),       # one chunk of K, one K slice
+    (65, 1024, 16, 2),        # U = 8: one tile, eight waves add into it
+    (2100, 256, 2048, 4),     # U = 512: all sixteen column tiles, two chunks
+]
+
+
+@pytest.mark.parametrize("M,cin,cout,k", EXACT_BF16_TILE)
+def test_exact_bf16_wave_per_32_rows(tbn, M, cin, cout, k):
+    flags = tbn.TBN_FLAG_LARGE_BATCH | tbn.TBN_FLAG_TILE_KERNEL
+    _exact_case(tbn, M, cin, cout, k, "bf16", flags, 41 * M + cin)
+    _exact_case(tbn, M, cin, cout, k, "bf16", flags | tbn.TBN_FLAG_RELU, 41 * M + cin + 1,
+                alpha_vals=[2.0 ** ((i % 5) - 2) for i in range(k)])
