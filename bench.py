@@ -359,13 +359,27 @@ def time_other_configs(torch, tbn, wl, iters=30):
         sweep[str(M)] = {"us": round(us, 2), "roof_us": round(roof, 2)}
     out["metric_layer_batch_sweep"] = sweep
     del w, x
-    for c in (wl.CFG3, wl.CFG3_MISALIGNED):
+    # long rows at a few hundred to a few thousand batch rows: the call without and with a workspace (split K)
+    for c in wl.FFN_DOWN:
+        w, x, _ = device_inputs(c, torch, wl)
+        tile, alpha = tbn.tbn_pack_tile(w, c.k, c.n_alpha)
+        y = torch.empty((c.M, c.cout), dtype=x.dtype, device="cuda")
+        need = tbn.tbn_linear_forward_workspace_bytes(x.dtype, c.M, c.cin, c.cout, c.k)
+        ws = torch.empty(max(need, 16), dtype=torch.uint8, device="cuda")
+        us = _timed_us(torch, lambda i: tbn.tbn_linear_forward(x, tile, alpha, c.cout, c.k, y=y), iters)
+        usw = _timed_us(torch, lambda i: tbn.tbn_linear_forward_ws(x, tile, alpha, c.cout, c.k, ws, y=y), iters)
+        byts = (c.M * c.cin + c.M * c.cout) * 2 + c.p // 8
+        alg_flop = 2.0 * c.M * c.cin * (c.p // c.cin)
+        out[c.name] = {"us": round(us, 2), "with_workspace_us": round(usw, 2), "workspace_bytes": need,
+                       "warm": _roof_fields(us, byts, alg_flop, ceil), "with_workspace": _roof_fields(usw, byts, alg_flop, ceil)}
+        del w, x, y, ws
+    for c in (wl.CFG3, wl.CFG3_MISALIGNED, *wl.CONV_MORE):
         w = torch.from_numpy(wl.draw_w_real(c.n, c.cfg, c.layer)).cuda()
-        xv, _ = wl.draw_x((c.N, c.C, c.H, c.W), c.cfg, c.layer, c.dtype)
-        x = torch.from_numpy(xv).cuda()
+        xv, xb = wl.draw_x((c.N, c.C, c.H, c.W), c.cfg, c.layer, c.dtype)
+        x = torch.from_numpy(xv).cuda() if xb is None else torch.from_numpy(xb.view(np.int16)).cuda().view(torch.bfloat16)
         tile, alpha = tbn.tbn_pack_tile(w, c.k, c.n_alpha)
         Ho, Wo = tbn.conv_out_hw(c.H, c.W, c.kh, c.kw, c.stride, c.pad)
-        byts = (x.numel() + c.N * c.O * Ho * Wo) * 4 + c.p // 8
+        byts = (x.numel() + c.N * c.O * Ho * Wo) * x.element_size() + c.p // 8
         nsets = int(max(2, -(-cold_target // byts) + 1))
         xs = [x] + [x.clone() for _ in range(nsets - 1)]
         ys = [torch.empty((c.N, c.O, Ho, Wo), dtype=x.dtype, device="cuda") for _ in range(nsets)]
@@ -377,8 +391,9 @@ def time_other_configs(torch, tbn, wl, iters=30):
         U = min(c.O, c.p // int(np.gcd(filt, c.p)))
         alg_flop = flop * U / c.O
         out[c.name] = {"us": round(us, 2), "cold_us": round(usc, 2), "dense_equiv_tflops": round(flop / us / 1e6, 1),
-                       "alg_gbs": round(byts / us / 1e3, 1), "warm": _roof_fields(us, byts, alg_flop, ceil, 3.0),
-                       "cold": _roof_fields(usc, byts, alg_flop, ceil, 3.0)}
+                       "alg_gbs": round(byts / us / 1e3, 1), "warm": _roof_fields(us, byts, alg_flop, ceil, 3.0 if c.dtype == "f32" else 1.0),
+                       "cold": _roof_fields(usc, byts, alg_flop, ceil, 3.0 if c.dtype == "f32" else 1.0)}
+        del x, xs, ys
     return out
 
 

@@ -546,46 +546,51 @@ ConvPlan plan_conv(const ConvArgs &a) {
                  ? kFtLarge : kFtSmall;
     const int kFB = 16 * pl.nft;
     const size_t bits_bytes = size_t(T) * n_chunks_of(a.C) * kCK * 4 * (kFB / 32);   // kFB filters * T * ceil(C/32) words
-    // Column blocks: one, unless even a single output row's patch is too wide for the larger staging budget (or the
-    // row has more than kMaxPix pixels); then the fewest equal blocks that fit.
-    int64_t cols = a.Wo, n_colblk = 1;
-    auto row_fits = [&](int64_t c) {
-        const int64_t PC = (c - 1) * a.sw + a.kw, vcols = PC < a.W ? PC : a.W, vrows = a.kh < a.H ? a.kh : a.H;
-        return c <= kMaxPix && vrows * vcols * (kCK / 2) <= int64_t(kItemsLarge);
-    };
-    while (!row_fits(cols)) {
-        if (cols == 1) return pl;
-        ++n_colblk;
-        cols = (a.Wo + n_colblk - 1) / n_colblk;
-    }
-    // balanced row blocks of at most kMaxPix pixels whose valid input patch fits the staging budget
-    int64_t rows = kMaxPix / cols;
-    if (rows > a.Ho) rows = a.Ho;
-    int64_t nblk0 = (a.Ho + rows - 1) / rows;
-    // With fewer workgroups than CUs (256), halve the row blocks as long as a block keeps at least 3 rows.
+    // A workgroup's block of output pixels is rows x cols (at most kMaxPix) whose input patch fits a staging budget.
+    // What a pixel costs is mostly the staging of its share of the patch, so among the ways to cut a row into equal
+    // column blocks (one block where the patch of a whole row fits) the plan takes the one with the fewest staged
+    // patch pixels per output pixel: a 56-wide map is cut into blocks of 4 rows x 28 columns (patch 6 x 30, 1.6 staged
+    // pixels per output) rather than 1 row x 56 (3 x 58, 3.1), a 14-wide map stays whole.
     const int64_t fblocks = (R + kFB - 1) / kFB;
-    while (nblk0 * n_colblk * a.N * fblocks < 256 && (a.Ho + 2 * nblk0 - 1) / (2 * nblk0) >= 3) nblk0 *= 2;
-    rows = (a.Ho + nblk0 - 1) / nblk0;
-    // the smaller staging budget first (less work per thread for the patches it covers)
-    for (int items : {kItemsSmall, kItemsLarge}) {
-        for (int64_t r = rows; r >= 1; --r) {
-            const int64_t PR = (r - 1) * a.sh + a.kh, PC = (cols - 1) * a.sw + a.kw;
-            const int64_t vrows = PR < a.H ? PR : a.H, vcols = PC < a.W ? PC : a.W;
-            const size_t lds = 2 * size_t(planes) * PR * PC * kPixStride + bits_bytes;
-            if (vrows * vcols * (kCK / 2) <= int64_t(items) && lds <= size_t(kPlanLdsMax)) {
+    double best_cost = 0;
+    for (int64_t n_colblk = 1; n_colblk <= 16; ++n_colblk) {
+        const int64_t cols = (a.Wo + n_colblk - 1) / n_colblk;
+        if (n_colblk > 1 && (cols < 7 || (a.Wo + cols - 1) / cols != n_colblk)) continue;
+        if (cols > kMaxPix) continue;
+        // balanced row blocks of at most kMaxPix pixels
+        int64_t rows = kMaxPix / cols;
+        if (rows > a.Ho) rows = a.Ho;
+        int64_t nblk0 = (a.Ho + rows - 1) / rows;
+        // With fewer workgroups than CUs (256), halve the row blocks as long as a block keeps at least 3 rows.
+        while (nblk0 * n_colblk * a.N * fblocks < 256 && (a.Ho + 2 * nblk0 - 1) / (2 * nblk0) >= 3) nblk0 *= 2;
+        rows = (a.Ho + nblk0 - 1) / nblk0;
+        bool found = false;
+        // the smaller staging budget first (less work per thread for the patches it covers)
+        for (int items : {kItemsSmall, kItemsLarge}) {
+            for (int64_t r = rows; r >= 1 && !found; --r) {
+                const int64_t PR = (r - 1) * a.sh + a.kh, PC = (cols - 1) * a.sw + a.kw;
+                const int64_t vrows = PR < a.H ? PR : a.H, vcols = PC < a.W ? PC : a.W;
+                const size_t lds = 2 * size_t(planes) * PR * PC * kPixStride + bits_bytes;
+                if (vrows * vcols * (kCK / 2) > int64_t(items) || lds > size_t(kPlanLdsMax)) continue;
                 const int64_t nblk = (a.Ho + r - 1) / r;
-                if (nblk * n_colblk > 0x7fffffffLL) return pl;
-                pl.ok = true;
-                pl.rows_per_blk = static_cast<int>(r);
-                pl.cols_per_blk = static_cast<int>(cols);
-                pl.n_colblk = static_cast<int>(n_colblk);
-                pl.PR = static_cast<int>(PR);
-                pl.PC = static_cast<int>(PC);
-                pl.nblk = static_cast<int>(nblk);
-                pl.lds = lds;
-                pl.items = items;
-                return pl;
+                if (nblk * n_colblk > 0x7fffffffLL) continue;
+                found = true;
+                // one block more per row has to pay for itself: 10 % per extra column block
+                const double cost = double(vrows * vcols) / double(r * cols) * (1.0 + 0.1 * double(n_colblk - 1));
+                if (!pl.ok || cost < best_cost) {
+                    best_cost = cost;
+                    pl.ok = true;
+                    pl.rows_per_blk = static_cast<int>(r);
+                    pl.cols_per_blk = static_cast<int>(cols);
+                    pl.n_colblk = static_cast<int>(n_colblk);
+                    pl.PR = static_cast<int>(PR);
+                    pl.PC = static_cast<int>(PC);
+                    pl.nblk = static_cast<int>(nblk);
+                    pl.lds = lds;
+                    pl.items = items;
+                }
             }
+            if (found) break;
         }
     }
     return pl;

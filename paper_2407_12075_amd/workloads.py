@@ -148,3 +148,18 @@ EXTRA = (
     LinearWorkload("ts_encoder_512_512_k4", 6, 1, 96, 512, 512, 4, 1, "f32"),
     LinearWorkload("ts_encoder_128_512_k2", 6, 2, 96, 128, 512, 2, 1, "f32"),
 )
+
+# Shapes beyond the named configurations that the benchmark's table also times (same recipe, further layers of
+# configurations 3 and 5): convolutions of the CNN section's networks at other map sizes, and a transformer's FFN
+# down-projection (long rows) at a few hundred to a few thousand tokens.
+CONV_MORE = (
+    ConvWorkload("conv3x3_64_56x56_k4_b32", 3, 2, 32, 64, 56, 56, 64, 3, 3, (1, 1), (1, 1), 4, 1),
+    ConvWorkload("conv3x3_64_56x56_k4_b32_bf16", 3, 2, 32, 64, 56, 56, 64, 3, 3, (1, 1), (1, 1), 4, 1, "bf16"),
+    ConvWorkload("conv3x3_128_28x28_k4_b64", 3, 3, 64, 128, 28, 28, 128, 3, 3, (1, 1), (1, 1), 4, 1),
+    ConvWorkload("conv3x3_64_112x112_k4_b8", 3, 4, 8, 64, 112, 112, 64, 3, 3, (1, 1), (1, 1), 4, 1),
+    ConvWorkload("conv3x3_3_32x32_to64_k2_b128", 3, 5, 128, 3, 32, 32, 64, 3, 3, (1, 1), (1, 1), 2, 1),
+    ConvWorkload("conv1x1_256_14x14_to1024_k8_b64_bf16", 3, 6, 64, 256, 14, 14, 1024, 1, 1, (1, 1), (0, 0), 8, 1, "bf16"),
+)
+
+FFN_DOWN = tuple(LinearWorkload(f"ffn_down_16384_4096_k8_b{m}", 5, 10, m, 16384, 4096, 8, 8, "bf16") for m in (256, 512, 1024, 2048))
+
