@@ -17,6 +17,10 @@ void set_error(const char *fmt, ...) {
     va_end(ap);
 }
 
+// An error left behind by an earlier HIP call of the process (outside this library) must not be reported as the
+// failure of the launch that follows: the entry points drop it before they enqueue anything.
+static void drop_stale_error() { (void)hipGetLastError(); }
+
 tbn_status check_launch(const char *what) {
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) {
@@ -52,6 +56,7 @@ static tbn_status check_tiling(int64_t n, int32_t k, int32_t n_alpha) {
 }
 
 static tbn_status dispatch_linear(const LinearArgs &a) {
+    drop_stale_error();
     if (!(a.flags & TBN_FLAG_FORCE_GENERIC)) {
         if (!(a.flags & TBN_FLAG_LARGE_BATCH) && linear_decode_supported(a)) return launch_linear_decode(a);
         if (!(a.flags & (TBN_FLAG_BLOCK_KERNEL | TBN_FLAG_STREAM_KERNEL)) && linear_tile_preferred(a)) return launch_linear_tile(a);
@@ -152,6 +157,7 @@ tbn_status tbn_pack_tile(const float *w_real, const float *a_real, int64_t n, in
                   need, workspace_bytes, workspace);
         return TBN_ERR_WORKSPACE;
     }
+    drop_stale_error();
     return launch_pack(w_real, a_real, n, k, n_alpha, tile_out, alpha_out, workspace,
                        static_cast<hipStream_t>(stream));
 }
@@ -164,6 +170,7 @@ tbn_status tbn_pack_tile_noalloc(const float *w_real, const float *a_real, int64
     }
     tbn_status st = check_tiling(n, k, n_alpha);
     if (st != TBN_OK) return st;
+    drop_stale_error();
     return launch_pack_noalloc(w_real, a_real, n, k, n_alpha, tile_out, alpha_out, static_cast<hipStream_t>(stream));
 }
 
@@ -271,6 +278,7 @@ tbn_status tbn_linear_coltiled_forward(const void *x, void *y, tbn_dtype dt, int
         set_error("n_alpha must be 1 or k (%d), got %d", k, n_alpha);
         return TBN_ERR_SHAPE;
     }
+    if (M == 0) return TBN_OK;   // an empty batch is legal and needs no workspace
     const int64_t q = in / k;
     const size_t xf_bytes = coltile_xf_bytes(dt, M, q), need = xf_bytes + 256;
     if (!workspace || workspace_bytes < need || (reinterpret_cast<uintptr_t>(workspace) & 15u)) {
@@ -278,7 +286,7 @@ tbn_status tbn_linear_coltiled_forward(const void *x, void *y, tbn_dtype dt, int
                   need, workspace_bytes, workspace);
         return TBN_ERR_WORKSPACE;
     }
-    if (M == 0) return TBN_OK;
+    drop_stale_error();
     hipStream_t s = static_cast<hipStream_t>(stream);
     if (k == 1) {   // one block: the flat layer with one tile copy, nothing to fold
         LinearArgs a{x, y, (int)dt, M, in, out, tile, n, 1, alpha, 1, flags, s};
@@ -354,6 +362,7 @@ tbn_status tbn_conv2d_forward(const void *x, void *y, tbn_dtype dt, int64_t N, i
 
     ConvArgs a{x, y, (int)dt, N, C, H, W, O, Ho, Wo, kh, kw, stride_h, stride_w, pad_h, pad_w,
                tile, n / k, k, alpha, n_alpha, flags, static_cast<hipStream_t>(stream)};
+    drop_stale_error();
     if (!(flags & TBN_FLAG_FORCE_GENERIC) && conv_mfma_supported(a)) return launch_conv_mfma(a);
     return launch_conv_generic(a);
 }

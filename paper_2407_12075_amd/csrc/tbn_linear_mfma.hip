@@ -1117,6 +1117,9 @@ bool linear_mfma_supported(const LinearArgs &a) {
     if (a.M > (int64_t(1) << 36)) return false;   // row blocks are counted in 32 bits
     if (reinterpret_cast<uintptr_t>(a.x) & 15u) return false;
     if (a.M < 16) return false;
+    // two alphas inside rows: the repair pass that follows the main kernel must be able to run (its limit on the
+    // batch), so that an unsupported shape is refused before anything is enqueued
+    if (a.n_alpha > 1 && a.p % a.in != 0 && a.M > int64_t(65535) * 16) return false;
     return true;
 }
 

@@ -393,6 +393,7 @@ SkinnyParams make_params(const LinearArgs &a) {
 // kernels win again.
 bool linear_skinny_supported(const LinearArgs &a) {
     if (!shape_ok(a)) return false;
+    if (a.n_alpha > 1 && a.p % a.in != 0 && a.M > int64_t(65535) * 16) return false;   // the repair pass could not follow
     if (a.M <= 64) return true;
     if ((a.flags & TBN_FLAG_LARGE_BATCH) || a.in < 256) return false;
     const int64_t U = unique_rows(a.out, a.in, a.p);

@@ -108,6 +108,19 @@ def _dev(t: torch.Tensor, name: str, dtype=None) -> int:
     return t.data_ptr()
 
 
+def _check_layer_tensors(fn: str, x: torch.Tensor, tile: torch.Tensor, alpha: torch.Tensor, n: int, k: int, *others):
+    """Sizes and devices the C side cannot see behind raw pointers: an undersized tile or alpha would be an
+    out-of-bounds device read.  (Illegal n, k, n_alpha are left to the C side, which reports them.)"""
+    words = tbn_tile_words(n, k) if k > 0 else 0
+    if words and tile.numel() < words:
+        raise ValueError(f"{fn}: tile has {tile.numel()} words, {words} needed")
+    if alpha.numel() < 1:
+        raise ValueError(f"{fn}: alpha is empty")
+    for t in (tile, alpha, *others):
+        if t is not None and t.device != x.device:
+            raise ValueError(f"{fn}: all tensors must live on {x.device}")
+
+
 def _dt(t: torch.Tensor) -> int:
     if t.dtype == torch.float32:
         return TBN_F32
@@ -142,6 +155,9 @@ def tbn_pack_tile(w_real: torch.Tensor, k: int, n_alpha: int = 1, a_real: Option
     need = tbn_pack_workspace_bytes(n, k, n_alpha)
     if workspace is None:
         workspace = torch.empty(max(need, 8), dtype=torch.uint8, device=dev)
+    if tile_out.numel() < words or alpha_out.numel() < n_alpha or any(t.device != dev for t in (tile_out, alpha_out, workspace)) \
+            or (a_real is not None and (a_real.numel() != n or a_real.device != dev)):
+        raise ValueError("tbn_pack_tile: tile_out, alpha_out, a_real or workspace too small or on another device")
     st = lib().tbn_pack_tile(_dev(w_real, "w_real", torch.float32),
                              None if a_real is None else _dev(a_real, "a_real", torch.float32),
                              n, k, n_alpha, _dev(tile_out, "tile_out", torch.int32),
@@ -155,6 +171,9 @@ def tbn_pack_tile(w_real: torch.Tensor, k: int, n_alpha: int = 1, a_real: Option
 def tbn_pack_tile_noalloc(w_real: torch.Tensor, k: int, n_alpha: int, tile_out: torch.Tensor, alpha_out: torch.Tensor,
                           a_real: Optional[torch.Tensor] = None, stream=None) -> None:
     """tbn_pack_tile without a workspace; the outputs are the caller's (this wrapper allocates nothing either)."""
+    if tile_out.numel() < tbn_tile_words(w_real.numel(), k) or alpha_out.numel() < n_alpha or tile_out.device != w_real.device \
+            or alpha_out.device != w_real.device or (a_real is not None and (a_real.numel() != w_real.numel() or a_real.device != w_real.device)):
+        raise ValueError("tbn_pack_tile_noalloc: tile_out, alpha_out or a_real too small or on another device")
     st = lib().tbn_pack_tile_noalloc(_dev(w_real, "w_real", torch.float32),
                                      None if a_real is None else _dev(a_real, "a_real", torch.float32),
                                      w_real.numel(), k, n_alpha, _dev(tile_out, "tile_out", torch.int32),
@@ -173,6 +192,7 @@ def tbn_linear_forward(x: torch.Tensor, tile: torch.Tensor, alpha: torch.Tensor,
         y = torch.empty((M, out_features), dtype=x.dtype, device=x.device)
     elif tuple(y.shape) != (M, out_features) or y.dtype != x.dtype:
         raise ValueError("y must be (M, out) with x's dtype")
+    _check_layer_tensors("tbn_linear_forward", x, tile, alpha, cin * out_features, k, y)
     st = lib().tbn_linear_forward(_dev(x, "x"), _dev(y, "y"), _dt(x), M, cin, out_features,
                                   _dev(tile, "tile", torch.int32), k, _dev(alpha, "alpha", torch.float32),
                                   alpha.numel(), flags, _stream(stream))
@@ -198,6 +218,7 @@ def tbn_linear_forward_ws(x: torch.Tensor, tile: torch.Tensor, alpha: torch.Tens
         y = torch.empty((M, out_features), dtype=x.dtype, device=x.device)
     elif tuple(y.shape) != (M, out_features) or y.dtype != x.dtype:
         raise ValueError("y must be (M, out) with x's dtype")
+    _check_layer_tensors("tbn_linear_forward_ws", x, tile, alpha, cin * out_features, k, y, workspace)
     ws_ptr = None if workspace is None else _dev(workspace, "workspace")
     ws_bytes = 0 if workspace is None else workspace.numel() * workspace.element_size()
     st = lib().tbn_linear_forward_ws(_dev(x, "x"), _dev(y, "y"), _dt(x), M, cin, out_features,
@@ -251,6 +272,7 @@ def tbn_linear_coltiled_forward(x: torch.Tensor, tile: torch.Tensor, alpha: torc
         raise ValueError("y must be (M, out) with x's dtype")
     if workspace is None:
         workspace = torch.empty(max(tbn_linear_coltiled_workspace_bytes(x, k), 16), dtype=torch.uint8, device=x.device)
+    _check_layer_tensors("tbn_linear_coltiled_forward", x, tile, alpha, cin * out_features, k, y, workspace)
     st = lib().tbn_linear_coltiled_forward(_dev(x, "x"), _dev(y, "y"), _dt(x), M, cin, out_features,
                                            _dev(tile, "tile", torch.int32), k, _dev(alpha, "alpha", torch.float32),
                                            alpha.numel(), flags, _dev(workspace, "workspace"),
@@ -272,6 +294,7 @@ def tbn_conv2d_forward(x: torch.Tensor, tile: torch.Tensor, alpha: torch.Tensor,
         y = torch.empty((N, out_channels, max(Ho, 0), max(Wo, 0)), dtype=x.dtype, device=x.device)
     elif tuple(y.shape) != (N, out_channels, Ho, Wo) or y.dtype != x.dtype:
         raise ValueError("y must be (N, O, Ho, Wo) with x's dtype")
+    _check_layer_tensors("tbn_conv2d_forward", x, tile, alpha, out_channels * C * kh * kw, k, y)
     st = lib().tbn_conv2d_forward(_dev(x, "x"), _dev(y, "y"), _dt(x), N, C, H, W, out_channels, kh, kw,
                                   stride[0], stride[1], pad[0], pad[1], _dev(tile, "tile", torch.int32), k,
                                   _dev(alpha, "alpha", torch.float32), alpha.numel(), flags, _stream(stream))
