@@ -13,8 +13,8 @@
 //     have to issue -- and above all the global -> LDS wave-loads, which block the wave's whole instruction
 //     stream whenever the CU's load path is busy.  The workgroup therefore has eight waves: four MFMA waves
 //     (one per SIMD) that only read LDS and multiply, and four load waves that issue every wave-load of the
-//     main loop and otherwise sleep at the round's barrier.  (LOADERS = false builds the same kernel with
-//     the MFMA waves loading for themselves, for comparison.)
+//     main loop and otherwise sleep at the round's barrier (with the MFMA waves loading for themselves, one
+//     wave-load in an MFMA slot each, the same kernel measured 46.1 us against 42.6 on 8192 x 4096 -> 4096).
 //   * MFMA wave (g, h) owns 128 rows x 64 columns of the block over the K stages congruent to g (mod 2):
 //     4 x 2 MFMA tiles, the +-1 rows as the row operand, six LDS operand reads per eight MFMAs.  The two
 //     K groups add their partial sums through LDS at the end.
@@ -146,11 +146,10 @@ __device__ __forceinline__ void block_coords(const BlockParams &P, uint32_t &vro
     }
 }
 
-// RELU: fused max(0, .) of Algorithm 1.  LOADERS: waves 4 .. 7 issue the loads (512 threads), else the MFMA
-// waves do it themselves between their MFMAs (256 threads).  SPLIT: the workgroup takes one of P.splits equal parts
-// of K and writes float32 partial sums to P.partial instead of Y.
-template <bool RELU, bool LOADERS, bool SPLIT>
-__global__ __launch_bounds__(LOADERS ? 512 : 256, 1) void linear_block_bf16_kernel(const uint16_t *__restrict__ x,
+// RELU: fused max(0, .) of Algorithm 1.  SPLIT: the workgroup takes one of P.splits equal parts of K and writes
+// float32 partial sums to P.partial instead of Y.  512 threads: waves 0 .. 3 multiply, waves 4 .. 7 load.
+template <bool RELU, bool SPLIT>
+__global__ __launch_bounds__(512, 1) void linear_block_bf16_kernel(const uint16_t *__restrict__ x,
                                                                                      uint16_t *__restrict__ y,
                                                                                      const uint32_t *__restrict__ tile,
                                                                                      const float *__restrict__ alpha,
@@ -235,7 +234,7 @@ __global__ __launch_bounds__(LOADERS ? 512 : 256, 1) void linear_block_bf16_kern
     // =================================================================================================
     // load waves
     // =================================================================================================
-    if (LOADERS && wave >= 4) {
+    if (wave >= 4) {
         // rounds 0 .. 2 at once; then, at the top of every round, the loads of round + 3 into the slot that the
         // barrier has just freed
         for (int32_t d = 0; d < 3 && d < n_rounds; ++d) issue_round(d);
@@ -270,9 +269,6 @@ __global__ __launch_bounds__(LOADERS ? 512 : 256, 1) void linear_block_bf16_kern
         const int t = P.n_alpha == 1 ? 0 : (lane < P.reps ? lane : P.reps - 1);
         const uint32_t off = static_cast<uint32_t>(t) * 4u;
         asm volatile("global_load_dword %0, %1, %2" : "=v"(alpha_lanes) : "v"(off), "s"(alpha));
-    }
-    if (!LOADERS) {
-        for (int32_t d = 0; d < 3 && d < n_rounds; ++d) issue_round(d);
     }
 
     // sign table: entry e, element i is +1 if bit i of e is set, else -1
@@ -315,10 +311,6 @@ __global__ __launch_bounds__(LOADERS ? 512 : 256, 1) void linear_block_bf16_kern
     };
 
     // ---- first operands -------------------------------------------------------------------------
-    if (!LOADERS) {
-        if (n_rounds >= 3) __builtin_amdgcn_s_waitcnt(vmcnt_imm(8 + 8 + 1));
-        else __builtin_amdgcn_s_waitcnt(vmcnt_imm(0));
-    }
     lds_wait<0>();   // the table
     __builtin_amdgcn_s_barrier();   // table written, round 0 readable
     lds_read2x8(win[0], w_rd);      // windows of round 0: chunk slot 0, piece 0
@@ -392,12 +384,6 @@ __global__ __launch_bounds__(LOADERS ? 512 : 256, 1) void linear_block_bf16_kern
     // of the first K step have been requested into set 0.
     auto round = [&](auto par_c, int32_t g) __attribute__((always_inline)) {
         constexpr int PAR = decltype(par_c)::value;
-        if (!LOADERS) {
-            // the loads of round g + 2 (eight, and the tile chunk with an even round) are younger than those of
-            // round g + 1 and may stay in flight; past the end, where fewer loads were issued, everything lands
-            if (g + 2 < n_rounds) __builtin_amdgcn_s_waitcnt(vmcnt_imm(PAR == 0 ? 9 : 8));
-            else __builtin_amdgcn_s_waitcnt(vmcnt_imm(0));
-        }
         __builtin_amdgcn_s_barrier();
         const uint32_t cur = static_cast<uint32_t>((g & (kNB - 1)) * kSlotBytes);
         const uint32_t nxt = static_cast<uint32_t>(((g + 1) & (kNB - 1)) * kSlotBytes);
@@ -406,43 +392,16 @@ __global__ __launch_bounds__(LOADERS ? 512 : 256, 1) void linear_block_bf16_kern
         const uint32_t w_addr = w_rd + static_cast<uint32_t>((((g + 1) >> 1) % kTileSlots) * kTileSlotBytes + (PAR == 0 ? 2048 : 0));
         u32x4_t &wc = win[PAR];       // this round's windows
         u32x4_t &wx = win[PAR ^ 1];   // the next round's
-        const bool load_now = !LOADERS && g + 3 < n_rounds;   // uniform
-        auto loads = [&](auto slot_c) __attribute__((always_inline)) {   // MFMA waves that load for themselves: one per slot
-            constexpr int SLOT = decltype(slot_c)::value;
-            if constexpr (!LOADERS) {
-                if (load_now) {
-                    if constexpr (SLOT == 6) issue_x(Int<0>{}, g + 3);
-                    if constexpr (SLOT == 7) issue_x(Int<1>{}, g + 3);
-                    if constexpr (SLOT == 14) issue_x(Int<2>{}, g + 3);
-                    if constexpr (SLOT == 15) issue_x(Int<3>{}, g + 3);
-                    if constexpr (SLOT == 22) issue_x(Int<4>{}, g + 3);
-                    if constexpr (SLOT == 23) issue_x(Int<5>{}, g + 3);
-                    if constexpr (SLOT == 30) issue_x(Int<6>{}, g + 3);
-                    if constexpr (SLOT == 31) {
-                        issue_x(Int<7>{}, g + 3);
-                        if constexpr (PAR == 1) issue_tile(g + 3);
-                    }
-                }
-            }
-        };
         kstep(Int<0>{}, Int<0>{}, a_rd[1] + cur, wc[0], wc[2], Int<1>{}, [&](auto slot_c) __attribute__((always_inline)) {
             constexpr int SLOT = decltype(slot_c)::value;
             if constexpr (SLOT == 6) lds_read2x8(wx, w_addr);
-            if constexpr (SLOT >= 0) loads(Int<SLOT>{});
         });
-        kstep(Int<1>{}, Int<1>{}, a_rd[2] + cur, wc[1], wc[3], Int<0>{}, [&](auto slot_c) __attribute__((always_inline)) {
-            constexpr int SLOT = decltype(slot_c)::value;
-            if constexpr (SLOT >= 0) loads(Int<8 + SLOT>{});
-        });
+        kstep(Int<1>{}, Int<1>{}, a_rd[2] + cur, wc[1], wc[3], Int<0>{}, [&](auto) __attribute__((always_inline)) {});
         kstep(Int<0>{}, Int<0>{}, a_rd[3] + cur, wc[1], wc[3], Int<1>{}, [&](auto slot_c) __attribute__((always_inline)) {
             constexpr int SLOT = decltype(slot_c)::value;
             if constexpr (SLOT == -1) tie(wx);   // the window read is older than this step's operands
-            if constexpr (SLOT >= 0) loads(Int<16 + SLOT>{});
         });
-        kstep(Int<1>{}, Int<0>{}, a_rd[0] + nxt, wx[0], wx[2], Int<0>{}, [&](auto slot_c) __attribute__((always_inline)) {
-            constexpr int SLOT = decltype(slot_c)::value;
-            if constexpr (SLOT >= 0) loads(Int<24 + SLOT>{});
-        });
+        kstep(Int<1>{}, Int<0>{}, a_rd[0] + nxt, wx[0], wx[2], Int<0>{}, [&](auto) __attribute__((always_inline)) {});
     };
 
     // One plain loop over pairs of rounds; the operands that its last round requests (of a round that does not
@@ -689,10 +648,6 @@ bool linear_block_supported(const LinearArgs &a) {
     return blocks <= 0x7fffffffLL;
 }
 
-#ifndef TBN_BLOCK_LOADERS
-#define TBN_BLOCK_LOADERS 1
-#endif
-
 // Split K: how many workgroups share a block's K loop so that the grid about fills the chip (0: no split).  A part
 // is a whole number of round pairs (256 elements of K) and at least one.  The split costs a second launch and a
 // round trip of the float32 partial sums, about 12 us more fixed time than one kernel on MI355X, so it is taken
@@ -730,7 +685,7 @@ tbn_status launch_linear_split(const LinearArgs &a, int splits, void *workspace)
     P.partial = static_cast<float *>(workspace);
     const int64_t wgs = int64_t(P.vrows) * P.tiles_n;
     typedef void (*kernel_t)(const uint16_t *, uint16_t *, const uint32_t *, const float *, BlockParams);
-    static const kernel_t kernel = &linear_block_bf16_kernel<false, true, true>;
+    static const kernel_t kernel = &linear_block_bf16_kernel<false, true>;
     static const tbn_status attr = set_lds_limit_once(reinterpret_cast<const void *>(kernel), kLdsBytes);
     if (attr != TBN_OK) {
         set_error("tbn_linear_forward_ws: cannot reserve %d bytes of LDS for the block kernel", kLdsBytes);
@@ -755,9 +710,8 @@ tbn_status launch_linear_block(const LinearArgs &a) {
     P.stream_stores = int64_t(P.tiles_m) * P.tiles_n > device_cus() ? 1 : 0;
     const dim3 grid(static_cast<unsigned>(int64_t(P.tiles_m) * P.tiles_n));
     const bool relu = (a.flags & TBN_FLAG_RELU) != 0;
-    constexpr bool kLoaders = TBN_BLOCK_LOADERS != 0;
     typedef void (*kernel_t)(const uint16_t *, uint16_t *, const uint32_t *, const float *, BlockParams);
-    static const kernel_t kernels[2] = {&linear_block_bf16_kernel<false, kLoaders, false>, &linear_block_bf16_kernel<true, kLoaders, false>};
+    static const kernel_t kernels[2] = {&linear_block_bf16_kernel<false, false>, &linear_block_bf16_kernel<true, false>};
     // dynamic LDS above the default limit has to be allowed once per kernel (thread-safe static initialisation)
     static const tbn_status attr[2] = {set_lds_limit_once(reinterpret_cast<const void *>(kernels[0]), kLdsBytes),
                                        set_lds_limit_once(reinterpret_cast<const void *>(kernels[1]), kLdsBytes)};
@@ -765,7 +719,7 @@ tbn_status launch_linear_block(const LinearArgs &a) {
         set_error("tbn_linear_forward: cannot reserve %d bytes of LDS for the block kernel", kLdsBytes);
         return TBN_ERR_DEVICE;
     }
-    hipLaunchKernelGGL(kernels[relu ? 1 : 0], grid, dim3(kLoaders ? 512 : 256), kLdsBytes, a.stream,
+    hipLaunchKernelGGL(kernels[relu ? 1 : 0], grid, dim3(512), kLdsBytes, a.stream,
                        static_cast<const uint16_t *>(a.x), static_cast<uint16_t *>(a.y), a.tile, a.alpha, P);
     return check_launch("tbn_linear_forward (matrix-core kernel with load waves)");
 }
