@@ -129,8 +129,7 @@ template <int V> using Int = std::integral_constant<int, V>;
 // Workgroups that share rows of X are given consecutive slots on one XCD (workgroup ids are dealt
 // round-robin to the 8 XCDs), so the later column blocks find X in that XCD's L2.
 // With split K the unit that shares data is a (row block, split) pair: vrow counts those.
-__device__ __forceinline__ void block_coords(const BlockParams &P, uint32_t &vrow, uint32_t &tile_n) {
-    const uint32_t bid = blockIdx.x;
+__device__ __forceinline__ void block_coords(const BlockParams &P, uint32_t bid, uint32_t &vrow, uint32_t &tile_n) {
     const uint32_t xcd = bid & 7, slot = bid >> 3;
     const uint32_t tiles_n = static_cast<uint32_t>(P.tiles_n);
     const uint32_t per_xcd_full = (P.vrows / 8) * tiles_n;   // slots per XCD in the regular part
@@ -148,7 +147,11 @@ __device__ __forceinline__ void block_coords(const BlockParams &P, uint32_t &vro
 
 // RELU: fused max(0, .) of Algorithm 1.  SPLIT: the workgroup takes one of P.splits equal parts of K and writes
 // float32 partial sums to P.partial instead of Y.  512 threads: waves 0 .. 3 multiply, waves 4 .. 7 load.
-template <bool RELU, bool SPLIT>
+// PERSIST (grids of more blocks than CUs; rounds in fours): the workgroup walks blocks blockIdx.x, + gridDim.x, ...;
+// while the MFMA waves hand over and store a block, the load waves already have the first two rounds of the next
+// one in flight, so that only the first block of a workgroup waits for memory before its first MFMA.  The ring's
+// slots 0 and 1 take those rounds, which is why the hand-over then uses slots 2 and 3.
+template <bool RELU, bool SPLIT, bool PERSIST>
 __global__ __launch_bounds__(512, 1) void linear_block_bf16_kernel(const uint16_t *__restrict__ x,
                                                                                      uint16_t *__restrict__ y,
                                                                                      const uint32_t *__restrict__ tile,
@@ -164,18 +167,11 @@ __global__ __launch_bounds__(512, 1) void linear_block_bf16_kernel(const uint16_
     const int ln = lane & 31;    // operand lane inside a 32 x 32 tile
     const int lg = lane >> 5;    // K half of the operand registers
 
-    uint32_t tile_m, tile_n;
-    block_coords(P, tile_m, tile_n);
-    uint32_t split = 0;
-    if (SPLIT) {
-        const uint32_t vrow = tile_m;
-        tile_m = vrow / static_cast<uint32_t>(P.splits);
-        split = vrow - tile_m * static_cast<uint32_t>(P.splits);
-    }
-    const uint32_t round0 = split * static_cast<uint32_t>(P.n_rounds);   // first round of this workgroup's part of K (even)
-    const int64_t m0 = int64_t(tile_m) * kBM;
-    const int32_t n0 = static_cast<int32_t>(tile_n) * kBN;
+    static_assert(!(SPLIT && PERSIST), "a split grid never has more workgroups than CUs");
+    constexpr int kXchg = PERSIST ? kRingOff + 2 * kSlotBytes : kXchgOff;   // hand-over area
     const int32_t n_rounds = P.n_rounds;
+    const uint32_t n_blocks = P.vrows * static_cast<uint32_t>(P.tiles_n);
+    uint32_t bid = blockIdx.x;
 
     // ---- the loads of a round, a quarter per loading wave -----------------------------------------------
     // Activations: wave-load j of loader li fills 1 KiB of K group li / 2's 16 KiB: piece q = 8*(li % 2) + j, row
@@ -187,11 +183,27 @@ __global__ __launch_bounds__(512, 1) void linear_block_bf16_kernel(const uint16_
     // tile row that operand lane l of column half h supplies for MFMA tile tn, i.e. column
     // 64*h + 16*(l/8) + 8*((l/4)%2) + 4*tn + l%4 of the block (with this numbering a lane ends up with eight
     // adjacent columns of one row of Y).
-    const unsigned char *x_blk = reinterpret_cast<const unsigned char *>(x) + m0 * P.in * 2 + (grp * 128 - kBias) + round0 * 256u;
-    const unsigned char *tile_bytes = reinterpret_cast<const unsigned char *>(tile) + round0 * 16u;
+    uint32_t split = 0;
+    int64_t m0 = 0;
+    int32_t n0 = 0;
+    const unsigned char *x_blk = nullptr;
+    const unsigned char *tile_bytes = nullptr;
     uint32_t a_off[8];
-    uint32_t t_off;
-    {
+    uint32_t t_off = 0;
+    auto set_block = [&](uint32_t b) __attribute__((always_inline)) {
+        uint32_t tile_m, tile_n;
+        block_coords(P, b, tile_m, tile_n);
+        split = 0;
+        if (SPLIT) {
+            const uint32_t vrow = tile_m;
+            tile_m = vrow / static_cast<uint32_t>(P.splits);
+            split = vrow - tile_m * static_cast<uint32_t>(P.splits);
+        }
+        const uint32_t round0 = split * static_cast<uint32_t>(P.n_rounds);   // first round of this workgroup's part of K (even)
+        m0 = int64_t(tile_m) * kBM;
+        n0 = static_cast<int32_t>(tile_n) * kBN;
+        x_blk = reinterpret_cast<const unsigned char *>(x) + m0 * P.in * 2 + (grp * 128 - kBias) + round0 * 256u;
+        tile_bytes = reinterpret_cast<const unsigned char *>(tile) + round0 * 16u;
         const int64_t last = P.M - 1 - m0;
 #pragma unroll
         for (int j = 0; j < 8; ++j) {
@@ -205,7 +217,8 @@ __global__ __launch_bounds__(512, 1) void linear_block_bf16_kernel(const uint16_
         int32_t u = n0 + (rho & 64) + 16 * (l >> 3) + 8 * ((l >> 2) & 1) + 4 * ((rho >> 5) & 1) + (l & 3);
         u = u < P.U ? u : P.U - 1;   // columns past U repeat the last one; they are never written
         t_off = static_cast<uint32_t>(u) * (static_cast<uint32_t>(P.in) >> 3) + static_cast<uint32_t>((S >> 7) * 16);
-    }
+    };
+    set_block(bid);
     unsigned char *const ring_mine = lds_raw + kRingOff + grp * 16384 + wn * 8192;
     unsigned char *const tring_mine = lds_raw + kTileOff + li * 1024;
     // issue order per round, which the wait counts rely on: eight activation wave-loads, then (even rounds) the
@@ -235,28 +248,48 @@ __global__ __launch_bounds__(512, 1) void linear_block_bf16_kernel(const uint16_
     // load waves
     // =================================================================================================
     if (wave >= 4) {
-        // rounds 0 .. 2 at once; then, at the top of every round, the loads of round + 3 into the slot that the
-        // barrier has just freed
-        for (int32_t d = 0; d < 3 && d < n_rounds; ++d) issue_round(d);
-        // round 0 is readable once it has landed (two younger rounds may be in flight)
-        if (n_rounds >= 3) __builtin_amdgcn_s_waitcnt(vmcnt_imm(8 + 8 + 1));
-        else __builtin_amdgcn_s_waitcnt(vmcnt_imm(0));
-        __builtin_amdgcn_s_barrier();   // meets the MFMA waves' "table written, round 0 readable"
-        for (int32_t g = 0; g < n_rounds; ++g) {
-            // round g + 1 has to be readable when the MFMA waves pass this barrier; the loads of round g + 2 (eight,
-            // and the tile chunk with an even round) are younger and may stay in flight
-            if (g + 2 < n_rounds) {
-                if (g & 1) __builtin_amdgcn_s_waitcnt(vmcnt_imm(8));
-                else __builtin_amdgcn_s_waitcnt(vmcnt_imm(9));
+        if (PERSIST) { issue_round(0); issue_round(1); }
+        for (;;) {
+            if (PERSIST) {
+                // rounds 0 and 1 of this block are in flight (issued at kernel start, or while the previous block was
+                // handed over); round 0 and its tile chunk have to land, round 1's eight loads are younger
+                __builtin_amdgcn_s_waitcnt(vmcnt_imm(8));
+                __builtin_amdgcn_s_barrier();   // meets the MFMA waves' "round 0 readable; the hand-over area is free"
+                issue_round(2);
             } else {
-                __builtin_amdgcn_s_waitcnt(vmcnt_imm(0));
+                // rounds 0 .. 2 at once; then, at the top of every round, the loads of round + 3 into the slot that the
+                // barrier has just freed
+                for (int32_t d = 0; d < 3 && d < n_rounds; ++d) issue_round(d);
+                // round 0 is readable once it has landed (two younger rounds may be in flight)
+                if (n_rounds >= 3) __builtin_amdgcn_s_waitcnt(vmcnt_imm(8 + 8 + 1));
+                else __builtin_amdgcn_s_waitcnt(vmcnt_imm(0));
+                __builtin_amdgcn_s_barrier();   // meets the MFMA waves' "table written, round 0 readable"
             }
+            for (int32_t g = 0; g < n_rounds; ++g) {
+                // round g + 1 has to be readable when the MFMA waves pass this barrier; the loads of round g + 2 (eight,
+                // and the tile chunk with an even round) are younger and may stay in flight
+                if (g + 2 < n_rounds) {
+                    if (g & 1) __builtin_amdgcn_s_waitcnt(vmcnt_imm(8));
+                    else __builtin_amdgcn_s_waitcnt(vmcnt_imm(9));
+                } else {
+                    __builtin_amdgcn_s_waitcnt(vmcnt_imm(0));
+                }
+                __builtin_amdgcn_s_barrier();
+                if (g + 3 < n_rounds) issue_round(g + 3);
+            }
+            // the barrier of the last round has freed ring slots 0 .. 2 and the tile slot of chunk 0
+            const uint32_t next = bid + gridDim.x;
+            const bool more = PERSIST && next < n_blocks;
+            if (more) {
+                bid = next;
+                set_block(bid);
+                issue_round(0);
+                issue_round(1);
+            }
+            __builtin_amdgcn_s_barrier();   // the two barriers of the hand-over
             __builtin_amdgcn_s_barrier();
-            if (g + 3 < n_rounds) issue_round(g + 3);
+            if (!more) return;
         }
-        __builtin_amdgcn_s_barrier();   // the two barriers of the hand-over
-        __builtin_amdgcn_s_barrier();
-        return;
     }
 
     // =================================================================================================
@@ -294,13 +327,6 @@ __global__ __launch_bounds__(512, 1) void linear_block_bf16_kernel(const uint16_
     asm volatile("" : "+v"(bsh[0]), "+v"(bsh[1]));
 
     f32x16_t acc[4][2];
-#pragma unroll
-    for (int i = 0; i < 4; ++i)
-#pragma unroll
-        for (int j = 0; j < 2; ++j)
-#pragma unroll
-            for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.f;
-
     Frag A[2][4];       // [operand set][tm]
     Frag B[2][2];       // [operand set][tn]
     u32x4_t win[2];     // [round parity]: words 0-1 the 64 window bits of column tn = 0, words 2-3 of tn = 1
@@ -310,24 +336,11 @@ __global__ __launch_bounds__(512, 1) void linear_block_bf16_kernel(const uint16_
         lds_read16<kTableOff>(dst, addr);
     };
 
-    // ---- first operands -------------------------------------------------------------------------
-    lds_wait<0>();   // the table
-    __builtin_amdgcn_s_barrier();   // table written, round 0 readable
-    lds_read2x8(win[0], w_rd);      // windows of round 0: chunk slot 0, piece 0
-    lds_wait<0>();
-    tie(win[0]);
-    table_read(B[0][0].q, win[0][0], bsh[0]);
-    lds_read16<0>(A[0][0].q, a_rd[0]);
-    table_read(B[0][1].q, win[0][2], bsh[0]);
-    lds_read16<4096>(A[0][1].q, a_rd[0]);
-    lds_read16<8192>(A[0][2].q, a_rd[0]);
-    lds_read16<12288>(A[0][3].q, a_rd[0]);
     auto settle = [&]() {   // all of operand set 0 has landed
         lds_wait<0>();
         tie(B[0][0].q); tie(B[0][1].q);
         tie(A[0][0].q); tie(A[0][1].q); tie(A[0][2].q); tie(A[0][3].q);
     };
-    settle();
 
     // ---- one K step: 8 MFMAs ---------------------------------------------------------------------
     // Multiplies with operand set S and requests the operands of the following K step into the other set: six
@@ -404,6 +417,28 @@ __global__ __launch_bounds__(512, 1) void linear_block_bf16_kernel(const uint16_
         kstep(Int<1>{}, Int<0>{}, a_rd[0] + nxt, wx[0], wx[2], Int<0>{}, [&](auto) __attribute__((always_inline)) {});
     };
 
+    lds_wait<0>();   // the table
+    for (;;) {   // one block per pass (a single pass unless PERSIST)
+#pragma unroll
+    for (int i = 0; i < 4; ++i)
+#pragma unroll
+        for (int j = 0; j < 2; ++j)
+#pragma unroll
+            for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.f;
+
+    // ---- first operands -------------------------------------------------------------------------
+    __builtin_amdgcn_s_barrier();   // table written, round 0 readable (PERSIST: and every wave is done with the hand-over area)
+    lds_read2x8(win[0], w_rd);      // windows of round 0: chunk slot 0, piece 0
+    lds_wait<0>();
+    tie(win[0]);
+    table_read(B[0][0].q, win[0][0], bsh[0]);
+    lds_read16<0>(A[0][0].q, a_rd[0]);
+    table_read(B[0][1].q, win[0][2], bsh[0]);
+    lds_read16<4096>(A[0][1].q, a_rd[0]);
+    lds_read16<8192>(A[0][2].q, a_rd[0]);
+    lds_read16<12288>(A[0][3].q, a_rd[0]);
+    settle();
+
     // One plain loop over pairs of rounds; the operands that its last round requests (of a round that does not
     // exist) land before anything else touches their registers.
     for (int32_t g = 0; g < n_rounds; g += 2) {
@@ -422,9 +457,9 @@ __global__ __launch_bounds__(512, 1) void linear_block_bf16_kernel(const uint16_
     __builtin_amdgcn_s_barrier();
     asm volatile("s_nop 15");
     asm volatile("s_nop 15");
-    const uint32_t xchg_mine = static_cast<uint32_t>(kXchgOff + li * 16384);
+    const uint32_t xchg_mine = static_cast<uint32_t>(kXchg + li * 16384);
     {
-        const uint32_t dst = static_cast<uint32_t>(kXchgOff + (li ^ 2) * 16384) + static_cast<uint32_t>(lane) * 16u;
+        const uint32_t dst = static_cast<uint32_t>(kXchg + (li ^ 2) * 16384) + static_cast<uint32_t>(lane) * 16u;
 #pragma unroll
         for (int half = 0; half < 2; ++half) {
             u32x4_t s[8];
@@ -565,6 +600,12 @@ __global__ __launch_bounds__(512, 1) void linear_block_bf16_kernel(const uint16_
             }
         }
     }
+    // the next block of this workgroup, if any
+    const uint32_t next = bid + gridDim.x;
+    if (!PERSIST || next >= n_blocks) break;
+    bid = next;
+    set_block(bid);
+    }
 }
 
 // Second pass of split K: z = partial[0] + partial[1] + ... (ascending, float32), y[m, u + t*U] = alpha[t] * z.
@@ -685,7 +726,7 @@ tbn_status launch_linear_split(const LinearArgs &a, int splits, void *workspace)
     P.partial = static_cast<float *>(workspace);
     const int64_t wgs = int64_t(P.vrows) * P.tiles_n;
     typedef void (*kernel_t)(const uint16_t *, uint16_t *, const uint32_t *, const float *, BlockParams);
-    static const kernel_t kernel = &linear_block_bf16_kernel<false, true>;
+    static const kernel_t kernel = &linear_block_bf16_kernel<false, true, false>;
     static const tbn_status attr = set_lds_limit_once(reinterpret_cast<const void *>(kernel), kLdsBytes);
     if (attr != TBN_OK) {
         set_error("tbn_linear_forward_ws: cannot reserve %d bytes of LDS for the block kernel", kLdsBytes);
@@ -711,15 +752,23 @@ tbn_status launch_linear_block(const LinearArgs &a) {
     const dim3 grid(static_cast<unsigned>(int64_t(P.tiles_m) * P.tiles_n));
     const bool relu = (a.flags & TBN_FLAG_RELU) != 0;
     typedef void (*kernel_t)(const uint16_t *, uint16_t *, const uint32_t *, const float *, BlockParams);
-    static const kernel_t kernels[2] = {&linear_block_bf16_kernel<false, false>, &linear_block_bf16_kernel<true, false>};
+    // more blocks than CUs and rounds in fours: one persistent workgroup per CU
+    int cus = device_cus() & ~7;
+    if (cus < 8) cus = 8;
+    const bool persist = int64_t(P.tiles_m) * P.tiles_n > cus && P.n_rounds >= 4 && P.n_rounds % 4 == 0;
+    static const kernel_t kernels[4] = {&linear_block_bf16_kernel<false, false, false>, &linear_block_bf16_kernel<true, false, false>,
+                                        &linear_block_bf16_kernel<false, false, true>, &linear_block_bf16_kernel<true, false, true>};
     // dynamic LDS above the default limit has to be allowed once per kernel (thread-safe static initialisation)
-    static const tbn_status attr[2] = {set_lds_limit_once(reinterpret_cast<const void *>(kernels[0]), kLdsBytes),
-                                       set_lds_limit_once(reinterpret_cast<const void *>(kernels[1]), kLdsBytes)};
-    if (attr[relu ? 1 : 0] != TBN_OK) {
+    static const tbn_status attr[4] = {set_lds_limit_once(reinterpret_cast<const void *>(kernels[0]), kLdsBytes),
+                                       set_lds_limit_once(reinterpret_cast<const void *>(kernels[1]), kLdsBytes),
+                                       set_lds_limit_once(reinterpret_cast<const void *>(kernels[2]), kLdsBytes),
+                                       set_lds_limit_once(reinterpret_cast<const void *>(kernels[3]), kLdsBytes)};
+    const int which = (relu ? 1 : 0) + (persist ? 2 : 0);
+    if (attr[which] != TBN_OK) {
         set_error("tbn_linear_forward: cannot reserve %d bytes of LDS for the block kernel", kLdsBytes);
         return TBN_ERR_DEVICE;
     }
-    hipLaunchKernelGGL(kernels[relu ? 1 : 0], grid, dim3(512), kLdsBytes, a.stream,
+    hipLaunchKernelGGL(kernels[which], persist ? dim3(static_cast<unsigned>(cus)) : grid, dim3(512), kLdsBytes, a.stream,
                        static_cast<const uint16_t *>(a.x), static_cast<uint16_t *>(a.y), a.tile, a.alpha, P);
     return check_launch("tbn_linear_forward (matrix-core kernel with load waves)");
 }
