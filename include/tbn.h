@@ -241,6 +241,37 @@ tbn_status tbn_linear_coltiled_forward(const void *x, void *y, tbn_dtype dt, int
                                        size_t workspace_bytes, void *stream);
 
 /*
+ * Binary activations (the Conclusion names tiled-bit layers in models with binary weights and binary
+ * activations as the first direction of future work and gives no formula).  The reading built here takes the
+ * paper's own binarisation: an activation becomes +1 or -1 by the rule that Eq. 3 applies to a weight sum (+1
+ * where the value is greater than zero, -1 otherwise: zero and not-a-number give -1), and the layer operation
+ * stated after Eq. 8 is applied to those signs unchanged; no scalar is attached to the activations.
+ *
+ *   s[m, j] = +1 if x[m, j] > 0 else -1
+ *   y[m, o] = sum_{j<in} s[m, j] * alpha[(o*in + j) / p or 0] * t[(o*in + j) % p],  p = in*out/k
+ *
+ * Rows of sign bits: tbn_sign_row_words(in) = ceil(in / 32) words per row; activation j of row m is bit j % 32 of
+ * word j / 32 of that row (1 for +1); the unused high bits of a row's last word are written as zero by
+ * tbn_sign_pack and ignored by tbn_linear_forward_binact.
+ *
+ *   tbn_sign_pack             : x DEVICE, M x in, row-major, dense, element type dt, read only;
+ *                               xbits DEVICE, M * tbn_sign_row_words(in) words, fully overwritten.
+ *   tbn_linear_forward_binact : xbits DEVICE, rows of sign bits as above, read only; y DEVICE, M x out, row-major,
+ *                               dense, element type y_dt, fully overwritten; tile, alpha, k, n_alpha as for
+ *                               tbn_linear_forward; flags 0 or TBN_FLAG_RELU (| TBN_FLAG_FORCE_GENERIC).
+ * The sums of +-1 products are integers and computed exactly; an output is alpha times such an integer (one
+ * float32 product, rounded once more for bfloat16 outputs) unless n_alpha = k and a weight row crosses a tile
+ * end, in which case the row's pieces are added in float32 in ascending order of j.
+ * M == 0 is legal and does nothing.  xbits and y must not overlap.
+ * Errors: TBN_ERR_NULL, TBN_ERR_SHAPE, TBN_ERR_UNSUPPORTED, TBN_ERR_DEVICE.
+ */
+size_t tbn_sign_row_words(int64_t in);
+tbn_status tbn_sign_pack(const void *x, tbn_dtype dt, int64_t M, int64_t in, uint32_t *xbits, void *stream);
+tbn_status tbn_linear_forward_binact(const uint32_t *xbits, void *y, tbn_dtype y_dt, int64_t M, int64_t in,
+                                     int64_t out, const uint32_t *tile, int32_t k, const float *alpha,
+                                     int32_t n_alpha, uint32_t flags, void *stream);
+
+/*
  * Measurement aids.  No part of the method (the paper reports no kernel timings; its Section "GPU Inference Kernel"
  * measures memory only): they give the benchmark its denominators, measured the same way as the layer kernels.
  *

@@ -300,6 +300,49 @@ tbn_status tbn_linear_coltiled_forward(const void *x, void *y, tbn_dtype dt, int
     return dispatch_linear(a);
 }
 
+size_t tbn_sign_row_words(int64_t in) { return in > 0 ? static_cast<size_t>((in + 31) / 32) : 0; }
+
+tbn_status tbn_sign_pack(const void *x, tbn_dtype dt, int64_t M, int64_t in, uint32_t *xbits, void *stream) {
+    if (M > 0 && (!x || !xbits)) {
+        set_error("tbn_sign_pack: x and xbits must not be NULL");
+        return TBN_ERR_NULL;
+    }
+    if (dt != TBN_F32 && dt != TBN_BF16) {
+        set_error("tbn_sign_pack: unknown dtype %d", (int)dt);
+        return TBN_ERR_UNSUPPORTED;
+    }
+    if (M < 0 || in <= 0) {
+        set_error("tbn_sign_pack: M (%lld) must be >= 0 and in (%lld) positive", (long long)M, (long long)in);
+        return TBN_ERR_SHAPE;
+    }
+    int64_t xs;
+    if (!mul_ok(M, in, &xs) || xs > (int64_t(1) << 40)) {
+        set_error("tbn_sign_pack: sizes beyond the supported range");
+        return TBN_ERR_UNSUPPORTED;
+    }
+    if (M == 0) return TBN_OK;
+    drop_stale_error();
+    return launch_sign_pack(x, (int)dt, M, in, xbits, static_cast<hipStream_t>(stream));
+}
+
+tbn_status tbn_linear_forward_binact(const uint32_t *xbits, void *y, tbn_dtype y_dt, int64_t M, int64_t in,
+                                     int64_t out, const uint32_t *tile, int32_t k, const float *alpha,
+                                     int32_t n_alpha, uint32_t flags, void *stream) {
+    if (flags & ~(TBN_FLAG_RELU | TBN_FLAG_FORCE_GENERIC)) {
+        set_error("tbn_linear_forward_binact: unknown flag bits 0x%x", flags);
+        return TBN_ERR_UNSUPPORTED;
+    }
+    int64_t n;
+    tbn_status st = check_linear_args("tbn_linear_forward_binact", xbits, y, y_dt, M, in, out, tile, alpha, flags, &n);
+    if (st != TBN_OK) return st;
+    st = check_tiling(n, k, n_alpha);
+    if (st != TBN_OK) return st;
+    if (M == 0) return TBN_OK;
+    drop_stale_error();
+    return launch_linear_binact(xbits, y, (int)y_dt, M, in, out, tile, n / k, k, alpha, n_alpha, flags,
+                                static_cast<hipStream_t>(stream));
+}
+
 tbn_status tbn_diag_empty_launch(void *stream) { return launch_diag_empty(static_cast<hipStream_t>(stream)); }
 
 tbn_status tbn_diag_stream(const void *src, void *dst, size_t bytes, void *sink, void *stream) {

@@ -80,6 +80,12 @@ tbn_status launch_linear_mfma(const LinearArgs &a);
 tbn_status launch_coltile_fold(const void *x, void *xf, int dt, int64_t M, int64_t in, int32_t k,
                                const float *alpha, int32_t n_alpha, float *one_out, hipStream_t stream);
 
+// binary activations: rows of sign bits (32 per word, ceil(in / 32) words per row) and the layer on them
+tbn_status launch_sign_pack(const void *x, int dt, int64_t M, int64_t in, uint32_t *xbits, hipStream_t stream);
+tbn_status launch_linear_binact(const uint32_t *xbits, void *y, int dt, int64_t M, int64_t in, int64_t out,
+                                const uint32_t *tile, int64_t p, int32_t k, const float *alpha, int32_t n_alpha,
+                                uint32_t flags, hipStream_t stream);
+
 tbn_status launch_conv_generic(const ConvArgs &a);
 tbn_status launch_conv_generic_tile_ends(const ConvArgs &a);   // only the channels whose filter holds a tile end
 bool conv_mfma_supported(const ConvArgs &a);

@@ -78,6 +78,13 @@ def lib() -> ctypes.CDLL:
         L.tbn_linear_coltiled_forward.restype = ctypes.c_int
         L.tbn_linear_coltiled_forward.argtypes = [_c_vp, _c_vp, ctypes.c_int, _c_i64, _c_i64, _c_i64, _c_vp, _c_i32,
                                                   _c_vp, _c_i32, _c_u32, _c_vp, _c_sz, _c_vp]
+        L.tbn_sign_row_words.restype = _c_sz
+        L.tbn_sign_row_words.argtypes = [_c_i64]
+        L.tbn_sign_pack.restype = ctypes.c_int
+        L.tbn_sign_pack.argtypes = [_c_vp, ctypes.c_int, _c_i64, _c_i64, _c_vp, _c_vp]
+        L.tbn_linear_forward_binact.restype = ctypes.c_int
+        L.tbn_linear_forward_binact.argtypes = [_c_vp, _c_vp, ctypes.c_int, _c_i64, _c_i64, _c_i64, _c_vp, _c_i32, _c_vp,
+                                                _c_i32, ctypes.c_uint32, _c_vp]
         L.tbn_diag_empty_launch.restype = ctypes.c_int
         L.tbn_diag_empty_launch.argtypes = [_c_vp]
         L.tbn_diag_stream.restype = ctypes.c_int
@@ -298,6 +305,46 @@ def tbn_conv2d_forward(x: torch.Tensor, tile: torch.Tensor, alpha: torch.Tensor,
     st = lib().tbn_conv2d_forward(_dev(x, "x"), _dev(y, "y"), _dt(x), N, C, H, W, out_channels, kh, kw,
                                   stride[0], stride[1], pad[0], pad[1], _dev(tile, "tile", torch.int32), k,
                                   _dev(alpha, "alpha", torch.float32), alpha.numel(), flags, _stream(stream))
+    if st != TBN_OK:
+        _raise(st)
+    return y
+
+
+def tbn_sign_row_words(cin: int) -> int:
+    return int(lib().tbn_sign_row_words(cin))
+
+
+def tbn_sign_pack(x: torch.Tensor, xbits: Optional[torch.Tensor] = None, stream=None) -> torch.Tensor:
+    """Rows of sign bits of x (M, in): int32 (M, ceil(in / 32)), bit j % 32 of word j // 32 set where x[m, j] > 0."""
+    if x.dim() != 2:
+        raise ValueError("x must be (M, in)")
+    M, cin = x.shape
+    words = tbn_sign_row_words(cin)
+    if xbits is None:
+        xbits = torch.empty((M, words), dtype=torch.int32, device=x.device)
+    elif tuple(xbits.shape) != (M, words) or xbits.device != x.device:
+        raise ValueError(f"xbits must be ({M}, {words}) on {x.device}")
+    st = lib().tbn_sign_pack(_dev(x, "x"), _dt(x), M, cin, _dev(xbits, "xbits", torch.int32), _stream(stream))
+    if st != TBN_OK:
+        _raise(st)
+    return xbits
+
+
+def tbn_linear_forward_binact(xbits: torch.Tensor, cin: int, tile: torch.Tensor, alpha: torch.Tensor, out_features: int,
+                              k: int, dtype: torch.dtype = torch.float32, y: Optional[torch.Tensor] = None, flags: int = 0,
+                              stream=None) -> torch.Tensor:
+    """The layer on rows of sign bits (M, ceil(in / 32)); y has shape (M, out_features) and the given dtype."""
+    if xbits.dim() != 2 or xbits.shape[1] != tbn_sign_row_words(cin):
+        raise ValueError("xbits must be (M, ceil(in / 32))")
+    M = xbits.shape[0]
+    if y is None:
+        y = torch.empty((M, out_features), dtype=dtype, device=xbits.device)
+    elif tuple(y.shape) != (M, out_features):
+        raise ValueError("y must be (M, out)")
+    _check_layer_tensors("tbn_linear_forward_binact", xbits, tile, alpha, cin * out_features, k, y)
+    st = lib().tbn_linear_forward_binact(_dev(xbits, "xbits", torch.int32), _dev(y, "y"), _dt(y), M, cin, out_features,
+                                         _dev(tile, "tile", torch.int32), k, _dev(alpha, "alpha", torch.float32),
+                                         alpha.numel(), flags, _stream(stream))
     if st != TBN_OK:
         _raise(st)
     return y
