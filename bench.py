@@ -28,6 +28,7 @@ if ROOT not in sys.path:
 
 HBM_PEAK_GBS = 8000.0          # MI355X HBM3E
 MFMA_BF16_PEAK_TFLOPS = 2500.0  # dense bf16
+MFMA_FP4_PEAK_TFLOPS = 10100.0  # dense 4-bit float (the binary-activation kernel multiplies +-1 in that format)
 
 
 def parse_args():
@@ -373,6 +374,24 @@ def time_other_configs(torch, tbn, wl, iters=30):
         out[c.name] = {"us": round(us, 2), "with_workspace_us": round(usw, 2), "workspace_bytes": need,
                        "warm": _roof_fields(us, byts, alg_flop, ceil), "with_workspace": _roof_fields(usw, byts, alg_flop, ceil)}
         del w, x, y, ws
+    # binary activations (sign bits in, bfloat16 out): the sign packing of X and the layer on the bits; the matrix
+    # time is priced at the 4-bit float rate (10.1 PFLOP/s dense), the format the kernel multiplies in
+    for c in (wl.METRIC, *wl.CFG5):
+        w, x, _ = device_inputs(c, torch, wl)
+        tile, alpha = tbn.tbn_pack_tile(w, c.k, c.n_alpha)
+        bits = tbn.tbn_sign_pack(x)
+        y = torch.empty((c.M, c.cout), dtype=x.dtype, device="cuda")
+        usp = _timed_us(torch, lambda i: tbn.tbn_sign_pack(x, xbits=bits), iters)
+        us = _timed_us(torch, lambda i: tbn.tbn_linear_forward_binact(bits, c.cin, tile, alpha, c.cout, c.k, y=y), iters)
+        byts = c.M * c.cin // 8 + c.M * c.cout * 2 + c.p // 8
+        alg_flop = 2.0 * c.M * c.cin * (c.p // c.cin)
+        t_hbm, t_mfma = byts / (HBM_PEAK_GBS * 1e3), alg_flop / (MFMA_FP4_PEAK_TFLOPS * 1e6)
+        out[c.name + ":binary_activations"] = {
+            "us": round(us, 2), "sign_pack_us": round(usp, 2), "sign_pack_gbs": round(c.M * c.cin * 2 / usp / 1e3, 1),
+            "alg_gbs": round(byts / us / 1e3, 1), "roof_us": round(max(t_hbm, t_mfma), 2),
+            "bound": "hbm" if t_hbm >= t_mfma else "mfma", "frac_of_roof": round(max(t_hbm, t_mfma) / us, 3),
+            "real_valued_us": out[c.name]["us"]}
+        del w, x, y, bits
     for c in (wl.CFG3, wl.CFG3_MISALIGNED, *wl.CONV_MORE):
         w = torch.from_numpy(wl.draw_w_real(c.n, c.cfg, c.layer)).cuda()
         xv, xb = wl.draw_x((c.N, c.C, c.H, c.W), c.cfg, c.layer, c.dtype)
