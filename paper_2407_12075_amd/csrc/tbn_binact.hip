@@ -30,6 +30,13 @@ typedef uint32_t u32x4_t __attribute__((ext_vector_type(4)));
 typedef int i32x8_t __attribute__((ext_vector_type(8)));
 typedef float f32x4_t __attribute__((ext_vector_type(4)));
 typedef float f32x16_t __attribute__((ext_vector_type(16)));
+typedef float f32x2_t __attribute__((ext_vector_type(2)));
+typedef __bf16 bf16x2_t __attribute__((ext_vector_type(2)));
+
+__device__ __forceinline__ uint32_t pack_bf16x2(float a, float b) {
+    const f32x2_t f = {a, b};
+    return __builtin_bit_cast(uint32_t, __builtin_convertvector(f, bf16x2_t));   // round to nearest even in hardware
+}
 
 // ---- sign bits ------------------------------------------------------------------------------------------
 
@@ -193,6 +200,9 @@ __global__ __launch_bounds__(256, 2) void binact_mfma_kernel(const uint32_t *__r
     const int64_t m0 = int64_t(tile_m) * 128 + (wave >> 1) * 64;   // this wave's first batch row
     const int32_t n0 = static_cast<int32_t>(tile_n) * 128 + (wave & 1) * 64;   // and first distinct column
 
+    // alpha of replica t in lane t (replicas past the 64th are fetched one by one in the epilogue)
+    const float alpha_lanes = alpha[P.n_alpha == 1 ? 0 : (lane < P.reps ? lane : P.reps - 1)];
+
     // table: entry e holds, for bit i of e, the 4-bit float +1.0 (0x2) or -1.0 (0xA) at bits 4i .. 4i+3
     {
         uint32_t v = 0;
@@ -250,24 +260,31 @@ __global__ __launch_bounds__(256, 2) void binact_mfma_kernel(const uint32_t *__r
     load(raw[0], 0);
     load(raw[1], 1 < last ? 1 : last);
     __syncthreads();   // the table is written
-    i32x8_t F[2][4] = {};   // [operand set][A0, A1, B0, B1]; the upper four words of an operand are not read in this format
-    expand(F[0][0], raw[0][0][0]); expand(F[0][1], raw[0][1][0]); expand(F[0][2], raw[0][2][0]); expand(F[0][3], raw[0][3][0]);
+    i32x8_t F[3][4] = {};   // [operand set][A0, A1, B0, B1]; the upper four words of an operand are not read in this format
+#pragma unroll
+    for (int f = 0; f < 4; ++f) {
+        expand(F[0][f], raw[0][f][0]);
+        expand(F[1][f], raw[0][f][1]);
+    }
     constexpr int kOne = 0x7f7f7f7f;   // scale 2^0 in every byte
-    // One super-step: four groups of four instructions.  In front of each instruction one operand of the next group
-    // is looked up, in the order in which that group needs them (A0, B0, B1, A1); the lookups of this group's own
-    // operands were issued a group ago.  The last super-step loads itself once more and looks up operands nobody
-    // multiplies: the body stays one straight line of code, which is what keeps the order written here.
+    // One super-step: four groups of four instructions.  In front of each instruction one operand of the group after
+    // the next is looked up (a lookup takes longer to arrive than two instructions take to run, so one group ahead is
+    // not enough), in the order in which that group needs them (A0, B0, B1, A1).  Three operand sets rotate with the
+    // groups.  The last super-step loads itself once more and looks up operands nobody multiplies: the body stays one
+    // straight line of code, which is what keeps the order written here.
     auto step = [&](auto c_c, int32_t S) __attribute__((always_inline)) {
         constexpr int C = decltype(c_c)::value, N1 = (C + 1) % 3, N2 = (C + 2) % 3;
         load(raw[N2], S + 2 < last ? S + 2 : last);
 #pragma unroll
         for (int i = 0; i < 4; ++i) {
-            const int s = i & 1, n = s ^ 1;
+            const int s = (C + i) % 3, n = (C + i + 2) % 3;   // group 4 S + i uses set (4 S + i) % 3 = (C + i) % 3
 #pragma unroll
             for (int q = 0; q < 4; ++q) {
                 constexpr int kOrder[4] = {0, 2, 3, 1};
                 const int f = kOrder[q];
-                expand(F[n][f], i < 3 ? raw[C][f][i + 1] : raw[N1][f][0]);
+                expand(F[n][f], i < 2 ? raw[C][f][i + 2] : raw[N1][f][i - 2]);
+                __builtin_amdgcn_sched_group_barrier(0x2, 4, 0);     // the four addresses, then the four reads: a read
+                __builtin_amdgcn_sched_group_barrier(0x100, 4, 0);   // does not follow its own address directly
                 __builtin_amdgcn_sched_barrier(0);
                 const int tm = q >> 1, tn = q & 1;
                 acc[tm][tn] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(F[s][2 + tn], F[s][tm], acc[tm][tn], 4, 4, 0, kOne, 0, kOne);
@@ -311,7 +328,8 @@ __global__ __launch_bounds__(256, 2) void binact_mfma_kernel(const uint32_t *__r
             const f32x4_t z1 = *reinterpret_cast<const f32x4_t *>(zt + row * kTurnStride + 8 * c8 + 4);
             YT *yrow = y + m * P.out + col;
             for (int32_t t = 0; t < P.reps; ++t) {
-                const float al = alpha[P.n_alpha == 1 ? 0 : t];
+                const float al = t < 64 ? __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, alpha_lanes), t))
+                                        : alpha[P.n_alpha == 1 ? 0 : t];
                 float v[8];
 #pragma unroll
                 for (int i = 0; i < 4; ++i) {
@@ -329,8 +347,7 @@ __global__ __launch_bounds__(256, 2) void binact_mfma_kernel(const uint32_t *__r
                 } else {
                     u32x4_t o;
 #pragma unroll
-                    for (int i = 0; i < 4; ++i)
-                        o[i] = static_cast<uint32_t>(f32_to_bf16_bits(v[2 * i])) | (static_cast<uint32_t>(f32_to_bf16_bits(v[2 * i + 1])) << 16);
+                    for (int i = 0; i < 4; ++i) o[i] = pack_bf16x2(v[2 * i], v[2 * i + 1]);
                     *reinterpret_cast<u32x4_t *>(yrow + int64_t(t) * P.U) = o;
                 }
             }

@@ -4,7 +4,7 @@ alpha times one integer (one alpha for the layer, or weight rows inside one tile
 the oracle's float64 product rounded to float32 bit for bit, and a bfloat16 output that value rounded once more;
 rows that cross tile ends with k alphas add a few float32 products and are held to 1e-6 of the largest magnitude.
 Shapes span the matrix-core kernel (several blocks, ragged rows and columns, one to three super-steps and more, all
-register-set rotations) and the shape-agnostic kernel (rows that are no whole words, tiles shorter than a row,
+register-set rotations, K dealt to one and to two waves per tile) and the shape-agnostic kernel (rows that are no whole words, tiles shorter than a row,
 tiles that end inside words).
 """
 import numpy as np
@@ -120,6 +120,7 @@ MFMA = [
     (300, 4096, 1024, 8, 8),      # sixteen super-steps, 128 distinct columns
     (1, 4096, 64, 8, 8),          # a single batch row, eight distinct columns
     (513, 2048, 768, 3, 3),       # 256 distinct columns: two column blocks
+    (2100, 1536, 4096, 2, 2),     # 17 x 16 blocks, more than the chip has CUs: every wave runs all six super-steps
 ]
 
 
@@ -163,6 +164,29 @@ GENERIC = [
 @pytest.mark.parametrize("dtype", ["f32", "bf16"])
 def test_forward_general_kernel(tbn, M, cin, out, k, n_alpha, dtype):
     _check(tbn, M, cin, out, k, n_alpha, dtype, dirty_padding=True)
+
+
+def _random_shapes():
+    rng = np.random.default_rng(20240712)
+    shapes = []
+    for i in range(36):
+        if i % 3 == 0:   # shapes of the matrix-core kernel: in a multiple of 256, tile of whole rows, U a multiple of 8
+            cin = 256 * int(rng.integers(1, 9))
+            U = 8 * int(rng.integers(1, 40))
+            k = int(rng.choice([1, 2, 3, 4, 5, 8]))
+            shapes.append((int(rng.integers(1, 400)), cin, U * k, k, int(rng.choice([1, k]))))
+        else:
+            cin, out = int(rng.integers(1, 300)), int(rng.integers(1, 120))
+            n = cin * out
+            divs = [d for d in range(1, min(n, 64) + 1) if n % d == 0]
+            k = int(rng.choice(divs))
+            shapes.append((int(rng.integers(1, 40)), cin, out, k, int(rng.choice([1, k]))))
+    return shapes
+
+
+@pytest.mark.parametrize("M,cin,out,k,n_alpha", _random_shapes())
+def test_forward_random_shapes(tbn, M, cin, out, k, n_alpha):
+    _check(tbn, M, cin, out, k, n_alpha, "f32" if (M + cin) % 2 else "bf16", flags=(M % 2), dirty_padding=True)
 
 
 def test_forward_relu_general_kernel(tbn):
