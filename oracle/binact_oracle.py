@@ -61,3 +61,9 @@ def linear_forward(xbits, cin: int, tile, alpha, out: int, k: int) -> np.ndarray
     s = signs(xbits, cin)
     w_hat = tbn_oracle.materialise(tile, alpha, out * cin, k).reshape(out, cin)
     return s @ w_hat.T
+
+
+def linear_forward_signs(xbits, cin: int, tile, alpha, out: int, k: int) -> np.ndarray:
+    """The layer followed by the binarisation of its outputs (what the next binary-activation layer consumes):
+    rows of sign bits of Y, bit 1 where y > 0 (the rule of Eq. 3 once more); uint32 (M, ceil(out/32))."""
+    return sign_pack(linear_forward(xbits, cin, tile, alpha, out, k))

@@ -156,3 +156,26 @@ def test_b9_planted_mistakes_fail_the_pins():
     assert not np.array_equal(ba.sign_pack(xz), ba.sign_pack(np.where(xz == 0, 1.0, xz)))
     # one alpha where there are k
     assert not np.allclose(ba.linear_forward(xbits, 40, tile, alpha[:1].repeat(4), 12, 4), want)
+
+
+def test_b10_sign_outputs_by_loops_and_two_layer_chain():
+    """Bits out: the sign of every output by loops over the definition; a chain of two layers on bits equals the
+    real-valued C oracle fed with the +-1 values between the layers."""
+    M, cin, hid, out, k = 3, 40, 24, 10, 4
+    _, x, t1, a1 = _case(M, cin, hid, k, k, 91)
+    a1[1] = -a1[1]                                  # a negative alpha flips the signs of its copy
+    _, _, t2, a2 = _case(M, hid, out, 2, 1, 92)
+    xb = ba.sign_pack(x)
+    hb = ba.linear_forward_signs(xb, cin, t1, a1, hid, k)
+    assert hb.shape == (M, 1) and hb.dtype == np.uint32
+    y1 = flat.linear_forward_alg1(np.where(x > 0, 1.0, -1.0), t1, a1, hid, k)
+    for m in range(M):
+        for o in range(32):
+            assert _bit(hb[m], o) == (1 if (o < hid and y1[m, o] > 0) else 0)
+    want = flat.linear_forward_alg1(np.where(y1 > 0, 1.0, -1.0), t2, a2, out, 2)
+    got = ba.linear_forward(hb, hid, t2, a2, out, 2)
+    np.testing.assert_allclose(got, want, rtol=1e-12, atol=1e-12)
+    # an output that is exactly zero gives bit 0: all weights +1, half of the activations +1
+    tile = np.full(2, 0xFFFFFFFF, dtype=np.uint32)
+    half = np.array([[0x0000FFFF]], dtype=np.uint32)
+    assert int(ba.linear_forward_signs(half, 32, tile, np.array([1.0], dtype=np.float32), 2, 1)[0, 0]) == 0
