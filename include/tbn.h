@@ -71,6 +71,8 @@ typedef enum {
                                          no gain */
 #define TBN_FLAG_TILE_KERNEL 0x2000u  /* testing aid (linear only): take the kernel with one wave per 32 batch rows
                                          wherever it supports the shape */
+#define TBN_FLAG_SIGN_OUT 0x4000u     /* tbn_linear_forward_binact only: write the sign bits of the outputs instead
+                                         of the outputs (the input format of the next such layer) */
 
 /* Number of 32-bit words of a tile of n / k entries (ceil(n / k / 32)); 0 if n <= 0, k <= 0 or
  * k does not divide n (the paper requires n divisible by the compression factor). */
@@ -258,7 +260,11 @@ tbn_status tbn_linear_coltiled_forward(const void *x, void *y, tbn_dtype dt, int
  *                               xbits DEVICE, M * tbn_sign_row_words(in) words, fully overwritten.
  *   tbn_linear_forward_binact : xbits DEVICE, rows of sign bits as above, read only; y DEVICE, M x out, row-major,
  *                               dense, element type y_dt, fully overwritten; tile, alpha, k, n_alpha as for
- *                               tbn_linear_forward; flags 0 or TBN_FLAG_RELU (| TBN_FLAG_FORCE_GENERIC).
+ *                               tbn_linear_forward; flags 0 or TBN_FLAG_RELU, TBN_FLAG_SIGN_OUT (| TBN_FLAG_FORCE_GENERIC).
+ * With TBN_FLAG_SIGN_OUT the layer hands on what the next binary-activation layer consumes: y is then DEVICE,
+ * M * tbn_sign_row_words(out) words, rows of sign bits of the outputs (bit 1 where y[m, o] > 0, unused high bits
+ * zero), fully overwritten; y_dt is not looked at beyond its validity and TBN_FLAG_RELU changes nothing (a
+ * positive output stays positive).
  * The sums of +-1 products are integers and computed exactly; an output is alpha times such an integer (one
  * float32 product, rounded once more for bfloat16 outputs) unless n_alpha = k and a weight row crosses a tile
  * end, in which case the row's pieces are added in float32 in ascending order of j.

@@ -328,12 +328,13 @@ tbn_status tbn_sign_pack(const void *x, tbn_dtype dt, int64_t M, int64_t in, uin
 tbn_status tbn_linear_forward_binact(const uint32_t *xbits, void *y, tbn_dtype y_dt, int64_t M, int64_t in,
                                      int64_t out, const uint32_t *tile, int32_t k, const float *alpha,
                                      int32_t n_alpha, uint32_t flags, void *stream) {
-    if (flags & ~(TBN_FLAG_RELU | TBN_FLAG_FORCE_GENERIC)) {
+    if (flags & ~(TBN_FLAG_RELU | TBN_FLAG_FORCE_GENERIC | TBN_FLAG_SIGN_OUT)) {
         set_error("tbn_linear_forward_binact: unknown flag bits 0x%x", flags);
         return TBN_ERR_UNSUPPORTED;
     }
     int64_t n;
-    tbn_status st = check_linear_args("tbn_linear_forward_binact", xbits, y, y_dt, M, in, out, tile, alpha, flags, &n);
+    tbn_status st = check_linear_args("tbn_linear_forward_binact", xbits, y, y_dt, M, in, out, tile, alpha,
+                                      flags & ~TBN_FLAG_SIGN_OUT, &n);
     if (st != TBN_OK) return st;
     st = check_tiling(n, k, n_alpha);
     if (st != TBN_OK) return st;

@@ -120,9 +120,48 @@ struct BinactArgs {
     hipStream_t stream;
 };
 
-// One thread per output.  The flat weight index of (o, j) is f = o*in + j: tile bit f % p, alpha[f / p].  The
+// One output of the layer.  The flat weight index of (o, j) is f = o*in + j: tile bit f % p, alpha[f / p].  The
 // products of one tile copy are counted as integers (32 minus twice the differing bits per word) and scaled
 // once; with one alpha, or a tile of whole rows, an output is a single product of a float and an integer.
+__device__ __forceinline__ float binact_output(const uint32_t *__restrict__ xr, int64_t o, int64_t in, int64_t row_words,
+                                               const uint32_t *__restrict__ tile, int64_t p, int64_t n_words,
+                                               const float *__restrict__ alpha, int32_t n_alpha) {
+    const int64_t f0 = o * in;
+    int64_t q = f0 % p;          // tile position of the next weight
+    int64_t c = f0 / p;          // tile copy it belongs to
+    int32_t cnt = 0;             // sum of the +-1 products inside copy c so far
+    float acc = 0.f;
+    auto flush = [&]() {   // a tile copy ends; with one alpha for all copies the count simply runs on
+        if (n_alpha != 1) {
+            acc += alpha[c] * static_cast<float>(cnt);
+            cnt = 0;
+        }
+        ++c;
+        q = 0;
+    };
+    for (int64_t w = 0; w < row_words; ++w) {
+        const uint32_t xw = xr[w];
+        const int32_t nb = (in - 32 * w) < 32 ? static_cast<int32_t>(in - 32 * w) : 32;
+        if (q + nb <= p) {
+            const uint32_t win = tile_window32(tile, q, n_words);
+            const uint32_t mask = nb == 32 ? 0xffffffffu : ((1u << nb) - 1u);
+            cnt += nb - 2 * __popc((xw ^ win) & mask);
+            q += nb;
+            if (q == p) flush();
+        } else {   // the word crosses a tile end
+            for (int32_t b = 0; b < nb; ++b) {
+                const uint32_t tb = (tile[q >> 5] >> (q & 31)) & 1u;
+                cnt += (((xw >> b) & 1u) == tb) ? 1 : -1;
+                if (++q == p) flush();
+            }
+        }
+    }
+    if (n_alpha == 1) acc = alpha[0] * static_cast<float>(cnt);
+    else if (q != 0) acc += alpha[c] * static_cast<float>(cnt);   // the copy the row ends in
+    return acc;
+}
+
+// one thread per output
 template <typename YT>
 __global__ __launch_bounds__(256) void binact_generic_kernel(const uint32_t *__restrict__ xbits, YT *__restrict__ y,
                                                              int64_t total, int64_t in, int64_t out, int64_t row_words,
@@ -131,41 +170,24 @@ __global__ __launch_bounds__(256) void binact_generic_kernel(const uint32_t *__r
     const int64_t n_words = (p + 31) / 32;
     for (int64_t idx = int64_t(blockIdx.x) * blockDim.x + threadIdx.x; idx < total; idx += int64_t(gridDim.x) * blockDim.x) {
         const int64_t m = idx / out, o = idx - m * out;
-        const uint32_t *xr = xbits + m * row_words;
-        const int64_t f0 = o * in;
-        int64_t q = f0 % p;          // tile position of the next weight
-        int64_t c = f0 / p;          // tile copy it belongs to
-        int32_t cnt = 0;             // sum of the +-1 products inside copy c so far
-        float acc = 0.f;
-        auto flush = [&]() {   // a tile copy ends; with one alpha for all copies the count simply runs on
-            if (n_alpha != 1) {
-                acc += alpha[c] * static_cast<float>(cnt);
-                cnt = 0;
-            }
-            ++c;
-            q = 0;
-        };
-        for (int64_t w = 0; w < row_words; ++w) {
-            const uint32_t xw = xr[w];
-            const int32_t nb = (in - 32 * w) < 32 ? static_cast<int32_t>(in - 32 * w) : 32;
-            if (q + nb <= p) {
-                const uint32_t win = tile_window32(tile, q, n_words);
-                const uint32_t mask = nb == 32 ? 0xffffffffu : ((1u << nb) - 1u);
-                cnt += nb - 2 * __popc((xw ^ win) & mask);
-                q += nb;
-                if (q == p) flush();
-            } else {   // the word crosses a tile end
-                for (int32_t b = 0; b < nb; ++b) {
-                    const uint32_t tb = (tile[q >> 5] >> (q & 31)) & 1u;
-                    cnt += (((xw >> b) & 1u) == tb) ? 1 : -1;
-                    if (++q == p) flush();
-                }
-            }
-        }
-        if (n_alpha == 1) acc = alpha[0] * static_cast<float>(cnt);
-        else if (q != 0) acc += alpha[c] * static_cast<float>(cnt);   // the copy the row ends in
+        float acc = binact_output(xbits + m * row_words, o, in, row_words, tile, p, n_words, alpha, n_alpha);
         if (relu) acc = fmaxf(acc, 0.f);
         ElemIO<YT>::store(y + idx, acc);
+    }
+}
+
+// sign bits out: one thread per word of 32 outputs
+__global__ __launch_bounds__(256) void binact_generic_sign_kernel(const uint32_t *__restrict__ xbits, uint32_t *__restrict__ ybits,
+                                                                  int64_t total_words, int64_t in, int64_t out, int64_t row_words,
+                                                                  int64_t out_words, const uint32_t *__restrict__ tile, int64_t p,
+                                                                  const float *__restrict__ alpha, int32_t n_alpha) {
+    const int64_t n_words = (p + 31) / 32;
+    for (int64_t idx = int64_t(blockIdx.x) * blockDim.x + threadIdx.x; idx < total_words; idx += int64_t(gridDim.x) * blockDim.x) {
+        const int64_t m = idx / out_words, wo = idx - m * out_words;
+        uint32_t bits = 0;
+        for (int b = 0; b < 32 && 32 * wo + b < out; ++b)
+            bits |= (binact_output(xbits + m * row_words, 32 * wo + b, in, row_words, tile, p, n_words, alpha, n_alpha) > 0.f ? 1u : 0u) << b;
+        ybits[idx] = bits;
     }
 }
 
@@ -187,7 +209,8 @@ struct BinactMfmaParams {
 };
 
 // 256 threads = 4 waves in 2 x 2; a wave owns 64 batch rows x 64 distinct columns (2 x 2 MFMA tiles) over all of K.
-template <typename YT, bool RELU>
+// SIGN: the sign bits of the outputs are written instead of the outputs (U % 32 == 0; YT is then not used).
+template <typename YT, bool RELU, bool SIGN>
 __global__ __launch_bounds__(256, 2) void binact_mfma_kernel(const uint32_t *__restrict__ xbits, YT *__restrict__ y,
                                                              const uint32_t *__restrict__ tile,
                                                              const float *__restrict__ alpha, BinactMfmaParams P) {
@@ -318,6 +341,35 @@ __global__ __launch_bounds__(256, 2) void binact_mfma_kernel(const uint32_t *__r
     // a lane takes eight adjacent columns of one row; eight lanes cover the 64 columns of a row
     const int c8 = lane & 7, rsub = lane >> 3;
     const int32_t col = n0 + 8 * c8;
+    if constexpr (SIGN) {
+        // eight sign bits per lane and replica; the four lanes of a word OR their bytes together (every lane takes
+        // part in the exchanges, only the first lane of a live word stores)
+        uint32_t *yb = reinterpret_cast<uint32_t *>(y);
+        const int64_t out_words = P.out >> 5;
+#pragma unroll 1
+        for (int q = 0; q < 8; ++q) {
+            const int row = 8 * q + rsub;
+            const int64_t m = m0 + row;
+            const f32x4_t z0 = *reinterpret_cast<const f32x4_t *>(zt + row * kTurnStride + 8 * c8);
+            const f32x4_t z1 = *reinterpret_cast<const f32x4_t *>(zt + row * kTurnStride + 8 * c8 + 4);
+            const bool writer = m < P.M && col < P.U && (c8 & 3) == 0;
+            for (int32_t t = 0; t < P.reps; ++t) {
+                const float al = t < 64 ? __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, alpha_lanes), t))
+                                        : alpha[P.n_alpha == 1 ? 0 : t];
+                uint32_t w = 0;
+#pragma unroll
+                for (int i = 0; i < 4; ++i) {
+                    w |= (al * z0[i] > 0.f ? 1u : 0u) << i;
+                    w |= (al * z1[i] > 0.f ? 1u : 0u) << (4 + i);
+                }
+                w <<= 8 * (c8 & 3);
+                w |= __shfl_xor(w, 1);
+                w |= __shfl_xor(w, 2);
+                if (writer) yb[m * out_words + ((int64_t(t) * P.U + col) >> 5)] = w;
+            }
+        }
+        return;
+    }
     if (col < P.U) {
 #pragma unroll 1
         for (int q = 0; q < 8; ++q) {
@@ -359,6 +411,7 @@ bool binact_mfma_supported(const BinactArgs &a) {
     if (a.p % a.in != 0 || a.in % 256 != 0) return false;
     const int64_t U = a.p / a.in;
     if (U % 8 != 0 || a.out % U != 0) return false;
+    if ((a.flags & TBN_FLAG_SIGN_OUT) && U % 32 != 0) return false;   // a word of sign bits lies in one replica
     if (a.in > (int64_t(1) << 24) || a.out > (int64_t(1) << 30) || U > (int64_t(1) << 24)) return false;
     if ((reinterpret_cast<uintptr_t>(a.xbits) | reinterpret_cast<uintptr_t>(a.tile) | reinterpret_cast<uintptr_t>(a.y)) & 15u) return false;
     const int64_t blocks = ((a.M + 127) / 128) * ((U + 127) / 128);
@@ -366,21 +419,21 @@ bool binact_mfma_supported(const BinactArgs &a) {
 }
 
 // the permission for more than 64 KiB of LDS, once per process
-template <typename YT, bool RELU>
+template <typename YT, bool RELU, bool SIGN>
 static hipError_t allow_lds() {
-    static const hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(&binact_mfma_kernel<YT, RELU>),
+    static const hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(&binact_mfma_kernel<YT, RELU, SIGN>),
                                                     hipFuncAttributeMaxDynamicSharedMemorySize, kMfmaLds);
     return e;
 }
 
-template <typename YT, bool RELU>
+template <typename YT, bool RELU, bool SIGN = false>
 static tbn_status launch_mfma_t(const BinactArgs &a, const BinactMfmaParams &P, unsigned blocks) {
-    if (allow_lds<YT, RELU>() != hipSuccess) {
+    if (allow_lds<YT, RELU, SIGN>() != hipSuccess) {
         set_error("tbn_linear_forward_binact: the matrix-core kernel was refused %d bytes of LDS", kMfmaLds);
         (void)hipGetLastError();
         return TBN_ERR_DEVICE;
     }
-    hipLaunchKernelGGL((binact_mfma_kernel<YT, RELU>), dim3(blocks), dim3(256), kMfmaLds, a.stream, a.xbits,
+    hipLaunchKernelGGL((binact_mfma_kernel<YT, RELU, SIGN>), dim3(blocks), dim3(256), kMfmaLds, a.stream, a.xbits,
                        static_cast<YT *>(a.y), a.tile, a.alpha, P);
     return check_launch("tbn_linear_forward_binact (matrix-core kernel)");
 }
@@ -399,11 +452,21 @@ tbn_status launch_binact_mfma(const BinactArgs &a) {
     P.row_bytes = static_cast<int32_t>(a.in / 8);
     const unsigned blocks = static_cast<unsigned>(((a.M + 127) / 128) * P.tiles_n);
     const bool relu = (a.flags & TBN_FLAG_RELU) != 0;
+    if (a.flags & TBN_FLAG_SIGN_OUT) return launch_mfma_t<float, false, true>(a, P, blocks);
     if (a.dt == TBN_F32) return relu ? launch_mfma_t<float, true>(a, P, blocks) : launch_mfma_t<float, false>(a, P, blocks);
     return relu ? launch_mfma_t<uint16_t, true>(a, P, blocks) : launch_mfma_t<uint16_t, false>(a, P, blocks);
 }
 
 tbn_status launch_binact_generic(const BinactArgs &a) {
+    if (a.flags & TBN_FLAG_SIGN_OUT) {
+        const int64_t out_words = (a.out + 31) / 32, total_words = a.M * out_words;
+        int64_t blocks = (total_words + 255) / 256;
+        if (blocks > (1 << 20)) blocks = 1 << 20;
+        hipLaunchKernelGGL(binact_generic_sign_kernel, dim3(static_cast<unsigned>(blocks)), dim3(256), 0, a.stream, a.xbits,
+                           static_cast<uint32_t *>(a.y), total_words, a.in, a.out, (a.in + 31) / 32, out_words, a.tile, a.p,
+                           a.alpha, a.n_alpha);
+        return check_launch("tbn_linear_forward_binact (generic kernel, sign bits out)");
+    }
     const int64_t total = a.M * a.out;
     int64_t blocks = (total + 255) / 256;
     if (blocks > (1 << 20)) blocks = 1 << 20;

@@ -22,6 +22,7 @@ TBN_FLAG_BLOCK_KERNEL = 0x400
 TBN_FLAG_STREAM_KERNEL = 0x800
 TBN_FLAG_SPLIT_K = 0x1000
 TBN_FLAG_TILE_KERNEL = 0x2000
+TBN_FLAG_SIGN_OUT = 0x4000
 
 _STATUS = {1: "TBN_ERR_NULL", 2: "TBN_ERR_SHAPE", 3: "TBN_ERR_UNSUPPORTED", 4: "TBN_ERR_DEVICE",
            5: "TBN_ERR_WORKSPACE"}
@@ -337,12 +338,17 @@ def tbn_linear_forward_binact(xbits: torch.Tensor, cin: int, tile: torch.Tensor,
     if xbits.dim() != 2 or xbits.shape[1] != tbn_sign_row_words(cin):
         raise ValueError("xbits must be (M, ceil(in / 32))")
     M = xbits.shape[0]
+    if flags & TBN_FLAG_SIGN_OUT:   # rows of sign bits of the outputs
+        shape, ydt = (M, tbn_sign_row_words(out_features)), torch.int32
+    else:
+        shape, ydt = (M, out_features), dtype
     if y is None:
-        y = torch.empty((M, out_features), dtype=dtype, device=xbits.device)
-    elif tuple(y.shape) != (M, out_features):
-        raise ValueError("y must be (M, out)")
+        y = torch.empty(shape, dtype=ydt, device=xbits.device)
+    elif tuple(y.shape) != shape or (flags & TBN_FLAG_SIGN_OUT and y.dtype != torch.int32):
+        raise ValueError(f"y must be {shape}" + (" int32" if flags & TBN_FLAG_SIGN_OUT else ""))
     _check_layer_tensors("tbn_linear_forward_binact", xbits, tile, alpha, cin * out_features, k, y)
-    st = lib().tbn_linear_forward_binact(_dev(xbits, "xbits", torch.int32), _dev(y, "y"), _dt(y), M, cin, out_features,
+    st = lib().tbn_linear_forward_binact(_dev(xbits, "xbits", torch.int32), _dev(y, "y"),
+                                         TBN_F32 if flags & TBN_FLAG_SIGN_OUT else _dt(y), M, cin, out_features,
                                          _dev(tile, "tile", torch.int32), k, _dev(alpha, "alpha", torch.float32),
                                          alpha.numel(), flags, _stream(stream))
     if st != TBN_OK:

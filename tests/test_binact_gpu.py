@@ -193,6 +193,66 @@ def test_forward_relu_general_kernel(tbn):
     _check(tbn, 9, 100, 30, 3, 3, "f32", flags=1)
 
 
+def _check_sign_out(tbn, M, cin, out, k, n_alpha, flags=0):
+    xbits, tile, alpha = _layer(M, cin, out, k, n_alpha, 3 + M + cin + out + k)
+    if n_alpha > 1:
+        alpha[1] = -alpha[1]                      # a negative alpha flips the signs of its copy
+    ref = ba.linear_forward(xbits, cin, tile, alpha, out, k)
+    want = ba.sign_pack(ref)
+    y = tbn.tbn_linear_forward_binact(bits_dev(xbits), cin, dev(tile.view(np.int32)), dev(alpha), out, k, flags=0x4000 | flags)
+    torch.cuda.synchronize()
+    got = y.cpu().numpy().view(np.uint32)
+    assert got.shape == want.shape
+    p = cin * out // k
+    if n_alpha == 1 or p % cin == 0:
+        np.testing.assert_array_equal(got, want)
+    else:
+        # rows that cross tile ends add float32 products: a bit may differ only where the output is zero to rounding
+        diff = got ^ want
+        j = np.arange(out)
+        bad = ((diff[:, j // 32] >> (j % 32).astype(np.uint32)) & 1).astype(bool)
+        assert np.all(np.abs(ref[bad]) <= 1e-6 * np.abs(ref).max())
+        assert np.all((got[:, -1] >> np.uint32(out % 32 or 32)) == 0 if out % 32 else True)
+
+
+@pytest.mark.parametrize("M,cin,out,k,n_alpha", [MFMA[0], MFMA[1], MFMA[3], MFMA[5], MFMA[7], MFMA[8]])
+def test_sign_out_matrix_core_kernel(tbn, M, cin, out, k, n_alpha):
+    _check_sign_out(tbn, M, cin, out, k, n_alpha)
+
+
+@pytest.mark.parametrize("M,cin,out,k,n_alpha", GENERIC + [MFMA[2], MFMA[4], MFMA[6]])
+def test_sign_out_general_kernel(tbn, M, cin, out, k, n_alpha):
+    _check_sign_out(tbn, M, cin, out, k, n_alpha)
+
+
+def test_sign_out_both_kernels_agree_and_relu_changes_nothing(tbn):
+    M, cin, out, k, n_alpha = MFMA[3]
+    xbits, tile, alpha = _layer(M, cin, out, k, n_alpha, 8)
+    a = (bits_dev(xbits), cin, dev(tile.view(np.int32)), dev(alpha), out, k)
+    y0 = tbn.tbn_linear_forward_binact(*a, flags=0x4000)
+    y1 = tbn.tbn_linear_forward_binact(*a, flags=0x4000 | 0x100)
+    y2 = tbn.tbn_linear_forward_binact(*a, flags=0x4000 | 0x1)
+    torch.cuda.synchronize()
+    assert torch.equal(y0, y1) and torch.equal(y0, y2)
+
+
+def test_chain_of_two_layers_on_bits(tbn):
+    """real activations -> sign bits -> layer (bits out) -> layer (real out), against the oracle's chain."""
+    M, cin, hid, out = 200, 1024, 2048, 512
+    rng = np.random.default_rng(12)
+    x = rng.standard_normal((M, cin)).astype(np.float32)
+    t1, a1 = flat.pack_tile((0.02 * rng.standard_normal(hid * cin)).astype(np.float32), 4, 4)
+    t2, a2 = flat.pack_tile((0.02 * rng.standard_normal(out * hid)).astype(np.float32), 2, 2)
+    xb = tbn.tbn_sign_pack(dev(x))
+    hb = tbn.tbn_linear_forward_binact(xb, cin, dev(t1.view(np.int32)), dev(a1), hid, 4, flags=0x4000)
+    y = tbn.tbn_linear_forward_binact(hb, hid, dev(t2.view(np.int32)), dev(a2), out, 2)
+    torch.cuda.synchronize()
+    hb_ref = ba.linear_forward_signs(ba.sign_pack(x), cin, t1, a1, hid, 4)
+    np.testing.assert_array_equal(hb.cpu().numpy().view(np.uint32), hb_ref)
+    ref = ba.linear_forward(hb_ref, hid, t2, a2, out, 2)
+    np.testing.assert_array_equal(y.cpu().numpy(), ref.astype(np.float32))
+
+
 def test_end_to_end_from_real_activations(tbn):
     """sign_pack then forward on the bits it wrote, against the oracle on the real activations."""
     w = wl.METRIC
