@@ -342,30 +342,60 @@ __global__ __launch_bounds__(256, 2) void binact_mfma_kernel(const uint32_t *__r
     const int c8 = lane & 7, rsub = lane >> 3;
     const int32_t col = n0 + 8 * c8;
     if constexpr (SIGN) {
-        // eight sign bits per lane and replica; the four lanes of a word OR their bytes together (every lane takes
-        // part in the exchanges, only the first lane of a live word stores)
+        // alpha[t] * z is positive where z and alpha[t] have the same sign: the eight bits "z > 0" and the eight bits
+        // "z < 0" of a lane are formed once per row and the four lanes of a word OR their bytes together (every lane takes
+        // part in the exchanges).  A pass over eight rows has 16 words per replica; they are dealt to the lanes so that
+        // one store instruction writes the words of four replicas: lane l stores word l % 16 of the pass (row l / 2 % 8,
+        // half l % 2) for replicas l / 16, l / 16 + 4, ..., taking the "positive" or the "negative" word by the sign of
+        // that replica's alpha (zero or not a number: no bit).
         uint32_t *yb = reinterpret_cast<uint32_t *>(y);
         const int64_t out_words = P.out >> 5;
-#pragma unroll 1
+        const int slot = lane & 15, t_first = lane >> 4;
+        const int owner = (slot >> 1) * 8 + (slot & 1) * 4;   // a lane that holds word `slot` after the exchanges
+        const int32_t colw = n0 + 32 * (slot & 1);
+        const int32_t words_per_replica = P.U >> 5;
+        // the alphas of this lane's first four replicas (up to 16 replicas in all) are fetched once
+        float al_own[4];
+#pragma unroll
+        for (int c = 0; c < 4; ++c) {
+            const int32_t t = t_first + 4 * c;
+            al_own[c] = alpha[P.n_alpha == 1 ? 0 : (t < P.reps ? t : P.reps - 1)];
+        }
+#pragma unroll
         for (int q = 0; q < 8; ++q) {
             const int row = 8 * q + rsub;
-            const int64_t m = m0 + row;
             const f32x4_t z0 = *reinterpret_cast<const f32x4_t *>(zt + row * kTurnStride + 8 * c8);
             const f32x4_t z1 = *reinterpret_cast<const f32x4_t *>(zt + row * kTurnStride + 8 * c8 + 4);
-            const bool writer = m < P.M && col < P.U && (c8 & 3) == 0;
-            for (int32_t t = 0; t < P.reps; ++t) {
-                const float al = t < 64 ? __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, alpha_lanes), t))
-                                        : alpha[P.n_alpha == 1 ? 0 : t];
-                uint32_t w = 0;
+            uint32_t wp = 0, wn = 0;
 #pragma unroll
-                for (int i = 0; i < 4; ++i) {
-                    w |= (al * z0[i] > 0.f ? 1u : 0u) << i;
-                    w |= (al * z1[i] > 0.f ? 1u : 0u) << (4 + i);
+            for (int i = 0; i < 4; ++i) {
+                wp |= (z0[i] > 0.f ? 1u : 0u) << i;
+                wp |= (z1[i] > 0.f ? 1u : 0u) << (4 + i);
+                wn |= (z0[i] < 0.f ? 1u : 0u) << i;
+                wn |= (z1[i] < 0.f ? 1u : 0u) << (4 + i);
+            }
+            uint32_t both = (wp | (wn << 8)) << (16 * (c8 & 1));   // two lanes share a register for the first exchange
+            both |= __shfl_xor(both, 1);                           // bytes: pos(c8 even), neg(even), pos(odd), neg(odd)
+            const uint32_t pair_p = (both & 0xffu) | ((both >> 8) & 0xff00u), pair_n = ((both >> 8) & 0xffu) | ((both >> 16) & 0xff00u);
+            const uint32_t pn = pair_p | (pair_n << 16);           // low half: 16 "positive" bits of the lane pair, high half: "negative"
+            const uint32_t other = __shfl_xor(pn, 2);
+            const bool upper = (c8 & 2) != 0;                      // this pair holds bits 16 .. 31 of the word
+            const uint32_t lo = upper ? other : pn, hi = upper ? pn : other;
+            wp = (lo & 0xffffu) | (hi << 16);
+            wn = (lo >> 16) | (hi & 0xffff0000u);
+            const uint32_t sp = __shfl(wp, owner), sn = __shfl(wn, owner);   // the word this lane stores
+            const int64_t m = m0 + 8 * q + (slot >> 1);
+            if (m < P.M && colw < P.U) {
+                uint32_t *dst = yb + m * out_words + (colw >> 5);
+#pragma unroll
+                for (int c = 0; c < 4; ++c) {
+                    const int32_t t = t_first + 4 * c;
+                    if (t < P.reps) dst[int64_t(t) * words_per_replica] = al_own[c] > 0.f ? sp : (al_own[c] < 0.f ? sn : 0u);
                 }
-                w <<= 8 * (c8 & 3);
-                w |= __shfl_xor(w, 1);
-                w |= __shfl_xor(w, 2);
-                if (writer) yb[m * out_words + ((int64_t(t) * P.U + col) >> 5)] = w;
+                for (int32_t t = t_first + 16; t < P.reps; t += 4) {
+                    const float al = alpha[P.n_alpha == 1 ? 0 : t];
+                    dst[int64_t(t) * words_per_replica] = al > 0.f ? sp : (al < 0.f ? sn : 0u);
+                }
             }
         }
         return;
@@ -379,9 +409,7 @@ __global__ __launch_bounds__(256, 2) void binact_mfma_kernel(const uint32_t *__r
             const f32x4_t z0 = *reinterpret_cast<const f32x4_t *>(zt + row * kTurnStride + 8 * c8);
             const f32x4_t z1 = *reinterpret_cast<const f32x4_t *>(zt + row * kTurnStride + 8 * c8 + 4);
             YT *yrow = y + m * P.out + col;
-            for (int32_t t = 0; t < P.reps; ++t) {
-                const float al = t < 64 ? __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, alpha_lanes), t))
-                                        : alpha[P.n_alpha == 1 ? 0 : t];
+            auto emit = [&](int32_t t, float al) __attribute__((always_inline)) {
                 float v[8];
 #pragma unroll
                 for (int i = 0; i < 4; ++i) {
@@ -402,7 +430,11 @@ __global__ __launch_bounds__(256, 2) void binact_mfma_kernel(const uint32_t *__r
                     for (int i = 0; i < 4; ++i) o[i] = pack_bf16x2(v[2 * i], v[2 * i + 1]);
                     *reinterpret_cast<u32x4_t *>(yrow + int64_t(t) * P.U) = o;
                 }
-            }
+            };
+            const int32_t reps_in_lanes = P.reps < 64 ? P.reps : 64;
+            for (int32_t t = 0; t < reps_in_lanes; ++t)
+                emit(t, __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, alpha_lanes), t)));
+            for (int32_t t = 64; t < P.reps; ++t) emit(t, alpha[P.n_alpha == 1 ? 0 : t]);
         }
     }
 }
