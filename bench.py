@@ -383,6 +383,9 @@ def time_other_configs(torch, tbn, wl, iters=30):
         y = torch.empty((c.M, c.cout), dtype=x.dtype, device="cuda")
         usp = _timed_us(torch, lambda i: tbn.tbn_sign_pack(x, xbits=bits), iters)
         us = _timed_us(torch, lambda i: tbn.tbn_linear_forward_binact(bits, c.cin, tile, alpha, c.cout, c.k, y=y), iters)
+        yb = torch.empty((c.M, c.cout // 32), dtype=torch.int32, device="cuda")
+        uss = _timed_us(torch, lambda i: tbn.tbn_linear_forward_binact(bits, c.cin, tile, alpha, c.cout, c.k, y=yb,
+                                                                       flags=tbn.TBN_FLAG_SIGN_OUT), iters)
         byts = c.M * c.cin // 8 + c.M * c.cout * 2 + c.p // 8
         alg_flop = 2.0 * c.M * c.cin * (c.p // c.cin)
         t_hbm, t_mfma = byts / (HBM_PEAK_GBS * 1e3), alg_flop / (MFMA_FP4_PEAK_TFLOPS * 1e6)
@@ -390,8 +393,8 @@ def time_other_configs(torch, tbn, wl, iters=30):
             "us": round(us, 2), "sign_pack_us": round(usp, 2), "sign_pack_gbs": round(c.M * c.cin * 2 / usp / 1e3, 1),
             "alg_gbs": round(byts / us / 1e3, 1), "roof_us": round(max(t_hbm, t_mfma), 2),
             "bound": "hbm" if t_hbm >= t_mfma else "mfma", "frac_of_roof": round(max(t_hbm, t_mfma) / us, 3),
-            "real_valued_us": out[c.name]["us"]}
-        del w, x, y, bits
+            "sign_out_us": round(uss, 2), "real_valued_us": out[c.name]["us"]}
+        del w, x, y, yb, bits
     for c in (wl.CFG3, wl.CFG3_MISALIGNED, *wl.CONV_MORE):
         w = torch.from_numpy(wl.draw_w_real(c.n, c.cfg, c.layer)).cuda()
         xv, xb = wl.draw_x((c.N, c.C, c.H, c.W), c.cfg, c.layer, c.dtype)
