@@ -7,7 +7,7 @@
 //   * sign_pack: real activations -> rows of sign bits (one pass over X, 16 bytes per lane where rows are whole
 //     words, a wave ballot otherwise).
 //   * binact_mfma (tile of whole weight rows, in % 256 == 0): Z = S T^T on the matrix cores in the 4-bit float
-//     format (E2M1 holds +1 and -1 exactly; v_mfma_scale_f32_32x32x64_f8f6f4 with both scales 2^0 multiplies 64
+//     format (E2M1 holds +1 and -1 exactly; v_mfma_f32_32x32x64_f8f6f4, the form without block scales, multiplies 64
 //     elements of K per instruction, four times the bfloat16 rate; the float32 sums of +-1 products are exact).
 //     A lane's operand for one instruction is 32 sign bits; each byte of them becomes eight 4-bit values through a
 //     256-entry table in LDS that is stored once per lane (entry e of lane l at byte 256 e + 4 l: every read is
@@ -289,7 +289,7 @@ __global__ __launch_bounds__(256, 2) void binact_mfma_kernel(const uint32_t *__r
         expand(F[0][f], raw[0][f][0]);
         expand(F[1][f], raw[0][f][1]);
     }
-    constexpr int kOne = 0x7f7f7f7f;   // scale 2^0 in every byte
+    constexpr int kOne = 0;   // both scale operands zero: the compiler takes the form of the instruction without block scales
     // One super-step: four groups of four instructions.  In front of each instruction one operand of the group after
     // the next is looked up (a lookup takes longer to arrive than two instructions take to run, so one group ahead is
     // not enough), in the order in which that group needs them (A0, B0, B1, A1).  Three operand sets rotate with the
