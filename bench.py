@@ -270,6 +270,8 @@ def measure_ceilings(torch, tbn):
     blocks, iters = 1024, 2000
     us = _timed_us(torch, lambda i: tbn.tbn_diag_mfma(blocks, iters), 5, warm=2)
     out["mfma_bf16_loop_tflops"] = round(blocks * 4 * iters * 8 * 2.0 * 32 * 32 * 16 / us / 1e6, 1)
+    us = _timed_us(torch, lambda i: tbn.tbn_diag_mfma_fp4(blocks, iters), 5, warm=2)
+    out["mfma_fp4_loop_tflops"] = round(blocks * 4 * iters * 8 * 2.0 * 32 * 32 * 64 / us / 1e6, 1)
     return out
 
 

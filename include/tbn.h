@@ -287,11 +287,14 @@ tbn_status tbn_linear_forward_binact(const uint32_t *xbits, void *y, tbn_dtype y
  *                           be NULL or 4 bytes of device memory.
  *   tbn_diag_mfma         : `blocks` workgroups of four waves, every wave issues iters x 8 independent
  *                           32x32x16 bf16 MFMAs (2 * 32 * 32 * 16 flop each); out is NULL or blocks * 256 floats.
+ *   tbn_diag_mfma_fp4     : the same with 32x32x64 MFMAs on 4-bit float operands (2 * 32 * 32 * 64 flop each), the
+ *                           instruction of tbn_linear_forward_binact.
  * Errors: TBN_ERR_NULL, TBN_ERR_SHAPE, TBN_ERR_DEVICE.
  */
 tbn_status tbn_diag_empty_launch(void *stream);
 tbn_status tbn_diag_stream(const void *src, void *dst, size_t bytes, void *sink, void *stream);
 tbn_status tbn_diag_mfma(int32_t blocks, int32_t iters, float *out, void *stream);
+tbn_status tbn_diag_mfma_fp4(int32_t blocks, int32_t iters, float *out, void *stream);
 
 #ifdef __cplusplus
 }

@@ -363,6 +363,14 @@ tbn_status tbn_diag_mfma(int32_t blocks, int32_t iters, float *out, void *stream
     return launch_diag_mfma(blocks, iters, out, static_cast<hipStream_t>(stream));
 }
 
+tbn_status tbn_diag_mfma_fp4(int32_t blocks, int32_t iters, float *out, void *stream) {
+    if (blocks <= 0 || iters < 0 || blocks > (1 << 20)) {
+        set_error("tbn_diag_mfma_fp4: blocks must be in 1 .. 2^20, iters non-negative");
+        return TBN_ERR_SHAPE;
+    }
+    return launch_diag_mfma(blocks, iters, out, static_cast<hipStream_t>(stream), true);
+}
+
 tbn_status tbn_conv2d_forward(const void *x, void *y, tbn_dtype dt, int64_t N, int64_t C,
                               int64_t H, int64_t W, int64_t O, int32_t kh, int32_t kw,
                               int32_t stride_h, int32_t stride_w, int32_t pad_h, int32_t pad_w,

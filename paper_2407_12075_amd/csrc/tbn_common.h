@@ -94,7 +94,7 @@ tbn_status launch_conv_mfma(const ConvArgs &a);
 // measurement aids (tbn_diag.hip)
 tbn_status launch_diag_empty(hipStream_t stream);
 tbn_status launch_diag_stream(const void *src, void *dst, size_t bytes, uint32_t *sink, hipStream_t stream);
-tbn_status launch_diag_mfma(int32_t blocks, int32_t iters, float *out, hipStream_t stream);
+tbn_status launch_diag_mfma(int32_t blocks, int32_t iters, float *out, hipStream_t stream, bool fp4 = false);
 
 // number of distinct bit rows of the (rows x row_len) weight: row o repeats row o % U
 int64_t unique_rows(int64_t rows, int64_t row_len, int64_t p);

@@ -65,6 +65,31 @@ __global__ __launch_bounds__(256) void diag_mfma_kernel(int32_t iters, float *__
     if (out) out[int64_t(blockIdx.x) * blockDim.x + threadIdx.x] = s;
 }
 
+// the same with the 4-bit float form of the MFMA (32x32x64, both operands E2M1, no block scales): the instruction
+// of the binary-activation kernel
+__global__ __launch_bounds__(256) void diag_mfma_fp4_kernel(int32_t iters, float *__restrict__ out) {
+    typedef int i32x8_t __attribute__((ext_vector_type(8)));
+    i32x8_t a = {}, b = {};
+#pragma unroll
+    for (int e = 0; e < 4; ++e) {
+        a[e] = static_cast<int>(0x2a2a2a2au ^ (0x88888888u * ((threadIdx.x + e) & 1)));   // nibbles 0x2 / 0xA: +1 and -1
+        b[e] = static_cast<int>(0xa2a2a2a2u);
+    }
+    f32x16_t acc[8];
+#pragma unroll
+    for (int t = 0; t < 8; ++t)
+#pragma unroll
+        for (int e = 0; e < 16; ++e) acc[t][e] = 0.f;
+    for (int32_t it = 0; it < iters; ++it) {
+#pragma unroll
+        for (int t = 0; t < 8; ++t) acc[t] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(a, b, acc[t], 4, 4, 0, 0, 0, 0);
+    }
+    float s = 0.f;
+#pragma unroll
+    for (int t = 0; t < 8; ++t) s += acc[t][0];
+    if (out) out[int64_t(blockIdx.x) * blockDim.x + threadIdx.x] = s;
+}
+
 }  // namespace
 
 tbn_status launch_diag_empty(hipStream_t stream) {
@@ -84,7 +109,11 @@ tbn_status launch_diag_stream(const void *src, void *dst, size_t bytes, uint32_t
     return check_launch("tbn_diag_stream");
 }
 
-tbn_status launch_diag_mfma(int32_t blocks, int32_t iters, float *out, hipStream_t stream) {
+tbn_status launch_diag_mfma(int32_t blocks, int32_t iters, float *out, hipStream_t stream, bool fp4) {
+    if (fp4) {
+        hipLaunchKernelGGL(diag_mfma_fp4_kernel, dim3(static_cast<unsigned>(blocks)), dim3(256), 0, stream, iters, out);
+        return check_launch("tbn_diag_mfma_fp4");
+    }
     hipLaunchKernelGGL(diag_mfma_kernel, dim3(static_cast<unsigned>(blocks)), dim3(256), 0, stream, iters, out);
     return check_launch("tbn_diag_mfma");
 }

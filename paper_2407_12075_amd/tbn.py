@@ -92,6 +92,8 @@ def lib() -> ctypes.CDLL:
         L.tbn_diag_stream.argtypes = [_c_vp, _c_vp, _c_sz, _c_vp, _c_vp]
         L.tbn_diag_mfma.restype = ctypes.c_int
         L.tbn_diag_mfma.argtypes = [_c_i32, _c_i32, _c_vp, _c_vp]
+        L.tbn_diag_mfma_fp4.restype = ctypes.c_int
+        L.tbn_diag_mfma_fp4.argtypes = [_c_i32, _c_i32, _c_vp, _c_vp]
         _lib = L
     return _lib
 
@@ -372,5 +374,11 @@ def tbn_diag_stream(src: torch.Tensor, dst: Optional[torch.Tensor] = None, strea
 
 def tbn_diag_mfma(blocks: int, iters: int, stream=None) -> None:
     st = lib().tbn_diag_mfma(blocks, iters, None, _stream(stream))
+    if st != TBN_OK:
+        _raise(st)
+
+
+def tbn_diag_mfma_fp4(blocks: int, iters: int, stream=None) -> None:
+    st = lib().tbn_diag_mfma_fp4(blocks, iters, None, _stream(stream))
     if st != TBN_OK:
         _raise(st)

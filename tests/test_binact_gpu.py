@@ -4,7 +4,7 @@ alpha times one integer (one alpha for the layer, or weight rows inside one tile
 the oracle's float64 product rounded to float32 bit for bit, and a bfloat16 output that value rounded once more;
 rows that cross tile ends with k alphas add a few float32 products and are held to 1e-6 of the largest magnitude.
 Shapes span the matrix-core kernel (several blocks, ragged rows and columns, one to three super-steps and more, all
-register-set rotations, K dealt to one and to two waves per tile) and the shape-agnostic kernel (rows that are no whole words, tiles shorter than a row,
+register-set rotations) and the shape-agnostic kernel (rows that are no whole words, tiles shorter than a row,
 tiles that end inside words).
 """
 import numpy as np
@@ -120,7 +120,7 @@ MFMA = [
     (300, 4096, 1024, 8, 8),      # sixteen super-steps, 128 distinct columns
     (1, 4096, 64, 8, 8),          # a single batch row, eight distinct columns
     (513, 2048, 768, 3, 3),       # 256 distinct columns: two column blocks
-    (2100, 1536, 4096, 2, 2),     # 17 x 16 blocks, more than the chip has CUs: every wave runs all six super-steps
+    (2100, 1536, 4096, 2, 2),     # 17 x 16 blocks, more than the chip has CUs, six super-steps
 ]
 
 
