@@ -41,6 +41,9 @@ def parse_args():
     ap.add_argument("--all-configs", action="store_true", help="also time the other layer shapes (extra lines on stderr)")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="run only a plain device copy of 256 MiB (for scaling rocprofv3 FETCH_SIZE / WRITE_SIZE)")
+    ap.add_argument("--binact-only", action="store_true",
+                    help="run only the binary-activation path on the metric shape: sign packing, the layer with bf16 outputs and "
+                         "with sign-bit outputs, --steps times each (for rocprofv3 counter runs of these kernels)")
     return ap.parse_args()
 
 
@@ -84,6 +87,24 @@ def main():
             b.copy_(a)
         torch.cuda.synchronize()
         print(json.dumps({"copy_bytes_read": a.numel(), "copy_bytes_written": b.numel(), "launches": 5}))
+        return
+
+    if args.binact_only:
+        c = wl.METRIC
+        w, x, _ = device_inputs(c, torch, wl)
+        tile, alpha = tbn.tbn_pack_tile(w, c.k, c.n_alpha)
+        bits = tbn.tbn_sign_pack(x)
+        y = torch.empty((c.M, c.cout), dtype=torch.bfloat16, device="cuda")
+        yb = torch.empty((c.M, c.cout // 32), dtype=torch.int32, device="cuda")
+        for _ in range(args.steps):
+            tbn.tbn_sign_pack(x, xbits=bits)
+            tbn.tbn_linear_forward_binact(bits, c.cin, tile, alpha, c.cout, c.k, y=y)
+            tbn.tbn_linear_forward_binact(bits, c.cin, tile, alpha, c.cout, c.k, y=yb, flags=tbn.TBN_FLAG_SIGN_OUT)
+        torch.cuda.synchronize()
+        print(json.dumps({"workload": c.name, "calls_of_each": args.steps,
+                          "algorithmic_bytes": {"sign_pack": c.M * c.cin * 2 + c.M * c.cin // 8,
+                                                "layer_bf16_out": c.M * c.cin // 8 + c.p // 8 + c.M * c.cout * 2,
+                                                "layer_sign_out": c.M * c.cin // 8 + c.p // 8 + c.M * c.cout // 8}}))
         return
 
     big = wl.METRIC                       # batch 8192

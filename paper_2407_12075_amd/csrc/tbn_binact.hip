@@ -204,6 +204,8 @@ struct BinactMfmaParams {
     int32_t reps;       // out / U
     int32_t n_alpha;
     int32_t tiles_n;    // column blocks of 128
+    uint32_t tiles_m;   // row blocks of 128
+    int32_t xcd_order;  // deal the column blocks of a row block to one XCD
     int32_t n_super;    // in / 256
     int32_t row_bytes;  // in / 8
 };
@@ -219,7 +221,24 @@ __global__ __launch_bounds__(256, 2) void binact_mfma_kernel(const uint32_t *__r
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int ln = lane & 31, lh = lane >> 5;
     const uint32_t bid = blockIdx.x;
-    const uint32_t tile_m = bid / static_cast<uint32_t>(P.tiles_n), tile_n = bid - tile_m * static_cast<uint32_t>(P.tiles_n);
+    // Workgroup ids are dealt round-robin to the 8 XCDs: the column blocks of one row block take consecutive slots of
+    // one XCD, so that the rows of sign bits they share come from that XCD's L2 (the remaining row blocks: plain order).
+    uint32_t tile_m, tile_n;
+    {
+        const uint32_t tiles_n = static_cast<uint32_t>(P.tiles_n), xcd = bid & 7, slot = bid >> 3;
+        // (with real outputs and many column blocks the plain order measured 4 % faster: 8192 x 4096 -> 16384, k = 2 and 8)
+        const uint32_t full = P.xcd_order ? (P.tiles_m / 8) * tiles_n : 0u;   // slots per XCD in the regular part
+        if (slot < full) {
+            const uint32_t q = slot / tiles_n;
+            tile_n = slot - q * tiles_n;
+            tile_m = q * 8 + xcd;
+        } else {
+            const uint32_t rest = bid - full * 8;
+            const uint32_t q = rest / tiles_n;
+            tile_n = rest - q * tiles_n;
+            tile_m = (P.xcd_order ? (P.tiles_m / 8) * 8 : 0u) + q;
+        }
+    }
     const int64_t m0 = int64_t(tile_m) * 128 + (wave >> 1) * 64;   // this wave's first batch row
     const int32_t n0 = static_cast<int32_t>(tile_n) * 128 + (wave & 1) * 64;   // and first distinct column
 
@@ -480,6 +499,8 @@ tbn_status launch_binact_mfma(const BinactArgs &a) {
     P.reps = static_cast<int32_t>(a.out / U);
     P.n_alpha = a.n_alpha;
     P.tiles_n = static_cast<int32_t>((U + 127) / 128);
+    P.tiles_m = static_cast<uint32_t>((a.M + 127) / 128);
+    P.xcd_order = ((a.flags & TBN_FLAG_SIGN_OUT) || P.tiles_n <= 4) ? 1 : 0;
     P.n_super = static_cast<int32_t>(a.in / 256);
     P.row_bytes = static_cast<int32_t>(a.in / 8);
     const unsigned blocks = static_cast<unsigned>(((a.M + 127) / 128) * P.tiles_n);
