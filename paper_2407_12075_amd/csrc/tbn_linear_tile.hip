@@ -61,6 +61,7 @@ struct TileParams {
     int32_t in, out, U;
     int32_t reps, n_alpha;
     int32_t col_groups;   // groups of NT * 32 distinct columns
+    uint32_t row_tiles;   // tiles of 32 batch rows
     int32_t k_per_wave;   // K slice of a wave (whole chunks)
 };
 
@@ -122,10 +123,25 @@ __global__ __launch_bounds__(64 * KW) void linear_tile_kernel(const XT *__restri
     }
     __syncthreads();
 
-    const int64_t bid = blockIdx.x;
-    const int64_t rt = bid / P.col_groups;
-    const int32_t cg = static_cast<int32_t>(bid - rt * P.col_groups);
-    const int64_t m0 = rt * 32;
+    // Workgroup ids are dealt round-robin to the 8 XCDs: the column groups of one row tile take consecutive slots of
+    // one XCD, so that the rows of X they share are fetched from HBM once and then found in that XCD's L2 (plain order
+    // fetched X once per column group: 58 MB instead of 19 on 12608 x 384 -> 1536, float32).
+    uint32_t rt;
+    int32_t cg;
+    {
+        const uint32_t bid = blockIdx.x, groups = static_cast<uint32_t>(P.col_groups), xcd = bid & 7, slot = bid >> 3;
+        const uint32_t full = (P.row_tiles / 8) * groups;   // slots per XCD in the regular part
+        if (slot < full) {
+            const uint32_t q = slot / groups;
+            cg = static_cast<int32_t>(slot - q * groups);
+            rt = q * 8 + xcd;
+        } else {   // the remaining row tiles: plain order
+            const uint32_t rest = bid - full * 8, q = rest / groups;
+            cg = static_cast<int32_t>(rest - q * groups);
+            rt = (P.row_tiles / 8) * 8 + q;
+        }
+    }
+    const int64_t m0 = int64_t(rt) * 32;
     const int32_t u0 = cg * (NT * 32);
     const int32_t k_begin = wave * P.k_per_wave;
 
@@ -441,6 +457,7 @@ tbn_status launch_linear_tile(const LinearArgs &a) {
     int nt, groups, kw;
     plan(a, nt, groups, kw);
     P.col_groups = groups;
+    P.row_tiles = static_cast<uint32_t>((a.M + 31) / 32);
     P.k_per_wave = P.in / kw;
     const unsigned grid = static_cast<unsigned>(((a.M + 31) / 32) * groups);
     const bool relu = (a.flags & TBN_FLAG_RELU) != 0;
