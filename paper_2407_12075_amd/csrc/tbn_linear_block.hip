@@ -26,11 +26,12 @@
 //   * A byte of tile bits becomes the +-1 bf16 MFMA operand through a 256-entry table in LDS.
 //   * The replicated, alpha-scaled output is most of the bytes this kernel moves (eight ninths at k = 8).  It
 //     is written with 16-byte stores that cover whole 128-byte lines (the wave turns its sums round through
-//     LDS first).  When the grid has more blocks than the chip has CUs, so that some workgroups store while
-//     others load, the stores are non-temporal: the output then does not push the activations, which the
-//     other column blocks of the same rows still need, out of the XCD's L2 (8192 x 4096 -> 16384, k = 8: 146 us
-//     against 164).  When all workgroups store at the same time, plain stores are faster (8192 x 4096 -> 4096,
-//     k = 8: 37.7 us against 42.4): the last-level cache then takes the burst.
+//     LDS first).  Where persistent workgroups walk blocks of long rows with many column blocks the stores are
+//     non-temporal (STREAM, a compile-time form: a run-time choice between the two stores is merged into a plain one
+//     by the compiler): the output then does not push the activations, which the other column blocks of the same
+//     rows still need, out of the XCD's L2 (8192 x 4096 -> 16384, k = 4 / 8: 221 / 135 us against 258 / 149).  When
+//     all workgroups store at the same time, plain stores are faster (8192 x 4096 -> 4096, k = 8: 37.7 us against
+//     42.4): the last-level cache then takes the burst.
 //   * Split K (SPLIT = true, for grids that would leave most CUs idle and callers that bring a workspace):
 //     the K loop of a block is dealt to S workgroups; each writes its float32 partial sums of the 128 x 128
 //     block to the workspace, [split][M][U], and a second kernel adds the S partial sums of every output in
@@ -79,7 +80,6 @@ struct BlockParams {
     int32_t tiles_n;      // column blocks of U
     uint32_t tiles_m;
     int32_t n_rounds;     // rounds of 128 elements of K per workgroup (even): in / 128, or in / 128 / splits
-    int32_t stream_stores;   // write Y with non-temporal stores
     int32_t splits;       // workgroups that share the K loop of a block (1: none)
     uint32_t vrows;       // tiles_m * splits: (row block, split) pairs
     float *partial;       // split K: [split][M][U] float32 partial sums
@@ -151,7 +151,7 @@ __device__ __forceinline__ void block_coords(const BlockParams &P, uint32_t bid,
 // while the MFMA waves hand over and store a block, the load waves already have the first two rounds of the next
 // one in flight, so that only the first block of a workgroup waits for memory before its first MFMA.  The ring's
 // slots 0 and 1 take those rounds, which is why the hand-over then uses slots 2 and 3.
-template <bool RELU, bool SPLIT, bool PERSIST>
+template <bool RELU, bool SPLIT, bool PERSIST, bool STREAM = false>
 __global__ __launch_bounds__(512, 1) void linear_block_bf16_kernel(const uint16_t *__restrict__ x,
                                                                                      uint16_t *__restrict__ y,
                                                                                      const uint32_t *__restrict__ tile,
@@ -594,7 +594,8 @@ __global__ __launch_bounds__(512, 1) void linear_block_bf16_kernel(const uint16_
                 uint32_t off = z_lane + static_cast<uint32_t>(i) * out_bytes8;
                 asm volatile("" : "+v"(off));   // scalar base + 32-bit lane offset
                 if (col_ok && rr + 8 * i < rows_left) {
-                    if (P.stream_stores) __builtin_nontemporal_store(pk, (global_u32x4_t *)(dst + off));
+                    // a compile-time choice: the compiler merges the two stores of a run-time one into a plain store
+                    if constexpr (STREAM) __builtin_nontemporal_store(pk, (global_u32x4_t *)(dst + off));
                     else *(global_u32x4_t *)(dst + off) = pk;
                 }
             }
@@ -660,7 +661,6 @@ void fill_params(const LinearArgs &a, BlockParams &P) {
     P.tiles_m = static_cast<uint32_t>((a.M + kBM - 1) / kBM);
     P.tiles_n = (P.U + kBN - 1) / kBN;
     P.n_rounds = P.in / 128;
-    P.stream_stores = 0;
     P.splits = 1;
     P.vrows = P.tiles_m;
     P.partial = nullptr;
@@ -748,7 +748,6 @@ tbn_status launch_linear_split(const LinearArgs &a, int splits, void *workspace)
 tbn_status launch_linear_block(const LinearArgs &a) {
     BlockParams P;
     fill_params(a, P);
-    P.stream_stores = int64_t(P.tiles_m) * P.tiles_n > device_cus() ? 1 : 0;
     const dim3 grid(static_cast<unsigned>(int64_t(P.tiles_m) * P.tiles_n));
     const bool relu = (a.flags & TBN_FLAG_RELU) != 0;
     typedef void (*kernel_t)(const uint16_t *, uint16_t *, const uint32_t *, const float *, BlockParams);
@@ -756,14 +755,24 @@ tbn_status launch_linear_block(const LinearArgs &a) {
     int cus = device_cus() & ~7;
     if (cus < 8) cus = 8;
     const bool persist = int64_t(P.tiles_m) * P.tiles_n > cus && P.n_rounds >= 4 && P.n_rounds % 4 == 0;
-    static const kernel_t kernels[4] = {&linear_block_bf16_kernel<false, false, false>, &linear_block_bf16_kernel<true, false, false>,
-                                        &linear_block_bf16_kernel<false, false, true>, &linear_block_bf16_kernel<true, false, true>};
+    // Non-temporal stores (a form of its own: the choice has to be made at compile time) where a persistent workgroup
+    // walks blocks of long rows and a row block has at least eight column blocks: the output then does not push the
+    // activations, which the other column blocks of the same rows still need, out of the XCD's L2 (8192 x 4096 ->
+    // 16384, k = 2 / 4 / 8 / 16: 418 / 221 / 135 / 98 us against 421 / 258 / 149 / 100).  With short rows or few column
+    // blocks plain stores are faster (8192 x 1024 -> 4096, k = 2: 39 us against 48 - 51; 16384 x 4096 -> 4096, k = 8:
+    // 70 against 75), as they are when every workgroup stores at the same time (one block per CU: 37.7 against 42.4).
+    const bool stream = persist && P.n_rounds >= 32 && P.tiles_n >= 8;
+    static const kernel_t kernels[6] = {&linear_block_bf16_kernel<false, false, false>, &linear_block_bf16_kernel<true, false, false>,
+                                        &linear_block_bf16_kernel<false, false, true>, &linear_block_bf16_kernel<true, false, true>,
+                                        &linear_block_bf16_kernel<false, false, true, true>, &linear_block_bf16_kernel<true, false, true, true>};
     // dynamic LDS above the default limit has to be allowed once per kernel (thread-safe static initialisation)
-    static const tbn_status attr[4] = {set_lds_limit_once(reinterpret_cast<const void *>(kernels[0]), kLdsBytes),
+    static const tbn_status attr[6] = {set_lds_limit_once(reinterpret_cast<const void *>(kernels[0]), kLdsBytes),
                                        set_lds_limit_once(reinterpret_cast<const void *>(kernels[1]), kLdsBytes),
                                        set_lds_limit_once(reinterpret_cast<const void *>(kernels[2]), kLdsBytes),
-                                       set_lds_limit_once(reinterpret_cast<const void *>(kernels[3]), kLdsBytes)};
-    const int which = (relu ? 1 : 0) + (persist ? 2 : 0);
+                                       set_lds_limit_once(reinterpret_cast<const void *>(kernels[3]), kLdsBytes),
+                                       set_lds_limit_once(reinterpret_cast<const void *>(kernels[4]), kLdsBytes),
+                                       set_lds_limit_once(reinterpret_cast<const void *>(kernels[5]), kLdsBytes)};
+    const int which = (relu ? 1 : 0) + (stream ? 4 : persist ? 2 : 0);
     if (attr[which] != TBN_OK) {
         set_error("tbn_linear_forward: cannot reserve %d bytes of LDS for the block kernel", kLdsBytes);
         return TBN_ERR_DEVICE;

@@ -322,7 +322,13 @@ __global__ __launch_bounds__(64 * KW) void linear_tile_kernel(const XT *__restri
                     if (m >= P.M) continue;
                     f32x4_t v = al * z[i];
                     if (RELU) { v[0] = fmaxf(v[0], 0.f); v[1] = fmaxf(v[1], 0.f); v[2] = fmaxf(v[2], 0.f); v[3] = fmaxf(v[3], 0.f); }
-                    *reinterpret_cast<f32x4_t *>(y + m * P.out + int64_t(rep) * P.U + u) = v;
+                    f32x4_t *dst = reinterpret_cast<f32x4_t *>(y + m * P.out + int64_t(rep) * P.U + u);
+                    // Non-temporal where K is split among the waves of a workgroup (long rows: the layer then reads more
+                    // than it writes and the output should not push X out of the L2: 12608 x 1536 -> 384 20.1 us against
+                    // 21.3); plain otherwise (384 -> 1536: 27.0 against 28.7 non-temporal).  A compile-time choice: the
+                    // compiler merges the two stores of a run-time one into a plain store.
+                    if constexpr (KW > 1) __builtin_nontemporal_store(v, dst);
+                    else *dst = v;
                 }
             }
         } else {
