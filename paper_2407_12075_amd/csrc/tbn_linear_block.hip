@@ -708,7 +708,7 @@ int linear_split_plan(const LinearArgs &a) {
         if (blocks * s <= cus && pairs % s == 0) best = s;
     if (!best || (a.flags & TBN_FLAG_SPLIT_K)) return best;
     const double R = double(a.in) / 128.0;
-    const double one = blocks < 128 ? 8.0 + 0.26 * R * (1.0 + double(blocks) / 256.0) : 12.0 + 0.55 * R;
+    const double one = blocks <= 128 ? 8.0 + 0.26 * R * (1.0 + double(blocks) / 256.0) : 12.0 + 0.55 * R;
     const double split = 20.0 + 0.55 * R / best + 8.0 * double(blocks) / 128.0;
     return split < 0.9 * one ? best : 0;
 }
