@@ -25,13 +25,23 @@
 //     Tile bits are never fetched lane by lane from global memory.
 //   * A byte of tile bits becomes the +-1 bf16 MFMA operand through a 256-entry table in LDS.
 //   * The replicated, alpha-scaled output is most of the bytes this kernel moves (eight ninths at k = 8).  It
-//     is written with 16-byte stores that cover whole 128-byte lines (the wave turns its sums round through
-//     LDS first).  Where persistent workgroups walk blocks of long rows with many column blocks the stores are
-//     non-temporal (STREAM, a compile-time form: a run-time choice between the two stores is merged into a plain one
-//     by the compiler): the output then does not push the activations, which the other column blocks of the same
-//     rows still need, out of the XCD's L2 (8192 x 4096 -> 16384, k = 4 / 8: 221 / 135 us against 258 / 149).  When
-//     all workgroups store at the same time, plain stores are faster (8192 x 4096 -> 4096, k = 8: 37.7 us against
-//     42.4): the last-level cache then takes the burst.
+//     is written with 16-byte stores that cover whole 128-byte lines (the sums are turned round through LDS
+//     first).  With one block per workgroup the MFMA waves write it themselves with plain stores: all workgroups
+//     store at the same time and the last-level cache takes the burst (8192 x 4096 -> 4096, k = 8: 37.7 us
+//     against 42.4 with non-temporal stores).
+//   * Grids of more blocks than CUs (PERSIST): one workgroup per CU walks blocks, and the stores of a block run
+//     under the K loop of the next one.  Of waves 4 .. 7 two load (two quarters of a round each) and two store: the
+//     MFMA waves leave the sums of a finished block in LDS, a store wave takes two 64 x 64 quarters into 128
+//     registers and writes them, scaled, a few (replica, quarter, 32 rows) units per round, with non-temporal
+//     stores (next to a running loop, plain stores push the activations that the other column blocks of the same
+//     rows still need out of the XCD's L2: 16384 x 4096 -> 4096, k = 8: 81 us against 65).  Stores and loads have
+//     waves of their own because the vector-memory counter counts both, in issue order: a wave that did both
+//     waited for its stores whenever it waited for a round of loads (8192 x 4096 -> 16384, k = 8: block loops of
+//     28.7 us against 24.7).  The first two rounds of the next block are issued inside the last rounds of the
+//     current one, whose ring slots 0 and 1 are free by then; between two loops lie 2.2 us (the K groups add their
+//     sums, the store waves take them over).  8192 x 4096 -> 16384, k = 2 / 4 / 8 / 16: 410 / 211 / 117 / 86 us
+//     against 410 / 216 / 127 / 97 with the stores after each loop; 32768 x 4096 -> 4096, k = 8: 137 against 152.
+//     What stays exposed is the stores of a workgroup's last block.
 //   * Split K (SPLIT = true, for grids that would leave most CUs idle and callers that bring a workspace):
 //     the K loop of a block is dealt to S workgroups; each writes its float32 partial sums of the 128 x 128
 //     block to the workspace, [split][M][U], and a second kernel adds the S partial sums of every output in
@@ -126,6 +136,13 @@ __device__ __forceinline__ uint32_t pack2(float a, float b) {
 
 template <int V> using Int = std::integral_constant<int, V>;
 
+// 16-byte store to a scalar base plus a 32-bit lane offset (NT: non-temporal)
+template <bool NT>
+__device__ __forceinline__ void global_store16(unsigned char *base, uint32_t off, const u32x4_t &v) {
+    if constexpr (NT) asm volatile("global_store_dwordx4 %0, %1, %2 nt" : : "v"(off), "v"(v), "s"(base) : "memory");
+    else asm volatile("global_store_dwordx4 %0, %1, %2" : : "v"(off), "v"(v), "s"(base) : "memory");
+}
+
 // Workgroups that share rows of X are given consecutive slots on one XCD (workgroup ids are dealt
 // round-robin to the 8 XCDs), so the later column blocks find X in that XCD's L2.
 // With split K the unit that shares data is a (row block, split) pair: vrow counts those.
@@ -148,10 +165,9 @@ __device__ __forceinline__ void block_coords(const BlockParams &P, uint32_t bid,
 // RELU: fused max(0, .) of Algorithm 1.  SPLIT: the workgroup takes one of P.splits equal parts of K and writes
 // float32 partial sums to P.partial instead of Y.  512 threads: waves 0 .. 3 multiply, waves 4 .. 7 load.
 // PERSIST (grids of more blocks than CUs; rounds in fours): the workgroup walks blocks blockIdx.x, + gridDim.x, ...;
-// while the MFMA waves hand over and store a block, the load waves already have the first two rounds of the next
-// one in flight, so that only the first block of a workgroup waits for memory before its first MFMA.  The ring's
-// slots 0 and 1 take those rounds, which is why the hand-over then uses slots 2 and 3.
-template <bool RELU, bool SPLIT, bool PERSIST, bool STREAM = false>
+// waves 4 and 5 load, waves 6 and 7 write the replicas of the block before.  The ring's slots 0 and 1 take the
+// first rounds of the next block while the current one ends, which is why the hand-over then uses slots 2 and 3.
+template <bool RELU, bool SPLIT, bool PERSIST>
 __global__ __launch_bounds__(512, 1) void linear_block_bf16_kernel(const uint16_t *__restrict__ x,
                                                                                      uint16_t *__restrict__ y,
                                                                                      const uint32_t *__restrict__ tile,
@@ -161,7 +177,7 @@ __global__ __launch_bounds__(512, 1) void linear_block_bf16_kernel(const uint16_
     const int tid = threadIdx.x;
     const int lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-    const int li = wave & 3;     // which quarter of a round's loads this wave issues (if it loads at all)
+    const int li = wave & 3;     // MFMA wave: which quarter of the block it owns
     const int grp = li >> 1;     // K group
     const int wn = li & 1;       // column half
     const int ln = lane & 31;    // operand lane inside a 32 x 32 tile
@@ -169,27 +185,32 @@ __global__ __launch_bounds__(512, 1) void linear_block_bf16_kernel(const uint16_
 
     static_assert(!(SPLIT && PERSIST), "a split grid never has more workgroups than CUs");
     constexpr int kXchg = PERSIST ? kRingOff + 2 * kSlotBytes : kXchgOff;   // hand-over area
+    // Waves 4 .. 7.  One block per workgroup: four load waves, each issues a quarter of a round's loads (quarter q:
+    // K group q / 2, row-slot half q % 2).  PERSIST: waves 4 and 5 load (two quarters each: K group = wave - 4),
+    // waves 6 and 7 write the replicas of the block before (the quarters of MFMA waves 2*(wave - 6) and + 1).
+    constexpr int NQ = PERSIST ? 2 : 1;   // quarters per load wave (and per store wave)
+    const int first_q = PERSIST ? 2 * (wave & 1) : (wave & 3);
     const int32_t n_rounds = P.n_rounds;
     const uint32_t n_blocks = P.vrows * static_cast<uint32_t>(P.tiles_n);
     uint32_t bid = blockIdx.x;
 
-    // ---- the loads of a round, a quarter per loading wave -----------------------------------------------
-    // Activations: wave-load j of loader li fills 1 KiB of K group li / 2's 16 KiB: piece q = 8*(li % 2) + j, row
-    // slot sr = 8*q + lane/8, chunk slot lane%8.  Row-slot block sr/32 holds row block (sr/32 + 2*grp) % 4 of the
+    // ---- the loads of a round, a quarter at a time ------------------------------------------------------
+    // Activations: wave-load j of quarter q fills 1 KiB of K group q / 2's 16 KiB: piece 8*(q % 2) + j, row slot
+    // sr = 8*piece + lane/8, chunk slot lane%8.  Row-slot block sr/32 holds row block (sr/32 + 2*grp) % 4 of the
     // block (so that each K group ends with the sums it keeps in its first accumulators), chunk slot s of row
     // slot sr holds 16-byte chunk s ^ ((sr >> 1) & 7) of the round's 128 bytes of that row.  Rows past M repeat
-    // row M - 1.  Tile chunk (two rounds: 256 bits = two 16-byte pieces per tile row): lane i of loader li fills
-    // slot S = 64*li + i of the chunk's 256: piece S / 128, LDS row S % 128; LDS row 64*h + 32*tn + l holds the
+    // row M - 1.  Tile chunk (two rounds: 256 bits = two 16-byte pieces per tile row): lane i of quarter q fills
+    // slot S = 64*q + i of the chunk's 256: piece S / 128, LDS row S % 128; LDS row 64*h + 32*tn + l holds the
     // tile row that operand lane l of column half h supplies for MFMA tile tn, i.e. column
     // 64*h + 16*(l/8) + 8*((l/4)%2) + 4*tn + l%4 of the block (with this numbering a lane ends up with eight
     // adjacent columns of one row of Y).
     uint32_t split = 0;
     int64_t m0 = 0;
     int32_t n0 = 0;
-    const unsigned char *x_blk = nullptr;
+    const unsigned char *x_blk[NQ] = {};
     const unsigned char *tile_bytes = nullptr;
-    uint32_t a_off[8];
-    uint32_t t_off = 0;
+    uint32_t a_off[NQ][8];
+    uint32_t t_off[NQ];
     auto set_block = [&](uint32_t b) __attribute__((always_inline)) {
         uint32_t tile_m, tile_n;
         block_coords(P, b, tile_m, tile_n);
@@ -202,93 +223,260 @@ __global__ __launch_bounds__(512, 1) void linear_block_bf16_kernel(const uint16_
         const uint32_t round0 = split * static_cast<uint32_t>(P.n_rounds);   // first round of this workgroup's part of K (even)
         m0 = int64_t(tile_m) * kBM;
         n0 = static_cast<int32_t>(tile_n) * kBN;
-        x_blk = reinterpret_cast<const unsigned char *>(x) + m0 * P.in * 2 + (grp * 128 - kBias) + round0 * 256u;
         tile_bytes = reinterpret_cast<const unsigned char *>(tile) + round0 * 16u;
         const int64_t last = P.M - 1 - m0;
 #pragma unroll
-        for (int j = 0; j < 8; ++j) {
-            const int sr = 8 * (8 * wn + j) + (lane >> 3);
-            const int r = ((((sr >> 5) + 2 * grp) & 3) << 5) + (sr & 31);
-            const uint32_t rr = static_cast<uint32_t>(r < last ? r : last);
-            const int chunk = (lane & 7) ^ ((sr >> 1) & 7);
-            a_off[j] = rr * static_cast<uint32_t>(P.in) * 2u + static_cast<uint32_t>(chunk * 16 + kBias - (j & 3) * 1024);
+        for (int q = 0; q < NQ; ++q) {
+            const int lq = first_q + q, gq = lq >> 1, hq = lq & 1;
+            x_blk[q] = reinterpret_cast<const unsigned char *>(x) + m0 * P.in * 2 + (gq * 128 - kBias) + round0 * 256u;
+#pragma unroll
+            for (int j = 0; j < 8; ++j) {
+                const int sr = 8 * (8 * hq + j) + (lane >> 3);
+                const int r = ((((sr >> 5) + 2 * gq) & 3) << 5) + (sr & 31);
+                const uint32_t rw = static_cast<uint32_t>(r < last ? r : last);
+                const int chunk = (lane & 7) ^ ((sr >> 1) & 7);
+                a_off[q][j] = rw * static_cast<uint32_t>(P.in) * 2u + static_cast<uint32_t>(chunk * 16 + kBias - (j & 3) * 1024);
+            }
+            const int S = 64 * lq + lane, rho = S & 127, l = rho & 31;
+            int32_t u = n0 + (rho & 64) + 16 * (l >> 3) + 8 * ((l >> 2) & 1) + 4 * ((rho >> 5) & 1) + (l & 3);
+            u = u < P.U ? u : P.U - 1;   // columns past U repeat the last one; they are never written
+            t_off[q] = static_cast<uint32_t>(u) * (static_cast<uint32_t>(P.in) >> 3) + static_cast<uint32_t>((S >> 7) * 16);
         }
-        const int S = 64 * li + lane, rho = S & 127, l = rho & 31;
-        int32_t u = n0 + (rho & 64) + 16 * (l >> 3) + 8 * ((l >> 2) & 1) + 4 * ((rho >> 5) & 1) + (l & 3);
-        u = u < P.U ? u : P.U - 1;   // columns past U repeat the last one; they are never written
-        t_off = static_cast<uint32_t>(u) * (static_cast<uint32_t>(P.in) >> 3) + static_cast<uint32_t>((S >> 7) * 16);
     };
     set_block(bid);
-    unsigned char *const ring_mine = lds_raw + kRingOff + grp * 16384 + wn * 8192;
-    unsigned char *const tring_mine = lds_raw + kTileOff + li * 1024;
-    // issue order per round, which the wait counts rely on: eight activation wave-loads, then (even rounds) the
-    // tile chunk of this round and the next
-    auto issue_x = [&](auto j_c, int32_t round_) {
-        constexpr int J = decltype(j_c)::value;
-        const unsigned char *src = x_blk + static_cast<uint32_t>(round_) * 256u;   // wave-uniform
+    // issue order per round, which the wait counts rely on: eight activation wave-loads per quarter, then (even
+    // rounds) a quarter's share of the tile chunk of this round and the next
+    auto issue_x = [&](auto q_c, auto j_c, int32_t round_) {
+        constexpr int Q = decltype(q_c)::value, J = decltype(j_c)::value;
+        const int lq = first_q + Q;
+        unsigned char *const ring_q = lds_raw + kRingOff + (lq >> 1) * 16384 + (lq & 1) * 8192;
+        const unsigned char *src = x_blk[Q] + static_cast<uint32_t>(round_) * 256u;   // wave-uniform
         asm volatile("" : "+s"(src));   // one scalar base, the lane offset stays a 32-bit register
-        uint32_t off = a_off[J];
+        uint32_t off = a_off[Q][J];
         asm volatile("" : "+v"(off));
-        wave_load<(J & 3)>(src, off, ring_mine + (round_ & (kNB - 1)) * kSlotBytes + (J >> 2) * 4096);
+        wave_load<(J & 3)>(src, off, ring_q + (round_ & (kNB - 1)) * kSlotBytes + (J >> 2) * 4096);
     };
-    auto issue_tile = [&](int32_t round_) {   // round_ is even
+    auto issue_tile = [&](auto q_c, int32_t round_) {   // round_ is even
+        constexpr int Q = decltype(q_c)::value;
         const unsigned char *src = tile_bytes + static_cast<uint32_t>(round_) * 16u;   // 128 bits per round
         asm volatile("" : "+s"(src));
-        uint32_t off = t_off;
+        uint32_t off = t_off[Q];
         asm volatile("" : "+v"(off));
-        __builtin_amdgcn_global_load_lds(src + off, tring_mine + ((round_ >> 1) % kTileSlots) * kTileSlotBytes, 16, 0, 0);
+        __builtin_amdgcn_global_load_lds(src + off, lds_raw + kTileOff + (first_q + Q) * 1024 + ((round_ >> 1) % kTileSlots) * kTileSlotBytes, 16, 0, 0);
+    };
+    auto issue_quarter = [&](auto q_c, int32_t round_) {
+        issue_x(q_c, Int<0>{}, round_); issue_x(q_c, Int<1>{}, round_); issue_x(q_c, Int<2>{}, round_); issue_x(q_c, Int<3>{}, round_);
+        issue_x(q_c, Int<4>{}, round_); issue_x(q_c, Int<5>{}, round_); issue_x(q_c, Int<6>{}, round_); issue_x(q_c, Int<7>{}, round_);
     };
     auto issue_round = [&](int32_t round_) {
-        issue_x(Int<0>{}, round_); issue_x(Int<1>{}, round_); issue_x(Int<2>{}, round_); issue_x(Int<3>{}, round_);
-        issue_x(Int<4>{}, round_); issue_x(Int<5>{}, round_); issue_x(Int<6>{}, round_); issue_x(Int<7>{}, round_);
-        if ((round_ & 1) == 0) issue_tile(round_);
+        issue_quarter(Int<0>{}, round_);
+        if constexpr (NQ == 2) issue_quarter(Int<1>{}, round_);
+        if ((round_ & 1) == 0) {
+            issue_tile(Int<0>{}, round_);
+            if constexpr (NQ == 2) issue_tile(Int<1>{}, round_);
+        }
     };
+    constexpr int kOdd = 8 * NQ, kEven = 9 * NQ;   // loads of an odd and of an even round per load wave
+
+    // a lane's place in the stores of a replica: eight lanes per row of Y, eight adjacent columns each
+    const int g8 = lane & 7, rr = lane >> 3;
+    const uint32_t z_lane = (static_cast<uint32_t>(rr) * static_cast<uint32_t>(P.out) + static_cast<uint32_t>(8 * g8)) * 2u;
+    const uint32_t out_bytes8 = static_cast<uint32_t>(P.out) * 16u;   // eight rows of Y in bytes
+    const uint32_t rep_bytes = static_cast<uint32_t>(P.U) * 2u;
+    const uint32_t xchg_mine = static_cast<uint32_t>(kXchg + li * 16384);
+
+    // =================================================================================================
+    // store waves (PERSIST)
+    // =================================================================================================
+    // MFMA wave q leaves the sums of its 64 x 64 quarter of a finished block in the hand-over area; a store wave
+    // takes two quarters into registers (128 per lane) and writes them, scaled, one (replica, quarter, 32 rows)
+    // unit after the other, spread evenly over the rounds in which the MFMA waves multiply the next block: the
+    // matrix pipe does not wait for the stores, which are most of the bytes this kernel moves.  The stores have
+    // waves of their own because the vector-memory counter counts loads and stores alike and in issue order: a
+    // wave that did both would wait for its stores whenever it waits for a round of loads.
+    if (PERSIST && wave >= 6) {
+        float alpha_lanes;
+        {
+            const int t = P.n_alpha == 1 ? 0 : (lane < P.reps ? lane : P.reps - 1);
+            const uint32_t off = static_cast<uint32_t>(t) * 4u;
+            asm volatile("global_load_dword %0, %1, %2\n\ts_waitcnt vmcnt(0)" : "=v"(alpha_lanes) : "v"(off), "s"(alpha) : "memory");
+        }
+        float zr[2][2][4][8];   // [quarter][32-row half][row rr + 8*i][column 8*g8 + e]
+        unsigned char *st_base = nullptr;   // &Y[first row of quarter 0][first column of quarter 0], replica 0
+        int64_t st_rows = 0;          // rows of the quarters that exist (may be <= 0)
+        bool st_col_ok[2] = {false, false};
+        int32_t st_rot = 0;           // the replica a block starts with: workgroups that store at the same time write different ones
+        int32_t st_next = 0, st_total = 0, st_credit = 0;   // units written / to write; spreads them over the rounds
+        auto store_unit = [&](int32_t uidx) __attribute__((always_inline)) {
+            const int32_t sub = uidx & 3, half = sub & 1, q = sub >> 1;
+            int32_t t = (uidx >> 2) + st_rot;
+            t = t >= P.reps ? t - P.reps : t;
+            const float al = __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, alpha_lanes), t));
+            unsigned char *dst = st_base + static_cast<uint32_t>(t) * rep_bytes + static_cast<uint32_t>(half) * 4u * out_bytes8 + static_cast<uint32_t>(q) * 128u;
+            const int64_t rows_left = st_rows - 32 * half;
+            auto emit = [&](auto q_c, auto half_c) __attribute__((always_inline)) {
+                constexpr int Q = decltype(q_c)::value, H = decltype(half_c)::value;
+#pragma unroll
+                for (int i = 0; i < 4; ++i) {
+                    float v[8];
+#pragma unroll
+                    for (int e = 0; e < 8; ++e) {
+                        v[e] = al * zr[Q][H][i][e];
+                        if (RELU) v[e] = fmaxf(v[e], 0.f);
+                    }
+                    const u32x4_t pk = {pack2(v[0], v[1]), pack2(v[2], v[3]), pack2(v[4], v[5]), pack2(v[6], v[7])};
+                    if (st_col_ok[Q] && rr + 8 * i < rows_left) global_store16<true>(dst, z_lane + static_cast<uint32_t>(i) * out_bytes8, pk);
+                }
+            };
+            if (sub == 0) emit(Int<0>{}, Int<0>{});
+            else if (sub == 1) emit(Int<0>{}, Int<1>{});
+            else if (sub == 2) emit(Int<1>{}, Int<0>{});
+            else emit(Int<1>{}, Int<1>{});
+        };
+        for (;;) {
+            const int64_t cur_m0 = m0;
+            const int32_t cur_n0 = n0;
+            __builtin_amdgcn_s_barrier();   // the block's first barrier
+            for (int32_t g = 0; g < n_rounds; ++g) {
+                __builtin_amdgcn_s_barrier();
+                st_credit += st_total;
+                for (; st_credit >= n_rounds && st_next < st_total; st_credit -= n_rounds) store_unit(st_next++);
+            }
+            while (st_next < st_total) store_unit(st_next++);
+            const uint32_t next = bid + gridDim.x;
+            const bool more = next < n_blocks;
+            if (more) {
+                bid = next;
+                set_block(bid);
+            }
+            __builtin_amdgcn_s_barrier();   // the two barriers of the hand-over
+            __builtin_amdgcn_s_barrier();
+            __builtin_amdgcn_s_barrier();   // the sums of the finished block are in the hand-over area
+            // the same turn-round as in the epilogue of the MFMA waves below: eight lanes take one row's 64 columns
+            {
+                const int ch_a = 2 * g8 + (g8 >> 2), ch_b = 2 * g8 + 1 - (g8 >> 2);
+#pragma unroll
+                for (int q = 0; q < 2; ++q) {
+                    const uint32_t area = static_cast<uint32_t>(kXchg + (first_q + q) * 16384);
+                    u32x4_t za[2][4], zb[2][4];
+#pragma unroll
+                    for (int h = 0; h < 2; ++h)
+#pragma unroll
+                        for (int i = 0; i < 4; ++i) {
+                            const int r = rr + 8 * i;
+                            const int s_r = ((r >> 1) & 7) ^ (2 * (r & 1));
+                            lds_read16<0>(za[h][i], area + static_cast<uint32_t>(h * 8192 + r * 256 + ((ch_a ^ s_r) << 4)));
+                            lds_read16<0>(zb[h][i], area + static_cast<uint32_t>(h * 8192 + r * 256 + ((ch_b ^ s_r) << 4)));
+                        }
+                    lds_wait<0>();
+#pragma unroll
+                    for (int h = 0; h < 2; ++h)
+#pragma unroll
+                        for (int i = 0; i < 4; ++i) {
+                            tie(za[h][i]);
+                            tie(zb[h][i]);
+#pragma unroll
+                            for (int e = 0; e < 4; ++e) {
+                                zr[q][h][i][e] = __uint_as_float(g8 < 4 ? za[h][i][e] : zb[h][i][e]);
+                                zr[q][h][i][4 + e] = __uint_as_float(g8 < 4 ? zb[h][i][e] : za[h][i][e]);
+                            }
+                        }
+                }
+            }
+            {
+                const int64_t row0 = cur_m0 + 64 * (first_q >> 1);
+                st_base = reinterpret_cast<unsigned char *>(y) + (row0 * P.out + cur_n0) * 2;
+                st_rows = P.M - row0;
+                st_col_ok[0] = cur_n0 + 8 * g8 < P.U;
+                st_col_ok[1] = cur_n0 + 64 + 8 * g8 < P.U;
+                st_rot = static_cast<int32_t>(static_cast<uint32_t>(cur_m0 >> 7) % static_cast<uint32_t>(P.reps));
+                st_next = 0;
+                st_total = 4 * P.reps;
+                st_credit = 0;
+            }
+            if (!more) {
+                while (st_next < st_total) store_unit(st_next++);
+                return;
+            }
+        }
+    }
 
     // =================================================================================================
     // load waves
     // =================================================================================================
     if (wave >= 4) {
-        if (PERSIST) { issue_round(0); issue_round(1); }
-        for (;;) {
-            if (PERSIST) {
-                // rounds 0 and 1 of this block are in flight (issued at kernel start, or while the previous block was
-                // handed over); round 0 and its tile chunk have to land, round 1's eight loads are younger
-                __builtin_amdgcn_s_waitcnt(vmcnt_imm(8));
+        if constexpr (PERSIST) {
+            // One workgroup walks blocks.  The last three rounds of a block load nothing for it, and ring slots 0 and 1
+            // are free by then: the activations of the next block's rounds 0 and 1 are issued there, one round each,
+            // and its first tile chunk behind the last round's barrier (that slot of the tile ring is read until then),
+            // so the hand-over between two blocks waits for no load to be issued.
+            issue_round(0);
+            issue_round(1);
+            __builtin_amdgcn_s_waitcnt(vmcnt_imm(kOdd));   // round 0 and its tile chunk; round 1's loads are younger
+            for (;;) {
                 __builtin_amdgcn_s_barrier();   // meets the MFMA waves' "round 0 readable; the hand-over area is free"
                 issue_round(2);
-            } else {
-                // rounds 0 .. 2 at once; then, at the top of every round, the loads of round + 3 into the slot that the
-                // barrier has just freed
-                for (int32_t d = 0; d < 3 && d < n_rounds; ++d) issue_round(d);
-                // round 0 is readable once it has landed (two younger rounds may be in flight)
-                if (n_rounds >= 3) __builtin_amdgcn_s_waitcnt(vmcnt_imm(8 + 8 + 1));
-                else __builtin_amdgcn_s_waitcnt(vmcnt_imm(0));
-                __builtin_amdgcn_s_barrier();   // meets the MFMA waves' "table written, round 0 readable"
+                const uint32_t next = bid + gridDim.x;
+                const bool more = next < n_blocks;
+                for (int32_t g = 0; g < n_rounds; ++g) {
+                    // round g + 1 has to be readable when the MFMA waves pass this barrier; what was issued after its
+                    // loads may stay in flight: round g + 2 (with the tile chunk if that round is even), or, at the end of
+                    // a block, the next block's round 0
+                    if (g + 2 < n_rounds) {
+                        if (g & 1) __builtin_amdgcn_s_waitcnt(vmcnt_imm(kOdd));
+                        else __builtin_amdgcn_s_waitcnt(vmcnt_imm(kEven));
+                    } else if (!more) {
+                        __builtin_amdgcn_s_waitcnt(vmcnt_imm(0));
+                    } else if (g + 2 == n_rounds) {
+                        __builtin_amdgcn_s_waitcnt(vmcnt_imm(8 * NQ));
+                    }
+                    __builtin_amdgcn_s_barrier();
+                    if (g + 3 < n_rounds) {
+                        issue_round(g + 3);
+                    } else if (more) {
+                        if (g + 3 == n_rounds) {
+                            bid = next;
+                            set_block(bid);
+                            issue_quarter(Int<0>{}, 0);
+                            issue_quarter(Int<1>{}, 0);
+                        } else if (g + 2 == n_rounds) {
+                            issue_quarter(Int<0>{}, 1);
+                            issue_quarter(Int<1>{}, 1);
+                        } else {
+                            issue_tile(Int<0>{}, 0);
+                            issue_tile(Int<1>{}, 0);
+                        }
+                    }
+                }
+                __builtin_amdgcn_s_barrier();   // the two barriers of the hand-over
+                __builtin_amdgcn_s_barrier();
+                __builtin_amdgcn_s_barrier();   // the store waves take the sums of the finished block
+                if (!more) return;
+                __builtin_amdgcn_s_waitcnt(vmcnt_imm(0));   // rounds 0 and 1 and the tile chunk of the next block
             }
+        } else {
+            // rounds 0 .. 2 at once; then, at the top of every round, the loads of round + 3 into the slot that the
+            // barrier has just freed
+            for (int32_t d = 0; d < 3 && d < n_rounds; ++d) issue_round(d);
+            // round 0 is readable once it has landed (two younger rounds may be in flight)
+            if (n_rounds >= 3) __builtin_amdgcn_s_waitcnt(vmcnt_imm(kOdd + kEven));
+            else __builtin_amdgcn_s_waitcnt(vmcnt_imm(0));
+            __builtin_amdgcn_s_barrier();   // meets the MFMA waves' "table written, round 0 readable"
             for (int32_t g = 0; g < n_rounds; ++g) {
-                // round g + 1 has to be readable when the MFMA waves pass this barrier; the loads of round g + 2 (eight,
-                // and the tile chunk with an even round) are younger and may stay in flight
+                // round g + 1 has to be readable when the MFMA waves pass this barrier; the loads of round g + 2 (with
+                // the tile chunk if that round is even) are younger and may stay in flight
                 if (g + 2 < n_rounds) {
-                    if (g & 1) __builtin_amdgcn_s_waitcnt(vmcnt_imm(8));
-                    else __builtin_amdgcn_s_waitcnt(vmcnt_imm(9));
+                    if (g & 1) __builtin_amdgcn_s_waitcnt(vmcnt_imm(kOdd));
+                    else __builtin_amdgcn_s_waitcnt(vmcnt_imm(kEven));
                 } else {
                     __builtin_amdgcn_s_waitcnt(vmcnt_imm(0));
                 }
                 __builtin_amdgcn_s_barrier();
                 if (g + 3 < n_rounds) issue_round(g + 3);
             }
-            // the barrier of the last round has freed ring slots 0 .. 2 and the tile slot of chunk 0
-            const uint32_t next = bid + gridDim.x;
-            const bool more = PERSIST && next < n_blocks;
-            if (more) {
-                bid = next;
-                set_block(bid);
-                issue_round(0);
-                issue_round(1);
-            }
             __builtin_amdgcn_s_barrier();   // the two barriers of the hand-over
             __builtin_amdgcn_s_barrier();
-            if (!more) return;
+            return;
         }
     }
 
@@ -457,7 +645,6 @@ __global__ __launch_bounds__(512, 1) void linear_block_bf16_kernel(const uint16_
     __builtin_amdgcn_s_barrier();
     asm volatile("s_nop 15");
     asm volatile("s_nop 15");
-    const uint32_t xchg_mine = static_cast<uint32_t>(kXchg + li * 16384);
     {
         const uint32_t dst = static_cast<uint32_t>(kXchg + (li ^ 2) * 16384) + static_cast<uint32_t>(lane) * 16u;
 #pragma unroll
@@ -513,11 +700,30 @@ __global__ __launch_bounds__(512, 1) void linear_block_bf16_kernel(const uint16_
     // sits at chunk position ch ^ s(r), s(r) = ((r >> 1) & 7) ^ (2 * (r & 1)): the writes (lanes = rows) and the
     // reads (eight lanes per row; a lane reads chunks 2*g8 and 2*g8 + 1, the upper four lanes in the other
     // order) are then free of bank conflicts.
-    const int g8 = lane & 7, rr = lane >> 3;
+    if constexpr (PERSIST) {
+        // the store waves write the replicas: leave both 32-row halves in this wave's part of the hand-over area (all of
+        // which the wave has read by now), in the layout described above
+        const int s_w = ((ln >> 1) & 7) ^ (2 * (ln & 1));
+#pragma unroll
+        for (int tm = 0; tm < 2; ++tm)
+#pragma unroll
+            for (int q = 0; q < 4; ++q)
+#pragma unroll
+                for (int tn = 0; tn < 2; ++tn) {
+                    const int ch = 4 * q + 2 * lg + tn;
+                    u32x4_t v;
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) v[e] = __float_as_uint(acc[tm][tn][4 * q + e]);
+                    lds_write16<0>(xchg_mine + static_cast<uint32_t>(tm * 8192 + ln * 256 + ((ch ^ s_w) << 4)), v);
+                }
+        lds_wait<0>();
+        __builtin_amdgcn_s_barrier();   // the store waves take the sums from here
+            const uint32_t next = bid + gridDim.x;
+        if (next >= n_blocks) break;
+        bid = next;
+        continue;
+    }
     const bool col_ok = n0 + 64 * wn + 8 * g8 < P.U;
-    const uint32_t z_lane = (static_cast<uint32_t>(rr) * static_cast<uint32_t>(P.out) + static_cast<uint32_t>(8 * g8)) * 2u;
-    const uint32_t out_bytes8 = static_cast<uint32_t>(P.out) * 16u;   // eight rows of Y in bytes
-    const uint32_t rep_bytes = static_cast<uint32_t>(P.U) * 2u;
 #pragma unroll
     for (int tm = 0; tm < 2; ++tm) {
         float zr[4][8];
@@ -593,19 +799,11 @@ __global__ __launch_bounds__(512, 1) void linear_block_bf16_kernel(const uint16_
                 asm volatile("" : "+s"(dst));
                 uint32_t off = z_lane + static_cast<uint32_t>(i) * out_bytes8;
                 asm volatile("" : "+v"(off));   // scalar base + 32-bit lane offset
-                if (col_ok && rr + 8 * i < rows_left) {
-                    // a compile-time choice: the compiler merges the two stores of a run-time one into a plain store
-                    if constexpr (STREAM) __builtin_nontemporal_store(pk, (global_u32x4_t *)(dst + off));
-                    else *(global_u32x4_t *)(dst + off) = pk;
-                }
+                if (col_ok && rr + 8 * i < rows_left) *(global_u32x4_t *)(dst + off) = pk;
             }
         }
     }
-    // the next block of this workgroup, if any
-    const uint32_t next = bid + gridDim.x;
-    if (!PERSIST || next >= n_blocks) break;
-    bid = next;
-    set_block(bid);
+    break;   // one block per workgroup
     }
 }
 
@@ -755,24 +953,16 @@ tbn_status launch_linear_block(const LinearArgs &a) {
     int cus = device_cus() & ~7;
     if (cus < 8) cus = 8;
     const bool persist = int64_t(P.tiles_m) * P.tiles_n > cus && P.n_rounds >= 4 && P.n_rounds % 4 == 0;
-    // Non-temporal stores (a form of its own: the choice has to be made at compile time) where a persistent workgroup
-    // walks blocks of long rows and a row block has at least eight column blocks: the output then does not push the
-    // activations, which the other column blocks of the same rows still need, out of the XCD's L2 (8192 x 4096 ->
-    // 16384, k = 2 / 4 / 8 / 16: 418 / 221 / 135 / 98 us against 421 / 258 / 149 / 100).  With short rows or few column
-    // blocks plain stores are faster (8192 x 1024 -> 4096, k = 2: 39 us against 48 - 51; 16384 x 4096 -> 4096, k = 8:
-    // 70 against 75), as they are when every workgroup stores at the same time (one block per CU: 37.7 against 42.4).
-    const bool stream = persist && P.n_rounds >= 32 && P.tiles_n >= 8;
-    static const kernel_t kernels[6] = {&linear_block_bf16_kernel<false, false, false>, &linear_block_bf16_kernel<true, false, false>,
-                                        &linear_block_bf16_kernel<false, false, true>, &linear_block_bf16_kernel<true, false, true>,
-                                        &linear_block_bf16_kernel<false, false, true, true>, &linear_block_bf16_kernel<true, false, true, true>};
+    // (its store waves write with non-temporal stores whatever the shape: next to a running K loop, plain stores push
+    // the activations that the other column blocks of the same rows still need out of the XCD's L2)
+    static const kernel_t kernels[4] = {&linear_block_bf16_kernel<false, false, false>, &linear_block_bf16_kernel<true, false, false>,
+                                        &linear_block_bf16_kernel<false, false, true>, &linear_block_bf16_kernel<true, false, true>};
     // dynamic LDS above the default limit has to be allowed once per kernel (thread-safe static initialisation)
-    static const tbn_status attr[6] = {set_lds_limit_once(reinterpret_cast<const void *>(kernels[0]), kLdsBytes),
+    static const tbn_status attr[4] = {set_lds_limit_once(reinterpret_cast<const void *>(kernels[0]), kLdsBytes),
                                        set_lds_limit_once(reinterpret_cast<const void *>(kernels[1]), kLdsBytes),
                                        set_lds_limit_once(reinterpret_cast<const void *>(kernels[2]), kLdsBytes),
-                                       set_lds_limit_once(reinterpret_cast<const void *>(kernels[3]), kLdsBytes),
-                                       set_lds_limit_once(reinterpret_cast<const void *>(kernels[4]), kLdsBytes),
-                                       set_lds_limit_once(reinterpret_cast<const void *>(kernels[5]), kLdsBytes)};
-    const int which = (relu ? 1 : 0) + (stream ? 4 : persist ? 2 : 0);
+                                       set_lds_limit_once(reinterpret_cast<const void *>(kernels[3]), kLdsBytes)};
+    const int which = (relu ? 1 : 0) + (persist ? 2 : 0);
     if (attr[which] != TBN_OK) {
         set_error("tbn_linear_forward: cannot reserve %d bytes of LDS for the block kernel", kLdsBytes);
         return TBN_ERR_DEVICE;

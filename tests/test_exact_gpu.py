@@ -116,6 +116,19 @@ def test_exact_bf16_relu_and_scalars(tbn):
     _exact_case(tbn, 5120, 512, 2048, 2, "bf16", tbn.TBN_FLAG_LARGE_BATCH | tbn.TBN_FLAG_RELU, 7, alpha_vals=[0.5, 2])
 
 
+def test_exact_bf16_persistent_blocks_with_store_waves(tbn):
+    """More blocks than CUs: a workgroup walks blocks, two of its waves load and two write the replicas of the block
+    before while the next one is multiplied.  Ragged rows and columns (stores masked lane by lane), several replicas
+    with their own scalars, more replica units than rounds."""
+    L = tbn.TBN_FLAG_LARGE_BATCH
+    # 33 x 8 blocks; rows end inside the last row block, U = 1000 ends inside the last column block; 4 rounds
+    _exact_case(tbn, 4174, 512, 2000, 2, "bf16", L, 21, alpha_vals=[0.5, 2])
+    # 17 x 16 blocks, 8 rounds, four replicas, fused ReLU
+    _exact_case(tbn, 2100, 1024, 8192, 4, "bf16", L | tbn.TBN_FLAG_RELU, 22, alpha_vals=[1, 2, 0.5, 4])
+    # 9 x 29 blocks, 4 rounds, eight replicas: eight (replica, quarter, half) units per round and store wave
+    _exact_case(tbn, 1100, 512, 29696, 8, "bf16", L, 23, alpha_vals=[1, 2, 0.5, 4, 0.25, 8, 1, 2])
+
+
 # shapes that stay on the one-block-per-tile kernels: K no multiple of 512, tiles that end inside rows
 EXACT_BLOCK = [
     (70, 8192, 80, 4),        # U = 20 distinct rows, long K
