@@ -442,14 +442,23 @@ bool linear_tile_supported(const LinearArgs &a) {
     return ((a.M + 31) / 32) * groups <= 0x7fffffffLL;
 }
 
-// bfloat16: where this kernel beats the small-batch and the streaming kernels (measured on 4096 x 4096, k = 8:
-// batch 256 / 512 9.3 / 10.3 us against 16.6 / 15.6; equal at 128 and at 1024, slower beyond): more than 64 batch
-// rows, at least four K slices, at most about one wave per SIMD.
+// bfloat16: where this kernel beats the small-batch and the streaming kernels.  Graph replays, microseconds per call,
+// this kernel / the small-batch kernel:
+//   * at least four K slices and at most about one wave per SIMD.  4096 x 4096, k = 8, batch 256 / 512: 9.3 / 10.3
+//     against 16.6 / 15.6 (equal at 128 and at 1024, slower beyond).  Batch 17 - 64, 512 distinct columns, in = 1024 /
+//     1536 / 2048 / 3072 / 8192: 5.1 / 5.6 / 6.3 / 7.4 / 12.8 against 7.9 / 7.5 / 8.0 / 8.1 / 13.6; at in = 4096 the
+//     small-batch kernel keeps those batches (8.3 against 8.5);
+//   * short rows (fewer K slices) where the small-batch kernel would need more than one workgroup per CU: batch 160 /
+//     256, 512 distinct columns, in = 256 / 512 / 768: 4.7 / 5.8 / 7.0 against 6.7 - 6.9 / 9.0 - 9.3 / 11.0 - 11.4 (with 256
+//     workgroups or fewer the small-batch kernel is the faster one: 4.2 / 5.3 / 6.4 against 4.7 / 5.9 / 7.1).
 bool linear_tile_preferred(const LinearArgs &a) {
-    if (a.dt != TBN_BF16 || a.M <= 64 || !linear_tile_supported(a)) return false;
+    if (a.dt != TBN_BF16 || a.M <= 16 || !linear_tile_supported(a)) return false;
     int nt, groups, kw;
     plan(a, nt, groups, kw);
-    return kw >= 4 && ((a.M + 31) / 32) * groups * kw <= 1024;
+    if (kw >= 4) return ((a.M + 31) / 32) * groups * kw <= 1024 && (a.M > 64 || a.in < 4096 || a.in >= 8192);
+    const int64_t U = a.p / a.in;
+    const int64_t small_grid = ((U + 15) / 16) * ((a.M + 15) / 16);   // workgroups of the small-batch kernel
+    return a.M > 64 && a.in >= 256 && small_grid > 256 && small_grid <= 512;
 }
 
 tbn_status launch_linear_tile(const LinearArgs &a) {
