@@ -442,23 +442,35 @@ bool linear_tile_supported(const LinearArgs &a) {
     return ((a.M + 31) / 32) * groups <= 0x7fffffffLL;
 }
 
-// bfloat16: where this kernel beats the small-batch and the streaming kernels.  Graph replays, microseconds per call,
-// this kernel / the small-batch kernel:
-//   * at least four K slices and at most about one wave per SIMD.  4096 x 4096, k = 8, batch 256 / 512: 9.3 / 10.3
-//     against 16.6 / 15.6 (equal at 128 and at 1024, slower beyond).  Batch 17 - 64, 512 distinct columns, in = 1024 /
-//     1536 / 2048 / 3072 / 8192: 5.1 / 5.6 / 6.3 / 7.4 / 12.8 against 7.9 / 7.5 / 8.0 / 8.1 / 13.6; at in = 4096 the
-//     small-batch kernel keeps those batches (8.3 against 8.5);
-//   * short rows (fewer K slices) where the small-batch kernel would need more than one workgroup per CU: batch 160 /
-//     256, 512 distinct columns, in = 256 / 512 / 768: 4.7 / 5.8 / 7.0 against 6.7 - 6.9 / 9.0 - 9.3 / 11.0 - 11.4 (with 256
-//     workgroups or fewer the small-batch kernel is the faster one: 4.2 / 5.3 / 6.4 against 4.7 / 5.9 / 7.1).
+// bfloat16: where this kernel beats the small-batch, the streaming and the block kernels.  Graph replays, microseconds
+// per call, this kernel / what the dispatch would take otherwise:
+//   * at least four K slices and at most about two waves per SIMD.  512 distinct columns, in = 4096, batch 256 / 512 /
+//     1024 / 2048: 8.8 / 8.9 / 10.3 / 15.8 against 16.6 / 15.6 / 15.0 / 15.4; in = 2048, batch 1024 / 2048: 7.2 / 10.5
+//     against 10.7 / 10.9; 128 distinct columns, batch 4096, in = 2048 / 4096: 7.2 / 10.4 against 10.7 / 17.8.  Batch
+//     17 - 64, 512 distinct columns, in = 1024 / 1536 / 2048 / 3072 / 8192: 5.1 / 5.6 / 6.3 / 7.4 / 12.8 against 7.9 / 7.5 /
+//     8.0 / 8.1 / 13.6 for the small-batch kernel; at in = 4096 that kernel keeps those batches (8.3 against 8.5);
+//   * short rows (fewer K slices), up to 512 waves, where the small-batch kernel would need more than one workgroup
+//     per CU: in = 512, 512 distinct columns, batch 512 / 1024 / 2048: 6.0 / 6.4 / 7.2 against 7.4 / 7.6 / 7.7 (batch
+//     4096: 9.4 against 9.0, left to the block kernel); batch 160 / 256, in = 256 / 768: 4.7 / 7.0 against 6.7 - 6.9 /
+//     11.0 - 11.4 (with 256 workgroups or fewer the small-batch kernel is the faster one: 4.2 / 6.4 against 4.7 / 7.1).
+// float32: the small-batch kernel's time grows with every further 256 workgroups (one per CU), this kernel's hardly
+// with the batch.  512 distinct columns, batch 197 / 400 / 800, this kernel / the small-batch kernel: in = 1024:
+// 10.1 / 10.3 / 10.6 against 14.0 / 26.5 / 46.0; in = 4096: 23.0 / 23.2 / 23.6 against 24.2 / 47.0 / 80.8; in = 384:
+// 12.6 / 12.8 / 13.2 against 8.3 / 15.2 / 25.6.  So: more than 512 of its workgroups, or more than 256 with rows of at
+// least 1024.
 bool linear_tile_preferred(const LinearArgs &a) {
-    if (a.dt != TBN_BF16 || a.M <= 16 || !linear_tile_supported(a)) return false;
+    if (a.M <= 16 || !linear_tile_supported(a)) return false;
+    if (a.dt == TBN_F32) {
+        const int64_t grid = ((a.p / a.in + 15) / 16) * ((a.M + 15) / 16);   // workgroups of the small-batch kernel
+        return a.M > 64 && (grid > 512 || (grid > 256 && a.in >= 1024));
+    }
     int nt, groups, kw;
     plan(a, nt, groups, kw);
-    if (kw >= 4) return ((a.M + 31) / 32) * groups * kw <= 1024 && (a.M > 64 || a.in < 4096 || a.in >= 8192);
+    const int64_t waves1 = ((a.M + 31) / 32) * groups;
+    if (kw >= 4) return waves1 * kw <= 2048 && (a.M > 64 || a.in < 4096 || a.in >= 8192);
     const int64_t U = a.p / a.in;
     const int64_t small_grid = ((U + 15) / 16) * ((a.M + 15) / 16);   // workgroups of the small-batch kernel
-    return a.M > 64 && a.in >= 256 && small_grid > 256 && small_grid <= 512;
+    return a.M > 64 && small_grid > 256 && waves1 <= 512;
 }
 
 tbn_status launch_linear_tile(const LinearArgs &a) {
