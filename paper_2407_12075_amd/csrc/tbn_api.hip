@@ -72,7 +72,7 @@ static tbn_status dispatch_linear(const LinearArgs &a) {
             if (stream && linear_stream_supported(a)) return launch_linear_stream(a);
             if (linear_block_supported(a)) return launch_linear_block(a);
             // float32, tile of whole rows, few distinct rows: memory-bound layers, one wave per 32 batch rows
-            if (a.dt == TBN_F32 && linear_tile_supported(a)) return launch_linear_tile(a);
+            if (a.dt == TBN_F32 && U > 0 && U <= 512 && linear_tile_supported(a)) return launch_linear_tile(a);
         }
         if (linear_mfma_supported(a)) return launch_linear_mfma(a);
         if (linear_rows_supported(a)) return launch_linear_rows(a);

@@ -426,14 +426,15 @@ void plan(const LinearArgs &a, int &nt, int &groups, int &kw) {
 
 }  // namespace
 
-// Shapes this kernel takes: tile of whole rows, K in chunks of 256 bytes, at most 512 distinct columns (every
-// column group reads its rows of X again), 16-byte loads and stores possible.
+// Shapes this kernel takes: tile of whole rows, K in chunks of 256 bytes, 16-byte loads and stores possible.  Every
+// group of 64 (bfloat16) or up to 128 (float32) distinct columns reads its rows of X again, from L2: with many distinct
+// columns the kernel is for small batches only, which linear_tile_preferred and the dispatch see to.
 bool linear_tile_supported(const LinearArgs &a) {
     if (a.dt != TBN_F32 && a.dt != TBN_BF16) return false;
     const int64_t ce = a.dt == TBN_F32 ? chunk_elems<float>() : chunk_elems<uint16_t>();
     if (a.in % ce != 0 || a.p % a.in != 0) return false;
     const int64_t U = a.p / a.in;
-    if (U > a.out || a.out % U != 0 || U % (a.dt == TBN_F32 ? 4 : 8) != 0 || U > 512) return false;
+    if (U > a.out || a.out % U != 0 || U % (a.dt == TBN_F32 ? 4 : 8) != 0 || U > (1 << 20)) return false;
     if (a.in > (1 << 20) || a.out > (1 << 22) || a.p >= (int64_t(1) << 36)) return false;
     if (a.M < 1 || a.M > (int64_t(1) << 34)) return false;
     if ((reinterpret_cast<uintptr_t>(a.x) & 15u) || (reinterpret_cast<uintptr_t>(a.y) & 15u)) return false;
@@ -448,7 +449,9 @@ bool linear_tile_supported(const LinearArgs &a) {
 //     1024 / 2048: 8.8 / 8.9 / 10.3 / 15.8 against 16.6 / 15.6 / 15.0 / 15.4; in = 2048, batch 1024 / 2048: 7.2 / 10.5
 //     against 10.7 / 10.9; 128 distinct columns, batch 4096, in = 2048 / 4096: 7.2 / 10.4 against 10.7 / 17.8.  Batch
 //     17 - 64, 512 distinct columns, in = 1024 / 1536 / 2048 / 3072 / 8192: 5.1 / 5.6 / 6.3 / 7.4 / 12.8 against 7.9 / 7.5 /
-//     8.0 / 8.1 / 13.6 for the small-batch kernel; at in = 4096 that kernel keeps those batches (8.3 against 8.5);
+//     8.0 / 8.1 / 13.6 for the small-batch kernel; at in = 4096 that kernel keeps those batches (8.3 against 8.5).
+//     The number of distinct columns is not limited: 4096 of them at batch 100 / 256, in = 1024: 5.4 / 7.3 against
+//     10.6 / 10.0 with the streaming kernel, in = 4096: 9.0 / 15.1 against 20.4 / 20.6;
 //   * short rows (fewer K slices), up to 512 waves, where the small-batch kernel would need more than one workgroup
 //     per CU: in = 512, 512 distinct columns, batch 512 / 1024 / 2048: 6.0 / 6.4 / 7.2 against 7.4 / 7.6 / 7.7 (batch
 //     4096: 9.4 against 9.0, left to the block kernel); batch 160 / 256, in = 256 / 768: 4.7 / 7.0 against 6.7 - 6.9 /
@@ -462,7 +465,7 @@ bool linear_tile_preferred(const LinearArgs &a) {
     if (a.M <= 16 || !linear_tile_supported(a)) return false;
     if (a.dt == TBN_F32) {
         const int64_t grid = ((a.p / a.in + 15) / 16) * ((a.M + 15) / 16);   // workgroups of the small-batch kernel
-        return a.M > 64 && (grid > 512 || (grid > 256 && a.in >= 1024));
+        return a.M > 64 && grid <= 2048 && (grid > 512 || (grid > 256 && a.in >= 1024));   // beyond 2048 that kernel declines
     }
     int nt, groups, kw;
     plan(a, nt, groups, kw);

@@ -129,6 +129,16 @@ def test_exact_bf16_persistent_blocks_with_store_waves(tbn):
     _exact_case(tbn, 1100, 512, 29696, 8, "bf16", L, 23, alpha_vals=[1, 2, 0.5, 4, 0.25, 8, 1, 2])
 
 
+def test_exact_one_wave_per_32_rows_many_distinct_columns(tbn):
+    """The kernel with one wave per 32 batch rows on more than 512 distinct columns (many column groups, each reading
+    its rows of X again), as the default dispatch picks it for small batches, and forced on a larger one."""
+    _exact_case(tbn, 100, 1024, 16384, 4, "bf16", 0, 31, alpha_vals=[1, 2, 0.5, 4])      # 4096 distinct columns, K in four slices
+    _exact_case(tbn, 257, 512, 4096, 2, "bf16", 0, 32, alpha_vals=[2, 0.5])              # 2048 distinct columns, short rows, ragged batch
+    _exact_case(tbn, 100, 1024, 4096, 4, "f32", 0, 33, alpha_vals=[1, 2, 0.5, 4])        # float32, 1024 distinct columns
+    _exact_case(tbn, 1000, 1536, 6144, 4, "bf16", tbn.TBN_FLAG_TILE_KERNEL, 34)          # 1536 distinct columns, forced
+    _exact_case(tbn, 333, 768, 2304, 3, "f32", tbn.TBN_FLAG_TILE_KERNEL, 35, alpha_vals=[1, 0.5, 2])   # 768 distinct columns, three replicas
+
+
 # shapes that stay on the one-block-per-tile kernels: K no multiple of 512, tiles that end inside rows
 EXACT_BLOCK = [
     (70, 8192, 80, 4),        # U = 20 distinct rows, long K
