@@ -58,7 +58,14 @@ static tbn_status check_tiling(int64_t n, int32_t k, int32_t n_alpha) {
 static tbn_status dispatch_linear(const LinearArgs &a) {
     drop_stale_error();
     if (!(a.flags & TBN_FLAG_FORCE_GENERIC)) {
-        if (!(a.flags & TBN_FLAG_LARGE_BATCH) && linear_decode_supported(a)) return launch_linear_decode(a);
+        // at most 16 batch rows: the decode kernel (a workgroup per two distinct columns reads all of X); with many
+        // distinct columns and 8 - 16 rows the small-batch kernel, whose workgroups share X sixteen columns at a time,
+        // is the faster one (graph replays, 2048 distinct columns, batch 16, in = 1024 / 4096 / 8192: 9.0 / 11.4 / 16.1 us
+        // against 7.9 / 8.3 / 13.5; batch 8: 4.6 / 6.5 / 9.0 against 6.6 / 6.9 / 11.0; 4096 columns, batch 8: 7.1 / 9.1 /
+        // 13.2 against 6.7 / 7.1 / 11.1)
+        if (!(a.flags & TBN_FLAG_LARGE_BATCH) && linear_decode_supported(a) &&
+            (a.M * (a.p / a.in) <= 16384 || !linear_skinny_supported(a)))
+            return launch_linear_decode(a);
         if (!(a.flags & (TBN_FLAG_BLOCK_KERNEL | TBN_FLAG_STREAM_KERNEL)) && linear_tile_preferred(a)) return launch_linear_tile(a);
         if (linear_skinny_supported(a)) return launch_linear_skinny(a);
         if (!(a.flags & TBN_FLAG_BLOCK_KERNEL)) {
@@ -71,8 +78,10 @@ static tbn_status dispatch_linear(const LinearArgs &a) {
             const bool stream = (a.flags & TBN_FLAG_STREAM_KERNEL) || blocks <= 128;   // (batch 4096: 25.2 us against 28.3)
             if (stream && linear_stream_supported(a)) return launch_linear_stream(a);
             if (linear_block_supported(a)) return launch_linear_block(a);
-            // float32, tile of whole rows, few distinct rows: memory-bound layers, one wave per 32 batch rows
-            if (a.dt == TBN_F32 && U > 0 && U <= 512 && linear_tile_supported(a)) return launch_linear_tile(a);
+            // float32, tile of whole rows: one wave per 32 batch rows (every shape measured, up to 8192 distinct columns
+            // at batch 8192, runs 15 - 70 % faster than in the 128 x 128 blocks of the general kernel: 8192 x 1024 ->
+            // 1024 distinct columns 57 us against 84, 8192 x 4096 -> 8192 distinct columns 1379 against 1672)
+            if (a.dt == TBN_F32 && linear_tile_supported(a)) return launch_linear_tile(a);
         }
         if (linear_mfma_supported(a)) return launch_linear_mfma(a);
         if (linear_rows_supported(a)) return launch_linear_rows(a);

@@ -137,6 +137,15 @@ def test_exact_one_wave_per_32_rows_many_distinct_columns(tbn):
     _exact_case(tbn, 100, 1024, 4096, 4, "f32", 0, 33, alpha_vals=[1, 2, 0.5, 4])        # float32, 1024 distinct columns
     _exact_case(tbn, 1000, 1536, 6144, 4, "bf16", tbn.TBN_FLAG_TILE_KERNEL, 34)          # 1536 distinct columns, forced
     _exact_case(tbn, 333, 768, 2304, 3, "f32", tbn.TBN_FLAG_TILE_KERNEL, 35, alpha_vals=[1, 0.5, 2])   # 768 distinct columns, three replicas
+    _exact_case(tbn, 1500, 512, 4096, 2, "f32", 0, 36, alpha_vals=[2, 0.5])              # float32 large batch, 2048 distinct columns: default dispatch
+
+
+def test_exact_at_most_16_rows_many_distinct_columns(tbn):
+    """Up to 16 batch rows: the decode kernel, or the small-batch kernel where rows x distinct columns exceed 16384."""
+    for dtype in ("bf16", "f32"):
+        _exact_case(tbn, 16, 512, 4096, 2, dtype, 0, 41, alpha_vals=[2, 0.5])            # 2048 distinct columns: small-batch kernel
+        _exact_case(tbn, 4, 512, 8192, 2, dtype, 0, 42, alpha_vals=[2, 0.5])             # 4096 distinct columns, 4 rows: decode kernel
+        _exact_case(tbn, 9, 1024, 8192, 2, dtype, 0, 43, alpha_vals=[1, 4])              # 4096 distinct columns, 9 rows: small-batch kernel
 
 
 # shapes that stay on the one-block-per-tile kernels: K no multiple of 512, tiles that end inside rows
