@@ -77,7 +77,11 @@ static tbn_status dispatch_linear(const LinearArgs &a) {
             if ((a.flags & TBN_FLAG_TILE_KERNEL) && linear_tile_supported(a)) return launch_linear_tile(a);
             const bool stream = (a.flags & TBN_FLAG_STREAM_KERNEL) || blocks <= 128;   // (batch 4096: 25.2 us against 28.3)
             if (stream && linear_stream_supported(a)) return launch_linear_stream(a);
-            if (linear_block_supported(a)) return launch_linear_block(a);
+            // (rows of 256: two rounds per block, too few for the persistent form; on grids of more than two blocks per CU
+            // the general kernel with two workgroups per CU is 10 - 25 % faster: 8192 x 256 -> 4096 distinct columns 36 us
+            // against 43)
+            const bool short_rows = a.in < 512 && blocks > 512 && linear_mfma_supported(a);
+            if (!short_rows && linear_block_supported(a)) return launch_linear_block(a);
             // float32, tile of whole rows: one wave per 32 batch rows (every shape measured, up to 8192 distinct columns
             // at batch 8192, runs 15 - 70 % faster than in the 128 x 128 blocks of the general kernel: 8192 x 1024 ->
             // 1024 distinct columns 57 us against 84, 8192 x 4096 -> 8192 distinct columns 1379 against 1672)

@@ -38,7 +38,7 @@
 //     waves of their own because the vector-memory counter counts both, in issue order: a wave that did both
 //     waited for its stores whenever it waited for a round of loads (8192 x 4096 -> 16384, k = 8: block loops of
 //     28.7 us against 24.7).  The first two rounds of the next block are issued inside the last rounds of the
-//     current one, whose ring slots 0 and 1 are free by then; between two loops lie 2.2 us (the K groups add their
+//     current one, into the two ring slots behind its last round, which are free by then; between two loops lie 2.2 us (the K groups add their
 //     sums, the store waves take them over).  8192 x 4096 -> 16384, k = 2 / 4 / 8 / 16: 410 / 211 / 117 / 86 us
 //     against 410 / 216 / 127 / 97 with the stores after each loop; 32768 x 4096 -> 4096, k = 8: 137 against 152.
 //     What stays exposed is the stores of a workgroup's last block.
@@ -164,9 +164,10 @@ __device__ __forceinline__ void block_coords(const BlockParams &P, uint32_t bid,
 
 // RELU: fused max(0, .) of Algorithm 1.  SPLIT: the workgroup takes one of P.splits equal parts of K and writes
 // float32 partial sums to P.partial instead of Y.  512 threads: waves 0 .. 3 multiply, waves 4 .. 7 load.
-// PERSIST (grids of more blocks than CUs; rounds in fours): the workgroup walks blocks blockIdx.x, + gridDim.x, ...;
-// waves 4 and 5 load, waves 6 and 7 write the replicas of the block before.  The ring's slots 0 and 1 take the
-// first rounds of the next block while the current one ends, which is why the hand-over then uses slots 2 and 3.
+// PERSIST (grids of more blocks than CUs; at least four rounds): the workgroup walks blocks blockIdx.x, + gridDim.x, ...;
+// waves 4 and 5 load, waves 6 and 7 write the replicas of the block before.  The
+// first rounds of the next block start in the ring slot behind the current block's last round, and the hand-over uses
+// the slots of the last two rounds.
 template <bool RELU, bool SPLIT, bool PERSIST>
 __global__ __launch_bounds__(512, 1) void linear_block_bf16_kernel(const uint16_t *__restrict__ x,
                                                                                      uint16_t *__restrict__ y,
@@ -184,7 +185,13 @@ __global__ __launch_bounds__(512, 1) void linear_block_bf16_kernel(const uint16_
     const int lg = lane >> 5;    // K half of the operand registers
 
     static_assert(!(SPLIT && PERSIST), "a split grid never has more workgroups than CUs");
-    constexpr int kXchg = PERSIST ? kRingOff + 2 * kSlotBytes : kXchgOff;   // hand-over area
+    // Ring slot of round g of a block: (g + ph) % 4.  ph is 0 with one block per workgroup; a persistent workgroup
+    // starts a block in the slot after the last one of the block before, ph' = (ph + rounds) % 4 (0 or 2: rounds come
+    // in pairs).  Hand-over area: with one block per workgroup the start of the ring; PERSIST: the slots of a block's
+    // last two rounds, which are the two slots behind those that take the first two rounds of the next block.
+    auto xchg_base = [&](int32_t phase) -> uint32_t {
+        return PERSIST ? static_cast<uint32_t>(kRingOff + ((P.n_rounds - 2 + phase) & 3) * kSlotBytes) : static_cast<uint32_t>(kXchgOff);
+    };
     // Waves 4 .. 7.  One block per workgroup: four load waves, each issues a quarter of a round's loads (quarter q:
     // K group q / 2, row-slot half q % 2).  PERSIST: waves 4 and 5 load (two quarters each: K group = wave - 4),
     // waves 6 and 7 write the replicas of the block before (the quarters of MFMA waves 2*(wave - 6) and + 1).
@@ -246,7 +253,7 @@ __global__ __launch_bounds__(512, 1) void linear_block_bf16_kernel(const uint16_
     set_block(bid);
     // issue order per round, which the wait counts rely on: eight activation wave-loads per quarter, then (even
     // rounds) a quarter's share of the tile chunk of this round and the next
-    auto issue_x = [&](auto q_c, auto j_c, int32_t round_) {
+    auto issue_x = [&](auto q_c, auto j_c, int32_t round_, int32_t phase) {
         constexpr int Q = decltype(q_c)::value, J = decltype(j_c)::value;
         const int lq = first_q + Q;
         unsigned char *const ring_q = lds_raw + kRingOff + (lq >> 1) * 16384 + (lq & 1) * 8192;
@@ -254,7 +261,7 @@ __global__ __launch_bounds__(512, 1) void linear_block_bf16_kernel(const uint16_
         asm volatile("" : "+s"(src));   // one scalar base, the lane offset stays a 32-bit register
         uint32_t off = a_off[Q][J];
         asm volatile("" : "+v"(off));
-        wave_load<(J & 3)>(src, off, ring_q + (round_ & (kNB - 1)) * kSlotBytes + (J >> 2) * 4096);
+        wave_load<(J & 3)>(src, off, ring_q + ((round_ + phase) & (kNB - 1)) * kSlotBytes + (J >> 2) * 4096);
     };
     auto issue_tile = [&](auto q_c, int32_t round_) {   // round_ is even
         constexpr int Q = decltype(q_c)::value;
@@ -264,13 +271,13 @@ __global__ __launch_bounds__(512, 1) void linear_block_bf16_kernel(const uint16_
         asm volatile("" : "+v"(off));
         __builtin_amdgcn_global_load_lds(src + off, lds_raw + kTileOff + (first_q + Q) * 1024 + ((round_ >> 1) % kTileSlots) * kTileSlotBytes, 16, 0, 0);
     };
-    auto issue_quarter = [&](auto q_c, int32_t round_) {
-        issue_x(q_c, Int<0>{}, round_); issue_x(q_c, Int<1>{}, round_); issue_x(q_c, Int<2>{}, round_); issue_x(q_c, Int<3>{}, round_);
-        issue_x(q_c, Int<4>{}, round_); issue_x(q_c, Int<5>{}, round_); issue_x(q_c, Int<6>{}, round_); issue_x(q_c, Int<7>{}, round_);
+    auto issue_quarter = [&](auto q_c, int32_t round_, int32_t phase) {
+        issue_x(q_c, Int<0>{}, round_, phase); issue_x(q_c, Int<1>{}, round_, phase); issue_x(q_c, Int<2>{}, round_, phase); issue_x(q_c, Int<3>{}, round_, phase);
+        issue_x(q_c, Int<4>{}, round_, phase); issue_x(q_c, Int<5>{}, round_, phase); issue_x(q_c, Int<6>{}, round_, phase); issue_x(q_c, Int<7>{}, round_, phase);
     };
-    auto issue_round = [&](int32_t round_) {
-        issue_quarter(Int<0>{}, round_);
-        if constexpr (NQ == 2) issue_quarter(Int<1>{}, round_);
+    auto issue_round = [&](int32_t round_, int32_t phase = 0) {
+        issue_quarter(Int<0>{}, round_, phase);
+        if constexpr (NQ == 2) issue_quarter(Int<1>{}, round_, phase);
         if ((round_ & 1) == 0) {
             issue_tile(Int<0>{}, round_);
             if constexpr (NQ == 2) issue_tile(Int<1>{}, round_);
@@ -283,7 +290,6 @@ __global__ __launch_bounds__(512, 1) void linear_block_bf16_kernel(const uint16_
     const uint32_t z_lane = (static_cast<uint32_t>(rr) * static_cast<uint32_t>(P.out) + static_cast<uint32_t>(8 * g8)) * 2u;
     const uint32_t out_bytes8 = static_cast<uint32_t>(P.out) * 16u;   // eight rows of Y in bytes
     const uint32_t rep_bytes = static_cast<uint32_t>(P.U) * 2u;
-    const uint32_t xchg_mine = static_cast<uint32_t>(kXchg + li * 16384);
 
     // =================================================================================================
     // store waves (PERSIST)
@@ -333,6 +339,7 @@ __global__ __launch_bounds__(512, 1) void linear_block_bf16_kernel(const uint16_
             else if (sub == 2) emit(Int<1>{}, Int<0>{});
             else emit(Int<1>{}, Int<1>{});
         };
+        int32_t ph = 0;
         for (;;) {
             const int64_t cur_m0 = m0;
             const int32_t cur_n0 = n0;
@@ -357,7 +364,7 @@ __global__ __launch_bounds__(512, 1) void linear_block_bf16_kernel(const uint16_
                 const int ch_a = 2 * g8 + (g8 >> 2), ch_b = 2 * g8 + 1 - (g8 >> 2);
 #pragma unroll
                 for (int q = 0; q < 2; ++q) {
-                    const uint32_t area = static_cast<uint32_t>(kXchg + (first_q + q) * 16384);
+                    const uint32_t area = xchg_base(ph) + static_cast<uint32_t>((first_q + q) * 16384);
                     u32x4_t za[2][4], zb[2][4];
 #pragma unroll
                     for (int h = 0; h < 2; ++h)
@@ -393,6 +400,7 @@ __global__ __launch_bounds__(512, 1) void linear_block_bf16_kernel(const uint16_
                 st_next = 0;
                 st_total = 4 * P.reps;
                 st_credit = 0;
+                ph = (ph + n_rounds) & 3;
             }
             if (!more) {
                 while (st_next < st_total) store_unit(st_next++);
@@ -406,16 +414,18 @@ __global__ __launch_bounds__(512, 1) void linear_block_bf16_kernel(const uint16_
     // =================================================================================================
     if (wave >= 4) {
         if constexpr (PERSIST) {
-            // One workgroup walks blocks.  The last three rounds of a block load nothing for it, and ring slots 0 and 1
+            // One workgroup walks blocks.  The last three rounds of a block load nothing for it, and the two ring slots behind its last round
             // are free by then: the activations of the next block's rounds 0 and 1 are issued there, one round each,
             // and its first tile chunk behind the last round's barrier (that slot of the tile ring is read until then),
             // so the hand-over between two blocks waits for no load to be issued.
             issue_round(0);
             issue_round(1);
             __builtin_amdgcn_s_waitcnt(vmcnt_imm(kOdd));   // round 0 and its tile chunk; round 1's loads are younger
+            int32_t ph = 0;
             for (;;) {
                 __builtin_amdgcn_s_barrier();   // meets the MFMA waves' "round 0 readable; the hand-over area is free"
-                issue_round(2);
+                issue_round(2, ph);
+                const int32_t ph_next = (ph + n_rounds) & 3;
                 const uint32_t next = bid + gridDim.x;
                 const bool more = next < n_blocks;
                 for (int32_t g = 0; g < n_rounds; ++g) {
@@ -432,16 +442,16 @@ __global__ __launch_bounds__(512, 1) void linear_block_bf16_kernel(const uint16_
                     }
                     __builtin_amdgcn_s_barrier();
                     if (g + 3 < n_rounds) {
-                        issue_round(g + 3);
+                        issue_round(g + 3, ph);
                     } else if (more) {
                         if (g + 3 == n_rounds) {
                             bid = next;
                             set_block(bid);
-                            issue_quarter(Int<0>{}, 0);
-                            issue_quarter(Int<1>{}, 0);
+                            issue_quarter(Int<0>{}, 0, ph_next);
+                            issue_quarter(Int<1>{}, 0, ph_next);
                         } else if (g + 2 == n_rounds) {
-                            issue_quarter(Int<0>{}, 1);
-                            issue_quarter(Int<1>{}, 1);
+                            issue_quarter(Int<0>{}, 1, ph_next);
+                            issue_quarter(Int<1>{}, 1, ph_next);
                         } else {
                             issue_tile(Int<0>{}, 0);
                             issue_tile(Int<1>{}, 0);
@@ -452,6 +462,7 @@ __global__ __launch_bounds__(512, 1) void linear_block_bf16_kernel(const uint16_
                 __builtin_amdgcn_s_barrier();
                 __builtin_amdgcn_s_barrier();   // the store waves take the sums of the finished block
                 if (!more) return;
+                ph = ph_next;
                 __builtin_amdgcn_s_waitcnt(vmcnt_imm(0));   // rounds 0 and 1 and the tile chunk of the next block
             }
         } else {
@@ -491,6 +502,8 @@ __global__ __launch_bounds__(512, 1) void linear_block_bf16_kernel(const uint16_
         const uint32_t off = static_cast<uint32_t>(t) * 4u;
         asm volatile("global_load_dword %0, %1, %2" : "=v"(alpha_lanes) : "v"(off), "s"(alpha));
     }
+
+    int32_t ph = 0;   // ring phase of the current block
 
     // sign table: entry e, element i is +1 if bit i of e is set, else -1
     if (tid < 256) {
@@ -586,8 +599,8 @@ __global__ __launch_bounds__(512, 1) void linear_block_bf16_kernel(const uint16_
     auto round = [&](auto par_c, int32_t g) __attribute__((always_inline)) {
         constexpr int PAR = decltype(par_c)::value;
         __builtin_amdgcn_s_barrier();
-        const uint32_t cur = static_cast<uint32_t>((g & (kNB - 1)) * kSlotBytes);
-        const uint32_t nxt = static_cast<uint32_t>(((g + 1) & (kNB - 1)) * kSlotBytes);
+        const uint32_t cur = static_cast<uint32_t>(((g + ph) & (kNB - 1)) * kSlotBytes);
+        const uint32_t nxt = static_cast<uint32_t>(((g + 1 + ph) & (kNB - 1)) * kSlotBytes);
         // windows of the next round: an even round reads the second piece of its own chunk, an odd round the
         // first piece of the next chunk
         const uint32_t w_addr = w_rd + static_cast<uint32_t>((((g + 1) >> 1) % kTileSlots) * kTileSlotBytes + (PAR == 0 ? 2048 : 0));
@@ -619,12 +632,15 @@ __global__ __launch_bounds__(512, 1) void linear_block_bf16_kernel(const uint16_
     lds_read2x8(win[0], w_rd);      // windows of round 0: chunk slot 0, piece 0
     lds_wait<0>();
     tie(win[0]);
-    table_read(B[0][0].q, win[0][0], bsh[0]);
-    lds_read16<0>(A[0][0].q, a_rd[0]);
-    table_read(B[0][1].q, win[0][2], bsh[0]);
-    lds_read16<4096>(A[0][1].q, a_rd[0]);
-    lds_read16<8192>(A[0][2].q, a_rd[0]);
-    lds_read16<12288>(A[0][3].q, a_rd[0]);
+    {
+        const uint32_t first = a_rd[0] + static_cast<uint32_t>(ph * kSlotBytes);
+        table_read(B[0][0].q, win[0][0], bsh[0]);
+        lds_read16<0>(A[0][0].q, first);
+        table_read(B[0][1].q, win[0][2], bsh[0]);
+        lds_read16<4096>(A[0][1].q, first);
+        lds_read16<8192>(A[0][2].q, first);
+        lds_read16<12288>(A[0][3].q, first);
+    }
     settle();
 
     // One plain loop over pairs of rounds; the operands that its last round requests (of a round that does not
@@ -645,8 +661,9 @@ __global__ __launch_bounds__(512, 1) void linear_block_bf16_kernel(const uint16_
     __builtin_amdgcn_s_barrier();
     asm volatile("s_nop 15");
     asm volatile("s_nop 15");
+    const uint32_t xchg_mine = xchg_base(ph) + static_cast<uint32_t>(li * 16384);
     {
-        const uint32_t dst = static_cast<uint32_t>(kXchg + (li ^ 2) * 16384) + static_cast<uint32_t>(lane) * 16u;
+        const uint32_t dst = xchg_base(ph) + static_cast<uint32_t>((li ^ 2) * 16384) + static_cast<uint32_t>(lane) * 16u;
 #pragma unroll
         for (int half = 0; half < 2; ++half) {
             u32x4_t s[8];
@@ -721,6 +738,7 @@ __global__ __launch_bounds__(512, 1) void linear_block_bf16_kernel(const uint16_
             const uint32_t next = bid + gridDim.x;
         if (next >= n_blocks) break;
         bid = next;
+        ph = (ph + n_rounds) & 3;
         continue;
     }
     const bool col_ok = n0 + 64 * wn + 8 * g8 < P.U;
@@ -949,10 +967,10 @@ tbn_status launch_linear_block(const LinearArgs &a) {
     const dim3 grid(static_cast<unsigned>(int64_t(P.tiles_m) * P.tiles_n));
     const bool relu = (a.flags & TBN_FLAG_RELU) != 0;
     typedef void (*kernel_t)(const uint16_t *, uint16_t *, const uint32_t *, const float *, BlockParams);
-    // more blocks than CUs and rounds in fours: one persistent workgroup per CU
+    // more blocks than CUs and at least four rounds: one persistent workgroup per CU
     int cus = device_cus() & ~7;
     if (cus < 8) cus = 8;
-    const bool persist = int64_t(P.tiles_m) * P.tiles_n > cus && P.n_rounds >= 4 && P.n_rounds % 4 == 0;
+    const bool persist = int64_t(P.tiles_m) * P.tiles_n > cus && P.n_rounds >= 4;
     // (its store waves write with non-temporal stores whatever the shape: next to a running K loop, plain stores push
     // the activations that the other column blocks of the same rows still need out of the XCD's L2)
     static const kernel_t kernels[4] = {&linear_block_bf16_kernel<false, false, false>, &linear_block_bf16_kernel<true, false, false>,

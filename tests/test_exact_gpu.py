@@ -125,6 +125,9 @@ def test_exact_bf16_persistent_blocks_with_store_waves(tbn):
     _exact_case(tbn, 4174, 512, 2000, 2, "bf16", L, 21, alpha_vals=[0.5, 2])
     # 17 x 16 blocks, 8 rounds, four replicas, fused ReLU
     _exact_case(tbn, 2100, 1024, 8192, 4, "bf16", L | tbn.TBN_FLAG_RELU, 22, alpha_vals=[1, 2, 0.5, 4])
+    # 6 and 10 rounds (K = 768, 1280): consecutive blocks of a workgroup start in different ring slots
+    _exact_case(tbn, 4174, 768, 2000, 2, "bf16", L, 24, alpha_vals=[0.5, 2])
+    _exact_case(tbn, 2100, 1280, 8192, 4, "bf16", L | tbn.TBN_FLAG_RELU, 25, alpha_vals=[1, 2, 0.5, 4])
     # 9 x 29 blocks, 4 rounds, eight replicas: eight (replica, quarter, half) units per round and store wave
     _exact_case(tbn, 1100, 512, 29696, 8, "bf16", L, 23, alpha_vals=[1, 2, 0.5, 4, 0.25, 8, 1, 2])
 
