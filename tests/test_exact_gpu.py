@@ -151,6 +151,24 @@ def test_exact_at_most_16_rows_many_distinct_columns(tbn):
         _exact_case(tbn, 9, 1024, 8192, 2, dtype, 0, 43, alpha_vals=[1, 4])              # 4096 distinct columns, 9 rows: small-batch kernel
 
 
+@pytest.mark.parametrize("M,cin,cout,k", [(16640, 512, 8192, 32), (33000, 768, 8192, 64), (9000, 1024, 16384, 16)])
+def test_persistent_blocks_many_replicas_equal_general_kernel(tbn, M, cin, cout, k):
+    """Many replicas per block (more store units than rounds) on grids of more blocks than CUs, at sizes the dense
+    oracle does not finish in seconds: in exact arithmetic (activations in {-1, 0, 1}, powers of two as scalars) the
+    persistent block kernel must agree bit for bit with the general one-block-per-tile kernel, which the oracle tests
+    above cover, whatever the order of the sums."""
+    g = torch.Generator(device="cuda")
+    g.manual_seed(1000 + k)
+    x = (torch.randint(0, 8, (M, cin), device="cuda", generator=g) - 3).clamp_(-1, 1).to(torch.bfloat16)   # mostly zeros and ones
+    tile = torch.randint(-2 ** 31, 2 ** 31 - 1, (cin * cout // k // 32,), device="cuda", dtype=torch.int32, generator=g)
+    alpha = torch.tensor([2.0 ** ((i % 5) - 2) for i in range(k)], device="cuda", dtype=torch.float32)
+    y_persistent = tbn.tbn_linear_forward(x, tile, alpha, cout, k, flags=tbn.TBN_FLAG_LARGE_BATCH)
+    y_general = tbn.tbn_linear_forward(x, tile, alpha, cout, k, flags=tbn.TBN_FLAG_LARGE_BATCH | tbn.TBN_FLAG_BLOCK_KERNEL)
+    torch.cuda.synchronize()
+    assert torch.equal(y_persistent.view(torch.int16), y_general.view(torch.int16))
+    assert float(y_general.float().abs().max()) > 0
+
+
 # shapes that stay on the one-block-per-tile kernels: K no multiple of 512, tiles that end inside rows
 EXACT_BLOCK = [
     (70, 8192, 80, 4),        # U = 20 distinct rows, long K
