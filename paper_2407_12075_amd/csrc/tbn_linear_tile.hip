@@ -402,7 +402,7 @@ tbn_status launch_nt(const LinearArgs &a, const TileParams &P, unsigned grid, in
     return TBN_ERR_UNSUPPORTED;
 }
 
-// column tiles per wave: as few groups as possible, then as even as possible (float32, U = 384: three groups of four
+// column tiles per wave: as few groups as possible, then as even as possible (float32, U = 384: three groups of four, see below
 // tiles; U = 96: one group of three; bfloat16 takes at most two tiles per wave: its use is small batches, where more
 // waves count for more than fewer passes over X: 4096 x 4096, k = 8 at batch 256 / 512 9.3 / 10.3 us against 13.6 /
 // 14.0 with four); K slices per workgroup: as many (8, 4) as leave a wave at least two chunks and the chip at most
@@ -421,6 +421,14 @@ void plan(const LinearArgs &a, int &nt, int &groups, int &kw) {
             kw = cand;
             break;
         }
+    }
+    // float32 with K in one slice (one wave per workgroup) and fewer than one and a half waves per SIMD: one more
+    // column group where the tiles divide evenly, for more waves in flight (12608 x 384 -> 384 distinct columns: four
+    // groups of three tiles 25.8 us against three groups of four 27.8; with more waves the extra pass over X costs more
+    // than it gains: 1536 distinct columns 51.4 against 49.5)
+    if (a.dt == TBN_F32 && kw == 1 && waves1 < 1536 && nt > 2 && tiles % (groups + 1) == 0) {
+        groups += 1;
+        nt = static_cast<int>(tiles / groups);
     }
 }
 
