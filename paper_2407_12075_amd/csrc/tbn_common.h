@@ -90,6 +90,8 @@ tbn_status launch_conv_generic(const ConvArgs &a);
 tbn_status launch_conv_generic_tile_ends(const ConvArgs &a);   // only the channels whose filter holds a tile end
 bool conv_mfma_supported(const ConvArgs &a);
 tbn_status launch_conv_mfma(const ConvArgs &a);
+bool conv_direct_supported(const ConvArgs &a);   // tile of whole filters, any window: vector-ALU kernel, 16 filters per workgroup
+tbn_status launch_conv_direct(const ConvArgs &a);
 
 // measurement aids (tbn_diag.hip)
 tbn_status launch_diag_empty(hipStream_t stream);

@@ -159,6 +159,8 @@ CONV_MORE = (
     ConvWorkload("conv3x3_64_112x112_k4_b8", 3, 4, 8, 64, 112, 112, 64, 3, 3, (1, 1), (1, 1), 4, 1),
     ConvWorkload("conv3x3_3_32x32_to64_k2_b128", 3, 5, 128, 3, 32, 32, 64, 3, 3, (1, 1), (1, 1), 2, 1),
     ConvWorkload("conv1x1_256_14x14_to1024_k8_b64_bf16", 3, 6, 64, 256, 14, 14, 1024, 1, 1, (1, 1), (0, 0), 8, 1, "bf16"),
+    # a 7x7, stride 2 first layer (the networks of the CNN section leave it untiled; here it is tiled to time that window)
+    ConvWorkload("conv7x7s2_3_224x224_to64_k4_b32", 3, 7, 32, 3, 224, 224, 64, 7, 7, (2, 2), (3, 3), 4, 1),
 )
 
 FFN_DOWN = tuple(LinearWorkload(f"ffn_down_16384_4096_k8_b{m}", 5, 10, m, 16384, 4096, 8, 8, "bf16") for m in (256, 512, 1024, 2048))

@@ -410,6 +410,12 @@ CONV_SMALL = [
     (2, 64, 5, 130, 16, 1, 1, (1, 1), (0, 0), 2, 1),     # 1x1, 130 pixels per row: two blocks of 65
     (1, 32, 9, 150, 24, 3, 3, (2, 2), (1, 1), 3, 3),     # stride 2, 75 outputs per row in three blocks of 25; two alphas
     (1, 64, 4, 224, 8, 3, 3, (1, 1), (1, 1), 2, 2),      # 224 wide: four blocks of 56
+    # windows the matrix-core kernel does not take, tile of whole filters: the direct kernel (16 filters per workgroup)
+    (2, 3, 37, 41, 64, 7, 7, (2, 2), (3, 3), 4, 4),      # a 7x7, stride 2 first layer: 16 distinct filters, 147 weights each
+    (3, 16, 18, 18, 40, 5, 5, (1, 1), (2, 2), 2, 1),     # 5x5: 20 distinct filters (two filter groups, the second ragged), one alpha
+    (1, 24, 20, 30, 12, 5, 3, (1, 2), (2, 0), 3, 3),     # 5x3, mixed stride and padding, 4 distinct filters, 360 weights each
+    (2, 40, 12, 12, 8, 4, 4, (2, 2), (1, 1), 1, 1),      # 4x4, k = 1: 640 weights per filter (two staging passes)
+    (1, 2, 300, 5, 6, 2, 2, (1, 1), (0, 0), 6, 6),       # 2x2, one distinct filter, 1196 output pixels (five pixel blocks)
 ]
 
 
