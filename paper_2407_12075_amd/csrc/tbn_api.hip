@@ -89,6 +89,8 @@ static tbn_status dispatch_linear(const LinearArgs &a) {
         }
         if (linear_mfma_supported(a)) return launch_linear_mfma(a);
         if (linear_rows_supported(a)) return launch_linear_rows(a);
+        // row lengths and alignments that none of the kernels above takes (in no multiple of 8), tile of whole rows
+        if (linear_direct_supported(a)) return launch_linear_direct(a);
     }
     return launch_linear_generic(a);
 }

@@ -55,6 +55,8 @@ tbn_status launch_pack_noalloc(const float *w, const float *a, int64_t n, int32_
                                uint32_t *tile_out, float *alpha_out, hipStream_t stream);
 
 tbn_status launch_linear_generic(const LinearArgs &a);
+bool linear_direct_supported(const LinearArgs &a);   // tile of whole rows, any row length and alignment: vector-ALU kernel
+tbn_status launch_linear_direct(const LinearArgs &a);
 bool linear_skinny_supported(const LinearArgs &a); // small-batch (decode-shaped) matrix-core kernel
 tbn_status launch_linear_skinny(const LinearArgs &a);
 bool linear_decode_supported(const LinearArgs &a); // at most 16 batch rows, tile of whole rows: latency-built GEMV kernel

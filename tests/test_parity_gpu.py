@@ -153,6 +153,13 @@ LINEAR_SMALL = [
     (150, 1024, 256, 2, 2),    # aligned, 128 distinct rows: one column block, 16-byte stores, second row block partly filled
     (4, 40, 16, 4, 1),         # p = 160: smallest tile the small-batch kernel takes
     (3, 160, 9, 9, 9),         # p = in = 160
+    # row lengths that are no multiple of 8, tile of whole rows: the direct kernel (a thread per batch row, 16 distinct columns)
+    (300, 196, 384, 4, 4),     # a Mixer's token-mixing layer: 96 distinct columns, rows of 196 elements
+    (70, 300, 300, 4, 1),      # 75 distinct columns: five column groups, the last ragged; one alpha
+    (33, 2050, 1026, 2, 2),    # five staging passes of K, the last one short
+    (200, 77, 33, 3, 3),       # odd row length: one element per load (bfloat16 rows start at odd 2-byte offsets)
+    (1, 196, 256, 1, 1),       # one batch row, k = 1
+    (131, 1001, 26, 2, 1),     # odd row length over two staging passes; two row blocks, the second with three rows
 ]
 
 
