@@ -160,10 +160,23 @@ GENERIC = [
 ]
 
 
-@pytest.mark.parametrize("M,cin,out,k,n_alpha", GENERIC)
+# tile of whole rows with shapes the matrix-core kernel declines: the direct kernel (a thread per batch row, 32 distinct
+# columns per workgroup, tile words through LDS)
+DIRECT = [
+    (300, 196, 384, 4, 4),        # rows of 196 bits: six whole words and a masked one; 96 distinct columns
+    (150, 1000, 250, 5, 5),       # 50 distinct columns: two column groups, the second ragged
+    (131, 4128, 64, 2, 1),        # 129 words per row: two staging passes, the second with one word; ragged row block
+    (40, 3000, 96, 3, 3),         # rows start at bit offsets that are no multiples of 32
+    (1, 77, 33, 1, 1),            # k = 1, odd everything
+    (260, 320, 128, 2, 2),        # whole words, 64 distinct columns (a multiple of 32: sign bits out take this kernel too)
+]
+
+
+@pytest.mark.parametrize("flags", [0, 0x100])   # default dispatch; the one-thread-per-output kernel forced
+@pytest.mark.parametrize("M,cin,out,k,n_alpha", GENERIC + DIRECT)
 @pytest.mark.parametrize("dtype", ["f32", "bf16"])
-def test_forward_general_kernel(tbn, M, cin, out, k, n_alpha, dtype):
-    _check(tbn, M, cin, out, k, n_alpha, dtype, dirty_padding=True)
+def test_forward_general_kernel(tbn, M, cin, out, k, n_alpha, dtype, flags):
+    _check(tbn, M, cin, out, k, n_alpha, dtype, flags=flags, dirty_padding=True)
 
 
 def _random_shapes():
@@ -220,9 +233,10 @@ def test_sign_out_matrix_core_kernel(tbn, M, cin, out, k, n_alpha):
     _check_sign_out(tbn, M, cin, out, k, n_alpha)
 
 
-@pytest.mark.parametrize("M,cin,out,k,n_alpha", GENERIC + [MFMA[2], MFMA[4], MFMA[6]])
-def test_sign_out_general_kernel(tbn, M, cin, out, k, n_alpha):
-    _check_sign_out(tbn, M, cin, out, k, n_alpha)
+@pytest.mark.parametrize("flags", [0, 0x100])
+@pytest.mark.parametrize("M,cin,out,k,n_alpha", GENERIC + DIRECT + [MFMA[2], MFMA[4], MFMA[6]])
+def test_sign_out_general_kernel(tbn, M, cin, out, k, n_alpha, flags):
+    _check_sign_out(tbn, M, cin, out, k, n_alpha, flags=flags)
 
 
 def test_sign_out_both_kernels_agree_and_relu_changes_nothing(tbn):
