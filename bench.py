@@ -41,6 +41,9 @@ def parse_args():
     ap.add_argument("--all-configs", action="store_true", help="also time the other layer shapes (extra lines on stderr)")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="run only a plain device copy of 256 MiB (for scaling rocprofv3 FETCH_SIZE / WRITE_SIZE)")
+    ap.add_argument("--odd-shapes", action="store_true",
+                    help="time shapes the matrix-core kernels decline (row lengths no multiple of 8, 5x5 / 7x7 windows, sign rows "
+                         "no multiple of 256 bits): default dispatch against the one-thread-per-output kernels; prints one JSON object")
     ap.add_argument("--binact-only", action="store_true",
                     help="run only the binary-activation path on the metric shape: sign packing, the layer with bf16 outputs and "
                          "with sign-bit outputs, --steps times each (for rocprofv3 counter runs of these kernels)")
@@ -87,6 +90,10 @@ def main():
             b.copy_(a)
         torch.cuda.synchronize()
         print(json.dumps({"copy_bytes_read": a.numel(), "copy_bytes_written": b.numel(), "launches": 5}))
+        return
+
+    if args.odd_shapes:
+        print(json.dumps(odd_shapes(torch, tbn, max(3, min(args.steps, 20)))))
         return
 
     if args.binact_only:
@@ -439,6 +446,48 @@ def time_other_configs(torch, tbn, wl, iters=30):
                        "alg_gbs": round(byts / us / 1e3, 1), "warm": _roof_fields(us, byts, alg_flop, ceil, 3.0 if c.dtype == "f32" else 1.0),
                        "cold": _roof_fields(usc, byts, alg_flop, ceil, 3.0 if c.dtype == "f32" else 1.0)}
         del x, xs, ys
+    return out
+
+
+def odd_shapes(torch, tbn, iters):
+    """Shapes outside the matrix-core kernels' range (seeded synthetic inputs, tiles of whole rows / filters):
+    microseconds per call with the default dispatch (the direct kernels on the vector ALUs) and with
+    TBN_FLAG_FORCE_GENERIC (one thread per output)."""
+    g = torch.Generator(device="cuda")
+    g.manual_seed(240712075)
+    out = {}
+
+    def both(fn):
+        fn(0)
+        fn(tbn.TBN_FLAG_FORCE_GENERIC)
+        d = _timed_us(torch, lambda i: fn(0), iters, warm=1)
+        f = _timed_us(torch, lambda i: fn(tbn.TBN_FLAG_FORCE_GENERIC), max(2, iters // 4), warm=1)
+        return {"us": round(d, 1), "one_thread_per_output_us": round(f, 1), "ratio": round(f / d, 1)}
+
+    for M, cin, cout, k, dt in ((8192, 196, 384, 4, torch.float32), (8192, 196, 384, 4, torch.bfloat16), (8192, 300, 300, 4, torch.float32),
+                                (8192, 2050, 1026, 2, torch.bfloat16), (1024, 196, 384, 4, torch.float32)):
+        w = torch.randn(cin * cout, device="cuda", generator=g) * 0.02
+        x = torch.randn((M, cin), device="cuda", generator=g).to(dt)
+        tile, alpha = tbn.tbn_pack_tile(w, k, k)
+        y = torch.empty((M, cout), device="cuda", dtype=dt)
+        out[f"linear_{M}x{cin}_to_{cout}_k{k}_{'f32' if dt == torch.float32 else 'bf16'}"] = both(
+            lambda fl: tbn.tbn_linear_forward(x, tile, alpha, cout, k, y=y, flags=fl))
+    for N, C, H, O, kk, st, pd, k, dt in ((32, 3, 224, 64, 7, 2, 3, 4, torch.float32), (32, 3, 224, 64, 7, 2, 3, 4, torch.bfloat16),
+                                          (32, 64, 28, 64, 5, 1, 2, 4, torch.float32)):
+        w = torch.randn(O * C * kk * kk, device="cuda", generator=g) * 0.02
+        x = torch.randn((N, C, H, H), device="cuda", generator=g).to(dt)
+        tile, alpha = tbn.tbn_pack_tile(w, k, 1)
+        y = tbn.tbn_conv2d_forward(x, tile, alpha, O, kk, kk, k, (st, st), (pd, pd))
+        out[f"conv{kk}x{kk}s{st}_{C}_{H}x{H}_to{O}_k{k}_b{N}_{'f32' if dt == torch.float32 else 'bf16'}"] = both(
+            lambda fl: tbn.tbn_conv2d_forward(x, tile, alpha, O, kk, kk, k, (st, st), (pd, pd), y=y, flags=fl))
+    for M, cin, cout, k in ((8192, 4128, 4096, 8), (8192, 3000, 3072, 6), (8192, 1024, 1000, 4)):
+        w = torch.randn(cin * cout, device="cuda", generator=g) * 0.02
+        x = torch.randn((M, cin), device="cuda", generator=g).bfloat16()
+        tile, alpha = tbn.tbn_pack_tile(w, k, k)
+        bits = tbn.tbn_sign_pack(x)
+        y = torch.empty((M, cout), device="cuda", dtype=torch.bfloat16)
+        out[f"binary_activations_{M}x{cin}_to_{cout}_k{k}"] = both(
+            lambda fl: tbn.tbn_linear_forward_binact(bits, cin, tile, alpha, cout, k, y=y, flags=fl))
     return out
 
 
