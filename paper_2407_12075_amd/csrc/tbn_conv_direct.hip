@@ -18,7 +18,7 @@ namespace tbn {
 
 namespace {
 
-constexpr int kFG = 16;        // distinct filters per workgroup
+constexpr int kMaxFG = 16;     // distinct filters per workgroup: 16, or 4 where 16 would leave most of the chip idle
 constexpr int kPixels = 256;   // output pixels per workgroup
 constexpr int kStage = 512;    // (channel, tap) positions of a filter staged per pass
 
@@ -31,7 +31,7 @@ struct DirectParams {
     int32_t n_alpha, relu;
 };
 
-template <typename T>
+template <typename T, int kFG>
 __global__ __launch_bounds__(kPixels) void conv_direct_kernel(const T *__restrict__ x, T *__restrict__ y,
                                                               const uint32_t *__restrict__ tile,
                                                               const float *__restrict__ alpha, DirectParams P) {
@@ -66,6 +66,7 @@ __global__ __launch_bounds__(kPixels) void conv_direct_kernel(const T *__restric
             }
         }
         __syncthreads();
+#pragma unroll 4
         for (int32_t e = 0; e < n; ++e) {
             const int32_t yi = yi0 + dy, xi = xi0 + dx;
             float xv = 0.f;
@@ -111,7 +112,7 @@ bool conv_direct_supported(const ConvArgs &a) {
     if (U < 1 || U > a.O || a.O % U != 0) return false;
     if (a.n_alpha != 1 && a.n_alpha != a.O / U) return false;
     if (a.C * a.H * a.W >= (int64_t(1) << 31) || a.Ho * a.Wo >= (int64_t(1) << 31)) return false;
-    if (a.N > 65535 || (U + kFG - 1) / kFG > 65535 || (a.Ho * a.Wo + kPixels - 1) / kPixels > 0x7fffffffLL) return false;
+    if (a.N > 65535 || (U + 3) / 4 > 65535 || (a.Ho * a.Wo + kPixels - 1) / kPixels > 0x7fffffffLL) return false;
     return true;
 }
 
@@ -125,14 +126,22 @@ tbn_status launch_conv_direct(const ConvArgs &a) {
     P.reps = static_cast<int32_t>(a.O / P.U);
     P.n_alpha = a.n_alpha;
     P.relu = (a.flags & TBN_FLAG_RELU) ? 1 : 0;
-    const dim3 grid(static_cast<unsigned>((a.Ho * a.Wo + kPixels - 1) / kPixels), static_cast<unsigned>((P.U + kFG - 1) / kFG),
-                    static_cast<unsigned>(a.N));
-    if (a.dt == TBN_F32)
-        hipLaunchKernelGGL(conv_direct_kernel<float>, grid, dim3(kPixels), 0, a.stream, static_cast<const float *>(a.x),
-                           static_cast<float *>(a.y), a.tile, a.alpha, P);
-    else
-        hipLaunchKernelGGL(conv_direct_kernel<uint16_t>, grid, dim3(kPixels), 0, a.stream, static_cast<const uint16_t *>(a.x),
-                           static_cast<uint16_t *>(a.y), a.tile, a.alpha, P);
+    // 16 distinct filters per workgroup; 4 where that would give the chip fewer than two workgroups per CU (an input
+    // element then feeds four sums instead of 16, but four times the threads work: 5x5, 64 -> 64 channels on 28 x 28
+    // maps, 32 images, 16 distinct filters: 128 workgroups at 16)
+    const int64_t pix_blocks = (a.Ho * a.Wo + kPixels - 1) / kPixels;
+    const bool narrow = pix_blocks * a.N * ((P.U + kMaxFG - 1) / kMaxFG) < 512;
+    const int fg = narrow ? 4 : kMaxFG;
+    const dim3 grid(static_cast<unsigned>(pix_blocks), static_cast<unsigned>((P.U + fg - 1) / fg), static_cast<unsigned>(a.N));
+#define TBN_CONV_DIRECT_LAUNCH(T, FG)                                                                                     \
+    hipLaunchKernelGGL((conv_direct_kernel<T, FG>), grid, dim3(kPixels), 0, a.stream, static_cast<const T *>(a.x),          \
+                       static_cast<T *>(a.y), a.tile, a.alpha, P)
+    if (a.dt == TBN_F32) {
+        if (narrow) TBN_CONV_DIRECT_LAUNCH(float, 4); else TBN_CONV_DIRECT_LAUNCH(float, kMaxFG);
+    } else {
+        if (narrow) TBN_CONV_DIRECT_LAUNCH(uint16_t, 4); else TBN_CONV_DIRECT_LAUNCH(uint16_t, kMaxFG);
+    }
+#undef TBN_CONV_DIRECT_LAUNCH
     return check_launch("tbn_conv2d_forward (direct kernel)");
 }
 
