@@ -380,6 +380,38 @@ def test_aligned_output_blocks_are_scaled_copies_at_full_size(tbn):
         assert torch.equal(yb[:, 0], yb[:, r])
 
 
+def test_bound_calls_repeat_the_library_call(tbn):
+    """tbn_bind marshals a call once; the callable it returns makes the same library call on the same buffers."""
+    g = torch.Generator(device="cuda")
+    g.manual_seed(5)
+    M, cin, cout, k = 300, 512, 1024, 4
+    w = torch.randn(cin * cout, device="cuda", generator=g)
+    x = torch.randn((M, cin), device="cuda", generator=g).to(torch.bfloat16)
+    tile_ref, alpha_ref = tbn.tbn_pack_tile(w, k, k)
+    y_ref = tbn.tbn_linear_forward(x, tile_ref, alpha_ref, cout, k)
+    tile = torch.zeros_like(tile_ref)
+    alpha = torch.zeros_like(alpha_ref)
+    ws = torch.empty(tbn.tbn_pack_workspace_bytes(w.numel(), k, k) + 8, dtype=torch.uint8, device="cuda")
+    y = torch.zeros_like(y_ref)
+    pack = tbn.tbn_bind(tbn.tbn_pack_tile, w, k, k, tile_out=tile, alpha_out=alpha, workspace=ws)
+    fwd = tbn.tbn_bind(tbn.tbn_linear_forward, x, tile, alpha, cout, k, y=y)
+    torch.cuda.synchronize()
+    assert int(tile.abs().max()) == 0 and float(y.float().abs().max()) == 0.0   # binding launches nothing
+    t, a = pack()
+    out = fwd()
+    torch.cuda.synchronize()
+    assert t is tile and a is alpha and out is y
+    assert torch.equal(tile, tile_ref) and torch.equal(alpha, alpha_ref) and torch.equal(y.view(torch.int16), y_ref.view(torch.int16))
+    x.neg_()                                   # the bound call reads the buffers as they are when it is invoked
+    fwd()
+    torch.cuda.synchronize()
+    assert torch.equal(y.view(torch.int16), (-y_ref.float()).to(torch.bfloat16).view(torch.int16))
+    with pytest.raises(ValueError):
+        tbn.tbn_bind(tbn.tbn_pack_tile, w, k, k)            # no workspace: the bound call would not own one
+    with pytest.raises(ValueError):
+        tbn.tbn_bind(tbn.tbn_tile_words, w.numel(), k)      # nothing to bind
+
+
 # ------------------------------------------------------------------------------ conv
 CONV_SMALL = [
     # N, C, H, W, O, kh, kw, stride, pad, k, n_alpha
