@@ -342,9 +342,10 @@ def time_other_configs(torch, tbn, wl, iters=30):
         nsets = int(min(96, max(2, -(-cold_target // byts) + 1)))
         xs = [x] + [x.clone() for _ in range(nsets - 1)]
         ys = [torch.empty((c.M, c.cout), dtype=x.dtype, device="cuda") for _ in range(nsets)]
-        warm = _timed_us(torch, lambda i: tbn.tbn_linear_forward(xs[0], tile, alpha, c.cout, c.k, y=ys[0], flags=flags), iters)
-        cold = _timed_us(torch, lambda i: tbn.tbn_linear_forward(xs[i % nsets], tile, alpha, c.cout, c.k, y=ys[i % nsets], flags=flags),
-                         max(iters, nsets), warm=nsets)
+        # calls marshalled once (tbn_bind), so that an eager timing of a short kernel shows the launch rather than Python
+        calls = [tbn.tbn_bind(tbn.tbn_linear_forward, xs[j], tile, alpha, c.cout, c.k, y=ys[j], flags=flags) for j in range(nsets)]
+        warm = _timed_us(torch, lambda i: calls[0](), iters)
+        cold = _timed_us(torch, lambda i: calls[i % nsets](), max(iters, nsets), warm=nsets)
         factor = 3.0 if c.dtype == "f32" else 1.0
         row = {"us": round(warm, 2), "cold_us": round(cold, 2), "cold_sets": nsets, "cold_set_bytes_total": int(nsets * byts),
                "dense_equiv_tflops": round(2.0 * c.M * c.cin * c.cout / warm / 1e6, 1),
@@ -391,7 +392,8 @@ def time_other_configs(torch, tbn, wl, iters=30):
     for M in (1, 16, 64, 128, 256, 512, 1024, 2048, 4096, 8192):
         xm = x[:M].contiguous()
         ym = torch.empty((M, c.cout), dtype=x.dtype, device="cuda")
-        us = _timed_us(torch, lambda i: tbn.tbn_linear_forward(xm, tile, alpha, c.cout, c.k, y=ym), iters)
+        call = tbn.tbn_bind(tbn.tbn_linear_forward, xm, tile, alpha, c.cout, c.k, y=ym)
+        us = _timed_us(torch, lambda i: call(), iters)
         byts = (M * c.cin + M * c.cout) * 2 + c.p // 8
         roof = max(byts / (HBM_PEAK_GBS * 1e3), 2.0 * M * c.cin * (c.p // c.cin) / (MFMA_BF16_PEAK_TFLOPS * 1e6))
         sweep[str(M)] = {"us": round(us, 2), "roof_us": round(roof, 2)}
