@@ -347,7 +347,8 @@ def time_other_configs(torch, tbn, wl, iters=30):
         warm = _timed_us(torch, lambda i: calls[0](), iters)
         cold = _timed_us(torch, lambda i: calls[i % nsets](), max(iters, nsets), warm=nsets)
         factor = 3.0 if c.dtype == "f32" else 1.0
-        row = {"us": round(warm, 2), "cold_us": round(cold, 2), "cold_sets": nsets, "cold_set_bytes_total": int(nsets * byts),
+        row = {"kernel": tbn.tbn_linear_forward_kernel(x.dtype, c.M, c.cin, c.cout, c.k, c.n_alpha, flags, x.data_ptr(), ys[0].data_ptr()),
+               "us": round(warm, 2), "cold_us": round(cold, 2), "cold_sets": nsets, "cold_set_bytes_total": int(nsets * byts),
                "dense_equiv_tflops": round(2.0 * c.M * c.cin * c.cout / warm / 1e6, 1),
                "alg_gbs": round(byts / warm / 1e3, 1), "alg_gbs_cold": round(byts / cold / 1e3, 1),
                "warm": _roof_fields(warm, byts, alg_flop, ceil, factor), "cold": _roof_fields(cold, byts, alg_flop, ceil, factor)}
@@ -396,7 +397,8 @@ def time_other_configs(torch, tbn, wl, iters=30):
         us = _timed_us(torch, lambda i: call(), iters)
         byts = (M * c.cin + M * c.cout) * 2 + c.p // 8
         roof = max(byts / (HBM_PEAK_GBS * 1e3), 2.0 * M * c.cin * (c.p // c.cin) / (MFMA_BF16_PEAK_TFLOPS * 1e6))
-        sweep[str(M)] = {"us": round(us, 2), "roof_us": round(roof, 2)}
+        sweep[str(M)] = {"kernel": tbn.tbn_linear_forward_kernel(x.dtype, M, c.cin, c.cout, c.k, c.n_alpha, 0, xm.data_ptr(), ym.data_ptr()),
+                         "us": round(us, 2), "roof_us": round(roof, 2)}
     out["metric_layer_batch_sweep"] = sweep
     del w, x
     # long rows at a few hundred to a few thousand batch rows: the call without and with a workspace (split K)

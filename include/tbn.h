@@ -148,6 +148,21 @@ tbn_status tbn_linear_forward(const void *x, void *y, tbn_dtype dt, int64_t M, i
                               int32_t n_alpha, uint32_t flags, void *stream);
 
 /*
+ * Which kernel family tbn_linear_forward would launch for these arguments (the layer operation stated after
+ * Eq. 8; the families differ in schedule, never in what is computed).  Host arithmetic only: nothing is launched and
+ * no pointer is dereferenced.
+ *
+ *   x, y : the pointers the forward call would get (any address space; only their alignment is looked at; NULL
+ *          counts as aligned).
+ * Returns a static string, one of "decode", "small-batch", "tile", "stream", "block", "general", "rows", "direct",
+ * "generic"; "" on sizes tbn_linear_forward would reject.  The choice also depends on the current device's number
+ * of CUs (256 is assumed where there is no device).  A help for tests and for reading a profile; a caller never
+ * needs it.
+ */
+const char *tbn_linear_forward_kernel(const void *x, const void *y, tbn_dtype dt, int64_t M, int64_t in, int64_t out,
+                                      int32_t k, int32_t n_alpha, uint32_t flags);
+
+/*
  * tbn_linear_forward with a caller-supplied workspace.  Same layer (the layer operation stated after Eq. 8), same
  * arguments; the workspace lets shapes whose output blocks would occupy only a fraction of the GPU and whose
  * rows are long (bfloat16, tile of whole weight rows, more than 64 and up to a few thousand batch rows, `in` of

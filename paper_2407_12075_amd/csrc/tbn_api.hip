@@ -55,8 +55,11 @@ static tbn_status check_tiling(int64_t n, int32_t k, int32_t n_alpha) {
     return TBN_OK;
 }
 
-static tbn_status dispatch_linear(const LinearArgs &a) {
-    drop_stale_error();
+// The kernel family that serves a fully-connected call (host arithmetic only: shapes, alignment of the pointers, the
+// number of CUs of the current device).
+enum class LinearKernel { Decode, Tile, Skinny, Stream, Block, Mfma, Rows, Direct, Generic };
+
+static LinearKernel choose_linear(const LinearArgs &a) {
     if (!(a.flags & TBN_FLAG_FORCE_GENERIC)) {
         // at most 16 batch rows: the decode kernel (a workgroup per two distinct columns reads all of X); with many
         // distinct columns and 8 - 16 rows the small-batch kernel, whose workgroups share X sixteen columns at a time,
@@ -65,32 +68,63 @@ static tbn_status dispatch_linear(const LinearArgs &a) {
         // 13.2 against 6.7 / 7.1 / 11.1)
         if (!(a.flags & TBN_FLAG_LARGE_BATCH) && linear_decode_supported(a) &&
             (a.M * (a.p / a.in) <= 16384 || !linear_skinny_supported(a)))
-            return launch_linear_decode(a);
-        if (!(a.flags & (TBN_FLAG_BLOCK_KERNEL | TBN_FLAG_STREAM_KERNEL)) && linear_tile_preferred(a)) return launch_linear_tile(a);
-        if (linear_skinny_supported(a)) return launch_linear_skinny(a);
+            return LinearKernel::Decode;
+        if (!(a.flags & (TBN_FLAG_BLOCK_KERNEL | TBN_FLAG_STREAM_KERNEL)) && linear_tile_preferred(a)) return LinearKernel::Tile;
+        if (linear_skinny_supported(a)) return LinearKernel::Skinny;
         if (!(a.flags & TBN_FLAG_BLOCK_KERNEL)) {
             // bfloat16, tile of whole rows: 128 x 128 blocks with load waves; the streaming kernel (64-row half
             // tiles, twice the workgroups) where the blocks would leave half of the CUs or more idle
             // (4096 x 4096, k = 8, batch 512 / 1024 / 2048: 16 / 17 / 20 us against 23 / 22 / 23)
             const int64_t U = a.p % a.in == 0 ? a.p / a.in : 0;
             const int64_t blocks = ((a.M + 127) / 128) * ((U + 127) / 128);
-            if ((a.flags & TBN_FLAG_TILE_KERNEL) && linear_tile_supported(a)) return launch_linear_tile(a);
+            if ((a.flags & TBN_FLAG_TILE_KERNEL) && linear_tile_supported(a)) return LinearKernel::Tile;
             const bool stream = (a.flags & TBN_FLAG_STREAM_KERNEL) || blocks <= 128;   // (batch 4096: 25.2 us against 28.3)
-            if (stream && linear_stream_supported(a)) return launch_linear_stream(a);
+            if (stream && linear_stream_supported(a)) return LinearKernel::Stream;
             // (rows of 256: two rounds per block, too few for the persistent form; on grids of more than two blocks per CU
             // the general kernel with two workgroups per CU is 10 - 25 % faster: 8192 x 256 -> 4096 distinct columns 36 us
             // against 43)
             const bool short_rows = a.in < 512 && blocks > 512 && linear_mfma_supported(a);
-            if (!short_rows && linear_block_supported(a)) return launch_linear_block(a);
+            if (!short_rows && linear_block_supported(a)) return LinearKernel::Block;
             // float32, tile of whole rows: one wave per 32 batch rows (every shape measured, up to 8192 distinct columns
             // at batch 8192, runs 15 - 70 % faster than in the 128 x 128 blocks of the general kernel: 8192 x 1024 ->
             // 1024 distinct columns 57 us against 84, 8192 x 4096 -> 8192 distinct columns 1379 against 1672)
-            if (a.dt == TBN_F32 && linear_tile_supported(a)) return launch_linear_tile(a);
+            if (a.dt == TBN_F32 && linear_tile_supported(a)) return LinearKernel::Tile;
         }
-        if (linear_mfma_supported(a)) return launch_linear_mfma(a);
-        if (linear_rows_supported(a)) return launch_linear_rows(a);
+        if (linear_mfma_supported(a)) return LinearKernel::Mfma;
+        if (linear_rows_supported(a)) return LinearKernel::Rows;
         // row lengths and alignments that none of the kernels above takes (in no multiple of 8), tile of whole rows
-        if (linear_direct_supported(a)) return launch_linear_direct(a);
+        if (linear_direct_supported(a)) return LinearKernel::Direct;
+    }
+    return LinearKernel::Generic;
+}
+
+static const char *linear_kernel_name(LinearKernel kn) {
+    switch (kn) {
+        case LinearKernel::Decode: return "decode";
+        case LinearKernel::Tile: return "tile";
+        case LinearKernel::Skinny: return "small-batch";
+        case LinearKernel::Stream: return "stream";
+        case LinearKernel::Block: return "block";
+        case LinearKernel::Mfma: return "general";
+        case LinearKernel::Rows: return "rows";
+        case LinearKernel::Direct: return "direct";
+        case LinearKernel::Generic: return "generic";
+    }
+    return "generic";
+}
+
+static tbn_status dispatch_linear(const LinearArgs &a) {
+    drop_stale_error();
+    switch (choose_linear(a)) {
+        case LinearKernel::Decode: return launch_linear_decode(a);
+        case LinearKernel::Tile: return launch_linear_tile(a);
+        case LinearKernel::Skinny: return launch_linear_skinny(a);
+        case LinearKernel::Stream: return launch_linear_stream(a);
+        case LinearKernel::Block: return launch_linear_block(a);
+        case LinearKernel::Mfma: return launch_linear_mfma(a);
+        case LinearKernel::Rows: return launch_linear_rows(a);
+        case LinearKernel::Direct: return launch_linear_direct(a);
+        case LinearKernel::Generic: break;
     }
     return launch_linear_generic(a);
 }
@@ -202,6 +236,16 @@ tbn_status tbn_linear_forward(const void *x, void *y, tbn_dtype dt, int64_t M, i
     LinearArgs a{x, y, (int)dt, M, in, out, tile, n / k, k, alpha, n_alpha, flags,
                  static_cast<hipStream_t>(stream)};
     return dispatch_linear(a);
+}
+
+const char *tbn_linear_forward_kernel(const void *x, const void *y, tbn_dtype dt, int64_t M, int64_t in, int64_t out,
+                                      int32_t k, int32_t n_alpha, uint32_t flags) {
+    int64_t n;
+    if ((dt != TBN_F32 && dt != TBN_BF16) || M <= 0 || in <= 0 || out <= 0 || k <= 0 || !mul_ok(in, out, &n) || n % k != 0 ||
+        (n_alpha != 1 && n_alpha != k))
+        return "";
+    LinearArgs a{x, const_cast<void *>(y), (int)dt, M, in, out, nullptr, n / k, k, nullptr, n_alpha, flags, nullptr};
+    return linear_kernel_name(choose_linear(a));
 }
 
 size_t tbn_linear_forward_workspace_bytes(tbn_dtype dt, int64_t M, int64_t in, int64_t out, int32_t k, uint32_t flags) {

@@ -61,6 +61,8 @@ def lib() -> ctypes.CDLL:
         L.tbn_linear_forward.restype = ctypes.c_int
         L.tbn_linear_forward.argtypes = [_c_vp, _c_vp, ctypes.c_int, _c_i64, _c_i64, _c_i64, _c_vp, _c_i32, _c_vp,
                                          _c_i32, _c_u32, _c_vp]
+        L.tbn_linear_forward_kernel.restype = ctypes.c_char_p
+        L.tbn_linear_forward_kernel.argtypes = [_c_vp, _c_vp, ctypes.c_int, _c_i64, _c_i64, _c_i64, _c_i32, _c_i32, _c_u32]
         L.tbn_linear_forward_workspace_bytes.restype = _c_sz
         L.tbn_linear_forward_workspace_bytes.argtypes = [ctypes.c_int, _c_i64, _c_i64, _c_i64, _c_i32, ctypes.c_uint32]
         L.tbn_linear_forward_ws.restype = ctypes.c_int
@@ -249,6 +251,14 @@ def tbn_linear_forward(x: torch.Tensor, tile: torch.Tensor, alpha: torch.Tensor,
     if st != TBN_OK:
         _raise(st)
     return y
+
+
+def tbn_linear_forward_kernel(dtype: torch.dtype, M: int, cin: int, out_features: int, k: int, n_alpha: int = 1,
+                              flags: int = 0, x_ptr: int = 0, y_ptr: int = 0) -> str:
+    """Name of the kernel family tbn_linear_forward would launch for these sizes ("" on sizes it rejects); x_ptr and
+    y_ptr are the addresses the call would get (only their alignment matters; 0 counts as aligned)."""
+    dt = TBN_F32 if dtype == torch.float32 else TBN_BF16
+    return lib().tbn_linear_forward_kernel(x_ptr or None, y_ptr or None, dt, M, cin, out_features, k, n_alpha, flags).decode()
 
 
 def tbn_linear_forward_workspace_bytes(dtype: torch.dtype, M: int, cin: int, out_features: int, k: int, flags: int = 0) -> int:

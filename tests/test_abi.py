@@ -119,3 +119,44 @@ def test_binding_refuses_host_tensors():
     w = torch.zeros(16)
     with pytest.raises(ValueError):
         tbn.tbn_pack_tile(w, 2)
+
+
+# Which kernel family serves which shape is host arithmetic (shapes, alignment, 256 CUs where there is no device):
+# the table the design states, pinned here so that a change of a dispatch rule shows up without a GPU.
+KERNEL_CHOICE = [
+    # dtype, M, in, out, k, flags, x address, expected family
+    ("bf16", 8192, 4096, 4096, 8, 0, 0, "block"),          # the metric shape
+    ("bf16", 8192, 4096, 16384, 2, 0, 0, "block"),         # more blocks than CUs: the persistent form of the same kernel
+    ("bf16", 4096, 4096, 4096, 8, 0, 0, "stream"),         # at most 128 blocks: 64-row half tiles
+    ("bf16", 1024, 4096, 4096, 8, 0, 0, "tile"),           # mid batches: a wave per 32 rows
+    ("bf16", 64, 4096, 4096, 8, 0, 0, "small-batch"),
+    ("bf16", 16, 4096, 4096, 8, 0, 0, "decode"),
+    ("bf16", 1, 4096, 4096, 8, 0, 0, "decode"),
+    ("bf16", 16, 4096, 4096, 8, "TBN_FLAG_LARGE_BATCH", 0, "small-batch"),   # the flag keeps the decode kernel out
+    ("bf16", 8192, 256, 16384, 4, 0, 0, "general"),        # rows of 256 on a large grid
+    ("f32", 12608, 384, 1536, 4, 0, 0, "tile"),            # ViT MLP
+    ("f32", 12608, 1536, 384, 4, 0, 0, "tile"),
+    ("f32", 8192, 196, 384, 4, 0, 0, "direct"),            # row length no multiple of 8
+    ("bf16", 8192, 2050, 1026, 2, 0, 0, "direct"),
+    ("bf16", 8192, 4096, 4096, 8, 0, 2, "direct"),         # activations not 16-byte aligned
+    ("f32", 64, 24, 10, 3, 0, 0, "generic"),               # tile of no whole rows, row length no multiple of 8
+    ("bf16", 8192, 4096, 4096, 8, "TBN_FLAG_FORCE_GENERIC", 0, "generic"),
+]
+
+
+@pytest.mark.parametrize("dtype,M,cin,out,k,flags,x_ptr,expected", KERNEL_CHOICE)
+def test_kernel_choice(lib, dtype, M, cin, out, k, flags, x_ptr, expected):
+    import torch
+    from paper_2407_12075_amd import tbn
+    dt = torch.float32 if dtype == "f32" else torch.bfloat16
+    if isinstance(flags, str):
+        flags = getattr(tbn, flags)
+    assert tbn.tbn_linear_forward_kernel(dt, M, cin, out, k, 1, flags, x_ptr=x_ptr) == expected
+
+
+def test_kernel_choice_rejects_what_the_forward_call_rejects(lib):
+    import torch
+    from paper_2407_12075_amd import tbn
+    assert tbn.tbn_linear_forward_kernel(torch.float32, 0, 8, 8, 2) == ""     # empty batch: nothing is launched
+    assert tbn.tbn_linear_forward_kernel(torch.float32, 4, 4, 4, 3) == ""     # n not divisible by k
+    assert tbn.tbn_linear_forward_kernel(torch.float32, 4, 4, 4, 2, n_alpha=3) == ""
