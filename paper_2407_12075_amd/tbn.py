@@ -105,6 +105,7 @@ def _raise(status: int):
 
 
 _recording = None   # list of (C function, marshalled arguments) while tbn_bind runs a wrapper
+_owned = None       # buffers a wrapper allocated for itself while tbn_bind runs it: the bound call keeps them alive
 
 
 def _call(name: str, *cargs) -> int:
@@ -115,25 +116,32 @@ def _call(name: str, *cargs) -> int:
     return f(*cargs)
 
 
+def _own(t: torch.Tensor) -> torch.Tensor:
+    if _owned is not None:
+        _owned.append(t)
+    return t
+
+
 def tbn_bind(fn, *args, **kwargs):
-    """Marshal once, launch many times: runs the wrapper `fn(*args, **kwargs)` (tbn_pack_tile, tbn_linear_forward or
-    tbn_linear_forward_ws) with all its checks and allocations but without launching, and returns a callable that
+    """Marshal once, launch many times: runs the wrapper `fn(*args, **kwargs)` (any of the layer, packing and sign-packing
+    wrappers of this module) with all its checks and allocations but without launching, and returns a callable that
     makes exactly that library call every time it is invoked and returns what the wrapper would have returned.  For
     loops that repeat a call on the same buffers (a serving loop refilling x in place): the Python side of a call
     drops from about 5 us to under 1 us.  The tensors, sizes, flags and the stream are those of the time of binding
     and are kept alive by the callable.  Not thread-safe while binding."""
-    global _recording
+    global _recording, _owned
     if _recording is not None:
         raise RuntimeError("tbn_bind: already binding")
-    _recording = []
+    _recording, _owned = [], []
     try:
         result = fn(*args, **kwargs)
     finally:
         calls, _recording = _recording, None
+        owned, _owned = _owned, None
     if not calls:
         raise ValueError("tbn_bind: the wrapper made no library call that can be bound")
 
-    def replay(_calls=tuple(calls), _keep=(args, kwargs), _result=result):
+    def replay(_calls=tuple(calls), _keep=(args, kwargs, owned), _result=result):
         for f, cargs in _calls:
             st = f(*cargs)
             if st != TBN_OK:
@@ -227,7 +235,7 @@ def tbn_pack_tile_noalloc(w_real: torch.Tensor, k: int, n_alpha: int, tile_out: 
     if tile_out.numel() < tbn_tile_words(w_real.numel(), k) or alpha_out.numel() < n_alpha or tile_out.device != w_real.device \
             or alpha_out.device != w_real.device or (a_real is not None and (a_real.numel() != w_real.numel() or a_real.device != w_real.device)):
         raise ValueError("tbn_pack_tile_noalloc: tile_out, alpha_out or a_real too small or on another device")
-    st = lib().tbn_pack_tile_noalloc(_dev(w_real, "w_real", torch.float32),
+    st = _call("tbn_pack_tile_noalloc", _dev(w_real, "w_real", torch.float32),
                                      None if a_real is None else _dev(a_real, "a_real", torch.float32),
                                      w_real.numel(), k, n_alpha, _dev(tile_out, "tile_out", torch.int32),
                                      _dev(alpha_out, "alpha_out", torch.float32), _stream(stream))
@@ -304,8 +312,8 @@ def tbn_pack_coltile(w_real: torch.Tensor, k: int, n_alpha: int = 1, a_real: Opt
     alpha_out = torch.empty(max(n_alpha, 1), dtype=torch.float32, device=dev)
     need = int(lib().tbn_pack_coltile_workspace_bytes(out, cin, k, n_alpha))
     if workspace is None:
-        workspace = torch.empty(max(need, 8), dtype=torch.uint8, device=dev)
-    st = lib().tbn_pack_coltile(_dev(w_real, "w_real", torch.float32),
+        workspace = _own(torch.empty(max(need, 8), dtype=torch.uint8, device=dev))
+    st = _call("tbn_pack_coltile", _dev(w_real, "w_real", torch.float32),
                                 None if a_real is None else _dev(a_real, "a_real", torch.float32),
                                 out, cin, k, n_alpha, _dev(tile_out, "tile_out", torch.int32),
                                 _dev(alpha_out, "alpha_out", torch.float32), _dev(workspace, "workspace"),
@@ -331,9 +339,9 @@ def tbn_linear_coltiled_forward(x: torch.Tensor, tile: torch.Tensor, alpha: torc
     elif tuple(y.shape) != (M, out_features) or y.dtype != x.dtype:
         raise ValueError("y must be (M, out) with x's dtype")
     if workspace is None:
-        workspace = torch.empty(max(tbn_linear_coltiled_workspace_bytes(x, k), 16), dtype=torch.uint8, device=x.device)
+        workspace = _own(torch.empty(max(tbn_linear_coltiled_workspace_bytes(x, k), 16), dtype=torch.uint8, device=x.device))
     _check_layer_tensors("tbn_linear_coltiled_forward", x, tile, alpha, cin * out_features, k, y, workspace)
-    st = lib().tbn_linear_coltiled_forward(_dev(x, "x"), _dev(y, "y"), _dt(x), M, cin, out_features,
+    st = _call("tbn_linear_coltiled_forward", _dev(x, "x"), _dev(y, "y"), _dt(x), M, cin, out_features,
                                            _dev(tile, "tile", torch.int32), k, _dev(alpha, "alpha", torch.float32),
                                            alpha.numel(), flags, _dev(workspace, "workspace"),
                                            workspace.numel() * workspace.element_size(), _stream(stream))
@@ -355,7 +363,7 @@ def tbn_conv2d_forward(x: torch.Tensor, tile: torch.Tensor, alpha: torch.Tensor,
     elif tuple(y.shape) != (N, out_channels, Ho, Wo) or y.dtype != x.dtype:
         raise ValueError("y must be (N, O, Ho, Wo) with x's dtype")
     _check_layer_tensors("tbn_conv2d_forward", x, tile, alpha, out_channels * C * kh * kw, k, y)
-    st = lib().tbn_conv2d_forward(_dev(x, "x"), _dev(y, "y"), _dt(x), N, C, H, W, out_channels, kh, kw,
+    st = _call("tbn_conv2d_forward", _dev(x, "x"), _dev(y, "y"), _dt(x), N, C, H, W, out_channels, kh, kw,
                                   stride[0], stride[1], pad[0], pad[1], _dev(tile, "tile", torch.int32), k,
                                   _dev(alpha, "alpha", torch.float32), alpha.numel(), flags, _stream(stream))
     if st != TBN_OK:
@@ -377,7 +385,7 @@ def tbn_sign_pack(x: torch.Tensor, xbits: Optional[torch.Tensor] = None, stream=
         xbits = torch.empty((M, words), dtype=torch.int32, device=x.device)
     elif tuple(xbits.shape) != (M, words) or xbits.device != x.device:
         raise ValueError(f"xbits must be ({M}, {words}) on {x.device}")
-    st = lib().tbn_sign_pack(_dev(x, "x"), _dt(x), M, cin, _dev(xbits, "xbits", torch.int32), _stream(stream))
+    st = _call("tbn_sign_pack", _dev(x, "x"), _dt(x), M, cin, _dev(xbits, "xbits", torch.int32), _stream(stream))
     if st != TBN_OK:
         _raise(st)
     return xbits
@@ -399,7 +407,7 @@ def tbn_linear_forward_binact(xbits: torch.Tensor, cin: int, tile: torch.Tensor,
     elif tuple(y.shape) != shape or (flags & TBN_FLAG_SIGN_OUT and y.dtype != torch.int32):
         raise ValueError(f"y must be {shape}" + (" int32" if flags & TBN_FLAG_SIGN_OUT else ""))
     _check_layer_tensors("tbn_linear_forward_binact", xbits, tile, alpha, cin * out_features, k, y)
-    st = lib().tbn_linear_forward_binact(_dev(xbits, "xbits", torch.int32), _dev(y, "y"),
+    st = _call("tbn_linear_forward_binact", _dev(xbits, "xbits", torch.int32), _dev(y, "y"),
                                          TBN_F32 if flags & TBN_FLAG_SIGN_OUT else _dt(y), M, cin, out_features,
                                          _dev(tile, "tile", torch.int32), k, _dev(alpha, "alpha", torch.float32),
                                          alpha.numel(), flags, _stream(stream))

@@ -412,6 +412,41 @@ def test_bound_calls_repeat_the_library_call(tbn):
         tbn.tbn_bind(tbn.tbn_tile_words, w.numel(), k)      # nothing to bind
 
 
+def test_bound_calls_of_the_other_layers(tbn):
+    """The convolution, the layer on sign bits with its sign packing, and the column-tiled layer (whose wrapper allocates
+    its own workspace, which the bound call must keep alive) as bound calls: each equals the direct call bit for bit,
+    also when invoked again after other allocations."""
+    g = torch.Generator(device="cuda")
+    g.manual_seed(6)
+    M, cin, cout, k = 200, 512, 256, 4
+    w = torch.randn(cin * cout, device="cuda", generator=g)
+    x = torch.randn((M, cin), device="cuda", generator=g)
+    tile, alpha = tbn.tbn_pack_tile(w, k, k)
+    # convolution
+    xc = torch.randn((2, 32, 14, 14), device="cuda", generator=g)
+    wc = torch.randn(64 * 32 * 9, device="cuda", generator=g)
+    tile_c, alpha_c = tbn.tbn_pack_tile(wc, 4, 1)
+    yc_ref = tbn.tbn_conv2d_forward(xc, tile_c, alpha_c, 64, 3, 3, 4, stride=(1, 1), pad=(1, 1))
+    conv = tbn.tbn_bind(tbn.tbn_conv2d_forward, xc, tile_c, alpha_c, 64, 3, 3, 4, stride=(1, 1), pad=(1, 1))
+    # sign bits and the layer on them
+    bits_ref = tbn.tbn_sign_pack(x)
+    yb_ref = tbn.tbn_linear_forward_binact(bits_ref, cin, tile, alpha, cout, k)
+    bits = torch.zeros_like(bits_ref)
+    sign = tbn.tbn_bind(tbn.tbn_sign_pack, x, xbits=bits)
+    binact = tbn.tbn_bind(tbn.tbn_linear_forward_binact, bits, cin, tile, alpha, cout, k)
+    # column-tiled layer, workspace allocated by the wrapper
+    tile_t, alpha_t = tbn.tbn_pack_coltile(w.view(cout, cin), k, k)
+    yt_ref = tbn.tbn_linear_coltiled_forward(x, tile_t, alpha_t, cout, k)
+    colt = tbn.tbn_bind(tbn.tbn_linear_coltiled_forward, x, tile_t, alpha_t, cout, k)
+    torch.cuda.synchronize()
+    for _ in range(2):
+        junk = [torch.full((1 << 20,), 7.0, device="cuda") for _ in range(8)]   # would reuse a freed workspace
+        yc, _, yb, yt = conv(), sign(), binact(), colt()
+        torch.cuda.synchronize()
+        assert torch.equal(yc, yc_ref) and torch.equal(bits, bits_ref) and torch.equal(yb, yb_ref) and torch.equal(yt, yt_ref)
+        del junk
+
+
 # ------------------------------------------------------------------------------ conv
 CONV_SMALL = [
     # N, C, H, W, O, kh, kw, stride, pad, k, n_alpha
